@@ -1,0 +1,294 @@
+/*
+ * MPZCH oracle -- TEST INFRASTRUCTURE, NOT THE PRODUCT.
+ *
+ * A plain, sequential, single-threaded CPU statement of what the batched
+ * remap path computes.  Only tests, the smoke check and the benchmark's
+ * cpu_baseline leg may load this file; the product path (the HIP library)
+ * shares no code with it and never calls it.
+ *
+ * What it follows (paper: "Multi-Probe Zero Collision Hash"):
+ *   - Sec. 3.1 (Auxiliary Tensors): identities I (int64, empty = -1) and
+ *     metadata M (here: int32 last-seen step).
+ *   - Sec. 3.2 + Algorithm 1: hash to a home slot, Pass 1 (discovery, read
+ *     only), Pass 2 (update / insert / evict), Case 3 (collision fallback to
+ *     the home slot, metadata of the home slot refreshed).
+ *   - Sec. 3.4 (Eviction Management): lazy TTL eviction -- a new ID takes
+ *     the first expired slot in its probe range; evicted slots are reported
+ *     so that the embedding rows can be reset.
+ *   - Sec. 3.6: input de-duplication (every copy of an ID gets one slot).
+ *   - Sec. 3.7: inference lookup is read-only.
+ *
+ * Readings where the paper is silent (the same readings bind the HIP path):
+ *   hash        = SplitMix64 finaliser of (id XOR seed);
+ *   home        = floor(hash * N / 2^64)          (multiply-high);
+ *   probe r     = (home + r) mod N, r < min(P, N) (window wraps);
+ *   expired     = step - M[s] > ttl               (M holds the last-seen step);
+ *   batch rule  = hits are refreshed before any allocation; misses allocate
+ *                 round-major / first-occurrence-position-minor, so that in
+ *                 every probe round the lowest first-occurrence batch index
+ *                 wins a contended slot;
+ *   invalid ids = negative ids: never stored, never match, map to the home
+ *                 slot of their bit pattern.
+ *
+ * Pins (tests/test_oracle_*.py): published SplitMix64 vectors; Table 1 of
+ * the paper at reduced scale; the balls-in-bins closed form for P = 1;
+ * textbook linear probing for P = N; a literal single-ID Algorithm 1 for
+ * batch size 1; exhaustive stable-matching enumeration for the batch rule;
+ * hand-worked TTL scenarios.
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { ORACLE_EVICT_NONE = 0, ORACLE_EVICT_TTL = 1 };
+
+typedef struct {
+    int64_t  num_slots;   /* N */
+    int32_t  max_probe;   /* P */
+    int32_t  policy;      /* ORACLE_EVICT_* */
+    int32_t  ttl;         /* steps */
+    int32_t  pad_;
+    uint64_t hash_seed;
+} oracle_cfg;
+
+/* stats layout shared by name (not by code) with the HIP library */
+enum {
+    ST_HIT_POS = 0,      /* positions whose id was resident at batch start   */
+    ST_MISS_POS,         /* valid positions whose id was not resident        */
+    ST_DISTINCT_MISS,    /* distinct ids among the miss positions            */
+    ST_INSERTS,          /* distinct missed ids placed in an empty slot      */
+    ST_EVICTIONS,        /* distinct missed ids placed by evicting           */
+    ST_COLLISIONS,       /* distinct missed ids that fell back to home       */
+    ST_INVALID_POS,      /* positions holding a negative id                  */
+    ST_HIT_PROBE_SUM,    /* sum over hit positions of (probe distance + 1)   */
+    ST_COUNT
+};
+
+/* SplitMix64 output function (public domain, Steele/Lea/Flood). */
+uint64_t oracle_mix64(uint64_t x)
+{
+    uint64_t z = x + 0x9E3779B97F4A7C15ULL;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+    return z ^ (z >> 31);
+}
+
+/* Algorithm 1, "h <- Hash(id)": uniform over [0, N). */
+int64_t oracle_home(int64_t id, uint64_t seed, int64_t num_slots)
+{
+    uint64_t h = oracle_mix64((uint64_t)id ^ seed);
+    return (int64_t)(((unsigned __int128)h * (unsigned __int128)(uint64_t)num_slots) >> 64);
+}
+
+static int64_t p_eff(const oracle_cfg *c)
+{
+    return c->max_probe < c->num_slots ? (int64_t)c->max_probe : c->num_slots;
+}
+
+static int64_t probe_slot(int64_t home, int64_t r, int64_t n_slots)
+{
+    return (home + r) % n_slots;
+}
+
+/* Sec. 3.4: an occupied slot is reclaimable once its last-seen step is more
+ * than ttl steps old; Sec. 3.1: an empty slot (-1) is always available. */
+static int claimable(const oracle_cfg *c, const int64_t *I, const int32_t *M,
+                     int64_t s, int32_t step)
+{
+    if (I[s] == -1) return 1;
+    if (c->policy == ORACLE_EVICT_TTL && I[s] >= 0 &&
+        (int64_t)step - (int64_t)M[s] > (int64_t)c->ttl) return 1;
+    return 0;
+}
+
+/* Pass 1 of Algorithm 1: first r with I[slot(r)] == id, else -1. */
+static int64_t discover(const oracle_cfg *c, const int64_t *I, int64_t id, int64_t home)
+{
+    int64_t P = p_eff(c);
+    for (int64_t r = 0; r < P; ++r)
+        if (I[probe_slot(home, r, c->num_slots)] == id) return r;
+    return -1;
+}
+
+typedef struct { int64_t id; int64_t pos; } id_pos;
+
+static int cmp_id_pos(const void *a, const void *b)
+{
+    const id_pos *x = (const id_pos *)a, *y = (const id_pos *)b;
+    if (x->id != y->id) return x->id < y->id ? -1 : 1;
+    if (x->pos != y->pos) return x->pos < y->pos ? -1 : 1;
+    return 0;
+}
+
+/*
+ * One training batch: insert + evict.  Returns 0, or -1 on bad arguments /
+ * out of memory.  out_evicted receives at most evicted_cap slots (in claim
+ * order); *out_num_evicted is the true count.  stats may be NULL.
+ */
+int oracle_remap(const oracle_cfg *c, int64_t *I, int32_t *M,
+                 const int64_t *ids, int64_t n, int32_t step,
+                 int64_t *out_slots,
+                 int64_t *out_evicted, int64_t evicted_cap, int64_t *out_num_evicted,
+                 int64_t *stats)
+{
+    if (!c || c->num_slots < 1 || c->max_probe < 1 || n < 0) return -1;
+    int64_t st[ST_COUNT];
+    memset(st, 0, sizeof st);
+    int64_t n_evicted = 0;
+    const int64_t N = c->num_slots, P = p_eff(c);
+
+    if (n > 0) {
+        /* Stage 0 (Sec. 3.6 de-duplication): first occurrence of every id. */
+        id_pos *sorted = (id_pos *)malloc((size_t)n * sizeof *sorted);
+        int64_t *first = (int64_t *)malloc((size_t)n * sizeof *first);   /* first-occurrence position */
+        int64_t *result = (int64_t *)malloc((size_t)n * sizeof *result); /* slot, valid at first positions */
+        int64_t *miss = (int64_t *)malloc((size_t)n * sizeof *miss);     /* first positions of missed ids */
+        if (!sorted || !first || !result || !miss) {
+            free(sorted); free(first); free(result); free(miss);
+            return -1;
+        }
+        for (int64_t j = 0; j < n; ++j) { sorted[j].id = ids[j]; sorted[j].pos = j; }
+        qsort(sorted, (size_t)n, sizeof *sorted, cmp_id_pos);
+        for (int64_t k = 0; k < n; ++k) {
+            if (k > 0 && sorted[k].id == sorted[k - 1].id)
+                first[sorted[k].pos] = first[sorted[k - 1].pos];
+            else
+                first[sorted[k].pos] = sorted[k].pos;
+        }
+        free(sorted);
+
+        /* Stage 1 (Pass 1 + "Update"): residents are found and refreshed
+         * before any allocation happens.  Only M is written, only I is read,
+         * so every id is discovered against the batch-start identities. */
+        int64_t n_miss = 0;
+        for (int64_t j = 0; j < n; ++j) {
+            if (first[j] != j) continue;
+            int64_t id = ids[j];
+            int64_t h = oracle_home(id, c->hash_seed, N);
+            if (id < 0) { result[j] = h; continue; }           /* invalid: no state change */
+            int64_t r = discover(c, I, id, h);
+            if (r >= 0) {
+                int64_t s = probe_slot(h, r, N);
+                M[s] = step;
+                result[j] = s;
+            } else {
+                result[j] = -1;
+                miss[n_miss++] = j;                             /* ascending position */
+            }
+        }
+        /* per-position hit statistics (duplicates included) */
+        for (int64_t j = 0; j < n; ++j) {
+            int64_t f = first[j];
+            if (ids[j] < 0) { st[ST_INVALID_POS]++; continue; }
+            if (result[f] >= 0) {
+                int64_t h = oracle_home(ids[j], c->hash_seed, N);
+                st[ST_HIT_POS]++;
+                st[ST_HIT_PROBE_SUM] += ((result[f] - h + N) % N) + 1;
+            } else {
+                st[ST_MISS_POS]++;
+            }
+        }
+        st[ST_DISTINCT_MISS] = n_miss;
+
+        /* Stage 2 (Pass 2 "Allocation", outcomes 1 and 2): round-major,
+         * position-minor.  A claim writes M = step, so the slot is no longer
+         * claimable for anyone visiting it later in this batch. */
+        for (int64_t r = 0; r < P; ++r) {
+            for (int64_t k = 0; k < n_miss; ++k) {
+                int64_t j = miss[k];
+                if (result[j] >= 0) continue;
+                int64_t id = ids[j];
+                int64_t s = probe_slot(oracle_home(id, c->hash_seed, N), r, N);
+                if (!claimable(c, I, M, s, step)) continue;
+                int was_occupied = (I[s] != -1);
+                I[s] = id;
+                M[s] = step;
+                result[j] = s;
+                if (was_occupied) {
+                    if (out_evicted && n_evicted < evicted_cap) out_evicted[n_evicted] = s;
+                    n_evicted++;
+                    st[ST_EVICTIONS]++;
+                } else {
+                    st[ST_INSERTS]++;
+                }
+            }
+        }
+
+        /* Stage 3 (Case 3, collision fallback): home slot, its metadata refreshed. */
+        for (int64_t k = 0; k < n_miss; ++k) {
+            int64_t j = miss[k];
+            if (result[j] >= 0) continue;
+            int64_t h = oracle_home(ids[j], c->hash_seed, N);
+            result[j] = h;
+            M[h] = step;
+            st[ST_COLLISIONS]++;
+        }
+
+        /* Stage 4: every copy of an id receives the slot of its first occurrence. */
+        for (int64_t j = 0; j < n; ++j) out_slots[j] = result[first[j]];
+
+        free(first); free(result); free(miss);
+    }
+    if (out_num_evicted) *out_num_evicted = n_evicted;
+    if (stats) memcpy(stats, st, sizeof st);
+    return 0;
+}
+
+/* Sec. 3.7: read-only lookup.  Miss -> home slot, found flag 0. */
+int oracle_lookup(const oracle_cfg *c, const int64_t *I,
+                  const int64_t *ids, int64_t n,
+                  int64_t *out_slots, uint8_t *out_found)
+{
+    if (!c || c->num_slots < 1 || c->max_probe < 1 || n < 0) return -1;
+    for (int64_t j = 0; j < n; ++j) {
+        int64_t id = ids[j];
+        int64_t h = oracle_home(id, c->hash_seed, c->num_slots);
+        int64_t r = id >= 0 ? discover(c, I, id, h) : -1;
+        out_slots[j] = r >= 0 ? probe_slot(h, r, c->num_slots) : h;
+        if (out_found) out_found[j] = (uint8_t)(r >= 0);
+    }
+    return 0;
+}
+
+/* Sec. 3.4: rows of reassigned slots go back to their initial value.
+ * row index = slot mod num_rows; init_row == NULL means all-zero bytes. */
+int oracle_reset_rows(const int64_t *slots, int64_t count,
+                      uint8_t *rows, int64_t num_rows, int64_t row_bytes, int64_t row_stride_bytes,
+                      const uint8_t *init_row)
+{
+    if (count < 0 || num_rows < 1 || row_bytes < 0 || row_stride_bytes < row_bytes) return -1;
+    for (int64_t k = 0; k < count; ++k) {
+        if (slots[k] < 0) return -1;
+        uint8_t *dst = rows + (slots[k] % num_rows) * row_stride_bytes;
+        if (init_row) memcpy(dst, init_row, (size_t)row_bytes);
+        else memset(dst, 0, (size_t)row_bytes);
+    }
+    return 0;
+}
+
+/*
+ * State checker over slots [lo, hi): every resident id must be found by a
+ * read-only lookup at exactly the slot that holds it.  That single condition
+ * implies that no id is stored twice and that every resident lies within
+ * min(P, N) probes of its home.  Also counts occupied slots and slots holding
+ * values that are neither -1 nor a valid id.  Returns the number of
+ * violations; *first_bad is the first offending slot (or -1).
+ */
+int64_t oracle_check_state(const oracle_cfg *c, const int64_t *I,
+                           int64_t lo, int64_t hi,
+                           int64_t *out_occupied, int64_t *first_bad)
+{
+    int64_t bad = 0, occ = 0, fb = -1;
+    for (int64_t s = lo; s < hi; ++s) {
+        int64_t x = I[s];
+        if (x == -1) continue;
+        if (x < -1) { if (fb < 0) fb = s; bad++; continue; }
+        occ++;
+        int64_t h = oracle_home(x, c->hash_seed, c->num_slots);
+        int64_t r = discover(c, I, x, h);
+        if (r < 0 || probe_slot(h, r, c->num_slots) != s) { if (fb < 0) fb = s; bad++; }
+    }
+    if (out_occupied) *out_occupied = occ;
+    if (first_bad) *first_bad = fb;
+    return bad;
+}

@@ -1,0 +1,20 @@
+"""MI355X-native MPZCH batched remap: thin Python binding over the C-ABI HIP library.
+
+The binding (``paper_2602_17050_amd.binding``) is loaded lazily so that the
+input generators in ``paper_2602_17050_amd.workloads`` can be imported on a
+machine without the built library.
+"""
+import importlib
+
+_BINDING_NAMES = (
+    "load_library", "MpzchTable", "MpzchError",
+    "mpzch_create", "mpzch_destroy", "mpzch_init_tensors", "mpzch_remap", "mpzch_lookup",
+    "mpzch_reset_rows", "mpzch_remap_jagged", "mpzch_status_string",
+    "EVICT_NONE", "EVICT_TTL", "EVICT_LRU", "STAT_NAMES",
+)
+
+
+def __getattr__(name):
+    if name in _BINDING_NAMES:
+        return getattr(importlib.import_module(__name__ + ".binding"), name)
+    raise AttributeError(f"module {__name__!r} has no attribute {name!r}")

@@ -1,0 +1,473 @@
+"""CPU-only pins of the oracle against things that are not the oracle.
+
+Each test names the passage of the paper (or the textbook fact) that fixes the
+expected value.  Helper code here is written independently of ``oracle/`` (Python
+big-integer arithmetic, dict/list based) so that a mistake in the C file cannot
+cancel out.
+"""
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+from hypothesis import given, settings, strategies as st
+
+import oracle
+from paper_2602_17050_amd import workloads as wl
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+M64 = (1 << 64) - 1
+
+
+# ---------------------------------------------------------------- independent helpers
+def py_mix64(x):
+    z = (x + 0x9E3779B97F4A7C15) & M64
+    z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & M64
+    z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & M64
+    return z ^ (z >> 31)
+
+
+def py_home(id_, seed, n_slots):
+    return (py_mix64((id_ & M64) ^ seed) * n_slots) >> 64
+
+
+def ids_with_home(target_home, seed, n_slots, count, start=0, avoid=()):
+    out, x = [], start
+    while len(out) < count:
+        if py_home(x, seed, n_slots) == target_home and x not in avoid:
+            out.append(x)
+        x += 1
+    return out
+
+
+class Alg1Table:
+    """Algorithm 1 for ONE id at a time, as printed: Pass 1 sets `exists`, Pass 2 walks
+    the range again doing update / insert / evict, Case 3 falls back to the home slot.
+    `meta` is split into the value written (the step) and the expiry test
+    step - M > ttl (Sec. 3.4: a slot whose stored time lies before now is expired)."""
+
+    def __init__(self, n_slots, max_probe, ttl, evict, seed):
+        self.I = [-1] * n_slots
+        self.M = [-1] * n_slots
+        self.N, self.P, self.ttl, self.evict, self.seed = n_slots, min(max_probe, n_slots), ttl, evict, seed
+
+    def lookup_one(self, id_, step):
+        h = py_home(id_, self.seed, self.N)
+        exists = False
+        for i in range(self.P):
+            if self.I[(h + i) % self.N] == id_:
+                exists = True
+                break
+        for i in range(self.P):
+            slot = (h + i) % self.N
+            id_curr, meta_curr = self.I[slot], self.M[slot]
+            if id_curr == id_ or id_curr == -1:
+                self.I[slot] = id_
+                self.M[slot] = step
+                return slot, False
+            if self.evict and not exists and step - meta_curr > self.ttl:
+                self.I[slot] = id_
+                self.M[slot] = step
+                return slot, True
+        self.M[h] = step
+        return h, False
+
+
+# ---------------------------------------------------------------- hash / home (Algorithm 1, "h <- Hash(id)")
+def test_mix64_matches_published_splitmix64_vectors():
+    with open(os.path.join(GOLDEN, "splitmix64_seed0.txt")) as f:
+        want = [int(l, 16) for l in f if l.strip() and not l.startswith("#")]
+    for i, w in enumerate(want):
+        assert oracle.mix64((i * 0x9E3779B97F4A7C15) & M64) == w
+
+
+@given(st.integers(-(1 << 63), (1 << 63) - 1), st.integers(0, M64), st.integers(1, (1 << 62)))
+@settings(max_examples=300, deadline=None)
+def test_home_is_multiply_high_of_seeded_hash(id_, seed, n_slots):
+    h = oracle.home(id_, seed, n_slots)
+    assert h == py_home(id_, seed, n_slots)
+    assert 0 <= h < n_slots
+
+
+def test_home_known_answers():
+    assert oracle.home(0, 0, 4096) == 3618
+    assert oracle.home(42, 7, 1000) == 968
+    assert oracle.home((1 << 63) - 1, 0x5EED, 10 ** 9) == 352618807
+
+
+# ---------------------------------------------------------------- batch size 1 == Algorithm 1
+@given(st.data())
+@settings(max_examples=150, deadline=None)
+def test_single_id_batches_equal_algorithm_1(data):
+    n_slots = data.draw(st.integers(1, 24))
+    max_probe = data.draw(st.integers(1, 30))
+    ttl = data.draw(st.integers(0, 3))
+    evict = data.draw(st.booleans())
+    seed = data.draw(st.integers(0, 1 << 32))
+    universe = data.draw(st.integers(1, 40))
+    calls = data.draw(st.lists(st.tuples(st.integers(0, universe), st.integers(0, 2)), min_size=1, max_size=80))
+    ref = Alg1Table(n_slots, max_probe, ttl, evict, seed)
+    t = oracle.Table(n_slots, max_probe, oracle.EVICT_TTL if evict else oracle.EVICT_NONE, ttl, seed)
+    step = 0
+    for id_, dstep in calls:
+        step += dstep
+        slot, evicted = ref.lookup_one(id_, step)
+        r = t.remap([id_], step)
+        assert r.slots[0] == slot
+        assert (len(r.evicted) == 1) == evicted
+        if evicted:
+            assert r.evicted[0] == slot
+        assert t.identities.tolist() == ref.I
+        assert t.metadata.tolist() == ref.M
+
+
+# ---------------------------------------------------------------- P = N, eviction off: textbook linear probing
+@given(st.data())
+@settings(max_examples=100, deadline=None)
+def test_full_range_probing_is_textbook_linear_probing(data):
+    """With an unbounded probe range and no eviction the occupied-slot SET of a linear
+    probing table does not depend on insertion order (Knuth, TAOCP vol. 3, 6.4), so any
+    batching must occupy the same slots as naive one-at-a-time insertion."""
+    n_slots = data.draw(st.integers(1, 40))
+    seed = data.draw(st.integers(0, 1 << 20))
+    ids = data.draw(st.lists(st.integers(0, 1 << 40), min_size=0, max_size=n_slots, unique=True))
+    occupied = set()
+    for x in ids:
+        s = py_home(x, seed, n_slots)
+        while s in occupied:
+            s = (s + 1) % n_slots
+        occupied.add(s)
+    cut = data.draw(st.integers(0, len(ids)))
+    t = oracle.Table(n_slots, n_slots, oracle.EVICT_NONE, 0, seed)
+    r1 = t.remap(ids[:cut], 1)
+    r2 = t.remap(ids[cut:], 2)
+    assert set(np.nonzero(t.identities >= 0)[0].tolist()) == occupied
+    slots = list(r1.slots) + list(r2.slots)
+    assert len(set(slots)) == len(ids)                      # everyone got a dedicated slot
+    for x, s in zip(ids, slots):
+        assert t.identities[s] == x
+    assert r1.stats["collisions"] == 0 and r2.stats["collisions"] == 0
+
+
+# ---------------------------------------------------------------- Table 1 (Sec. 3.3)
+def _table1():
+    rows = []
+    with open(os.path.join(GOLDEN, "table1_collision_rate.txt")) as f:
+        for l in f:
+            if l.strip() and not l.startswith("#"):
+                v = l.split()
+                rows.append((int(v[0]), float(v[2]), dict(zip((8, 16, 32, 64, 128, 256, 512), map(float, v[3:])))))
+    return rows
+
+
+N_IDS = 1_500_000           # the paper's 150 M ids at 1/100 scale; table sizes scale alike
+
+
+def _collision_pct(n_slots, max_probe, batch=4096):
+    """Ids arrive in batches that are small against the table, as in the paper (tens of
+    thousands of ids per call against 100-500 M slots, Sec. 3)."""
+    ids = wl.distinct_ids(N_IDS)
+    t = oracle.Table(n_slots, max_probe, oracle.EVICT_NONE, 0, wl.HASH_SEED_BASE)
+    coll = 0
+    step = 1
+    for lo in range(0, N_IDS, batch):
+        coll += t.remap(ids[lo:lo + batch], step).stats["collisions"]
+        step += 1
+    return 100.0 * coll / N_IDS, t
+
+
+def _close(got_pct, want_pct, rel=0.03):
+    """within 3 % relative or four standard deviations of the count at this sample size"""
+    want_cnt = want_pct / 100.0 * N_IDS
+    sigma_pct = 100.0 * math.sqrt(max(want_cnt, 1.0)) / N_IDS
+    return abs(got_pct - want_pct) <= max(rel * want_pct, 4.0 * sigma_pct)
+
+
+@pytest.mark.parametrize("row", [0, 1, 2, 4])
+def test_max_probe_1_is_plain_hashing_and_matches_table1_hash_column(row):
+    """With P = 1 the method is plain hash indexing: the fraction of ids without a slot of
+    their own follows the balls-in-bins closed form 1 - (N/n)(1 - exp(-n/N)), which is also
+    what Table 1's hash-baseline column prints."""
+    size_m, sigrid_pct, _ = _table1()[row]
+    n_slots = size_m * 10_000
+    got, _ = _collision_pct(n_slots, 1)
+    closed = 100.0 * (1.0 - (n_slots / N_IDS) * (1.0 - math.exp(-N_IDS / n_slots)))
+    assert abs(got - closed) < 0.15
+    assert abs(got - sigrid_pct) < 0.15
+
+
+@pytest.mark.parametrize("row,max_probe", [(0, 8), (0, 64), (1, 8), (1, 16), (1, 64), (2, 8), (2, 16), (2, 64),
+                                           (4, 8), (4, 16), (4, 64), (3, 32), (1, 512)])
+def test_table1_mpzch_cells_at_reduced_scale(row, max_probe):
+    size_m, _, cells = _table1()[row]
+    got, t = _collision_pct(size_m * 10_000, max_probe)
+    assert _close(got, cells[max_probe]), (got, cells[max_probe])
+    bad, occ, _ = t.check_state()
+    assert bad == 0
+    assert occ == N_IDS - round(got / 100.0 * N_IDS)         # every non-collided id owns one slot
+
+
+def test_table1_cell_is_insensitive_to_batching():
+    """The kernel sees the ids in batches (Sec. 3.3); as long as a batch is small against the
+    table, batching changes who wins a slot, not how many ids end without one."""
+    size_m, _, cells = _table1()[2]
+    a, _ = _collision_pct(size_m * 10_000, 8, batch=256)
+    b, _ = _collision_pct(size_m * 10_000, 8, batch=16384)
+    assert _close(a, cells[8]) and _close(b, cells[8])
+    assert abs(a - b) < 0.02 * cells[8]
+
+
+def test_zero_collisions_with_enough_capacity_and_probes():
+    """Sec. 3.3 / Sec. 4.1: table twice the cardinality and P = 64 gives zero collisions."""
+    got, _ = _collision_pct(3_000_000, 64)
+    assert got == 0.0
+
+
+# ---------------------------------------------------------------- batch rule: unique stable matching
+def _enumerate_stable(prefs, prio):
+    """prefs[a] = list of slots in probe order (claimable ones only); an agent prefers an
+    earlier list entry and prefers any entry to being unplaced.  A slot prefers the agent
+    with the smaller prio[(a, slot)].  Returns all stable matchings as dicts a -> slot/None."""
+    agents = sorted(prefs)
+    res = []
+    for choice in itertools.product(*[[None] + prefs[a] for a in agents]):
+        taken = [c for c in choice if c is not None]
+        if len(taken) != len(set(taken)):
+            continue
+        match = dict(zip(agents, choice))
+        holder = {s: a for a, s in match.items() if s is not None}
+        stable = True
+        for a in agents:
+            cur = match[a]
+            better = prefs[a] if cur is None else prefs[a][: prefs[a].index(cur)]
+            for s in better:
+                if s not in holder or prio[(a, s)] < prio[(holder[s], s)]:
+                    stable = False
+            if not stable:
+                break
+        if stable:
+            res.append(match)
+    return res
+
+
+@given(st.data())
+@settings(max_examples=120, deadline=None)
+def test_allocation_is_the_unique_stable_matching_under_round_then_position_priority(data):
+    """"For each probe round, the lowest first-occurrence batch index wins a contended
+    slot": equivalently, slots rank claimants by (round, position) and ids rank slots by
+    round.  Enumerate every assignment of the missed ids to claimable slots of their probe
+    windows, keep the stable ones: there must be exactly one, and it is the oracle's."""
+    n_slots = data.draw(st.integers(2, 10))
+    max_probe = data.draw(st.integers(1, 4))
+    ttl = data.draw(st.integers(0, 2))
+    seed = data.draw(st.integers(0, 1 << 16))
+    t = oracle.Table(n_slots, max_probe, oracle.EVICT_TTL, ttl, seed)
+    # build a state through the API: old residents (some will be expired, some refreshed)
+    old = data.draw(st.lists(st.integers(0, 60), max_size=8, unique=True))
+    t.remap(old, 0)
+    keep = data.draw(st.lists(st.sampled_from(old), max_size=4, unique=True)) if old else []
+    step = data.draw(st.integers(1, 4))
+    new = data.draw(st.lists(st.integers(100, 160), min_size=1, max_size=5, unique=True))
+    batch = data.draw(st.permutations(keep + new))
+    batch = list(batch) + data.draw(st.lists(st.sampled_from(batch), max_size=3))  # duplicates
+    I0 = t.identities.copy()
+    M0 = t.metadata.copy()
+    r = t.remap(batch, step)
+
+    P = min(max_probe, n_slots)
+    resident = set(I0[I0 >= 0].tolist())
+    first_pos = {}
+    for j, x in enumerate(batch):
+        first_pos.setdefault(x, j)
+    # hits refresh first (Sec. 3.2: existing entries are always prioritised)
+    M1 = M0.copy()
+    for x in first_pos:
+        if x in resident:
+            s = int(np.nonzero(I0 == x)[0][0])
+            M1[s] = step
+    claimable = [I0[s] == -1 or (I0[s] >= 0 and step - M1[s] > ttl) for s in range(n_slots)]
+    prefs, prio = {}, {}
+    for x, j in first_pos.items():
+        if x in resident:
+            continue
+        h = py_home(x, seed, n_slots)
+        prefs[x] = []
+        for rr in range(P):
+            s = (h + rr) % n_slots
+            if claimable[s]:
+                prefs[x].append(s)
+                prio[(x, s)] = (rr, j)
+    stable = _enumerate_stable(prefs, prio)
+    assert len(stable) == 1
+    want = stable[0]
+    for j, x in enumerate(batch):
+        if x in resident:
+            assert r.slots[j] == int(np.nonzero(I0 == x)[0][0])
+        elif want[x] is None:
+            assert r.slots[j] == py_home(x, seed, n_slots)
+        else:
+            assert r.slots[j] == want[x]
+    placed = {s: x for x, s in want.items() if s is not None}
+    for s in range(n_slots):
+        assert t.identities[s] == (placed[s] if s in placed else I0[s])
+    assert sorted(r.evicted.tolist()) == sorted(s for s in placed if I0[s] != -1)
+
+
+def test_round_major_worked_example():
+    """N = 8, P = 3, slot 4 freshly occupied.  b (position 0, home 4) and a (position 1,
+    home 5) miss.  Round 0: b finds 4 taken, a takes 5.  Round 1: b finds 5 taken.  Round 2:
+    b takes 6.  (Processing positions one after the other would give b = 5, a = 6.)"""
+    seed, n = 11, 8
+    occ = ids_with_home(4, seed, n, 1)[0]
+    b = ids_with_home(4, seed, n, 1, avoid={occ}, start=occ + 1)[0]
+    a = ids_with_home(5, seed, n, 1)[0]
+    t = oracle.Table(n, 3, oracle.EVICT_TTL, 5, seed)
+    assert t.remap([occ], 1).slots[0] == 4
+    r = t.remap([b, a], 2)
+    assert r.slots.tolist() == [6, 5]
+    assert t.identities[4] == occ and t.identities[5] == a and t.identities[6] == b
+    assert len(r.evicted) == 0
+
+
+# ---------------------------------------------------------------- TTL scenarios (Sec. 3.4)
+def test_ttl_lazy_eviction_by_hand():
+    seed, n = 3, 16
+    x, y, z = ids_with_home(7, seed, n, 3)
+    t = oracle.Table(n, 2, oracle.EVICT_TTL, 3, seed)
+    assert t.remap([x], 5).slots[0] == 7                       # x seen at step 5
+    w = ids_with_home(8, seed, n, 1)[0]
+    assert t.remap([w], 5).slots[0] == 8                       # window of home 7 (slots 7, 8) is full
+    # steps 6, 7, 8: x unseen for <= 3 steps -> not evictable; y collides and falls back to home
+    r = t.remap([y], 8)
+    assert r.slots[0] == 7 and len(r.evicted) == 0 and r.stats["collisions"] == 1
+    assert t.identities[7] == x
+    assert t.metadata[7] == 8                                   # Case 3 refreshes the home slot's metadata
+    # that refresh keeps x alive until step 12; w (last seen 5) expires at step 9
+    r = t.remap([y], 9)
+    assert r.slots[0] == 8 and r.evicted.tolist() == [8] and r.stats["evictions"] == 1
+    assert t.identities[8] == y and t.metadata[8] == 9
+    # step 12: x (last refreshed 8) is expired (12 - 8 > 3); lazy: nothing happens until someone needs a slot
+    assert t.lookup([x])[1][0] == 1
+    # x and z in one batch at step 12: x is a resident -> refreshed first, never evicted in that batch;
+    # y (last seen 9) is not expired (12 - 9 = 3); z finds no slot -> fallback
+    r = t.remap([z, x], 12)
+    assert r.slots.tolist() == [7, 7] and len(r.evicted) == 0
+    assert t.identities[7] == x and t.metadata[7] == 12
+    # step 13: y expired (13 - 9 > 3), x fresh -> z evicts y at slot 8
+    r = t.remap([z], 13)
+    assert r.slots[0] == 8 and r.evicted.tolist() == [8]
+
+
+def test_two_pass_prevents_duplicate_storage():
+    """Sec. 3.2: an id stored further down its range must be found (Pass 1) even though an
+    earlier slot of the range has expired meanwhile; it must not be inserted a second time."""
+    seed, n = 5, 16
+    a, b = ids_with_home(3, seed, n, 2)
+    t = oracle.Table(n, 4, oracle.EVICT_TTL, 2, seed)
+    t.remap([a], 1)                      # a -> 3
+    t.remap([b], 2)                      # b -> 4 (a still fresh)
+    assert t.identities[3] == a and t.identities[4] == b
+    r = t.remap([b], 10)                 # a expired long ago; b must stay at 4
+    assert r.slots[0] == 4 and len(r.evicted) == 0
+    assert t.identities[3] == a and t.identities[4] == b
+    assert t.metadata[4] == 10
+    assert (t.identities == b).sum() == 1
+
+
+def test_eviction_disabled_never_evicts():
+    seed, n = 9, 8
+    ids = ids_with_home(2, seed, n, 4)
+    t = oracle.Table(n, 2, oracle.EVICT_NONE, 0, seed)
+    t.remap(ids[:2], 0)
+    r = t.remap(ids[2:], 1000)
+    assert len(r.evicted) == 0 and r.stats["collisions"] == 2 and r.slots.tolist() == [2, 2]
+
+
+# ---------------------------------------------------------------- de-duplication, invalid ids, lookup, reset
+@given(st.data())
+@settings(max_examples=100, deadline=None)
+def test_duplicates_share_the_slot_of_their_first_occurrence(data):
+    n_slots = data.draw(st.integers(1, 32))
+    max_probe = data.draw(st.integers(1, 8))
+    seed = data.draw(st.integers(0, 99))
+    steps = data.draw(st.lists(st.lists(st.integers(-3, 30), max_size=40), min_size=1, max_size=6))
+    ta = oracle.Table(n_slots, max_probe, oracle.EVICT_TTL, 1, seed)
+    tb = oracle.Table(n_slots, max_probe, oracle.EVICT_TTL, 1, seed)
+    for step, batch in enumerate(steps):
+        ra = ta.remap(batch, step)
+        uniq = list(dict.fromkeys(batch))              # first occurrences, in order
+        rb = tb.remap(uniq, step)
+        lut = dict(zip(uniq, rb.slots.tolist()))
+        assert ra.slots.tolist() == [lut[x] for x in batch]
+        assert sorted(ra.evicted.tolist()) == sorted(rb.evicted.tolist())
+        assert np.array_equal(ta.identities, tb.identities) and np.array_equal(ta.metadata, tb.metadata)
+        st_ = ra.stats
+        assert st_["hit_pos"] + st_["miss_pos"] + st_["invalid_pos"] == len(batch)
+        assert st_["inserts"] + st_["evictions"] + st_["collisions"] == st_["distinct_miss"]
+        # negative ids never enter the table and map to the home of their bit pattern
+        assert (ta.identities >= -1).all()
+        for x, s in zip(batch, ra.slots.tolist()):
+            if x < 0:
+                assert s == py_home(x, seed, n_slots)
+        assert ta.check_state()[0] == 0
+
+
+@given(st.data())
+@settings(max_examples=60, deadline=None)
+def test_lookup_is_read_only_and_finds_exactly_the_residents(data):
+    n_slots = data.draw(st.integers(1, 32))
+    max_probe = data.draw(st.integers(1, 8))
+    seed = data.draw(st.integers(0, 99))
+    t = oracle.Table(n_slots, max_probe, oracle.EVICT_TTL, 1, seed)
+    for step in range(4):
+        t.remap(data.draw(st.lists(st.integers(0, 50), max_size=20)), step)
+    I0, M0 = t.identities.copy(), t.metadata.copy()
+    q = data.draw(st.lists(st.integers(-2, 60), max_size=30))
+    slots, found = t.lookup(q)
+    assert np.array_equal(t.identities, I0) and np.array_equal(t.metadata, M0)
+    for x, s, f in zip(q, slots.tolist(), found.tolist()):
+        where = np.nonzero(I0 == x)[0] if x >= 0 else []
+        if len(where):
+            assert f == 1 and s == where[0] and len(where) == 1
+        else:
+            assert f == 0 and s == py_home(x, seed, n_slots)
+
+
+def test_reset_rows_zeroes_exactly_the_named_rows():
+    rows = wl.embedding_pattern(10, 4)
+    want = rows.copy()
+    oracle.reset_rows([3, 13, 7], rows)                 # row = slot mod num_rows
+    want[[3, 7]] = 0
+    assert np.array_equal(rows, want)
+    init = np.arange(4, dtype=np.float32) + 0.5
+    oracle.reset_rows([9], rows, init)
+    want[9] = init
+    assert np.array_equal(rows, want)
+
+
+# ---------------------------------------------------------------- invariants on a churning stream
+def test_invariants_hold_on_a_churning_stream():
+    spec = wl.c1_spec()
+    t = oracle.Table(spec.num_slots, spec.max_probe, oracle.EVICT_TTL, spec.ttl, spec.hash_seed)
+    ever_occupied = np.zeros(spec.num_slots, dtype=bool)
+    total_evicted = 0
+    for step in range(1, 40):
+        ids = wl.zipf_ids(wl.rng_for(1, step), 1024, 1.1, 16384)
+        I0 = t.identities.copy()
+        r = t.remap(ids, step)
+        bad, occ, _ = t.check_state()
+        assert bad == 0
+        # a slot never becomes empty again; evicted slots were occupied and changed owner
+        assert not (ever_occupied & (t.identities == -1)).any()
+        ever_occupied |= t.identities >= 0
+        for s in r.evicted.tolist():
+            assert I0[s] >= 0 and t.identities[s] != I0[s]
+        # every slot touched this step carries the step; every returned slot is within range
+        assert (t.metadata[r.slots] == step).all()
+        # resident ids map back to their own slot
+        res = t.identities[t.identities >= 0]
+        ls, lf = t.lookup(res)
+        assert lf.all() and np.array_equal(ls, np.nonzero(t.identities >= 0)[0])
+        total_evicted += len(r.evicted)
+    assert total_evicted > 0                            # the stream really exercises eviction
