@@ -1,0 +1,229 @@
+/*
+ * mpzch.h -- C ABI of the MI355X (gfx950) batched MPZCH remap library.
+ *
+ * MPZCH ("Multi-Probe Zero Collision Hash") maps raw int64 feature ids to
+ * embedding-table slots: hash to a home slot, probe at most max_probe
+ * consecutive slots of an `identities` tensor, then hit / insert into an empty
+ * slot / evict an expired id / fall back to the home slot (paper Sec. 3.2 and
+ * Algorithm 1), with TTL eviction guided by a `metadata` tensor (Sec. 3.4) and
+ * reset of the embedding rows of reassigned slots (Sec. 3.4, last paragraph).
+ *
+ * Conventions that hold for every call
+ *   - DEVICE pointers are marked [dev], HOST pointers [host].  The caller owns
+ *     every tensor (identities, metadata, ids, outputs, embedding rows); a handle
+ *     owns only its configuration and a scratch area in device memory.
+ *   - Calls are asynchronous on `stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream).  No call synchronises with the host unless stated.
+ *   - One call per handle may be in flight at a time; calls issued on one stream
+ *     are ordered.  Two calls that touch the same identities tensor must not
+ *     overlap.
+ *   - Errors come back as status codes; nothing aborts or throws.  Argument
+ *     errors are found before anything is launched.  Data-dependent conditions
+ *     (negative ids, a truncated evicted list) are reported through device-side
+ *     counters, never through a host synchronisation.
+ *
+ * Definitions shared by all entry points (the paper leaves them open)
+ *   hash(id)   = SplitMix64 finaliser of ((uint64)id XOR hash_seed)
+ *   home(id)   = floor(hash(id) * num_slots / 2^64)
+ *   slot(id,r) = (home(id) + r) mod num_slots,  0 <= r < min(max_probe, num_slots)
+ *   empty slot : identities == -1            (Sec. 3.1)
+ *   metadata   : step at which the slot's id was last seen (int32)
+ *   expired    : policy TTL and  step - metadata > ttl     (Sec. 3.4)
+ *   valid ids  : 0 <= id <= 2^63 - 1.  Negative ids are never stored and never
+ *                match; their output is home(id) of their bit pattern.
+ * While mpzch_remap / mpzch_remap_jagged run, identities may transiently hold
+ * values <= -2; they are gone when the call's work on the stream has finished.
+ */
+#ifndef MPZCH_H
+#define MPZCH_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct mpzch_table mpzch_table_t; /* opaque: configuration + device scratch   */
+typedef struct mpzch_group mpzch_group_t; /* opaque: several tables remapped together */
+
+typedef enum {
+    MPZCH_OK = 0,
+    MPZCH_ERR_INVALID_ARG = 1,
+    MPZCH_ERR_ALLOC = 2,       /* device or host allocation failed */
+    MPZCH_ERR_HIP = 3,         /* a HIP runtime call failed        */
+    MPZCH_ERR_UNSUPPORTED = 4  /* e.g. MPZCH_EVICT_LRU             */
+} mpzch_status_t;
+
+typedef enum {
+    MPZCH_EVICT_NONE = 0, /* lookup + insert only (Sec. 3.3, eviction disabled)           */
+    MPZCH_EVICT_TTL = 1,  /* lazy TTL eviction (Sec. 3.4)                                 */
+    MPZCH_EVICT_LRU = 2   /* Sec. 3.4 last paragraph; not implemented: MPZCH_ERR_UNSUPPORTED */
+} mpzch_evict_kind_t;
+
+typedef struct {
+    int32_t kind; /* mpzch_evict_kind_t         */
+    int32_t ttl;  /* steps, >= 0; used with TTL */
+} mpzch_eviction_policy_t;
+
+/* Index of each counter in the int64 stats array written by the remap calls. */
+enum {
+    MPZCH_STAT_HIT_POS = 0,       /* positions whose id was resident at batch start        */
+    MPZCH_STAT_MISS_POS = 1,      /* valid positions whose id was not resident             */
+    MPZCH_STAT_DISTINCT_MISS = 2, /* distinct ids among the miss positions                 */
+    MPZCH_STAT_INSERTS = 3,       /* distinct missed ids placed in an empty slot           */
+    MPZCH_STAT_EVICTIONS = 4,     /* distinct missed ids placed by evicting an expired id  */
+    MPZCH_STAT_COLLISIONS = 5,    /* distinct missed ids left without a slot (Table 1)     */
+    MPZCH_STAT_INVALID_POS = 6,   /* positions holding a negative id                       */
+    MPZCH_STAT_HIT_PROBE_SUM = 7, /* sum over hit positions of (probe distance + 1)        */
+    MPZCH_STAT_COUNT = 8
+};
+
+#define MPZCH_MAX_BATCH ((int64_t)1 << 30) /* positions per remap / lookup call          */
+#define MPZCH_MAX_PROBE (1 << 20)          /* upper bound accepted for max_probe          */
+#define MPZCH_MAX_GROUP_TABLES 64          /* tables per mpzch_group_t                    */
+
+/*
+ * Creates a table handle (Algorithm 1's globals: P = max_probe; Sec. 3.4: policy).
+ * Allocates no tensor and touches no GPU: scratch is allocated by the first remap
+ * (or by mpzch_reserve) on the device that is current then.
+ * Errors: INVALID_ARG for num_slots < 1, max_probe < 1 or > MPZCH_MAX_PROBE, ttl < 0,
+ * unknown policy kind, out == NULL; UNSUPPORTED for MPZCH_EVICT_LRU.
+ * max_probe > num_slots is accepted and behaves as max_probe == num_slots.
+ */
+mpzch_status_t mpzch_create(int64_t num_slots, int32_t max_probe, mpzch_eviction_policy_t policy,
+                            uint64_t hash_seed, mpzch_table_t **out /* [host] */);
+
+/* Frees the handle and its scratch.  Synchronises the device first.  NULL is accepted. */
+mpzch_status_t mpzch_destroy(mpzch_table_t *t);
+
+/*
+ * Optional: allocate scratch for batches of up to max_n positions now (32 bytes per
+ * position) so that later remap calls allocate nothing.  Synchronises the device when it
+ * has to grow the scratch.  Errors: INVALID_ARG (max_n < 0 or > MPZCH_MAX_BATCH), ALLOC.
+ */
+mpzch_status_t mpzch_reserve(mpzch_table_t *t, int64_t max_n);
+
+/*
+ * Sec. 3.1 initial state: identities[0..num_slots) = -1, metadata[0..num_slots) = -1.
+ * metadata may be NULL.  identities [dev] int64[num_slots], metadata [dev] int32[num_slots].
+ */
+mpzch_status_t mpzch_init_tensors(const mpzch_table_t *t, int64_t *identities, int32_t *metadata,
+                                  void *stream);
+
+/*
+ * Training remap of one batch: lookup, insert and evict (Sec. 3.2, Algorithm 1; Sec. 3.3
+ * "Kernel Execution"; Sec. 3.4; Sec. 3.6 input de-duplication).  The batch is processed as
+ *   1. every id resident at the start of the call is found (Pass 1) and its metadata set
+ *      to `step` ("Update"), before anything is allocated;
+ *   2. the remaining distinct ids allocate: each takes the first slot of its probe range
+ *      that is empty or expired; where several ids want one slot the one that reaches it
+ *      in the earlier probe round wins, and within a round the id whose first occurrence
+ *      in the batch comes first; a claimed slot gets identities = id, metadata = step;
+ *   3. ids left without a slot fall back to their home slot, whose metadata is set to
+ *      `step` (Case 3);
+ *   4. every position receives the slot of its id (all copies of an id share one slot).
+ *
+ * identities [dev] int64[num_slots]  in/out
+ * metadata   [dev] int32[num_slots]  in/out
+ * ids        [dev] int64[n]          raw ids, 0 <= n <= MPZCH_MAX_BATCH
+ * step                               current time stamp, >= 0, non-decreasing over calls
+ * out_slots  [dev] int64[n]          remapped index of every position
+ * out_evicted_slots [dev] int64[evicted_cap]  slots that changed owner (Sec. 3.4: the rows
+ *                                    to reset), each once, order unspecified; may be NULL
+ *                                    when evicted_cap == 0
+ * out_num_evicted   [dev] int64[1]   number of such slots; when it exceeds evicted_cap
+ *                                    the list holds the first evicted_cap that were written
+ * out_stats  [dev] int64[MPZCH_STAT_COUNT] or NULL
+ * n == 0 is valid: outputs counts are written as zero, state is untouched.
+ * Errors: INVALID_ARG (NULL handle / required pointer, n out of range, step < 0,
+ * evicted_cap < 0), ALLOC (scratch), HIP.
+ */
+mpzch_status_t mpzch_remap(mpzch_table_t *t, int64_t *identities, int32_t *metadata,
+                           const int64_t *ids, int64_t n, int32_t step,
+                           int64_t *out_slots,
+                           int64_t *out_evicted_slots, int64_t evicted_cap, int64_t *out_num_evicted,
+                           int64_t *out_stats, void *stream);
+
+/*
+ * Inference lookup (Sec. 3.7): read-only, Pass 1 of Algorithm 1 for every position
+ * independently; needs no metadata and no scratch.
+ * out_slots [dev] int64[n]: the slot holding the id, or home(id) when it is not resident.
+ * out_found [dev] uint8[n] or NULL: 1 when resident.
+ */
+mpzch_status_t mpzch_lookup(const mpzch_table_t *t, const int64_t *identities,
+                            const int64_t *ids, int64_t n,
+                            int64_t *out_slots, uint8_t *out_found, void *stream);
+
+/*
+ * Reset of reassigned rows (Sec. 3.4: "upon eviction, both the embedding weights and the
+ * optimizer state are reset"): for k < min(*num_slots_dev, slots_cap):
+ *     rows[(slots[k] mod num_rows) * row_stride_bytes .. + row_bytes) <- init_row
+ * slots         [dev] int64[slots_cap]   e.g. out_evicted_slots of mpzch_remap
+ * num_slots_dev [dev] int64[1]           e.g. out_num_evicted; read on the device, so no
+ *                                        host synchronisation sits between remap and reset
+ * rows          [dev] any dtype; row_bytes > 0 and row_stride_bytes >= row_bytes, both
+ *               multiples of 4; rows 4-byte aligned (16-byte alignment of rows, stride and
+ *               row_bytes enables 128-bit stores)
+ * init_row      [dev] row_bytes bytes, or NULL for all-zero bits
+ * Call it once per tensor that has to be reset (weights, optimizer state).
+ */
+mpzch_status_t mpzch_reset_rows(const int64_t *slots, const int64_t *num_slots_dev, int64_t slots_cap,
+                                void *rows, int64_t num_rows, int64_t row_bytes, int64_t row_stride_bytes,
+                                const void *init_row, void *stream);
+
+/*
+ * Several tables remapped by one launch sequence (Sec. 3.4: one kernel serving tables of
+ * several features; Sec. 3.6: a keyed jagged batch of an embedding collection).
+ * tables [host] array of num_tables handles (1..MPZCH_MAX_GROUP_TABLES); the group keeps
+ * copies of their configuration, the handles may be destroyed afterwards.
+ */
+mpzch_status_t mpzch_group_create(mpzch_table_t *const *tables, int32_t num_tables,
+                                  mpzch_group_t **out /* [host] */);
+mpzch_status_t mpzch_group_destroy(mpzch_group_t *g);
+mpzch_status_t mpzch_group_reserve(mpzch_group_t *g, int64_t max_total_values);
+
+/*
+ * Feature-major keyed jagged batch: feature f owns values[feature_offsets[f] ..
+ * feature_offsets[f+1]) and is remapped into table f exactly as mpzch_remap would remap
+ * that slice on its own (positions compare by their order inside the slice).
+ *
+ * identities [host] array of num_tables [dev] int64 pointers (table f: num_slots_f entries)
+ * metadata   [host] array of num_tables [dev] int32 pointers
+ *            (the first call, and any call whose pointers differ from the previous one,
+ *            synchronises `stream` once to upload them)
+ * values     [dev] int64[total_values]
+ * feature_offsets [dev] int64[num_tables + 1], non-decreasing, [0] == 0, [num_tables] == total_values
+ * out_slots  [dev] int64[total_values]   slot inside the table of the value's feature
+ * out_evicted_slots [dev] int64, table f's list starts at evicted_offsets[f] and has room for
+ *            evicted_offsets[f+1] - evicted_offsets[f] entries
+ * evicted_offsets   [host] int64[num_tables + 1], non-decreasing
+ * out_num_evicted   [dev] int64[num_tables]
+ * out_stats  [dev] int64[num_tables * MPZCH_STAT_COUNT] or NULL
+ */
+mpzch_status_t mpzch_remap_jagged(mpzch_group_t *g, int64_t *const *identities, int32_t *const *metadata,
+                                  const int64_t *values, const int64_t *feature_offsets,
+                                  int64_t total_values, int32_t step,
+                                  int64_t *out_slots,
+                                  int64_t *out_evicted_slots, const int64_t *evicted_offsets,
+                                  int64_t *out_num_evicted, int64_t *out_stats, void *stream);
+
+/*
+ * Per-kernel timing for benchmarks.  While enabled, every kernel launched through the
+ * handle is bracketed by HIP events on the call's stream.  mpzch_kernel_times
+ * synchronises those events, adds up the durations per kernel and clears the record.
+ * names [host] receives up to cap pointers to static strings, ms [host] the summed
+ * milliseconds, launches [host] the number of launches; *count the number of kernels.
+ */
+mpzch_status_t mpzch_set_kernel_timing(mpzch_table_t *t, int32_t enable);
+mpzch_status_t mpzch_kernel_times(mpzch_table_t *t, const char **names, double *ms, int64_t *launches,
+                                  int32_t cap, int32_t *count);
+mpzch_status_t mpzch_group_set_kernel_timing(mpzch_group_t *g, int32_t enable);
+mpzch_status_t mpzch_group_kernel_times(mpzch_group_t *g, const char **names, double *ms, int64_t *launches,
+                                        int32_t cap, int32_t *count);
+
+const char *mpzch_status_string(int32_t status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MPZCH_H */

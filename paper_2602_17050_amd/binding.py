@@ -1,0 +1,266 @@
+"""Thin ctypes binding over libmpzch.so (the C ABI of include/mpzch.h).
+
+Argument marshalling only: torch tensors supply device memory and the current
+stream; every step of the path runs in the library's HIP kernels.  There is no
+fallback: if the library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libmpzch.so")
+
+EVICT_NONE, EVICT_TTL, EVICT_LRU = 0, 1, 2
+STAT_NAMES = ("hit_pos", "miss_pos", "distinct_miss", "inserts",
+              "evictions", "collisions", "invalid_pos", "hit_probe_sum")
+STAT_COUNT = len(STAT_NAMES)
+
+EXPORTED = (
+    "mpzch_create", "mpzch_destroy", "mpzch_reserve", "mpzch_init_tensors", "mpzch_remap",
+    "mpzch_lookup", "mpzch_reset_rows", "mpzch_group_create", "mpzch_group_destroy",
+    "mpzch_group_reserve", "mpzch_remap_jagged", "mpzch_set_kernel_timing", "mpzch_kernel_times",
+    "mpzch_group_set_kernel_timing", "mpzch_group_kernel_times", "mpzch_status_string",
+)
+
+
+class MpzchError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: {mpzch_status_string(status)} ({status})")
+
+
+class _Policy(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int32), ("ttl", ctypes.c_int32)]
+
+
+_lib = None
+
+
+def load_library(path: str | None = None):
+    """Loads the in-tree HIP library; fails loudly when it has not been built."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    path = path or _LIB_PATH
+    if not os.path.exists(path):
+        raise FileNotFoundError(
+            f"{path} is missing: build it with `python -m paper_2602_17050_amd.build` "
+            "(there is no CPU fallback)")
+    lib = ctypes.CDLL(path)
+    vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
+    lib.mpzch_create.argtypes = [i64, i32, _Policy, ctypes.c_uint64, ctypes.POINTER(vp)]
+    lib.mpzch_destroy.argtypes = [vp]
+    lib.mpzch_reserve.argtypes = [vp, i64]
+    lib.mpzch_init_tensors.argtypes = [vp, vp, vp, vp]
+    lib.mpzch_remap.argtypes = [vp, vp, vp, vp, i64, i32, vp, vp, i64, vp, vp, vp]
+    lib.mpzch_lookup.argtypes = [vp, vp, vp, i64, vp, vp, vp]
+    lib.mpzch_reset_rows.argtypes = [vp, vp, i64, vp, i64, i64, i64, vp, vp]
+    lib.mpzch_group_create.argtypes = [ctypes.POINTER(vp), i32, ctypes.POINTER(vp)]
+    lib.mpzch_group_destroy.argtypes = [vp]
+    lib.mpzch_group_reserve.argtypes = [vp, i64]
+    lib.mpzch_remap_jagged.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), vp, vp, i64, i32, vp, vp,
+                                       ctypes.POINTER(i64), vp, vp, vp]
+    for name in ("mpzch_kernel_times", "mpzch_group_kernel_times"):
+        getattr(lib, name).argtypes = [vp, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_double),
+                                       ctypes.POINTER(i64), i32, ctypes.POINTER(i32)]
+    lib.mpzch_set_kernel_timing.argtypes = [vp, i32]
+    lib.mpzch_group_set_kernel_timing.argtypes = [vp, i32]
+    lib.mpzch_status_string.argtypes = [i32]
+    lib.mpzch_status_string.restype = ctypes.c_char_p
+    for name in EXPORTED:
+        if name != "mpzch_status_string":
+            getattr(lib, name).restype = ctypes.c_int32
+    if path == _LIB_PATH:
+        _lib = lib
+    return lib
+
+
+def mpzch_status_string(status: int) -> str:
+    return load_library().mpzch_status_string(int(status)).decode()
+
+
+def _check(status: int, what: str):
+    if status != 0:
+        raise MpzchError(status, what)
+
+
+def _ptr(t, dtype=None):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device, contiguous tensors only"
+    if dtype is not None:
+        assert t.dtype == dtype, (t.dtype, dtype)
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+# ----------------------------------------------------------------------------- C-ABI names
+def mpzch_create(num_slots: int, max_probe: int, eviction_policy=(EVICT_TTL, 0), hash_seed: int = 0):
+    """Returns an opaque handle (ctypes.c_void_p).  eviction_policy = (kind, ttl)."""
+    h = ctypes.c_void_p()
+    pol = _Policy(int(eviction_policy[0]), int(eviction_policy[1]))
+    _check(load_library().mpzch_create(num_slots, max_probe, pol, ctypes.c_uint64(hash_seed & (2 ** 64 - 1)),
+                                       ctypes.byref(h)), "mpzch_create")
+    return h
+
+
+def mpzch_destroy(handle):
+    _check(load_library().mpzch_destroy(handle), "mpzch_destroy")
+
+
+def mpzch_reserve(handle, max_n: int):
+    _check(load_library().mpzch_reserve(handle, max_n), "mpzch_reserve")
+
+
+def mpzch_init_tensors(handle, identities, metadata=None):
+    _check(load_library().mpzch_init_tensors(handle, _ptr(identities, torch.int64), _ptr(metadata, torch.int32),
+                                             _stream()), "mpzch_init_tensors")
+
+
+def mpzch_remap(handle, identities, metadata, ids, step: int, out_slots, out_evicted_slots, out_num_evicted,
+                out_stats=None):
+    n = ids.numel()
+    cap = 0 if out_evicted_slots is None else out_evicted_slots.numel()
+    _check(load_library().mpzch_remap(handle, _ptr(identities, torch.int64), _ptr(metadata, torch.int32),
+                                      _ptr(ids, torch.int64), n, step, _ptr(out_slots, torch.int64),
+                                      _ptr(out_evicted_slots, torch.int64), cap, _ptr(out_num_evicted, torch.int64),
+                                      _ptr(out_stats, torch.int64), _stream()), "mpzch_remap")
+
+
+def mpzch_lookup(handle, identities, ids, out_slots, out_found=None):
+    _check(load_library().mpzch_lookup(handle, _ptr(identities, torch.int64), _ptr(ids, torch.int64), ids.numel(),
+                                       _ptr(out_slots, torch.int64), _ptr(out_found, torch.uint8), _stream()),
+           "mpzch_lookup")
+
+
+def mpzch_reset_rows(slots, num_slots_dev, rows, init_row=None, num_rows: int | None = None):
+    """rows: 2-D tensor (num_rows, dim); row = slot mod num_rows."""
+    assert rows.dim() == 2 and rows.stride(1) == 1
+    nrows = rows.shape[0] if num_rows is None else num_rows
+    row_bytes = rows.shape[1] * rows.element_size()
+    stride = rows.stride(0) * rows.element_size()
+    if init_row is not None:
+        assert init_row.is_cuda and init_row.is_contiguous() and init_row.numel() * init_row.element_size() == row_bytes
+    _check(load_library().mpzch_reset_rows(_ptr(slots, torch.int64), _ptr(num_slots_dev, torch.int64), slots.numel(),
+                                           ctypes.c_void_p(rows.data_ptr()), nrows, row_bytes, stride,
+                                           None if init_row is None else ctypes.c_void_p(init_row.data_ptr()),
+                                           _stream()), "mpzch_reset_rows")
+
+
+def mpzch_group_create(handles):
+    arr = (ctypes.c_void_p * len(handles))(*[h.value for h in handles])
+    g = ctypes.c_void_p()
+    _check(load_library().mpzch_group_create(arr, len(handles), ctypes.byref(g)), "mpzch_group_create")
+    return g
+
+
+def mpzch_group_destroy(group):
+    _check(load_library().mpzch_group_destroy(group), "mpzch_group_destroy")
+
+
+def mpzch_group_reserve(group, max_total_values: int):
+    _check(load_library().mpzch_group_reserve(group, max_total_values), "mpzch_group_reserve")
+
+
+def mpzch_remap_jagged(group, identities, metadata, values, feature_offsets, step: int, out_slots,
+                       out_evicted_slots, evicted_offsets, out_num_evicted, out_stats=None):
+    """identities / metadata: lists of device tensors; evicted_offsets: host list of ints."""
+    T = len(identities)
+    ip = (ctypes.c_void_p * T)(*[t.data_ptr() for t in identities])
+    mp = (ctypes.c_void_p * T)(*[t.data_ptr() for t in metadata])
+    eo = (ctypes.c_int64 * (T + 1))(*[int(x) for x in evicted_offsets])
+    _check(load_library().mpzch_remap_jagged(group, ip, mp, _ptr(values, torch.int64),
+                                             _ptr(feature_offsets, torch.int64), values.numel(), step,
+                                             _ptr(out_slots, torch.int64), _ptr(out_evicted_slots, torch.int64), eo,
+                                             _ptr(out_num_evicted, torch.int64), _ptr(out_stats, torch.int64),
+                                             _stream()), "mpzch_remap_jagged")
+
+
+def _times(fn, handle):
+    cap = 16
+    names = (ctypes.c_char_p * cap)()
+    ms = (ctypes.c_double * cap)()
+    cnt = (ctypes.c_int64 * cap)()
+    k = ctypes.c_int32()
+    _check(fn(handle, names, ms, cnt, cap, ctypes.byref(k)), "kernel_times")
+    return {names[i].decode(): (ms[i], cnt[i]) for i in range(k.value)}
+
+
+def mpzch_set_kernel_timing(handle, enable: bool):
+    _check(load_library().mpzch_set_kernel_timing(handle, int(enable)), "mpzch_set_kernel_timing")
+
+
+def mpzch_kernel_times(handle):
+    """{kernel name: (total ms, launches)} since the last read-out; synchronises."""
+    return _times(load_library().mpzch_kernel_times, handle)
+
+
+def mpzch_group_set_kernel_timing(group, enable: bool):
+    _check(load_library().mpzch_group_set_kernel_timing(group, int(enable)), "mpzch_group_set_kernel_timing")
+
+
+def mpzch_group_kernel_times(group):
+    return _times(load_library().mpzch_group_kernel_times, group)
+
+
+# ----------------------------------------------------------------------------- convenience
+class MpzchTable:
+    """Owns the tensors of one table (torch device memory) and its handle."""
+
+    def __init__(self, num_slots, max_probe, kind=EVICT_TTL, ttl=0, hash_seed=0, device="cuda", max_batch=0):
+        self.num_slots, self.max_probe, self.kind, self.ttl, self.hash_seed = num_slots, max_probe, kind, ttl, hash_seed
+        self.handle = mpzch_create(num_slots, max_probe, (kind, ttl), hash_seed)
+        self.identities = torch.empty(num_slots, dtype=torch.int64, device=device)
+        self.metadata = torch.empty(num_slots, dtype=torch.int32, device=device)
+        mpzch_init_tensors(self.handle, self.identities, self.metadata)
+        self.num_evicted = torch.zeros(1, dtype=torch.int64, device=device)
+        self.stats = torch.zeros(STAT_COUNT, dtype=torch.int64, device=device)
+        self._evicted = None
+        if max_batch:
+            mpzch_reserve(self.handle, max_batch)
+            self._evicted = torch.empty(max_batch, dtype=torch.int64, device=device)
+
+    def remap(self, ids, step, out_slots=None):
+        n = ids.numel()
+        if out_slots is None:
+            out_slots = torch.empty(n, dtype=torch.int64, device=ids.device)
+        if self._evicted is None or self._evicted.numel() < n:
+            self._evicted = torch.empty(max(n, 1), dtype=torch.int64, device=ids.device)
+        mpzch_remap(self.handle, self.identities, self.metadata, ids, step, out_slots, self._evicted,
+                    self.num_evicted, self.stats)
+        return out_slots
+
+    @property
+    def evicted(self):
+        """Evicted slots of the last remap (synchronises to read the count)."""
+        return self._evicted[: int(self.num_evicted.item())]
+
+    def reset_rows(self, rows, init_row=None):
+        mpzch_reset_rows(self._evicted, self.num_evicted, rows, init_row)
+
+    def lookup(self, ids, want_found=True):
+        out = torch.empty(ids.numel(), dtype=torch.int64, device=ids.device)
+        found = torch.empty(ids.numel(), dtype=torch.uint8, device=ids.device) if want_found else None
+        mpzch_lookup(self.handle, self.identities, ids, out, found)
+        return out, found
+
+    def stats_dict(self):
+        return dict(zip(STAT_NAMES, self.stats.tolist()))
+
+    def close(self):
+        if self.handle is not None:
+            mpzch_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

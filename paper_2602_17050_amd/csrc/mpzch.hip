@@ -1,0 +1,569 @@
+// Host side of the C ABI declared in include/mpzch.h: argument checks, scratch management and
+// kernel launches on the caller's stream.  No call here synchronises with the host except
+// where the header says so (scratch growth, descriptor upload, timing read-out, destroy).
+#include "../../include/mpzch.h"
+#include "mpzch_kernels.hpp"
+
+#include <cstring>
+#include <new>
+#include <vector>
+
+using namespace mpzch;
+
+namespace {
+
+struct TableCfg {
+    int64_t num_slots;
+    int32_t max_probe;
+    int32_t kind;
+    int32_t ttl;
+    uint64_t seed;
+};
+
+// ---- per-kernel timing --------------------------------------------------------------------
+enum KernelId { KDiscover = 0, KAllocate, KFinalize, KEmitDups, KCleanup, KLookup, KernelCount };
+const char *const kKernelNames[KernelCount] = {"k_discover", "k_allocate", "k_finalize",
+                                               "k_emit_dups", "k_cleanup", "k_lookup"};
+
+struct Timing {
+    bool enabled = false;
+    struct Rec { int kernel; hipEvent_t a, b; };
+    std::vector<Rec> used;
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> pool;
+
+    bool begin(int kernel, hipStream_t s)
+    {
+        if (!enabled) return true;
+        std::pair<hipEvent_t, hipEvent_t> ev;
+        if (!pool.empty()) {
+            ev = pool.back();
+            pool.pop_back();
+        } else {
+            if (hipEventCreate(&ev.first) != hipSuccess) return false;
+            if (hipEventCreate(&ev.second) != hipSuccess) { (void)hipEventDestroy(ev.first); return false; }
+        }
+        used.push_back({kernel, ev.first, ev.second});
+        return hipEventRecord(ev.first, s) == hipSuccess;
+    }
+    bool end(hipStream_t s)
+    {
+        if (!enabled) return true;
+        return hipEventRecord(used.back().b, s) == hipSuccess;
+    }
+    mpzch_status_t collect(const char **names, double *ms, int64_t *launches, int32_t cap, int32_t *count)
+    {
+        double acc[KernelCount] = {0};
+        int64_t cnt[KernelCount] = {0};
+        for (auto &r : used) {
+            if (hipEventSynchronize(r.b) != hipSuccess) return MPZCH_ERR_HIP;
+            float t = 0.f;
+            if (hipEventElapsedTime(&t, r.a, r.b) != hipSuccess) return MPZCH_ERR_HIP;
+            acc[r.kernel] += t;
+            cnt[r.kernel]++;
+            pool.push_back({r.a, r.b});
+        }
+        used.clear();
+        int32_t k = 0;
+        for (int i = 0; i < KernelCount && k < cap; ++i) {
+            if (!cnt[i]) continue;
+            names[k] = kKernelNames[i];
+            ms[k] = acc[i];
+            launches[k] = cnt[i];
+            ++k;
+        }
+        *count = k;
+        return MPZCH_OK;
+    }
+    void destroy()
+    {
+        for (auto &r : used) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+        for (auto &e : pool) { (void)hipEventDestroy(e.first); (void)hipEventDestroy(e.second); }
+        used.clear();
+        pool.clear();
+    }
+};
+
+// ---- device scratch -----------------------------------------------------------------------
+struct Scratch {
+    char *base = nullptr;
+    int64_t cap_n = 0;
+    uint32_t *miss_pos = nullptr;
+    uint32_t *miss_ent = nullptr;
+    long long *set_keys = nullptr;
+    uint32_t *set_minpos = nullptr;
+    Control *ctl[2] = {nullptr, nullptr};
+    int parity = 0;
+    int num_cus = 0;
+
+    static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+
+    mpzch_status_t ensure(int64_t n)
+    {
+        if (num_cus == 0) {
+            int dev = 0;
+            if (hipGetDevice(&dev) != hipSuccess) return MPZCH_ERR_HIP;
+            if (hipDeviceGetAttribute(&num_cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || num_cus < 1)
+                return MPZCH_ERR_HIP;
+        }
+        if (n <= cap_n && base) return MPZCH_OK;
+        if (n < 1024) n = 1024;
+        if (base) {
+            if (hipDeviceSynchronize() != hipSuccess) return MPZCH_ERR_HIP;
+            (void)hipFree(base);
+            base = nullptr;
+            cap_n = 0;
+        }
+        const size_t o_pos = 0;
+        const size_t o_ent = o_pos + align_up(4 * (size_t)n);
+        const size_t o_keys = o_ent + align_up(4 * (size_t)n);
+        const size_t o_min = o_keys + align_up(16 * (size_t)n);
+        const size_t o_ctl = o_min + align_up(8 * (size_t)n);
+        const size_t total = o_ctl + 2 * align_up(sizeof(Control));
+        if (hipMalloc((void **)&base, total) != hipSuccess) { base = nullptr; return MPZCH_ERR_ALLOC; }
+        miss_pos = (uint32_t *)(base + o_pos);
+        miss_ent = (uint32_t *)(base + o_ent);
+        set_keys = (long long *)(base + o_keys);
+        set_minpos = (uint32_t *)(base + o_min);
+        ctl[0] = (Control *)(base + o_ctl);
+        ctl[1] = (Control *)(base + o_ctl + align_up(sizeof(Control)));
+        // empty set (key -1, position 0xFFFFFFFF) and zero counters; set entries are re-emptied
+        // by every call, so this is the only full clear
+        if (hipMemset(base + o_keys, 0xFF, (o_ctl - o_keys)) != hipSuccess) return MPZCH_ERR_HIP;
+        if (hipMemset(base + o_ctl, 0, 2 * align_up(sizeof(Control))) != hipSuccess) return MPZCH_ERR_HIP;
+        if (hipDeviceSynchronize() != hipSuccess) return MPZCH_ERR_HIP;
+        cap_n = n;
+        parity = 0;
+        return MPZCH_OK;
+    }
+    void release()
+    {
+        if (base) { (void)hipDeviceSynchronize(); (void)hipFree(base); base = nullptr; }
+        cap_n = 0;
+    }
+};
+
+int pick_group(int32_t max_p_eff)
+{
+    if (max_p_eff <= 8) return 8;
+    if (max_p_eff <= 16) return 16;
+    if (max_p_eff <= 32) return 32;
+    return 64;
+}
+
+int grid_for(int64_t items, int64_t items_per_block, int num_cus, int blocks_per_cu)
+{
+    int64_t b = (items + items_per_block - 1) / items_per_block;
+    const int64_t cap = (int64_t)num_cus * blocks_per_cu;
+    if (b > cap) b = cap;
+    if (b < 1) b = 1;
+    return (int)b;
+}
+
+int32_t p_eff(const TableCfg &c) { return (int64_t)c.max_probe < c.num_slots ? c.max_probe : (int32_t)c.num_slots; }
+
+TableDesc make_desc(const TableCfg &c, int64_t *I, int32_t *M, int64_t ev_begin, int64_t ev_cap)
+{
+    TableDesc d;
+    d.I = I;
+    d.M = M;
+    d.N = c.num_slots;
+    d.seed = c.seed;
+    d.P = p_eff(c);
+    d.ttl = c.ttl;
+    d.evict = c.kind == MPZCH_EVICT_TTL ? 1 : 0;
+    d.pad_ = 0;
+    d.ev_begin = ev_begin;
+    d.ev_cap = ev_cap;
+    return d;
+}
+
+#define LAUNCH_CHECK()                                        \
+    do {                                                      \
+        if (hipGetLastError() != hipSuccess) return MPZCH_ERR_HIP; \
+    } while (0)
+
+template <bool TRAIN>
+mpzch_status_t launch_discover(int G, const Params &p, int grid, hipStream_t s)
+{
+    switch (G) {
+        case 8: hipLaunchKernelGGL((k_discover<8, TRAIN>), dim3(grid), dim3(kBlock), 0, s, p); break;
+        case 16: hipLaunchKernelGGL((k_discover<16, TRAIN>), dim3(grid), dim3(kBlock), 0, s, p); break;
+        case 32: hipLaunchKernelGGL((k_discover<32, TRAIN>), dim3(grid), dim3(kBlock), 0, s, p); break;
+        default: hipLaunchKernelGGL((k_discover<64, TRAIN>), dim3(grid), dim3(kBlock), 0, s, p); break;
+    }
+    LAUNCH_CHECK();
+    return MPZCH_OK;
+}
+
+mpzch_status_t launch_allocate(int G, const Params &p, int grid, hipStream_t s)
+{
+    switch (G) {
+        case 8: hipLaunchKernelGGL((k_allocate<8>), dim3(grid), dim3(kBlock), 0, s, p); break;
+        case 16: hipLaunchKernelGGL((k_allocate<16>), dim3(grid), dim3(kBlock), 0, s, p); break;
+        case 32: hipLaunchKernelGGL((k_allocate<32>), dim3(grid), dim3(kBlock), 0, s, p); break;
+        default: hipLaunchKernelGGL((k_allocate<64>), dim3(grid), dim3(kBlock), 0, s, p); break;
+    }
+    LAUNCH_CHECK();
+    return MPZCH_OK;
+}
+
+mpzch_status_t launch_finalize(int G, const Params &p, int grid, hipStream_t s)
+{
+    switch (G) {
+        case 8: hipLaunchKernelGGL((k_finalize<8>), dim3(grid), dim3(kBlock), 0, s, p); break;
+        case 16: hipLaunchKernelGGL((k_finalize<16>), dim3(grid), dim3(kBlock), 0, s, p); break;
+        case 32: hipLaunchKernelGGL((k_finalize<32>), dim3(grid), dim3(kBlock), 0, s, p); break;
+        default: hipLaunchKernelGGL((k_finalize<64>), dim3(grid), dim3(kBlock), 0, s, p); break;
+    }
+    LAUNCH_CHECK();
+    return MPZCH_OK;
+}
+
+#define TRY(expr)                                   \
+    do {                                            \
+        mpzch_status_t st__ = (expr);               \
+        if (st__ != MPZCH_OK) return st__;          \
+    } while (0)
+#define TIMED(tm, id, s, launch)                    \
+    do {                                            \
+        if (!(tm).begin((id), (s))) return MPZCH_ERR_HIP; \
+        TRY(launch);                                \
+        if (!(tm).end((s))) return MPZCH_ERR_HIP;   \
+    } while (0)
+
+// The launch sequence of one training remap (single table or group).
+mpzch_status_t run_remap(Scratch &sc, Timing &tm, Params p, int G, hipStream_t s)
+{
+    p.miss_pos = sc.miss_pos;
+    p.miss_ent = sc.miss_ent;
+    p.set_keys = sc.set_keys;
+    p.set_minpos = sc.set_minpos;
+    p.ctl = sc.ctl[sc.parity];
+    p.ctl_next = sc.ctl[sc.parity ^ 1];
+    sc.parity ^= 1;
+
+    const int gpw = kWave / G;                       // miss-list entries per wave in the group kernels
+    const int g_disc = grid_for(p.n, kBlock, sc.num_cus, 16);
+    const int g_grp = grid_for(p.n, (kBlock / kWave) * gpw, sc.num_cus, 8);
+    const int g_thr = grid_for(p.n, kBlock, sc.num_cus, 8);
+
+    TIMED(tm, KDiscover, s, (launch_discover<true>(G, p, g_disc, s)));
+    TIMED(tm, KAllocate, s, launch_allocate(G, p, g_grp, s));
+    TIMED(tm, KFinalize, s, launch_finalize(G, p, g_grp, s));
+    if (!tm.begin(KEmitDups, s)) return MPZCH_ERR_HIP;
+    hipLaunchKernelGGL(k_emit_dups, dim3(g_thr), dim3(kBlock), 0, s, p);
+    LAUNCH_CHECK();
+    if (!tm.end(s)) return MPZCH_ERR_HIP;
+    if (!tm.begin(KCleanup, s)) return MPZCH_ERR_HIP;
+    hipLaunchKernelGGL(k_cleanup, dim3(g_thr), dim3(kBlock), 0, s, p);
+    LAUNCH_CHECK();
+    if (!tm.end(s)) return MPZCH_ERR_HIP;
+    return MPZCH_OK;
+}
+
+mpzch_status_t fill64(int64_t *dst, int64_t count, long long value, hipStream_t s)
+{
+    if (count <= 0) return MPZCH_OK;
+    const int grid = (int)((count + kBlock - 1) / kBlock < 4096 ? (count + kBlock - 1) / kBlock : 4096);
+    hipLaunchKernelGGL(k_fill64, dim3(grid), dim3(kBlock), 0, s, (long long *)dst, count, value);
+    LAUNCH_CHECK();
+    return MPZCH_OK;
+}
+
+mpzch_status_t fill32(int32_t *dst, int64_t count, int32_t value, hipStream_t s)
+{
+    if (count <= 0) return MPZCH_OK;
+    const int grid = (int)((count + kBlock - 1) / kBlock < 4096 ? (count + kBlock - 1) / kBlock : 4096);
+    hipLaunchKernelGGL(k_fill32, dim3(grid), dim3(kBlock), 0, s, dst, count, value);
+    LAUNCH_CHECK();
+    return MPZCH_OK;
+}
+
+bool valid_cfg(int64_t num_slots, int32_t max_probe, mpzch_eviction_policy_t policy)
+{
+    if (num_slots < 1 || max_probe < 1 || max_probe > MPZCH_MAX_PROBE) return false;
+    if (policy.kind != MPZCH_EVICT_NONE && policy.kind != MPZCH_EVICT_TTL) return false;
+    if (policy.ttl < 0) return false;
+    return true;
+}
+
+}  // namespace
+
+struct mpzch_table {
+    TableCfg cfg;
+    Scratch sc;
+    Timing tm;
+};
+
+struct mpzch_group {
+    std::vector<TableCfg> cfgs;
+    Scratch sc;
+    Timing tm;
+    TableDesc *descs_dev = nullptr;
+    std::vector<TableDesc> descs_host;   // what descs_dev holds
+    bool uploaded = false;
+};
+
+extern "C" {
+
+mpzch_status_t mpzch_create(int64_t num_slots, int32_t max_probe, mpzch_eviction_policy_t policy,
+                            uint64_t hash_seed, mpzch_table_t **out)
+{
+    if (!out) return MPZCH_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (policy.kind == MPZCH_EVICT_LRU) return MPZCH_ERR_UNSUPPORTED;
+    if (!valid_cfg(num_slots, max_probe, policy)) return MPZCH_ERR_INVALID_ARG;
+    mpzch_table *t = new (std::nothrow) mpzch_table();
+    if (!t) return MPZCH_ERR_ALLOC;
+    t->cfg = {num_slots, max_probe, policy.kind, policy.ttl, hash_seed};
+    *out = t;
+    return MPZCH_OK;
+}
+
+mpzch_status_t mpzch_destroy(mpzch_table_t *t)
+{
+    if (!t) return MPZCH_OK;
+    t->sc.release();
+    t->tm.destroy();
+    delete t;
+    return MPZCH_OK;
+}
+
+mpzch_status_t mpzch_reserve(mpzch_table_t *t, int64_t max_n)
+{
+    if (!t || max_n < 0 || max_n > MPZCH_MAX_BATCH) return MPZCH_ERR_INVALID_ARG;
+    return t->sc.ensure(max_n);
+}
+
+mpzch_status_t mpzch_init_tensors(const mpzch_table_t *t, int64_t *identities, int32_t *metadata, void *stream)
+{
+    if (!t || !identities) return MPZCH_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    TRY(fill64(identities, t->cfg.num_slots, -1, s));
+    if (metadata) TRY(fill32(metadata, t->cfg.num_slots, -1, s));
+    return MPZCH_OK;
+}
+
+mpzch_status_t mpzch_remap(mpzch_table_t *t, int64_t *identities, int32_t *metadata,
+                           const int64_t *ids, int64_t n, int32_t step,
+                           int64_t *out_slots,
+                           int64_t *out_evicted_slots, int64_t evicted_cap, int64_t *out_num_evicted,
+                           int64_t *out_stats, void *stream)
+{
+    if (!t || !identities || !metadata || !out_num_evicted) return MPZCH_ERR_INVALID_ARG;
+    if (n < 0 || n > MPZCH_MAX_BATCH || step < 0 || evicted_cap < 0) return MPZCH_ERR_INVALID_ARG;
+    if (n > 0 && (!ids || !out_slots)) return MPZCH_ERR_INVALID_ARG;
+    if (evicted_cap > 0 && !out_evicted_slots) return MPZCH_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    if (n == 0) {
+        TRY(fill64(out_num_evicted, 1, 0, s));
+        if (out_stats) TRY(fill64(out_stats, MPZCH_STAT_COUNT, 0, s));
+        return MPZCH_OK;
+    }
+    TRY(t->sc.ensure(n));
+    Params p;
+    std::memset(&p, 0, sizeof p);
+    p.ids = ids;
+    p.n = n;
+    p.step = step;
+    p.num_tables = 1;
+    p.out_slots = out_slots;
+    p.t0 = make_desc(t->cfg, identities, metadata, 0, evicted_cap);
+    p.out_evicted = out_evicted_slots;
+    p.out_num_evicted = out_num_evicted;
+    p.out_stats = out_stats;
+    return run_remap(t->sc, t->tm, p, pick_group(p.t0.P), s);
+}
+
+mpzch_status_t mpzch_lookup(const mpzch_table_t *t, const int64_t *identities,
+                            const int64_t *ids, int64_t n,
+                            int64_t *out_slots, uint8_t *out_found, void *stream)
+{
+    if (!t || !identities) return MPZCH_ERR_INVALID_ARG;
+    if (n < 0 || n > MPZCH_MAX_BATCH) return MPZCH_ERR_INVALID_ARG;
+    if (n == 0) return MPZCH_OK;
+    if (!ids || !out_slots) return MPZCH_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    mpzch_table *mt = const_cast<mpzch_table *>(t);
+    if (mt->sc.num_cus == 0) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return MPZCH_ERR_HIP;
+        if (hipDeviceGetAttribute(&mt->sc.num_cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+            mt->sc.num_cus < 1)
+            return MPZCH_ERR_HIP;
+    }
+    Params p;
+    std::memset(&p, 0, sizeof p);
+    p.ids = ids;
+    p.n = n;
+    p.num_tables = 1;
+    p.out_slots = out_slots;
+    p.out_found = out_found;
+    p.t0 = make_desc(t->cfg, const_cast<int64_t *>(identities), nullptr, 0, 0);
+    const int grid = grid_for(n, kBlock, mt->sc.num_cus, 16);
+    TIMED(mt->tm, KLookup, s, (launch_discover<false>(pick_group(p.t0.P), p, grid, s)));
+    return MPZCH_OK;
+}
+
+mpzch_status_t mpzch_reset_rows(const int64_t *slots, const int64_t *num_slots_dev, int64_t slots_cap,
+                                void *rows, int64_t num_rows, int64_t row_bytes, int64_t row_stride_bytes,
+                                const void *init_row, void *stream)
+{
+    if (!num_slots_dev || slots_cap < 0 || !rows || num_rows < 1) return MPZCH_ERR_INVALID_ARG;
+    if (row_bytes < 4 || row_stride_bytes < row_bytes || (row_bytes & 3) || (row_stride_bytes & 3))
+        return MPZCH_ERR_INVALID_ARG;
+    if (((uintptr_t)rows & 3) || ((uintptr_t)init_row & 3)) return MPZCH_ERR_INVALID_ARG;
+    if (slots_cap == 0) return MPZCH_OK;
+    if (!slots) return MPZCH_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    const bool wide = !(row_bytes & 15) && !(row_stride_bytes & 15) && !((uintptr_t)rows & 15) &&
+                      !((uintptr_t)init_row & 15);
+    const int64_t chunks = wide ? row_bytes / 16 : row_bytes / 4;
+    if (chunks > 0x7FFFFFFF) return MPZCH_ERR_INVALID_ARG;
+    // the count lives on the device: size the grid for the capacity, bounded; the kernel strides
+    int64_t want = (slots_cap * chunks + kBlock - 1) / kBlock;
+    if (want > 8192) want = 8192;
+    if (want < 1) want = 1;
+    if (wide)
+        hipLaunchKernelGGL((k_reset_rows<u32x4>), dim3((int)want), dim3(kBlock), 0, s, slots, num_slots_dev, slots_cap,
+                           (char *)rows, num_rows, (int32_t)chunks, row_stride_bytes, (const u32x4 *)init_row);
+    else
+        hipLaunchKernelGGL((k_reset_rows<uint32_t>), dim3((int)want), dim3(kBlock), 0, s, slots, num_slots_dev,
+                           slots_cap, (char *)rows, num_rows, (int32_t)chunks, row_stride_bytes,
+                           (const uint32_t *)init_row);
+    LAUNCH_CHECK();
+    return MPZCH_OK;
+}
+
+mpzch_status_t mpzch_group_create(mpzch_table_t *const *tables, int32_t num_tables, mpzch_group_t **out)
+{
+    if (!out) return MPZCH_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!tables || num_tables < 1 || num_tables > MPZCH_MAX_GROUP_TABLES) return MPZCH_ERR_INVALID_ARG;
+    for (int i = 0; i < num_tables; ++i)
+        if (!tables[i]) return MPZCH_ERR_INVALID_ARG;
+    mpzch_group *g = new (std::nothrow) mpzch_group();
+    if (!g) return MPZCH_ERR_ALLOC;
+    for (int i = 0; i < num_tables; ++i) g->cfgs.push_back(tables[i]->cfg);
+    *out = g;
+    return MPZCH_OK;
+}
+
+mpzch_status_t mpzch_group_destroy(mpzch_group_t *g)
+{
+    if (!g) return MPZCH_OK;
+    g->sc.release();
+    g->tm.destroy();
+    if (g->descs_dev) (void)hipFree(g->descs_dev);
+    delete g;
+    return MPZCH_OK;
+}
+
+mpzch_status_t mpzch_group_reserve(mpzch_group_t *g, int64_t max_total_values)
+{
+    if (!g || max_total_values < 0 || max_total_values > MPZCH_MAX_BATCH) return MPZCH_ERR_INVALID_ARG;
+    return g->sc.ensure(max_total_values);
+}
+
+mpzch_status_t mpzch_remap_jagged(mpzch_group_t *g, int64_t *const *identities, int32_t *const *metadata,
+                                  const int64_t *values, const int64_t *feature_offsets,
+                                  int64_t total_values, int32_t step,
+                                  int64_t *out_slots,
+                                  int64_t *out_evicted_slots, const int64_t *evicted_offsets,
+                                  int64_t *out_num_evicted, int64_t *out_stats, void *stream)
+{
+    if (!g || !identities || !metadata || !feature_offsets || !evicted_offsets || !out_num_evicted)
+        return MPZCH_ERR_INVALID_ARG;
+    if (total_values < 0 || total_values > MPZCH_MAX_BATCH || step < 0) return MPZCH_ERR_INVALID_ARG;
+    if (total_values > 0 && (!values || !out_slots)) return MPZCH_ERR_INVALID_ARG;
+    const int T = (int)g->cfgs.size();
+    int32_t max_p = 1;
+    std::vector<TableDesc> descs((size_t)T);
+    for (int f = 0; f < T; ++f) {
+        if (!identities[f] || !metadata[f]) return MPZCH_ERR_INVALID_ARG;
+        const int64_t cap = evicted_offsets[f + 1] - evicted_offsets[f];
+        if (cap < 0 || evicted_offsets[f] < 0) return MPZCH_ERR_INVALID_ARG;
+        if (cap > 0 && !out_evicted_slots) return MPZCH_ERR_INVALID_ARG;
+        descs[f] = make_desc(g->cfgs[f], identities[f], metadata[f], evicted_offsets[f], cap);
+        if (descs[f].P > max_p) max_p = descs[f].P;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    if (total_values == 0) {
+        TRY(fill64(out_num_evicted, T, 0, s));
+        if (out_stats) TRY(fill64(out_stats, (int64_t)T * MPZCH_STAT_COUNT, 0, s));
+        return MPZCH_OK;
+    }
+    TRY(g->sc.ensure(total_values));
+    if (!g->descs_dev) {
+        if (hipMalloc((void **)&g->descs_dev, sizeof(TableDesc) * MPZCH_MAX_GROUP_TABLES) != hipSuccess) {
+            g->descs_dev = nullptr;
+            return MPZCH_ERR_ALLOC;
+        }
+    }
+    if (!g->uploaded || std::memcmp(g->descs_host.data(), descs.data(), sizeof(TableDesc) * (size_t)T) != 0) {
+        // earlier calls on this stream may still read the old descriptors
+        if (hipStreamSynchronize(s) != hipSuccess) return MPZCH_ERR_HIP;
+        if (hipMemcpy(g->descs_dev, descs.data(), sizeof(TableDesc) * (size_t)T, hipMemcpyHostToDevice) != hipSuccess)
+            return MPZCH_ERR_HIP;
+        g->descs_host = descs;
+        g->uploaded = true;
+    }
+    Params p;
+    std::memset(&p, 0, sizeof p);
+    p.ids = values;
+    p.n = total_values;
+    p.step = step;
+    p.num_tables = T;
+    p.out_slots = out_slots;
+    p.descs = g->descs_dev;
+    p.offsets = feature_offsets;
+    p.t0 = descs[0];
+    p.out_evicted = out_evicted_slots;
+    p.out_num_evicted = out_num_evicted;
+    p.out_stats = out_stats;
+    // a group of one table still goes through the descriptor path
+    if (T == 1) p.num_tables = 1;
+    return run_remap(g->sc, g->tm, p, pick_group(max_p), s);
+}
+
+mpzch_status_t mpzch_set_kernel_timing(mpzch_table_t *t, int32_t enable)
+{
+    if (!t) return MPZCH_ERR_INVALID_ARG;
+    t->tm.enabled = enable != 0;
+    return MPZCH_OK;
+}
+
+mpzch_status_t mpzch_kernel_times(mpzch_table_t *t, const char **names, double *ms, int64_t *launches,
+                                  int32_t cap, int32_t *count)
+{
+    if (!t || !names || !ms || !launches || !count || cap < 0) return MPZCH_ERR_INVALID_ARG;
+    return t->tm.collect(names, ms, launches, cap, count);
+}
+
+mpzch_status_t mpzch_group_set_kernel_timing(mpzch_group_t *g, int32_t enable)
+{
+    if (!g) return MPZCH_ERR_INVALID_ARG;
+    g->tm.enabled = enable != 0;
+    return MPZCH_OK;
+}
+
+mpzch_status_t mpzch_group_kernel_times(mpzch_group_t *g, const char **names, double *ms, int64_t *launches,
+                                        int32_t cap, int32_t *count)
+{
+    if (!g || !names || !ms || !launches || !count || cap < 0) return MPZCH_ERR_INVALID_ARG;
+    return g->tm.collect(names, ms, launches, cap, count);
+}
+
+const char *mpzch_status_string(int32_t status)
+{
+    switch (status) {
+        case MPZCH_OK: return "ok";
+        case MPZCH_ERR_INVALID_ARG: return "invalid argument";
+        case MPZCH_ERR_ALLOC: return "allocation failed";
+        case MPZCH_ERR_HIP: return "HIP runtime error";
+        case MPZCH_ERR_UNSUPPORTED: return "unsupported";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,108 @@
+"""Keyed jagged batch over several tables in one launch sequence vs per-table oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2602_17050_amd import binding as mp
+from paper_2602_17050_amd import workloads as wl
+from gpu_common import say
+
+pytestmark = pytest.mark.gpu
+
+
+class JaggedPair:
+    def __init__(self, specs):
+        self.specs = specs
+        self.handles = [mp.mpzch_create(t.num_slots, t.max_probe, (mp.EVICT_TTL if t.evict else mp.EVICT_NONE, t.ttl),
+                                        t.hash_seed) for t in specs]
+        self.group = mp.mpzch_group_create(self.handles)
+        self.I = [torch.empty(t.num_slots, dtype=torch.int64, device="cuda") for t in specs]
+        self.M = [torch.empty(t.num_slots, dtype=torch.int32, device="cuda") for t in specs]
+        for h, i, m in zip(self.handles, self.I, self.M):
+            mp.mpzch_init_tensors(h, i, m)
+        self.o = [oracle.Table(t.num_slots, t.max_probe, oracle.EVICT_TTL if t.evict else oracle.EVICT_NONE, t.ttl,
+                               t.hash_seed) for t in specs]
+
+    def step(self, values, offsets, step):
+        T = len(self.specs)
+        v = torch.from_numpy(values).cuda()
+        off = torch.from_numpy(offsets).cuda()
+        out = torch.empty(len(values), dtype=torch.int64, device="cuda")
+        ev_off = [int(x) for x in offsets]                  # room for every value of the feature
+        ev = torch.empty(max(len(values), 1), dtype=torch.int64, device="cuda")
+        nev = torch.zeros(T, dtype=torch.int64, device="cuda")
+        stats = torch.zeros(T * mp.STAT_COUNT, dtype=torch.int64, device="cuda")
+        mp.mpzch_remap_jagged(self.group, self.I, self.M, v, off, step, out, ev, ev_off, nev, stats)
+        torch.cuda.synchronize()
+        so, evs, sts = oracle.remap_jagged(self.o, values, offsets, step)
+        assert np.array_equal(out.cpu().numpy(), so)
+        nev_h = nev.cpu().numpy()
+        ev_h = ev.cpu().numpy()
+        st_h = stats.cpu().numpy().reshape(T, mp.STAT_COUNT)
+        for f in range(T):
+            assert nev_h[f] == len(evs[f]), (f, nev_h[f], len(evs[f]))
+            got = ev_h[ev_off[f]: ev_off[f] + nev_h[f]]
+            assert np.array_equal(np.sort(got), np.sort(evs[f])), f
+            assert dict(zip(mp.STAT_NAMES, st_h[f].tolist())) == sts[f], f
+        return sts
+
+    def check_state(self):
+        for f, o in enumerate(self.o):
+            assert np.array_equal(self.I[f].cpu().numpy(), o.identities), f
+            assert np.array_equal(self.M[f].cpu().numpy(), o.metadata), f
+
+    def close(self):
+        mp.mpzch_group_destroy(self.group)
+        for h in self.handles:
+            mp.mpzch_destroy(h)
+
+
+def test_config5_jagged_scaled():
+    """26 tables, log-uniform sizes (total capped at 2 M slots here), P = 16, TTL 5, 2 048
+    samples, pooling 1..50, Zipf(1.05) ids per feature, own hash seed per table."""
+    spec = wl.c5_spec(total_slots_cap=2_000_000, samples=2048)
+    jp = JaggedPair(spec.tables)
+    tot = dict(evictions=0, collisions=0, inserts=0, hit_pos=0)
+    for step in range(1, 13):
+        values, lengths, offsets = wl.c5_batch(spec, step)
+        say("c5 step", step, "values", len(values))
+        sts = jp.step(values, offsets, step)
+        for s in sts:
+            for k in tot:
+                tot[k] += s[k]
+    jp.check_state()
+    say("c5 totals", tot)
+    assert all(v > 0 for v in tot.values())
+    jp.close()
+
+
+def test_jagged_boundaries_and_empty_features():
+    """Feature boundaries inside a wavefront, empty features, different P per table."""
+    specs = [wl.TableSpec(50, 4, 1, True, 1), wl.TableSpec(7, 20, 0, True, 2), wl.TableSpec(300, 40, 2, False, 3),
+             wl.TableSpec(1000, 9, 1, True, 4), wl.TableSpec(64, 64, 1, True, 5)]
+    jp = JaggedPair(specs)
+    rng = np.random.Generator(np.random.Philox(key=77))
+    for step in range(10):
+        counts = [int(rng.integers(0, 90)), 0 if step % 2 else int(rng.integers(0, 40)), int(rng.integers(0, 700)),
+                  0 if step % 3 == 0 else int(rng.integers(0, 3000)), int(rng.integers(0, 200))]
+        vals = [rng.integers(-1, 4 * s.num_slots, size=c) for s, c in zip(specs, counts)]
+        values = np.concatenate(vals).astype(np.int64)
+        offsets = np.concatenate([[0], np.cumsum(counts)]).astype(np.int64)
+        say("jagged step", step, counts)
+        jp.step(values, offsets, step)
+        jp.check_state()
+    # an entirely empty batch
+    jp.step(np.empty(0, np.int64), np.zeros(len(specs) + 1, np.int64), 11)
+    jp.close()
+
+
+def test_group_of_one_table_equals_plain_remap():
+    spec = wl.TableSpec(500, 16, 1, True, 42)
+    jp = JaggedPair([spec])
+    rng = np.random.Generator(np.random.Philox(key=5))
+    for step in range(6):
+        values = rng.integers(0, 2000, size=1500).astype(np.int64)
+        jp.step(values, np.array([0, len(values)], np.int64), step)
+    jp.check_state()
+    jp.close()

@@ -1,0 +1,212 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle, bit for bit
+(out_slots, identities, metadata, evicted-slot set, counters, reset rows)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2602_17050_amd import binding as mp
+from paper_2602_17050_amd import workloads as wl
+from gpu_common import Pair, say
+
+pytestmark = pytest.mark.gpu
+
+
+def test_config1_tiny_table_every_step():
+    """4 096 slots, P = 8, TTL 3, fp32 4096x16 rows, 8 Zipf(1.1) batches of 1 024 ids (then
+    32 more steps so that eviction and fallback are well exercised)."""
+    p = Pair.from_spec(wl.c1_spec())
+    tot = dict(evictions=0, collisions=0, inserts=0)
+    batches = wl.c1_batches() + [(s, wl.zipf_ids(wl.rng_for(1, s), 1024, 1.1, 16384)) for s in range(9, 41)]
+    for step, ids in batches:
+        say("c1 step", step)
+        r = p.step(ids, step)
+        for k in tot:
+            tot[k] += r.stats[k]
+    assert tot["evictions"] > 0 and tot["inserts"] > 0
+    p.close()
+
+
+CASES = [
+    # (slots, max_probe, ttl, evict, universe, batch, steps)
+    (1, 1, 0, True, 4, 7, 6),
+    (2, 5, 1, True, 6, 33, 8),
+    (5, 3, 0, True, 12, 64, 10),
+    (17, 8, 2, True, 60, 100, 12),
+    (64, 9, 1, True, 300, 257, 12),
+    (100, 16, 3, True, 500, 1000, 12),
+    (100, 17, 3, False, 90, 500, 6),
+    (257, 32, 2, True, 2000, 4096, 10),
+    (300, 40, 1, True, 2000, 3000, 8),
+    (1000, 64, 2, True, 5000, 8191, 8),
+    (1000, 100, 2, True, 5000, 5000, 6),
+    (2048, 200, 1, True, 9000, 6000, 6),
+    (600, 600, 0, True, 3000, 2500, 6),
+    (50, 1, 1, True, 200, 640, 8),
+    (4099, 4, 5, True, 30000, 20000, 10),
+]
+
+
+@pytest.mark.parametrize("case", CASES, ids=[f"N{c[0]}_P{c[1]}" for c in CASES])
+def test_contended_small_tables(case):
+    """Small tables under heavy contention: many ids compete for few slots, windows wrap
+    around the table end, P crosses every group width (8/16/32/64 and multi-chunk)."""
+    n_slots, max_probe, ttl, evict, universe, batch, steps = case
+    rng = np.random.Generator(np.random.Philox(key=hash(case) & 0xFFFFFFFF))
+    p = Pair(n_slots, max_probe, ttl, evict, hash_seed=0xABC0 + n_slots)
+    step = 0
+    for k in range(steps):
+        step += int(rng.integers(0, 3))
+        kind = k % 4
+        if kind == 0:
+            ids = wl.zipf_ids(rng, batch, 1.1, universe)
+        elif kind == 1:
+            ids = rng.integers(0, universe, size=batch)                      # raw small ids
+        elif kind == 2:
+            ids = rng.integers(-3, universe, size=batch // 2 + 1)            # some negative ids
+        else:
+            ids = wl.rank_to_id(rng.integers(universe, 3 * universe, size=batch))  # mostly new ids
+        say("case", case, "step", step, "n", len(ids))
+        p.step(ids, step)
+        bad, _, _ = p.o.check_state()
+        assert bad == 0
+    p.lookup(rng.integers(-2, 2 * universe, size=999))
+    p.close()
+
+
+def test_empty_and_single_element_batches():
+    p = Pair(128, 8, 2, True, 7)
+    p.step(np.empty(0, np.int64), 0)
+    p.step(np.array([5]), 1)
+    p.step(np.empty(0, np.int64), 2)
+    p.step(np.array([5, 5, 5, -1, 6]), 3)
+    p.close()
+
+
+def test_config2_one_million_slots():
+    """1 M slots, P = 16, TTL 10, fp32 1Mx64 rows: prefill to load 0.3, then 50 batches of
+    65 536 Zipf(1.05) ids (+5 % never-seen ids) -- insert, evict and row reset."""
+    spec = wl.c2_spec()
+    p = Pair.from_spec(spec)
+    step0, pre = wl.c2_prefill()
+    p.step(pre, step0, check_state=False)
+    tot_ev = 0
+    for step in range(1, 51):
+        r = p.step(wl.c2_batch(step), step, check_state=(step % 10 == 0))
+        tot_ev += r.stats["evictions"]
+        if step % 10 == 0:
+            occ = int((p.o.identities >= 0).sum())
+            say(f"c2 step {step}: load {occ / spec.num_slots:.3f} evictions so far {tot_ev}")
+    assert tot_ev > 1000
+    p.check_state()
+    assert p.o.check_state()[0] == 0
+    p.close()
+
+
+def test_config3_lookup_scaled():
+    """Read-only lookups, P = 32, table prefilled to 80 %: 95 % Zipf(1.2) over residents,
+    5 % unseen ids -> home slot + found = 0.  (1/100 of the 100 M-slot table.)"""
+    spec = wl.c3_spec(1_000_000)
+    p = Pair(spec.num_slots, spec.max_probe, 0, False, spec.hash_seed)
+    n_res = 800_000
+    for k, lo in enumerate(range(0, n_res, 100_000)):
+        p.step(wl.c3_prefill_ids(lo, lo + 100_000), k, check_state=False)
+    p.check_state()
+    I0 = p.g.identities.clone()
+    for s in range(3):
+        so, fo = p.lookup(wl.c3_batch(s, 100_000, n_res))
+        assert 0.93 < fo.mean() < 0.96
+    assert torch.equal(I0, p.g.identities)                 # no writes
+    p.close()
+
+
+def test_config4_streaming_scaled():
+    """Streaming freshness at 1/500 scale: 1 M slots prefilled to 0.9, TTL 20, 10 % brand-new
+    ids per step, rows addressed as slot mod rows -> sustained eviction and reset."""
+    spec = wl.c4_spec(1 / 500)
+    t = spec.table
+    emb = wl.embedding_pattern(t.emb_rows, 32, np.float32)
+    p = Pair(t.num_slots, t.max_probe, t.ttl, True, t.hash_seed, emb)
+    for lo in range(0, spec.prefill_ids, 200_000):
+        p.step(wl.stream_prefill_ids(lo, min(lo + 200_000, spec.prefill_ids)), 0, check_state=False)
+    p.check_state()
+    tot_ev = 0
+    for step in range(spec.first_step, spec.first_step + 30):
+        r = p.step(wl.stream_batch(spec, step), step, check_state=(step % 10 == 0))
+        tot_ev += r.stats["evictions"]
+    say("c4 scaled evictions", tot_ev)
+    assert tot_ev > 30 * 0.05 * spec.batch
+    p.check_state()
+    p.close()
+
+
+def test_reset_rows_init_row_and_strides():
+    """rows <- a caller-supplied init row; narrow (4-byte) and wide (16-byte) store paths."""
+    dev = "cuda"
+    for dim, dtype in [(16, torch.float32), (3, torch.float32), (128, torch.bfloat16), (6, torch.bfloat16)]:
+        rows_np = wl.embedding_pattern(50, dim, np.float32)
+        rows = torch.from_numpy(rows_np).to(dev).to(dtype)
+        want = rows.clone()
+        slots = torch.tensor([3, 53, 7, 49, 0, 1000], dtype=torch.int64, device=dev)
+        cnt = torch.tensor([5], dtype=torch.int64, device=dev)       # the last entry is beyond the count
+        init = (torch.arange(dim, device=dev, dtype=torch.float32) + 0.5).to(dtype)
+        mp.mpzch_reset_rows(slots, cnt, rows, init)
+        want[[3, 7, 49, 0]] = init
+        assert torch.equal(rows, want)
+        mp.mpzch_reset_rows(slots, cnt, rows, None)
+        want[[3, 7, 49, 0]] = 0
+        assert torch.equal(rows, want)
+        cnt.fill_(100)                                              # count beyond capacity is clamped
+        mp.mpzch_reset_rows(slots[:2], cnt, rows, init)
+        want[3] = init
+        assert torch.equal(rows, want)
+
+
+def test_results_do_not_depend_on_scheduling():
+    """Same batches twice from scratch -> identical tensors (the claim protocol has one fixed
+    point whatever the interleaving of wavefronts)."""
+    outs = []
+    for _ in range(2):
+        g = mp.MpzchTable(3000, 16, mp.EVICT_TTL, 1, 99)
+        res = []
+        for step in range(12):
+            ids = torch.from_numpy(wl.zipf_ids(wl.rng_for(9, step), 20000, 1.05, 12000)).cuda()
+            res.append(g.remap(ids, step).clone())
+        torch.cuda.synchronize()
+        outs.append((torch.cat(res), g.identities.clone(), g.metadata.clone()))
+        g.close()
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+
+
+def test_evicted_list_truncation_reports_true_count():
+    g = mp.MpzchTable(64, 8, mp.EVICT_TTL, 0, 3)
+    ids0 = torch.arange(0, 64, dtype=torch.int64, device="cuda")
+    g.remap(ids0, 0)
+    out = torch.empty(64, dtype=torch.int64, device="cuda")
+    ev = torch.full((4,), -7, dtype=torch.int64, device="cuda")
+    nev = torch.zeros(1, dtype=torch.int64, device="cuda")
+    ids1 = torch.arange(1000, 1064, dtype=torch.int64, device="cuda")
+    mp.mpzch_remap(g.handle, g.identities, g.metadata, ids1, 5, out, ev, nev, None)
+    torch.cuda.synchronize()
+    o = oracle.Table(64, 8, oracle.EVICT_TTL, 0, 3)
+    o.remap(ids0.cpu().numpy(), 0)
+    r = o.remap(ids1.cpu().numpy(), 5)
+    assert int(nev.item()) == len(r.evicted) > 4
+    assert set(ev.tolist()) <= set(r.evicted.tolist()) and len(set(ev.tolist())) == 4
+    assert np.array_equal(out.cpu().numpy(), r.slots)
+    g.close()
+
+
+def test_bad_arguments_are_rejected_before_launch():
+    g = mp.MpzchTable(64, 8, mp.EVICT_TTL, 0, 3)
+    ids = torch.arange(4, dtype=torch.int64, device="cuda")
+    out = torch.empty(4, dtype=torch.int64, device="cuda")
+    with pytest.raises(mp.MpzchError):
+        mp.mpzch_remap(g.handle, g.identities, g.metadata, ids, -1, out, out, g.num_evicted, None)   # step < 0
+    with pytest.raises(mp.MpzchError):
+        mp.mpzch_remap(g.handle, g.identities, None, ids, 1, out, out, g.num_evicted, None)          # no metadata
+    rows = torch.zeros(4, 3, dtype=torch.bfloat16, device="cuda")                                     # 6-byte rows
+    with pytest.raises(mp.MpzchError):
+        mp.mpzch_reset_rows(out, g.num_evicted, rows)
+    g.close()
