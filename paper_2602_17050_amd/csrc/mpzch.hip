@@ -21,9 +21,8 @@ struct TableCfg {
 };
 
 // ---- per-kernel timing --------------------------------------------------------------------
-enum KernelId { KDiscover = 0, KAllocate, KFinalize, KEmitDups, KCleanup, KLookup, KernelCount };
-const char *const kKernelNames[KernelCount] = {"k_discover", "k_allocate", "k_finalize",
-                                               "k_emit_dups", "k_cleanup", "k_lookup"};
+enum KernelId { KDiscover = 0, KAllocate, KFinalize, KEmitDups, KLookup, KernelCount };
+const char *const kKernelNames[KernelCount] = {"k_discover", "k_allocate", "k_finalize", "k_emit_dups", "k_lookup"};
 
 struct Timing {
     bool enabled = false;
@@ -84,27 +83,40 @@ struct Timing {
 };
 
 // ---- device scratch -----------------------------------------------------------------------
+constexpr int kDiscoverBlocksPerCu = 16;   // grid caps (workgroups per compute unit)
+constexpr int kGroupBlocksPerCu = 8;
+
 struct Scratch {
     char *base = nullptr;
     int64_t cap_n = 0;
-    uint32_t *miss_pos = nullptr;
-    uint32_t *miss_ent = nullptr;
+    unsigned long long *miss_mask = nullptr;
+    uint32_t *ent = nullptr;
+    uint32_t *first_of = nullptr;
     long long *set_keys = nullptr;
     uint32_t *set_minpos = nullptr;
+    StatRow *rows_a = nullptr;
+    StatRow *rows_b = nullptr;
     Control *ctl[2] = {nullptr, nullptr};
     int parity = 0;
     int num_cus = 0;
 
     static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
+    mpzch_status_t query_device()
+    {
+        if (num_cus) return MPZCH_OK;
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return MPZCH_ERR_HIP;
+        if (hipDeviceGetAttribute(&num_cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || num_cus < 1)
+            return MPZCH_ERR_HIP;
+        return MPZCH_OK;
+    }
+
+    // 32 bytes per position (+ 1 bit for the miss mask) and two small fixed areas
     mpzch_status_t ensure(int64_t n)
     {
-        if (num_cus == 0) {
-            int dev = 0;
-            if (hipGetDevice(&dev) != hipSuccess) return MPZCH_ERR_HIP;
-            if (hipDeviceGetAttribute(&num_cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || num_cus < 1)
-                return MPZCH_ERR_HIP;
-        }
+        mpzch_status_t st = query_device();
+        if (st != MPZCH_OK) return st;
         if (n <= cap_n && base) return MPZCH_OK;
         if (n < 1024) n = 1024;
         if (base) {
@@ -113,23 +125,29 @@ struct Scratch {
             base = nullptr;
             cap_n = 0;
         }
-        const size_t o_pos = 0;
-        const size_t o_ent = o_pos + align_up(4 * (size_t)n);
-        const size_t o_keys = o_ent + align_up(4 * (size_t)n);
+        const size_t rows = (size_t)num_cus * kDiscoverBlocksPerCu * kWavesPerBlock;
+        const size_t o_mask = 0;
+        const size_t o_ent = o_mask + align_up(8 * (((size_t)n + 63) / 64));
+        const size_t o_first = o_ent + align_up(4 * (size_t)n);
+        const size_t o_keys = o_first + align_up(4 * (size_t)n);
         const size_t o_min = o_keys + align_up(16 * (size_t)n);
-        const size_t o_ctl = o_min + align_up(8 * (size_t)n);
+        const size_t o_rows = o_min + align_up(8 * (size_t)n);
+        const size_t o_ctl = o_rows + 2 * align_up(rows * sizeof(StatRow));
         const size_t total = o_ctl + 2 * align_up(sizeof(Control));
         if (hipMalloc((void **)&base, total) != hipSuccess) { base = nullptr; return MPZCH_ERR_ALLOC; }
-        miss_pos = (uint32_t *)(base + o_pos);
-        miss_ent = (uint32_t *)(base + o_ent);
+        miss_mask = (unsigned long long *)(base + o_mask);
+        ent = (uint32_t *)(base + o_ent);
+        first_of = (uint32_t *)(base + o_first);
         set_keys = (long long *)(base + o_keys);
         set_minpos = (uint32_t *)(base + o_min);
+        rows_a = (StatRow *)(base + o_rows);
+        rows_b = (StatRow *)(base + o_rows + align_up(rows * sizeof(StatRow)));
         ctl[0] = (Control *)(base + o_ctl);
         ctl[1] = (Control *)(base + o_ctl + align_up(sizeof(Control)));
         // empty set (key -1, position 0xFFFFFFFF) and zero counters; set entries are re-emptied
         // by every call, so this is the only full clear
-        if (hipMemset(base + o_keys, 0xFF, (o_ctl - o_keys)) != hipSuccess) return MPZCH_ERR_HIP;
-        if (hipMemset(base + o_ctl, 0, 2 * align_up(sizeof(Control))) != hipSuccess) return MPZCH_ERR_HIP;
+        if (hipMemset(base + o_keys, 0xFF, (o_rows - o_keys)) != hipSuccess) return MPZCH_ERR_HIP;
+        if (hipMemset(base + o_rows, 0, total - o_rows) != hipSuccess) return MPZCH_ERR_HIP;
         if (hipDeviceSynchronize() != hipSuccess) return MPZCH_ERR_HIP;
         cap_n = n;
         parity = 0;
@@ -234,28 +252,28 @@ mpzch_status_t launch_finalize(int G, const Params &p, int grid, hipStream_t s)
 // The launch sequence of one training remap (single table or group).
 mpzch_status_t run_remap(Scratch &sc, Timing &tm, Params p, int G, hipStream_t s)
 {
-    p.miss_pos = sc.miss_pos;
-    p.miss_ent = sc.miss_ent;
+    p.miss_mask = sc.miss_mask;
+    p.ent = sc.ent;
+    p.first_of = sc.first_of;
     p.set_keys = sc.set_keys;
     p.set_minpos = sc.set_minpos;
+    p.rows_a = sc.rows_a;
+    p.rows_b = sc.rows_b;
     p.ctl = sc.ctl[sc.parity];
     p.ctl_next = sc.ctl[sc.parity ^ 1];
     sc.parity ^= 1;
 
-    const int gpw = kWave / G;                       // miss-list entries per wave in the group kernels
-    const int g_disc = grid_for(p.n, kBlock, sc.num_cus, 16);
-    const int g_grp = grid_for(p.n, (kBlock / kWave) * gpw, sc.num_cus, 8);
-    const int g_thr = grid_for(p.n, kBlock, sc.num_cus, 8);
+    // k_discover: one 64-position chunk per wavefront pass; the other kernels walk the miss masks
+    const int g_disc = grid_for(p.n, kBlock, sc.num_cus, kDiscoverBlocksPerCu);
+    const int g_grp = grid_for(p.n, kBlock, sc.num_cus, kGroupBlocksPerCu);
+    p.waves_a = g_disc * kWavesPerBlock;
+    p.waves_b = g_grp * kWavesPerBlock;
 
     TIMED(tm, KDiscover, s, (launch_discover<true>(G, p, g_disc, s)));
     TIMED(tm, KAllocate, s, launch_allocate(G, p, g_grp, s));
     TIMED(tm, KFinalize, s, launch_finalize(G, p, g_grp, s));
     if (!tm.begin(KEmitDups, s)) return MPZCH_ERR_HIP;
-    hipLaunchKernelGGL(k_emit_dups, dim3(g_thr), dim3(kBlock), 0, s, p);
-    LAUNCH_CHECK();
-    if (!tm.end(s)) return MPZCH_ERR_HIP;
-    if (!tm.begin(KCleanup, s)) return MPZCH_ERR_HIP;
-    hipLaunchKernelGGL(k_cleanup, dim3(g_thr), dim3(kBlock), 0, s, p);
+    hipLaunchKernelGGL(k_emit_dups, dim3(g_grp), dim3(kBlock), 0, s, p);
     LAUNCH_CHECK();
     if (!tm.end(s)) return MPZCH_ERR_HIP;
     return MPZCH_OK;
@@ -385,13 +403,7 @@ mpzch_status_t mpzch_lookup(const mpzch_table_t *t, const int64_t *identities,
     if (!ids || !out_slots) return MPZCH_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)stream;
     mpzch_table *mt = const_cast<mpzch_table *>(t);
-    if (mt->sc.num_cus == 0) {
-        int dev = 0;
-        if (hipGetDevice(&dev) != hipSuccess) return MPZCH_ERR_HIP;
-        if (hipDeviceGetAttribute(&mt->sc.num_cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-            mt->sc.num_cus < 1)
-            return MPZCH_ERR_HIP;
-    }
+    TRY(mt->sc.query_device());
     Params p;
     std::memset(&p, 0, sizeof p);
     p.ids = ids;
@@ -400,7 +412,7 @@ mpzch_status_t mpzch_lookup(const mpzch_table_t *t, const int64_t *identities,
     p.out_slots = out_slots;
     p.out_found = out_found;
     p.t0 = make_desc(t->cfg, const_cast<int64_t *>(identities), nullptr, 0, 0);
-    const int grid = grid_for(n, kBlock, mt->sc.num_cus, 16);
+    const int grid = grid_for(n, kBlock, mt->sc.num_cus, kDiscoverBlocksPerCu);
     TIMED(mt->tm, KLookup, s, (launch_discover<false>(pick_group(p.t0.P), p, grid, s)));
     return MPZCH_OK;
 }
