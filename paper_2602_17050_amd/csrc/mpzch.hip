@@ -4,6 +4,7 @@
 #include "../../include/mpzch.h"
 #include "mpzch_kernels.hpp"
 
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -83,15 +84,33 @@ struct Timing {
 };
 
 // ---- device scratch -----------------------------------------------------------------------
-constexpr int kDiscoverBlocksPerCu = 16;   // grid caps (workgroups per compute unit)
-constexpr int kGroupBlocksPerCu = 8;
+// grid caps in workgroups per compute unit
+int env_int(const char *name, int dflt)
+{
+    const char *v = getenv(name);
+    if (!v || !*v) return dflt;
+    const int x = atoi(v);
+    return x > 0 ? x : dflt;
+}
+const int kDiscoverBlocksPerCuMax = 16;
+int discover_blocks_per_cu()
+{
+    static const int v = [] { int x = env_int("MPZCH_DISCOVER_BPC", 8); return x > kDiscoverBlocksPerCuMax ? kDiscoverBlocksPerCuMax : x; }();
+    return v;
+}
+int group_blocks_per_cu()
+{
+    static const int v = [] { int x = env_int("MPZCH_GROUP_BPC", 8); return x > kDiscoverBlocksPerCuMax ? kDiscoverBlocksPerCuMax : x; }();
+    return v;
+}
 
 struct Scratch {
     char *base = nullptr;
     int64_t cap_n = 0;
-    unsigned long long *miss_mask = nullptr;
+    uint32_t *list = nullptr;
     uint32_t *ent = nullptr;
     uint32_t *first_of = nullptr;
+    uint32_t *seg_cnt = nullptr;
     long long *set_keys = nullptr;
     uint32_t *set_minpos = nullptr;
     StatRow *rows_a = nullptr;
@@ -112,7 +131,7 @@ struct Scratch {
         return MPZCH_OK;
     }
 
-    // 32 bytes per position (+ 1 bit for the miss mask) and two small fixed areas
+    // 36 bytes per position and a few small fixed areas
     mpzch_status_t ensure(int64_t n)
     {
         mpzch_status_t st = query_device();
@@ -125,23 +144,26 @@ struct Scratch {
             base = nullptr;
             cap_n = 0;
         }
-        const size_t rows = (size_t)num_cus * kDiscoverBlocksPerCu * kWavesPerBlock;
-        const size_t o_mask = 0;
-        const size_t o_ent = o_mask + align_up(8 * (((size_t)n + 63) / 64));
-        const size_t o_first = o_ent + align_up(4 * (size_t)n);
-        const size_t o_keys = o_first + align_up(4 * (size_t)n);
+        const size_t max_blocks = (size_t)num_cus * kDiscoverBlocksPerCuMax;
+        const size_t per_pos = 4 * ((size_t)n + kWave);
+        const size_t o_list = 0;
+        const size_t o_ent = o_list + align_up(per_pos);
+        const size_t o_first = o_ent + align_up(per_pos);
+        const size_t o_seg = o_first + align_up(per_pos);
+        const size_t o_keys = o_seg + align_up(4 * max_blocks * kWavesPerBlock);
         const size_t o_min = o_keys + align_up(16 * (size_t)n);
         const size_t o_rows = o_min + align_up(8 * (size_t)n);
-        const size_t o_ctl = o_rows + 2 * align_up(rows * sizeof(StatRow));
+        const size_t o_ctl = o_rows + 2 * align_up(max_blocks * sizeof(StatRow));
         const size_t total = o_ctl + 2 * align_up(sizeof(Control));
         if (hipMalloc((void **)&base, total) != hipSuccess) { base = nullptr; return MPZCH_ERR_ALLOC; }
-        miss_mask = (unsigned long long *)(base + o_mask);
+        list = (uint32_t *)(base + o_list);
         ent = (uint32_t *)(base + o_ent);
         first_of = (uint32_t *)(base + o_first);
+        seg_cnt = (uint32_t *)(base + o_seg);
         set_keys = (long long *)(base + o_keys);
         set_minpos = (uint32_t *)(base + o_min);
         rows_a = (StatRow *)(base + o_rows);
-        rows_b = (StatRow *)(base + o_rows + align_up(rows * sizeof(StatRow)));
+        rows_b = (StatRow *)(base + o_rows + align_up(max_blocks * sizeof(StatRow)));
         ctl[0] = (Control *)(base + o_ctl);
         ctl[1] = (Control *)(base + o_ctl + align_up(sizeof(Control)));
         // empty set (key -1, position 0xFFFFFFFF) and zero counters; set entries are re-emptied
@@ -159,14 +181,6 @@ struct Scratch {
         cap_n = 0;
     }
 };
-
-int pick_group(int32_t max_p_eff)
-{
-    if (max_p_eff <= 8) return 8;
-    if (max_p_eff <= 16) return 16;
-    if (max_p_eff <= 32) return 32;
-    return 64;
-}
 
 int grid_for(int64_t items, int64_t items_per_block, int num_cus, int blocks_per_cu)
 {
@@ -201,38 +215,30 @@ TableDesc make_desc(const TableCfg &c, int64_t *I, int32_t *M, int64_t ev_begin,
     } while (0)
 
 template <bool TRAIN>
-mpzch_status_t launch_discover(int G, const Params &p, int grid, hipStream_t s)
+mpzch_status_t launch_discover(const Params &p, int grid, hipStream_t s)
 {
-    switch (G) {
-        case 8: hipLaunchKernelGGL((k_discover<8, TRAIN>), dim3(grid), dim3(kBlock), 0, s, p); break;
-        case 16: hipLaunchKernelGGL((k_discover<16, TRAIN>), dim3(grid), dim3(kBlock), 0, s, p); break;
-        case 32: hipLaunchKernelGGL((k_discover<32, TRAIN>), dim3(grid), dim3(kBlock), 0, s, p); break;
-        default: hipLaunchKernelGGL((k_discover<64, TRAIN>), dim3(grid), dim3(kBlock), 0, s, p); break;
-    }
+    hipLaunchKernelGGL((k_discover<TRAIN>), dim3(grid), dim3(kBlock), 0, s, p);
     LAUNCH_CHECK();
     return MPZCH_OK;
 }
 
-mpzch_status_t launch_allocate(int G, const Params &p, int grid, hipStream_t s)
+// max_p: largest min(max_probe, num_slots) of the tables involved
+mpzch_status_t launch_allocate(int32_t max_p, const Params &p, int grid, hipStream_t s)
 {
-    switch (G) {
-        case 8: hipLaunchKernelGGL((k_allocate<8>), dim3(grid), dim3(kBlock), 0, s, p); break;
-        case 16: hipLaunchKernelGGL((k_allocate<16>), dim3(grid), dim3(kBlock), 0, s, p); break;
-        case 32: hipLaunchKernelGGL((k_allocate<32>), dim3(grid), dim3(kBlock), 0, s, p); break;
-        default: hipLaunchKernelGGL((k_allocate<64>), dim3(grid), dim3(kBlock), 0, s, p); break;
-    }
+    if (max_p <= 8) hipLaunchKernelGGL((k_allocate_lane<8>), dim3(grid), dim3(kBlock), 0, s, p);
+    else if (max_p <= 16) hipLaunchKernelGGL((k_allocate_lane<16>), dim3(grid), dim3(kBlock), 0, s, p);
+    else if (max_p <= 32) hipLaunchKernelGGL((k_allocate_lane<32>), dim3(grid), dim3(kBlock), 0, s, p);
+    else hipLaunchKernelGGL(k_allocate_wave, dim3(grid), dim3(kBlock), 0, s, p);
     LAUNCH_CHECK();
     return MPZCH_OK;
 }
 
-mpzch_status_t launch_finalize(int G, const Params &p, int grid, hipStream_t s)
+mpzch_status_t launch_finalize(int32_t max_p, const Params &p, int grid, hipStream_t s)
 {
-    switch (G) {
-        case 8: hipLaunchKernelGGL((k_finalize<8>), dim3(grid), dim3(kBlock), 0, s, p); break;
-        case 16: hipLaunchKernelGGL((k_finalize<16>), dim3(grid), dim3(kBlock), 0, s, p); break;
-        case 32: hipLaunchKernelGGL((k_finalize<32>), dim3(grid), dim3(kBlock), 0, s, p); break;
-        default: hipLaunchKernelGGL((k_finalize<64>), dim3(grid), dim3(kBlock), 0, s, p); break;
-    }
+    if (max_p <= 8) hipLaunchKernelGGL((k_finalize_lane<8>), dim3(grid), dim3(kBlock), 0, s, p);
+    else if (max_p <= 16) hipLaunchKernelGGL((k_finalize_lane<16>), dim3(grid), dim3(kBlock), 0, s, p);
+    else if (max_p <= 32) hipLaunchKernelGGL((k_finalize_lane<32>), dim3(grid), dim3(kBlock), 0, s, p);
+    else hipLaunchKernelGGL(k_finalize_wave, dim3(grid), dim3(kBlock), 0, s, p);
     LAUNCH_CHECK();
     return MPZCH_OK;
 }
@@ -250,11 +256,12 @@ mpzch_status_t launch_finalize(int G, const Params &p, int grid, hipStream_t s)
     } while (0)
 
 // The launch sequence of one training remap (single table or group).
-mpzch_status_t run_remap(Scratch &sc, Timing &tm, Params p, int G, hipStream_t s)
+mpzch_status_t run_remap(Scratch &sc, Timing &tm, Params p, int32_t max_p, hipStream_t s)
 {
-    p.miss_mask = sc.miss_mask;
+    p.list = sc.list;
     p.ent = sc.ent;
     p.first_of = sc.first_of;
+    p.seg_cnt = sc.seg_cnt;
     p.set_keys = sc.set_keys;
     p.set_minpos = sc.set_minpos;
     p.rows_a = sc.rows_a;
@@ -263,15 +270,19 @@ mpzch_status_t run_remap(Scratch &sc, Timing &tm, Params p, int G, hipStream_t s
     p.ctl_next = sc.ctl[sc.parity ^ 1];
     sc.parity ^= 1;
 
-    // k_discover: one 64-position chunk per wavefront pass; the other kernels walk the miss masks
-    const int g_disc = grid_for(p.n, kBlock, sc.num_cus, kDiscoverBlocksPerCu);
-    const int g_grp = grid_for(p.n, kBlock, sc.num_cus, kGroupBlocksPerCu);
-    p.waves_a = g_disc * kWavesPerBlock;
-    p.waves_b = g_grp * kWavesPerBlock;
+    // k_discover: every wavefront owns one segment of seg_chunks 64-position chunks
+    const int g_disc = grid_for(p.n, kBlock, sc.num_cus, discover_blocks_per_cu());
+    const int64_t num_chunks = (p.n + kWave - 1) / kWave;
+    p.num_segs = g_disc * kWavesPerBlock;
+    p.seg_chunks = (int32_t)((num_chunks + p.num_segs - 1) / p.num_segs);
+    // the other kernels walk the segments' miss lists, one segment per wavefront pass
+    const int g_grp = grid_for((int64_t)p.num_segs, kWavesPerBlock, sc.num_cus, group_blocks_per_cu());
+    p.blocks_a = g_disc;
+    p.blocks_b = g_grp;
 
-    TIMED(tm, KDiscover, s, (launch_discover<true>(G, p, g_disc, s)));
-    TIMED(tm, KAllocate, s, launch_allocate(G, p, g_grp, s));
-    TIMED(tm, KFinalize, s, launch_finalize(G, p, g_grp, s));
+    TIMED(tm, KDiscover, s, (launch_discover<true>(p, g_disc, s)));
+    TIMED(tm, KAllocate, s, launch_allocate(max_p, p, g_grp, s));
+    TIMED(tm, KFinalize, s, launch_finalize(max_p, p, g_grp, s));
     if (!tm.begin(KEmitDups, s)) return MPZCH_ERR_HIP;
     hipLaunchKernelGGL(k_emit_dups, dim3(g_grp), dim3(kBlock), 0, s, p);
     LAUNCH_CHECK();
@@ -390,7 +401,7 @@ mpzch_status_t mpzch_remap(mpzch_table_t *t, int64_t *identities, int32_t *metad
     p.out_evicted = out_evicted_slots;
     p.out_num_evicted = out_num_evicted;
     p.out_stats = out_stats;
-    return run_remap(t->sc, t->tm, p, pick_group(p.t0.P), s);
+    return run_remap(t->sc, t->tm, p, p.t0.P, s);
 }
 
 mpzch_status_t mpzch_lookup(const mpzch_table_t *t, const int64_t *identities,
@@ -412,8 +423,10 @@ mpzch_status_t mpzch_lookup(const mpzch_table_t *t, const int64_t *identities,
     p.out_slots = out_slots;
     p.out_found = out_found;
     p.t0 = make_desc(t->cfg, const_cast<int64_t *>(identities), nullptr, 0, 0);
-    const int grid = grid_for(n, kBlock, mt->sc.num_cus, kDiscoverBlocksPerCu);
-    TIMED(mt->tm, KLookup, s, (launch_discover<false>(pick_group(p.t0.P), p, grid, s)));
+    const int grid = grid_for(n, kBlock, mt->sc.num_cus, discover_blocks_per_cu());
+    p.num_segs = grid * kWavesPerBlock;
+    p.seg_chunks = (int32_t)(((n + kWave - 1) / kWave + p.num_segs - 1) / p.num_segs);
+    TIMED(mt->tm, KLookup, s, (launch_discover<false>(p, grid, s)));
     return MPZCH_OK;
 }
 
@@ -535,7 +548,7 @@ mpzch_status_t mpzch_remap_jagged(mpzch_group_t *g, int64_t *const *identities, 
     p.out_stats = out_stats;
     // a group of one table still goes through the descriptor path
     if (T == 1) p.num_tables = 1;
-    return run_remap(g->sc, g->tm, p, pick_group(max_p), s);
+    return run_remap(g->sc, g->tm, p, max_p, s);
 }
 
 mpzch_status_t mpzch_set_kernel_timing(mpzch_table_t *t, int32_t enable)

@@ -1,27 +1,31 @@
 // Device code of the MPZCH batched remap for gfx950 (wave64).
 //
 // Kernel sequence of one training remap (paper Sec. 3.2 / Algorithm 1, Sec. 3.4, Sec. 3.6):
-//   k_discover   Pass 1 for every position: a G-lane group loads the probe window of one id
-//                with one coalesced access and finds the id by ballot + ffs.  Hits store
-//                metadata = step and the output slot.  Misses set their bit in a per-64-position
-//                miss mask and enter a scratch hash set that elects, per distinct missed id,
-//                the position of its first occurrence (input de-duplication of the ids that
-//                must allocate).
+//   k_discover   Pass 1 for every position.  A 16-lane group reads the 128-byte line that holds
+//                the id's home slot with one coalesced access and finds the id by ballot + ffs;
+//                the few ids whose window continues into further lines are compacted and
+//                scanned line by line.  Hits store metadata = step and the output slot.  Each
+//                wavefront owns a contiguous range of positions (a segment) and appends the
+//                positions that missed to its segment's list; at the end it enters them into a
+//                scratch hash set that elects, per distinct missed id, the position of its first
+//                occurrence (input de-duplication of the ids that must allocate).
 //   k_allocate   the elected positions claim slots.  A claim is a 64-bit atomic min of a tag
 //                (round, first position) into the identities word, so a slot always ends up
 //                with the claimant of the lowest (round, position); a claimant that is
-//                displaced is carried on by the displacing group from its next round.  The
+//                displaced is carried on by the displacing lane from its next round.  The
 //                fixed point is the unique stable assignment, the same one a sequential
 //                round-major / position-minor sweep produces.
 //   k_finalize   every elected id finds its tag in its window, replaces it by the id, sets
 //                metadata = step and reports evicted slots; ids without a tag fall back to home.
 //   k_emit_dups  the other copies of a missed id copy the slot of the elected position; the
 //                scratch set entries that were used are emptied again; counters are published.
+// k_allocate / k_finalize exist in two forms: one lane per claimant with the whole window in
+// registers (max_probe <= 32) and one wavefront per claimant scanning 64 slots per access.
 //
 // No kernel funnels work through one hot address: an atomic on a single address costs about
-// 12 ns on this GPU however many lanes it serves, so the miss list is a bit mask per wavefront
-// chunk (no shared cursor), counters are accumulated per wavefront and reduced once, and evicted
-// slots are staged in LDS and appended with one reservation per workgroup.
+// 12 ns on this GPU however many lanes it serves, so miss lists are per wavefront (no shared
+// cursor), counters are accumulated per workgroup and reduced once, and evicted slots are staged
+// in LDS and appended with one reservation per workgroup.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -33,6 +37,8 @@ constexpr int kBlock = 256;
 constexpr int kWavesPerBlock = kBlock / kWave;
 constexpr int kMaxTables = 64;
 constexpr int kStatCount = 8;
+constexpr int kLine = 16;              // identities per 128-byte line
+constexpr int kStage = 512;            // missed positions staged per wavefront before they are entered
 constexpr int kEvBuf = 256;            // evicted slots staged per wavefront before a flush
 
 enum Stat { kHitPos = 0, kMissPos, kDistinctMiss, kInserts, kEvictions, kCollisions, kInvalidPos, kHitProbeSum };
@@ -57,7 +63,7 @@ struct Control {
     unsigned long long stats[kMaxTables][kStatCount];
 };
 
-// Per-wavefront partial counters, written once with plain stores and summed by k_emit_dups.
+// Per-workgroup partial counters, written once with plain stores and summed by k_emit_dups.
 struct StatRow {
     unsigned long long v[kStatCount];
     long long table;
@@ -70,15 +76,20 @@ struct Params {
     int32_t num_tables;            // 1 => t0 is used and offsets/descs are ignored
     int64_t *out_slots;
     uint8_t *out_found;            // lookup only, may be null
-    // scratch
-    unsigned long long *miss_mask; // word c: which of the positions [64c, 64c + 64) missed
-    uint32_t *ent;                 // per miss position: its entry in the scratch set
-    uint32_t *first_of;            // per miss position: position of the first occurrence of its id
+    // scratch.  Segment s (one wavefront of k_discover) covers the 64-position chunks
+    // [s * seg_chunks, (s + 1) * seg_chunks); its missed positions are list[s * seg_chunks * 64 + k]
+    // for k < seg_cnt[s]; ent and first_of run parallel to list.
+    uint32_t *list;
+    uint32_t *ent;                 // entry of the position's id in the scratch set
+    uint32_t *first_of;            // position of the first occurrence of the position's id
+    uint32_t *seg_cnt;
+    int32_t seg_chunks;
+    int32_t num_segs;
     long long *set_keys;           // scratch hash set: key = id, empty = -1
     uint32_t *set_minpos;          // smallest position that inserted the key, empty = 0xFFFFFFFF
-    StatRow *rows_a;               // per wavefront of k_discover
-    StatRow *rows_b;               // per wavefront of k_finalize
-    int32_t waves_a, waves_b;
+    StatRow *rows_a;               // per workgroup of k_discover
+    StatRow *rows_b;               // per workgroup of k_finalize
+    int32_t blocks_a, blocks_b;
     Control *ctl;
     Control *ctl_next;
     // several tables
@@ -186,69 +197,7 @@ __device__ __forceinline__ uint32_t set_insert(const Params &p, int64_t id, uint
     return (uint32_t)e;
 }
 
-// ------------------------------------------------------------------ Pass 1 (discovery)
-// Probes the windows of the 64 ids held one per lane.  d is wave-uniform.  `on` marks lanes
-// whose id is valid and belongs to table d.  Returns, per lane, the probe distance of the hit
-// or -1.  A group of G lanes loads G consecutive slots per access; 64 / G ids per access.
-template <int G>
-__device__ __forceinline__ int probe_wave(const TableDesc &d, int64_t id, int64_t home, bool on)
-{
-    constexpr int IPI = kWave / G;           // ids per iteration
-    const int lane = lane_id();
-    const int g = lane / G, r = lane % G;
-    int my_dist = -1;
-    if (d.P <= G) {
-#pragma unroll
-        for (int t = 0; t < G; ++t) {
-            const int src = t * IPI + g;
-            const int64_t gid = shfl64(id, src);
-            const int64_t ghome = shfl64(home, src);
-            const bool act = __shfl((int)on, src) && r < d.P;
-            int64_t v = -1;
-            if (act) v = d.I[wrap(ghome + r, d.N)];
-            const uint64_t b = __ballot(act && v == gid);
-            const int first = group_first<G>(b, g);
-            const int got = __shfl(first, (lane % IPI) * G);
-            if (lane / IPI == t) my_dist = got;
-        }
-    } else {
-        // window longer than a group: scan it in chunks of G, stop at the first match
-        for (int t = 0; t < G; ++t) {
-            const int src = t * IPI + g;
-            const int64_t gid = shfl64(id, src);
-            const int64_t ghome = shfl64(home, src);
-            const bool gon = __shfl((int)on, src);
-            int first = -1;
-            for (int c = 0; c < d.P; c += G) {
-                const bool act = gon && first < 0 && (c + r) < d.P;
-                int64_t v = -1;
-                if (act) {
-                    int64_t s = ghome + c + r;          // home < N, c + r < P <= N
-                    v = d.I[wrap(s, d.N)];
-                }
-                const uint64_t b = __ballot(act && v == gid);
-                const int f = group_first<G>(b, g);
-                if (first < 0 && f >= 0) first = c + f;
-                if (__all(first >= 0 || !gon)) break;
-            }
-            const int got = __shfl(first, (lane % IPI) * G);
-            if (lane / IPI == t) my_dist = got;
-        }
-    }
-    return my_dist;
-}
-
-// contiguous range of 64-position chunks owned by this wavefront
-__device__ __forceinline__ void wave_chunk_range(int64_t n, int64_t &c_begin, int64_t &c_end, int64_t &wave_global)
-{
-    wave_global = ((int64_t)blockIdx.x * kBlock + threadIdx.x) / kWave;
-    const int64_t num_waves = (int64_t)gridDim.x * kWavesPerBlock;
-    const int64_t num_chunks = (n + kWave - 1) / kWave;
-    const int64_t per_wave = (num_chunks + num_waves - 1) / num_waves;
-    c_begin = wave_global * per_wave;
-    c_end = c_begin + per_wave < num_chunks ? c_begin + per_wave : num_chunks;
-}
-
+// ------------------------------------------------------------------ small wavefront helpers
 __device__ __forceinline__ unsigned long long wave_sum(unsigned long long x)
 {
     // rotation sum: afterwards every lane holds the wavefront total
@@ -257,19 +206,144 @@ __device__ __forceinline__ unsigned long long wave_sum(unsigned long long x)
     return x;
 }
 
-__device__ __forceinline__ uint64_t uniform64(uint64_t v)
+// Hands the next (64 / G) set bits of amask to the G-lane groups of the wavefront: returns this
+// group's bit index or -1, and removes the bits that were handed out.
+template <int G>
+__device__ __forceinline__ int next_bits(uint64_t &amask, int g)
 {
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
-    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
-    return ((uint64_t)hi << 32) | lo;
+    constexpr int GPW = kWave / G;
+    int b = -1;
+    uint64_t m = amask;
+#pragma unroll
+    for (int gg = 0; gg < GPW; ++gg) {
+        const int bb = m ? __ffsll((unsigned long long)m) - 1 : -1;
+        if (gg == g) b = bb;
+        m &= m - 1;
+    }
+    amask = m;
+    return b;
 }
 
-template <int G, bool TRAIN>
+// Region of the scratch set that serves the table owning `pos`: twice the number of positions
+// of that table, so it can never fill up.  The clamps keep the region inside [0, 2n) even if the
+// feature offsets break their contract.
+__device__ __forceinline__ void set_region(const Params &p, int64_t pos, uint64_t &base, uint64_t &size)
+{
+    if (p.num_tables <= 1) { base = 0; size = 2ull * (uint64_t)p.n; return; }
+    const int f = find_table(p.offsets, p.num_tables, pos);
+    int64_t lo = p.offsets[f], hi = p.offsets[f + 1];
+    if (f == p.num_tables - 1 || hi > p.n) hi = p.n;
+    if (hi <= pos) hi = pos + 1;
+    if (lo > pos) lo = pos;
+    if (lo < 0) lo = 0;
+    base = 2ull * (uint64_t)lo;
+    size = 2ull * (uint64_t)(hi - lo);
+}
+
+// Sums per-lane counters over the workgroup and stores one StatRow (or, when the wavefronts of
+// the workgroup ended on different tables, hands them over through atomics).  Must be reached
+// by all threads of the workgroup.
+__device__ __forceinline__ void block_stat_row(const Params &p, StatRow *rows, int num_rows, const int *idx,
+                                               const unsigned long long *vals, int count, int table,
+                                               unsigned long long (*s_red)[kStatCount], int *s_tab)
+{
+    const int lane = lane_id(), w = threadIdx.x / kWave;
+    for (int k = 0; k < count; ++k) {
+        const unsigned long long t = wave_sum(vals[k]);
+        if (lane == 0) s_red[w][idx[k]] = t;
+    }
+    if (lane == 0) s_tab[w] = table;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        bool same = true;
+        for (int i = 1; i < kWavesPerBlock; ++i) same = same && s_tab[i] == s_tab[0];
+        StatRow row;
+        for (int k = 0; k < kStatCount; ++k) row.v[k] = 0;
+        row.table = s_tab[0];
+        for (int i = 0; i < kWavesPerBlock; ++i)
+            for (int k = 0; k < count; ++k) {
+                const unsigned long long v = s_red[i][idx[k]];
+                if (same || i == 0) row.v[idx[k]] += v;
+                else if (v) atomicAdd(&p.ctl->stats[s_tab[i]][idx[k]], v);
+            }
+        if ((int)blockIdx.x < num_rows) rows[blockIdx.x] = row;
+    }
+}
+
+// ------------------------------------------------------------------ Pass 1 (discovery)
+// Probes the windows of the 64 ids held one per lane.  d is wave-uniform.  `on` marks lanes
+// whose id is valid and belongs to table d.  Returns, per lane, the probe distance of the hit
+// or -1.  Phase 1: each 16-lane group reads the 128-byte line holding the home slot of one id
+// (4 ids per access, 16 accesses in flight).  Phase 2: ids that were not found and whose window
+// goes on beyond that line are compacted and scanned 16 slots at a time.
+__device__ __forceinline__ int probe_lines(const TableDesc &d, int64_t id, int64_t home, bool on)
+{
+    constexpr int G = kLine, IPI = kWave / G;
+    const int lane = lane_id();
+    const int g = lane / G, r = lane % G;
+    const int base_off = (int)(((uintptr_t)d.I >> 3) & (G - 1));
+    int my_dist = -1;
+#pragma unroll
+    for (int t = 0; t < G; ++t) {
+        const int src = t * IPI + g;
+        const int64_t gid = shfl64(id, src);
+        const int64_t ghome = shfl64(home, src);
+        const bool gon = __shfl((int)on, src);
+        const int go = (int)((ghome + base_off) & (G - 1));     // slots between the line start and home
+        const int round = r - go;
+        const int64_t s = ghome + round;
+        const bool act = gon && round >= 0 && round < d.P && s < d.N;
+        int64_t v = -1;
+        if (act) v = d.I[s];
+        const int first = group_first<G>(__ballot(act && v == gid), g);
+        const int got = __shfl(first >= 0 ? first - go : -1, (lane % IPI) * G);
+        if (lane / IPI == t) my_dist = got;
+    }
+    // rounds already looked at for this lane's own id
+    const int o = (int)((home + base_off) & (G - 1));
+    int covered = G - o;
+    if (covered > d.P) covered = d.P;
+    if ((int64_t)covered > d.N - home) covered = (int)(d.N - home);
+    uint64_t um = __ballot(on && my_dist < 0 && covered < d.P);
+    while (um) {
+        const int b = next_bits<G>(um, g);
+        const bool gact = b >= 0;
+        const int src = gact ? b : 0;
+        const int64_t gid = shfl64(id, src);
+        const int64_t ghome = shfl64(home, src);
+        int first = -1;
+        for (int q0 = __shfl(covered, src); __any(gact && first < 0 && q0 < d.P); q0 += G) {
+            const int round = q0 + r;
+            const bool act = gact && first < 0 && round < d.P;
+            int64_t v = -1;
+            if (act) v = d.I[wrap(ghome + round, d.N)];
+            const int f = group_first<G>(__ballot(act && v == gid), g);
+            if (first < 0 && f >= 0) first = q0 + f;
+        }
+#pragma unroll
+        for (int gg = 0; gg < IPI; ++gg) {
+            const int bsel = __shfl(b, gg * G);
+            const int fsel = __shfl(first, gg * G);
+            if (bsel == lane) my_dist = fsel;
+        }
+    }
+    return my_dist;
+}
+
+template <bool TRAIN>
 __global__ __launch_bounds__(kBlock) void k_discover(Params p)
 {
+    __shared__ uint32_t s_stage[kWavesPerBlock][kStage];
+    __shared__ unsigned long long s_red[kWavesPerBlock][kStatCount];
+    __shared__ int s_tab[kWavesPerBlock];
+
     const int lane = lane_id();
-    int64_t c_begin, c_end, wave_global;
-    wave_chunk_range(p.n, c_begin, c_end, wave_global);
+    const int w = threadIdx.x / kWave;
+    const int64_t seg = (int64_t)blockIdx.x * kWavesPerBlock + w;       // this wavefront's segment
+    const int64_t num_chunks = (p.n + kWave - 1) / kWave;
+    const int64_t c_begin = seg * p.seg_chunks;
+    const int64_t c_end = c_begin + p.seg_chunks < num_chunks ? c_begin + p.seg_chunks : num_chunks;
+    const int64_t seg_base = c_begin * kWave;
     const bool multi = p.num_tables > 1;
     const bool want_stats = TRAIN && p.out_stats != nullptr;
 
@@ -282,6 +356,23 @@ __global__ __launch_bounds__(kBlock) void k_discover(Params p)
     // per-lane counters of the table currently being processed
     unsigned long long st_hit = 0, st_miss = 0, st_inv = 0, st_probe = 0;
     int st_table = 0;
+    int staged = 0, flushed = 0;                 // wave-uniform: missed positions in LDS / already entered
+
+    // enters the staged positions into the scratch set and appends them to the segment's list
+    auto flush_stage = [&]() {
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        for (int j = lane; j < staged; j += kWave) {
+            const uint32_t pos = s_stage[w][j];
+            uint64_t sb, ss;
+            set_region(p, (int64_t)pos, sb, ss);
+            const uint32_t e = set_insert(p, p.ids[pos], pos, sb, ss);
+            p.list[seg_base + flushed + j] = pos;
+            p.ent[seg_base + flushed + j] = e;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        flushed += staged;
+        staged = 0;
+    };
 
     for (int64_t c = c_begin; c < c_end; ++c) {
         const int64_t base = c * kWave;
@@ -289,31 +380,23 @@ __global__ __launch_bounds__(kBlock) void k_discover(Params p)
         const bool in_range = pos < p.n;
         const int64_t id = in_range ? p.ids[pos] : -1;
         bool todo = in_range;
-        uint64_t miss_bits = 0;
         // every pass handles the lanes that belong to one table (one pass unless the chunk
         // straddles a feature boundary)
         while (__any(todo)) {
             TableDesc d;
             int f = 0;
-            uint64_t set_base = 0, set_size = 2ull * (uint64_t)p.n;
             bool mine = todo;
             if (multi) {
                 const uint64_t tb = __ballot(todo);
-                const int first_lane = __ffsll((unsigned long long)tb) - 1;
-                const int64_t first_pos = base + first_lane;
-                f = find_table(p.offsets, p.num_tables, first_pos);
-                f = __builtin_amdgcn_readfirstlane(f);
-                // find_table skips empty features that share this offset.  The clamps keep every
-                // access in bounds (and the loop finite) even if the offsets break their contract.
-                int64_t seg_lo = p.offsets[f], seg_hi = p.offsets[f + 1];
+                const int64_t first_pos = base + __ffsll((unsigned long long)tb) - 1;
+                f = __builtin_amdgcn_readfirstlane(find_table(p.offsets, p.num_tables, first_pos));
+                // find_table skips empty features that share this offset; the clamp keeps the
+                // loop finite even if the offsets break their contract
+                int64_t seg_hi = p.offsets[f + 1];
                 if (f == p.num_tables - 1 || seg_hi > p.n) seg_hi = p.n;
                 if (seg_hi <= first_pos) seg_hi = first_pos + 1;
-                if (seg_lo > first_pos) seg_lo = first_pos;
-                if (seg_lo < 0) seg_lo = 0;
                 d = p.descs[f];
                 mine = todo && pos < seg_hi;
-                set_base = 2ull * (uint64_t)seg_lo;
-                set_size = 2ull * (uint64_t)(seg_hi - seg_lo);
             } else {
                 d = p.t0;
             }
@@ -333,7 +416,7 @@ __global__ __launch_bounds__(kBlock) void k_discover(Params p)
 
             const bool valid = mine && id >= 0;
             const int64_t home = mine ? home_slot(id, d.seed, d.N) : 0;
-            const int dist = probe_wave<G>(d, id, home, valid);
+            const int dist = probe_lines(d, id, home, valid);
             const bool hit = valid && dist >= 0;
             const int64_t slot = hit ? wrap(home + dist, d.N) : home;
 
@@ -348,11 +431,12 @@ __global__ __launch_bounds__(kBlock) void k_discover(Params p)
                     st_inv++;
                 }
                 const bool miss = valid && !hit;
-                miss_bits |= __ballot(miss);
+                const uint64_t mb = __ballot(miss);
                 if (miss) {
-                    p.ent[pos] = set_insert(p, id, (uint32_t)pos, set_base, set_size);
+                    s_stage[w][staged + __popcll(mb & ((1ull << lane) - 1ull))] = (uint32_t)pos;
                     st_miss++;
                 }
+                staged += __popcll(mb);
             } else {
                 if (mine) {
                     p.out_slots[pos] = slot;
@@ -361,167 +445,167 @@ __global__ __launch_bounds__(kBlock) void k_discover(Params p)
             }
             todo = todo && !mine;
         }
-        if (TRAIN && lane == 0) p.miss_mask[c] = miss_bits;
+        if (TRAIN && staged > kStage - kWave) flush_stage();
+    }
+    if (TRAIN) {
+        flush_stage();
+        if (lane == 0 && seg < p.num_segs) p.seg_cnt[seg] = (uint32_t)flushed;
     }
     if (want_stats) {
-        const unsigned long long a = wave_sum(st_hit), b = wave_sum(st_miss), x = wave_sum(st_inv),
-                                 y = wave_sum(st_probe);
-        if (lane == 0 && wave_global < p.waves_a) {
-            StatRow row;
-            for (int k = 0; k < kStatCount; ++k) row.v[k] = 0;
-            row.v[kHitPos] = a;
-            row.v[kMissPos] = b;
-            row.v[kInvalidPos] = x;
-            row.v[kHitProbeSum] = y;
-            row.table = st_table;
-            p.rows_a[wave_global] = row;
-        }
+        const int idx[4] = {kHitPos, kMissPos, kInvalidPos, kHitProbeSum};
+        const unsigned long long vals[4] = {st_hit, st_miss, st_inv, st_probe};
+        block_stat_row(p, p.rows_a, p.blocks_a, idx, vals, 4, st_table, s_red, s_tab);
     }
 }
 
-// ------------------------------------------------------------------ allocation
-// Loads, one miss position per lane, what k_allocate / k_finalize need of a 64-position chunk
-// and returns the ballot of the elected positions (first occurrence of their id).
-template <bool STORE_FIRST>
-__device__ __forceinline__ uint64_t load_chunk_agents(const Params &p, int64_t c, uint64_t mask, bool multi,
-                                                       int64_t &home, int &f)
+// ------------------------------------------------------------------ allocation, one lane per claimant
+// TTL test of Sec. 3.4 on a slot that holds an id
+__device__ __forceinline__ bool expired(const TableDesc &d, int32_t step, int64_t s)
 {
-    const int lane = lane_id();
-    const int64_t pos = c * kWave + lane;
-    bool agent = false;
-    home = 0;
-    f = 0;
-    if ((mask >> lane) & 1ull) {
-        uint32_t first;
-        if (STORE_FIRST) {
-            first = p.set_minpos[p.ent[pos]];
-            p.first_of[pos] = first;
-        } else {
-            first = p.first_of[pos];
-        }
-        agent = first == (uint32_t)pos;
-        if (agent) {
-            const int64_t id = p.ids[pos];
-            uint64_t seed = p.t0.seed;
-            int64_t n_slots = p.t0.N;
-            if (multi) {
-                f = find_table(p.offsets, p.num_tables, pos);
-                seed = p.descs[f].seed;
-                n_slots = p.descs[f].N;
-            }
-            home = home_slot(id, seed, n_slots);
-        }
-    }
-    return __ballot(agent);
+    return d.evict && (int64_t)step - (int64_t)d.M[s] > (int64_t)d.ttl;
 }
 
-// Hands the next (64 / G) set bits of amask to the groups of the wavefront: returns this
-// group's bit index or -1, and removes the bits that were handed out.
-template <int G>
-__device__ __forceinline__ int next_agent(uint64_t &amask, int g)
+// Deferred acceptance for the claimant at batch position cpos, starting at round cr, by one lane.
+// The whole window is loaded first (PMAX independent loads), then walked in probe order.
+template <int PMAX>
+__device__ __forceinline__ void claim_lane(const Params &p, const TableDesc &d, uint32_t cpos, int64_t home, int32_t cr)
 {
-    constexpr int GPW = kWave / G;
-    int b = -1;
-    uint64_t m = amask;
+    for (;;) {
+        int64_t v[PMAX];
 #pragma unroll
-    for (int gg = 0; gg < GPW; ++gg) {
-        const int bb = m ? __ffsll((unsigned long long)m) - 1 : -1;
-        if (gg == g) b = bb;
-        m &= m - 1;
+        for (int k = 0; k < PMAX; ++k) {
+            v[k] = 0;                                         // not claimable
+            if (k >= cr && k < d.P)
+                v[k] = __hip_atomic_load(&d.I[wrap(home + k, d.N)], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        // expiry of the slots that hold an id (second batch of independent loads)
+        uint32_t exp_bits = 0;
+        if (d.evict) {
+#pragma unroll
+            for (int k = 0; k < PMAX; ++k)
+                if (k >= cr && k < d.P && v[k] >= 0 && expired(d, p.step, wrap(home + k, d.N))) exp_bits |= 1u << k;
+        }
+        int64_t displaced = 0;
+        bool placed = false;
+#pragma unroll
+        for (int k = 0; k < PMAX; ++k) {
+            if (placed || k < cr || k >= d.P) continue;
+            uint32_t occ = 0;
+            bool cand;
+            if (v[k] == -1) cand = true;
+            else if (v[k] >= 0) { cand = (exp_bits >> k) & 1u; occ = 1; }
+            else { occ = tag_occ(v[k]); cand = v[k] > make_tag((uint32_t)k, cpos, occ); }
+            if (!cand) continue;
+            const int64_t mine = make_tag((uint32_t)k, cpos, occ);
+            const int64_t old = __hip_atomic_fetch_min(&d.I[wrap(home + k, d.N)], mine, __ATOMIC_RELAXED,
+                                                       __HIP_MEMORY_SCOPE_AGENT);
+            if (is_tag(old) && old < mine) continue;          // a better claim got there first
+            placed = true;
+            displaced = is_tag(old) ? old : 0;
+        }
+        if (!placed || !displaced) return;                    // settled, or out of slots (falls back later)
+        // carry the displaced claimant on from its next round (same table: same slot)
+        cpos = tag_pos(displaced);
+        cr = (int32_t)tag_round(displaced) + 1;
+        if (cr >= d.P) return;
+        home = home_slot(p.ids[cpos], d.seed, d.N);
     }
-    amask = m;
-    return b;
 }
 
-// One G-lane group per elected position runs deferred acceptance for it: propose to the first
-// slot of the window that is claimable and not held by a better tag; on displacing another tag
-// continue on behalf of its owner.
-template <int G>
-__global__ __launch_bounds__(kBlock) void k_allocate(Params p)
+template <int PMAX>
+__global__ __launch_bounds__(kBlock) void k_allocate_lane(Params p)
 {
     const int lane = lane_id();
-    const int g = lane / G, r = lane % G;
-    int64_t c_begin, c_end, wave_global;
-    wave_chunk_range(p.n, c_begin, c_end, wave_global);
+    const int64_t wave_global = ((int64_t)blockIdx.x * kBlock + threadIdx.x) / kWave;
+    const int64_t num_waves = (int64_t)gridDim.x * kWavesPerBlock;
     const bool multi = p.num_tables > 1;
-
-    for (int64_t c = c_begin; c < c_end; ++c) {
-        const uint64_t mask = uniform64(p.miss_mask[c]);
-        if (mask == 0) continue;
-        int64_t lane_home;
-        int lane_f;
-        uint64_t amask = load_chunk_agents<true>(p, c, mask, multi, lane_home, lane_f);
-        while (amask) {
-            const int b = next_agent<G>(amask, g);
-            // group-uniform state of the claimant carried by this group
-            bool active = b >= 0;
-            const int src = active ? b : 0;
-            uint32_t cpos = (uint32_t)(c * kWave + src);   // its position (priority within a round)
-            int64_t home = shfl64(lane_home, src);
-            int32_t cr = 0;                                 // next round to try
+    for (int64_t seg = wave_global; seg < p.num_segs; seg += num_waves) {
+        const uint32_t cnt = p.seg_cnt[seg];
+        const int64_t seg_base = seg * p.seg_chunks * kWave;
+        for (uint32_t j = lane; j < cnt; j += kWave) {
+            const uint32_t pos = p.list[seg_base + j];
+            const uint32_t first = p.set_minpos[p.ent[seg_base + j]];
+            p.first_of[seg_base + j] = first;
+            if (first != pos) continue;                       // a later copy of the id
             TableDesc d = p.t0;
-            if (multi) d = p.descs[__shfl(lane_f, src)];
-            while (__any(active)) {
-                // scan rounds cr + r of the claimant's window
-                const int32_t round = cr + r;
-                const bool inr = active && round < d.P;
-                bool cand = false;
-                uint32_t occ = 0;
-                int64_t s = 0;
-                if (inr) {
-                    s = wrap(home + round, d.N);
-                    const int64_t v = __hip_atomic_load(&d.I[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    if (v == -1) {
-                        cand = true;
-                    } else if (v >= 0) {
-                        if (d.evict && (int64_t)p.step - (int64_t)d.M[s] > (int64_t)d.ttl) { cand = true; occ = 1; }
-                    } else {
-                        occ = tag_occ(v);
-                        cand = v > make_tag((uint32_t)round, cpos, occ);   // held by a worse claim
+            if (multi) d = p.descs[find_table(p.offsets, p.num_tables, (int64_t)pos)];
+            claim_lane<PMAX>(p, d, pos, home_slot(p.ids[pos], d.seed, d.N), 0);
+        }
+    }
+}
+
+// ------------------------------------------------------------------ allocation, one wavefront per claimant
+__global__ __launch_bounds__(kBlock) void k_allocate_wave(Params p)
+{
+    const int lane = lane_id();
+    const int64_t wave_global = ((int64_t)blockIdx.x * kBlock + threadIdx.x) / kWave;
+    const int64_t num_waves = (int64_t)gridDim.x * kWavesPerBlock;
+    const bool multi = p.num_tables > 1;
+    for (int64_t seg = wave_global; seg < p.num_segs; seg += num_waves) {
+        const uint32_t cnt = p.seg_cnt[seg];
+        const int64_t seg_base = seg * p.seg_chunks * kWave;
+        for (uint32_t j0 = 0; j0 < cnt; j0 += kWave) {
+            // one list entry per lane; the elected ones are then served one after the other
+            uint32_t lpos = 0;
+            bool agent = false;
+            if (j0 + lane < cnt) {
+                lpos = p.list[seg_base + j0 + lane];
+                const uint32_t first = p.set_minpos[p.ent[seg_base + j0 + lane]];
+                p.first_of[seg_base + j0 + lane] = first;
+                agent = first == lpos;
+            }
+            uint64_t amask = __ballot(agent);
+            while (amask) {
+                const int src = __ffsll((unsigned long long)amask) - 1;
+                amask &= amask - 1;
+                uint32_t cpos = __shfl(lpos, src);                // claimant carried by the wavefront
+                TableDesc d = p.t0;
+                if (multi) d = p.descs[find_table(p.offsets, p.num_tables, (int64_t)cpos)];
+                int64_t home = home_slot(p.ids[cpos], d.seed, d.N);
+                int32_t cr = 0;
+                bool active = true;
+                while (active) {
+                    // lanes look at rounds cr .. cr + 63
+                    const int32_t round = cr + lane;
+                    bool cand = false;
+                    uint32_t occ = 0;
+                    int64_t s = 0;
+                    if (round < d.P) {
+                        s = wrap(home + round, d.N);
+                        const int64_t v = __hip_atomic_load(&d.I[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        if (v == -1) cand = true;
+                        else if (v >= 0) { cand = expired(d, p.step, s); occ = 1; }
+                        else { occ = tag_occ(v); cand = v > make_tag((uint32_t)round, cpos, occ); }
                     }
-                }
-                uint64_t cmask = __ballot(cand);
-                // propose to candidates in probe order until one accepts
-                bool settled = !active;     // this group is done with the current scan
-                bool placed = false;
-                int64_t displaced = 0;      // tag that was displaced (0 = none)
-                while (true) {
-                    const int first = settled ? -1 : group_first<G>(cmask, g);
-                    if (!settled && first < 0) settled = true;        // no candidate left in this scan
-                    if (__all(settled)) break;
-                    int64_t old = 0;
-                    if (!settled && r == first) {
-                        const int64_t mine = make_tag((uint32_t)round, cpos, occ);
-                        old = __hip_atomic_fetch_min(&d.I[s], mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    }
-                    if (!settled) {
-                        old = shfl64(old, g * G + first);
-                        const int64_t mine_first = make_tag((uint32_t)(cr + first), cpos, tag_occ(old));
-                        if (is_tag(old) && old < mine_first) {
-                            // a better claim got there first: this slot is lost for good
-                            cmask &= ~(1ull << (g * G + first));
-                        } else {
-                            placed = true;
-                            settled = true;
-                            displaced = is_tag(old) ? old : 0;
+                    uint64_t cmask = __ballot(cand);
+                    bool placed = false;
+                    int64_t displaced = 0;
+                    while (cmask && !placed) {
+                        const int first = __ffsll((unsigned long long)cmask) - 1;
+                        cmask &= cmask - 1;
+                        int64_t old = 0, mine = 0;
+                        if (lane == first) {
+                            mine = make_tag((uint32_t)round, cpos, occ);
+                            old = __hip_atomic_fetch_min(&d.I[s], mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                         }
+                        old = shfl64(old, first);
+                        mine = shfl64(mine, first);
+                        if (is_tag(old) && old < mine) continue;  // a better claim got there first
+                        placed = true;
+                        displaced = is_tag(old) ? old : 0;
                     }
-                }
-                if (active) {
                     if (placed) {
                         if (displaced) {
-                            // carry the displaced claimant on from its next round (same table:
-                            // both claimed the same slot)
                             cpos = tag_pos(displaced);
                             cr = (int32_t)tag_round(displaced) + 1;
                             home = home_slot(p.ids[cpos], d.seed, d.N);
-                            if (cr >= d.P) active = false;   // out of rounds: falls back at finalize
+                            if (cr >= d.P) active = false;        // out of rounds: falls back at finalize
                         } else {
                             active = false;
                         }
                     } else {
-                        cr += G;
-                        if (cr >= d.P) active = false;       // window exhausted: falls back at finalize
+                        cr += kWave;
+                        if (cr >= d.P) active = false;            // window exhausted: falls back at finalize
                     }
                 }
             }
@@ -534,6 +618,7 @@ __global__ __launch_bounds__(kBlock) void k_allocate(Params p)
 __device__ __forceinline__ void flush_evicted(const Params &p, const int64_t *buf, int &count, int table)
 {
     if (count == 0) return;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     const int lane = lane_id();
     unsigned long long base = 0;
     if (lane == 0) base = atomicAdd(&p.ctl->num_evicted[table], (unsigned long long)count);
@@ -544,120 +629,74 @@ __device__ __forceinline__ void flush_evicted(const Params &p, const int64_t *bu
         const int64_t at = (int64_t)base + i;
         if (at < ev_cap) p.out_evicted[ev_begin + at] = buf[i];
     }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     count = 0;
 }
 
-template <int G>
-__global__ __launch_bounds__(kBlock) void k_finalize(Params p)
-{
-    __shared__ int64_t s_ev[kWavesPerBlock][kEvBuf];
-    __shared__ int s_cnt[kWavesPerBlock];
-    __shared__ int s_tab[kWavesPerBlock];
-    __shared__ unsigned long long s_base;
-
-    const int lane = lane_id();
-    const int w = threadIdx.x / kWave;
-    const int g = lane / G, r = lane % G;
-    int64_t c_begin, c_end, wave_global;
-    wave_chunk_range(p.n, c_begin, c_end, wave_global);
-    const bool multi = p.num_tables > 1;
-    const bool want_stats = p.out_stats != nullptr;
-
+// Book-keeping shared by both forms of k_finalize: counters for one table at a time in
+// registers, evicted slots staged per wavefront in LDS.
+struct FinalizeState {
     int ev_cnt = 0, ev_table = 0;                       // wave-uniform
     unsigned long long st_ins = 0, st_evi = 0, st_col = 0;
     int st_table = 0;
+};
 
-    for (int64_t c = c_begin; c < c_end; ++c) {
-        const uint64_t mask = uniform64(p.miss_mask[c]);
-        if (mask == 0) continue;
-        int64_t lane_home;
-        int lane_f;
-        uint64_t amask = load_chunk_agents<false>(p, c, mask, multi, lane_home, lane_f);
-        while (amask) {
-            const int b = next_agent<G>(amask, g);
-            const bool active = b >= 0;
-            const int src = active ? b : 0;
-            const uint32_t cpos = (uint32_t)(c * kWave + src);
-            const int64_t home = shfl64(lane_home, src);
-            const int f = multi ? __shfl(lane_f, src) : 0;
-            TableDesc d = p.t0;
-            if (multi) d = p.descs[f];
-            // counters are kept in registers for one table at a time; where a chunk straddles a
-            // feature boundary (rare) they go straight to the per-table counters
-            bool direct = false;
-            if (want_stats && multi) {
-                const uint64_t am = __ballot(active);
-                const int f0 = __shfl(f, am ? __ffsll((unsigned long long)am) - 1 : 0);
-                direct = __any(active && f != f0);
-                if (f0 != st_table) {
-                    if (st_ins) atomicAdd(&p.ctl->stats[st_table][kInserts], st_ins);
-                    if (st_evi) atomicAdd(&p.ctl->stats[st_table][kEvictions], st_evi);
-                    if (st_col) atomicAdd(&p.ctl->stats[st_table][kCollisions], st_col);
-                    st_ins = st_evi = st_col = 0;
-                    st_table = f0;
+// Called by all lanes of the wavefront.  `done` lanes finished a claimant of table f with
+// outcome 0 = insert, 1 = eviction of slot s, 2 = collision.
+__device__ __forceinline__ void finalize_account(const Params &p, FinalizeState &fs, int64_t *s_ev_w, bool done,
+                                                 int outcome, int64_t s, int f, bool want_stats)
+{
+    const int lane = lane_id();
+    if (want_stats) {
+        if (p.num_tables > 1) {
+            const uint64_t dm = __ballot(done);
+            if (dm) {
+                const int f0 = __shfl(f, __ffsll((unsigned long long)dm) - 1);
+                if (f0 != fs.st_table) {
+                    // rare (feature boundary): hand the counters over through atomics
+                    if (fs.st_ins) atomicAdd(&p.ctl->stats[fs.st_table][kInserts], fs.st_ins);
+                    if (fs.st_evi) atomicAdd(&p.ctl->stats[fs.st_table][kEvictions], fs.st_evi);
+                    if (fs.st_col) atomicAdd(&p.ctl->stats[fs.st_table][kCollisions], fs.st_col);
+                    fs.st_ins = fs.st_evi = fs.st_col = 0;
+                    fs.st_table = f0;
                 }
             }
-            // find the slot that carries this claimant's tag
-            bool searching = active;
-            bool found = false;
-            bool ev_lane = false;        // this lane turned a tag on an occupied slot into the id
-            int64_t ev_slot = 0;
-            for (int32_t cc = 0; __any(searching); cc += G) {
-                const int32_t round = cc + r;
-                bool m = false;
-                if (searching && round < d.P) {
-                    const int64_t s = wrap(home + round, d.N);
-                    const int64_t v = __hip_atomic_load(&d.I[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    m = is_tag(v) && tag_pos(v) == cpos;
-                    if (m) {
-                        // the claim becomes the id; metadata gets the step (Algorithm 1, Pass 2)
-                        __hip_atomic_store(&d.I[s], p.ids[cpos], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        d.M[s] = p.step;
-                        p.out_slots[cpos] = s;
-                        if (tag_occ(v)) {
-                            ev_lane = true;
-                            ev_slot = s;
-                            if (direct) atomicAdd(&p.ctl->stats[f][kEvictions], 1ull); else st_evi++;
-                        } else {
-                            if (direct) atomicAdd(&p.ctl->stats[f][kInserts], 1ull); else st_ins++;
-                        }
-                    }
-                }
-                const int first = group_first<G>(__ballot(m), g);
-                if (searching) {
-                    if (first >= 0) { found = true; searching = false; }
-                    else if (cc + G >= d.P) searching = false;
-                }
-            }
-            if (active && !found && r == 0) {
-                // Case 3: no empty or evictable slot -> home slot, its metadata refreshed
-                d.M[home] = p.step;
-                p.out_slots[cpos] = home;
-                if (direct) atomicAdd(&p.ctl->stats[f][kCollisions], 1ull); else st_col++;
-            }
-            // stage evicted slots in LDS; all entries of the buffer belong to one table
-            uint64_t evm = __ballot(ev_lane);
-            while (evm) {
-                const int lead = __ffsll((unsigned long long)evm) - 1;
-                const int tf = __shfl(f, lead);
-                const bool sel = ev_lane && f == tf;
-                const uint64_t selm = __ballot(sel);
-                const int add = __popcll(selm);
-                if ((ev_cnt > 0 && tf != ev_table) || ev_cnt + add > kEvBuf) {
-                    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-                    flush_evicted(p, s_ev[w], ev_cnt, ev_table);
-                }
-                ev_table = tf;
-                if (sel) s_ev[w][ev_cnt + __popcll(selm & ((1ull << lane) - 1ull))] = ev_slot;
-                ev_cnt += add;
-                evm &= ~selm;
+        }
+        if (done) {
+            if (f != fs.st_table) {
+                atomicAdd(&p.ctl->stats[f][outcome == 0 ? kInserts : outcome == 1 ? kEvictions : kCollisions], 1ull);
+            } else {
+                fs.st_ins += outcome == 0;
+                fs.st_evi += outcome == 1;
+                fs.st_col += outcome == 2;
             }
         }
     }
+    // stage evicted slots in LDS; all entries of the buffer belong to one table
+    uint64_t evm = __ballot(done && outcome == 1);
+    while (evm) {
+        const int tf = __shfl(f, __ffsll((unsigned long long)evm) - 1);
+        const bool sel = done && outcome == 1 && f == tf;
+        const uint64_t selm = __ballot(sel);
+        const int add = __popcll(selm);
+        if ((fs.ev_cnt > 0 && tf != fs.ev_table) || fs.ev_cnt + add > kEvBuf) flush_evicted(p, s_ev_w, fs.ev_cnt, fs.ev_table);
+        fs.ev_table = tf;
+        if (sel) s_ev_w[fs.ev_cnt + __popcll(selm & ((1ull << lane) - 1ull))] = s;
+        fs.ev_cnt += add;
+        evm &= ~selm;
+    }
+}
 
-    // one reservation per workgroup when all its wavefronts staged for the same table
+// End of k_finalize: one reservation per workgroup when all its wavefronts staged for the same
+// table, then the per-workgroup counter row.  Must be reached by all threads.
+__device__ __forceinline__ void finalize_epilogue(const Params &p, FinalizeState &fs, int64_t (*s_ev)[kEvBuf],
+                                                  int *s_cnt, int *s_tab, unsigned long long *s_base,
+                                                  unsigned long long (*s_red)[kStatCount], bool want_stats)
+{
+    const int lane = lane_id(), w = threadIdx.x / kWave;
+    const bool multi = p.num_tables > 1;
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    if (lane == 0) { s_cnt[w] = ev_cnt; s_tab[w] = ev_table; }
+    if (lane == 0) { s_cnt[w] = fs.ev_cnt; s_tab[w] = fs.ev_table; }
     __syncthreads();
     int total = 0, before = 0, tab = -1;
     bool same = true;
@@ -670,30 +709,161 @@ __global__ __launch_bounds__(kBlock) void k_finalize(Params p)
     }
     if (total > 0) {
         if (same) {
-            if (threadIdx.x == 0) s_base = atomicAdd(&p.ctl->num_evicted[tab], (unsigned long long)total);
+            if (threadIdx.x == 0) *s_base = atomicAdd(&p.ctl->num_evicted[tab], (unsigned long long)total);
             __syncthreads();
-            const int64_t base = (int64_t)s_base + before;
+            const int64_t base = (int64_t)*s_base + before;
             const int64_t ev_begin = multi ? p.descs[tab].ev_begin : p.t0.ev_begin;
             const int64_t ev_cap = multi ? p.descs[tab].ev_cap : p.t0.ev_cap;
-            for (int i = lane; i < ev_cnt; i += kWave)
+            for (int i = lane; i < fs.ev_cnt; i += kWave)
                 if (base + i < ev_cap) p.out_evicted[ev_begin + base + i] = s_ev[w][i];
         } else {
-            flush_evicted(p, s_ev[w], ev_cnt, ev_table);
+            flush_evicted(p, s_ev[w], fs.ev_cnt, fs.ev_table);
         }
     }
-
+    __syncthreads();
     if (want_stats) {
-        const unsigned long long a = wave_sum(st_ins), b2 = wave_sum(st_evi), x = wave_sum(st_col);
-        if (lane == 0 && wave_global < p.waves_b) {
-            StatRow row;
-            for (int k = 0; k < kStatCount; ++k) row.v[k] = 0;
-            row.v[kInserts] = a;
-            row.v[kEvictions] = b2;
-            row.v[kCollisions] = x;
-            row.table = st_table;
-            p.rows_b[wave_global] = row;
+        const int idx[3] = {kInserts, kEvictions, kCollisions};
+        const unsigned long long vals[3] = {fs.st_ins, fs.st_evi, fs.st_col};
+        block_stat_row(p, p.rows_b, p.blocks_b, idx, vals, 3, fs.st_table, s_red, s_tab);
+    }
+}
+
+template <int PMAX>
+__global__ __launch_bounds__(kBlock) void k_finalize_lane(Params p)
+{
+    __shared__ int64_t s_ev[kWavesPerBlock][kEvBuf];
+    __shared__ unsigned long long s_red[kWavesPerBlock][kStatCount];
+    __shared__ int s_cnt[kWavesPerBlock];
+    __shared__ int s_tab[kWavesPerBlock];
+    __shared__ unsigned long long s_base;
+
+    const int lane = lane_id();
+    const int w = threadIdx.x / kWave;
+    const int64_t wave_global = ((int64_t)blockIdx.x * kBlock + threadIdx.x) / kWave;
+    const int64_t num_waves = (int64_t)gridDim.x * kWavesPerBlock;
+    const bool multi = p.num_tables > 1;
+    const bool want_stats = p.out_stats != nullptr;
+    FinalizeState fs;
+
+    for (int64_t seg = wave_global; seg < p.num_segs; seg += num_waves) {
+        const uint32_t cnt = p.seg_cnt[seg];
+        const int64_t seg_base = seg * p.seg_chunks * kWave;
+        for (uint32_t j0 = 0; j0 < cnt; j0 += kWave) {
+            bool agent = false;
+            uint32_t pos = 0;
+            if (j0 + lane < cnt) {
+                pos = p.list[seg_base + j0 + lane];
+                agent = p.first_of[seg_base + j0 + lane] == pos;
+            }
+            int outcome = 2, f = 0;
+            int64_t s_final = 0;
+            if (agent) {
+                TableDesc d = p.t0;
+                if (multi) { f = find_table(p.offsets, p.num_tables, (int64_t)pos); d = p.descs[f]; }
+                const int64_t id = p.ids[pos];
+                const int64_t home = home_slot(id, d.seed, d.N);
+                // find the slot that carries this claimant's tag: whole window first, then walk it
+                int64_t v[PMAX];
+#pragma unroll
+                for (int k = 0; k < PMAX; ++k) {
+                    v[k] = 0;
+                    if (k < d.P) v[k] = d.I[wrap(home + k, d.N)];
+                }
+                int at = -1;
+                uint32_t occ = 0;
+#pragma unroll
+                for (int k = 0; k < PMAX; ++k)
+                    if (at < 0 && k < d.P && is_tag(v[k]) && tag_pos(v[k]) == pos) { at = k; occ = tag_occ(v[k]); }
+                if (at >= 0) {
+                    // the claim becomes the id; metadata gets the step (Algorithm 1, Pass 2)
+                    s_final = wrap(home + at, d.N);
+                    d.I[s_final] = id;
+                    d.M[s_final] = p.step;
+                    outcome = (int)occ;
+                } else {
+                    // Case 3: no empty or evictable slot -> home slot, its metadata refreshed
+                    s_final = home;
+                    d.M[home] = p.step;
+                }
+                p.out_slots[pos] = s_final;
+            }
+            finalize_account(p, fs, s_ev[w], agent, outcome, s_final, f, want_stats);
         }
     }
+    finalize_epilogue(p, fs, s_ev, s_cnt, s_tab, &s_base, s_red, want_stats);
+}
+
+__global__ __launch_bounds__(kBlock) void k_finalize_wave(Params p)
+{
+    __shared__ int64_t s_ev[kWavesPerBlock][kEvBuf];
+    __shared__ unsigned long long s_red[kWavesPerBlock][kStatCount];
+    __shared__ int s_cnt[kWavesPerBlock];
+    __shared__ int s_tab[kWavesPerBlock];
+    __shared__ unsigned long long s_base;
+
+    const int lane = lane_id();
+    const int w = threadIdx.x / kWave;
+    const int64_t wave_global = ((int64_t)blockIdx.x * kBlock + threadIdx.x) / kWave;
+    const int64_t num_waves = (int64_t)gridDim.x * kWavesPerBlock;
+    const bool multi = p.num_tables > 1;
+    const bool want_stats = p.out_stats != nullptr;
+    FinalizeState fs;
+
+    for (int64_t seg = wave_global; seg < p.num_segs; seg += num_waves) {
+        const uint32_t cnt = p.seg_cnt[seg];
+        const int64_t seg_base = seg * p.seg_chunks * kWave;
+        for (uint32_t j0 = 0; j0 < cnt; j0 += kWave) {
+            uint32_t lpos = 0;
+            bool agent = false;
+            if (j0 + lane < cnt) {
+                lpos = p.list[seg_base + j0 + lane];
+                agent = p.first_of[seg_base + j0 + lane] == lpos;
+            }
+            uint64_t amask = __ballot(agent);
+            while (amask) {
+                const int src = __ffsll((unsigned long long)amask) - 1;
+                amask &= amask - 1;
+                const uint32_t cpos = __shfl(lpos, src);
+                int f = 0;
+                TableDesc d = p.t0;
+                if (multi) { f = find_table(p.offsets, p.num_tables, (int64_t)cpos); d = p.descs[f]; }
+                const int64_t id = p.ids[cpos];
+                const int64_t home = home_slot(id, d.seed, d.N);
+                // lanes look at 64 slots of the window per pass until the tag is found
+                bool found = false, mine = false;
+                uint32_t occ = 0;
+                int64_t s = 0;
+                for (int32_t c0 = 0; c0 < d.P && !found; c0 += kWave) {
+                    const int32_t round = c0 + lane;
+                    mine = false;
+                    if (round < d.P) {
+                        s = wrap(home + round, d.N);
+                        const int64_t v = d.I[s];
+                        mine = is_tag(v) && tag_pos(v) == cpos;
+                        occ = tag_occ(v);
+                    }
+                    found = __any(mine);
+                }
+                int outcome = 2;
+                int64_t s_final = home;
+                if (found) {
+                    if (mine) {
+                        d.I[s] = id;
+                        d.M[s] = p.step;
+                        p.out_slots[cpos] = s;
+                    }
+                    const int at = __ffsll((unsigned long long)__ballot(mine)) - 1;
+                    s_final = shfl64(s, at);
+                    outcome = (int)__shfl(occ, at);
+                } else if (lane == 0) {
+                    d.M[home] = p.step;
+                    p.out_slots[cpos] = home;
+                }
+                finalize_account(p, fs, s_ev[w], lane == 0, outcome, s_final, f, want_stats);
+            }
+        }
+    }
+    finalize_epilogue(p, fs, s_ev, s_cnt, s_tab, &s_base, s_red, want_stats);
 }
 
 // ------------------------------------------------------------------ duplicates, cleanup, counters
@@ -701,19 +871,21 @@ __global__ __launch_bounds__(kBlock) void k_emit_dups(Params p)
 {
     __shared__ unsigned long long s_bins[kMaxTables][kStatCount];
     const int lane = lane_id();
-    int64_t c_begin, c_end, wave_global;
-    wave_chunk_range(p.n, c_begin, c_end, wave_global);
+    const int64_t wave_global = ((int64_t)blockIdx.x * kBlock + threadIdx.x) / kWave;
+    const int64_t num_waves = (int64_t)gridDim.x * kWavesPerBlock;
 
-    for (int64_t c = c_begin; c < c_end; ++c) {
-        const uint64_t mask = uniform64(p.miss_mask[c]);
-        if (!((mask >> lane) & 1ull)) continue;
-        const int64_t pos = c * kWave + lane;
-        const uint32_t first = p.first_of[pos];
-        const uint32_t e = p.ent[pos];
-        if (first != (uint32_t)pos) p.out_slots[pos] = p.out_slots[first];
-        // empty the scratch set entry again (every copy of the id does; the stores agree)
-        p.set_keys[e] = -1;
-        p.set_minpos[e] = 0xFFFFFFFFu;
+    for (int64_t seg = wave_global; seg < p.num_segs; seg += num_waves) {
+        const uint32_t cnt = p.seg_cnt[seg];
+        const int64_t seg_base = seg * p.seg_chunks * kWave;
+        for (uint32_t j = lane; j < cnt; j += kWave) {
+            const uint32_t pos = p.list[seg_base + j];
+            const uint32_t first = p.first_of[seg_base + j];
+            const uint32_t e = p.ent[seg_base + j];
+            if (first != pos) p.out_slots[pos] = p.out_slots[first];
+            // empty the scratch set entry again (every copy of the id does; the stores agree)
+            p.set_keys[e] = -1;
+            p.set_minpos[e] = 0xFFFFFFFFu;
+        }
     }
 
     if (blockIdx.x == 0) {
@@ -724,8 +896,8 @@ __global__ __launch_bounds__(kBlock) void k_emit_dups(Params p)
             for (int i = threadIdx.x; i < nbins; i += kBlock)
                 s_bins[i / kStatCount][i % kStatCount] = p.ctl->stats[i / kStatCount][i % kStatCount];
             __syncthreads();
-            for (int i = threadIdx.x; i < p.waves_a + p.waves_b; i += kBlock) {
-                const StatRow *row = i < p.waves_a ? &p.rows_a[i] : &p.rows_b[i - p.waves_a];
+            for (int i = threadIdx.x; i < p.blocks_a + p.blocks_b; i += kBlock) {
+                const StatRow *row = i < p.blocks_a ? &p.rows_a[i] : &p.rows_b[i - p.blocks_a];
                 const int t = (int)row->table;
                 for (int k = 0; k < kStatCount; ++k) {
                     const unsigned long long v = row->v[k];
