@@ -45,7 +45,7 @@ def load_library(path: str | None = None):
     global _lib
     if _lib is not None and path is None:
         return _lib
-    path = path or _LIB_PATH
+    path = path or os.environ.get("MPZCH_LIBRARY") or _LIB_PATH   # env override: another build of the same ABI
     if not os.path.exists(path):
         raise FileNotFoundError(
             f"{path} is missing: build it with `python -m paper_2602_17050_amd.build` "

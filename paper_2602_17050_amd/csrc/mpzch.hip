@@ -110,6 +110,7 @@ struct Scratch {
     uint32_t *list = nullptr;
     uint32_t *ent = nullptr;
     uint32_t *first_of = nullptr;
+    uint8_t *hint = nullptr;
     uint32_t *seg_cnt = nullptr;
     long long *set_keys = nullptr;
     uint32_t *set_minpos = nullptr;
@@ -131,7 +132,7 @@ struct Scratch {
         return MPZCH_OK;
     }
 
-    // 36 bytes per position and a few small fixed areas
+    // 37 bytes per position and a few small fixed areas
     mpzch_status_t ensure(int64_t n)
     {
         mpzch_status_t st = query_device();
@@ -149,7 +150,8 @@ struct Scratch {
         const size_t o_list = 0;
         const size_t o_ent = o_list + align_up(per_pos);
         const size_t o_first = o_ent + align_up(per_pos);
-        const size_t o_seg = o_first + align_up(per_pos);
+        const size_t o_hint = o_first + align_up(per_pos);
+        const size_t o_seg = o_hint + align_up((size_t)n + kWave);
         const size_t o_keys = o_seg + align_up(4 * max_blocks * kWavesPerBlock);
         const size_t o_min = o_keys + align_up(16 * (size_t)n);
         const size_t o_rows = o_min + align_up(8 * (size_t)n);
@@ -159,6 +161,7 @@ struct Scratch {
         list = (uint32_t *)(base + o_list);
         ent = (uint32_t *)(base + o_ent);
         first_of = (uint32_t *)(base + o_first);
+        hint = (uint8_t *)(base + o_hint);
         seg_cnt = (uint32_t *)(base + o_seg);
         set_keys = (long long *)(base + o_keys);
         set_minpos = (uint32_t *)(base + o_min);
@@ -223,21 +226,25 @@ mpzch_status_t launch_discover(const Params &p, int grid, hipStream_t s)
 }
 
 // max_p: largest min(max_probe, num_slots) of the tables involved
-mpzch_status_t launch_allocate(int32_t max_p, const Params &p, int grid, hipStream_t s)
+mpzch_status_t launch_allocate(int32_t max_p, const Params &p, int num_cus, hipStream_t s)
 {
-    if (max_p <= 8) hipLaunchKernelGGL((k_allocate_lane<8>), dim3(grid), dim3(kBlock), 0, s, p);
-    else if (max_p <= 16) hipLaunchKernelGGL((k_allocate_lane<16>), dim3(grid), dim3(kBlock), 0, s, p);
-    else if (max_p <= 32) hipLaunchKernelGGL((k_allocate_lane<32>), dim3(grid), dim3(kBlock), 0, s, p);
-    else hipLaunchKernelGGL(k_allocate_wave, dim3(grid), dim3(kBlock), 0, s, p);
+    if (max_p <= 32) {
+        // one wavefront per workgroup, one segment per workgroup pass
+        const int grid = grid_for((int64_t)p.num_segs, 1, num_cus, 4 * group_blocks_per_cu());
+        if (max_p <= 8) hipLaunchKernelGGL((k_allocate_lane<8>), dim3(grid), dim3(kWave), 0, s, p);
+        else if (max_p <= 16) hipLaunchKernelGGL((k_allocate_lane<16>), dim3(grid), dim3(kWave), 0, s, p);
+        else hipLaunchKernelGGL((k_allocate_lane<32>), dim3(grid), dim3(kWave), 0, s, p);
+    } else {
+        const int grid = grid_for((int64_t)p.num_segs, kWavesPerBlock, num_cus, group_blocks_per_cu());
+        hipLaunchKernelGGL(k_allocate_wave, dim3(grid), dim3(kBlock), 0, s, p);
+    }
     LAUNCH_CHECK();
     return MPZCH_OK;
 }
 
 mpzch_status_t launch_finalize(int32_t max_p, const Params &p, int grid, hipStream_t s)
 {
-    if (max_p <= 8) hipLaunchKernelGGL((k_finalize_lane<8>), dim3(grid), dim3(kBlock), 0, s, p);
-    else if (max_p <= 16) hipLaunchKernelGGL((k_finalize_lane<16>), dim3(grid), dim3(kBlock), 0, s, p);
-    else if (max_p <= 32) hipLaunchKernelGGL((k_finalize_lane<32>), dim3(grid), dim3(kBlock), 0, s, p);
+    if (max_p <= 32) hipLaunchKernelGGL(k_finalize_lane, dim3(grid), dim3(kBlock), 0, s, p);
     else hipLaunchKernelGGL(k_finalize_wave, dim3(grid), dim3(kBlock), 0, s, p);
     LAUNCH_CHECK();
     return MPZCH_OK;
@@ -261,6 +268,7 @@ mpzch_status_t run_remap(Scratch &sc, Timing &tm, Params p, int32_t max_p, hipSt
     p.list = sc.list;
     p.ent = sc.ent;
     p.first_of = sc.first_of;
+    p.hint = sc.hint;
     p.seg_cnt = sc.seg_cnt;
     p.set_keys = sc.set_keys;
     p.set_minpos = sc.set_minpos;
@@ -281,7 +289,7 @@ mpzch_status_t run_remap(Scratch &sc, Timing &tm, Params p, int32_t max_p, hipSt
     p.blocks_b = g_grp;
 
     TIMED(tm, KDiscover, s, (launch_discover<true>(p, g_disc, s)));
-    TIMED(tm, KAllocate, s, launch_allocate(max_p, p, g_grp, s));
+    TIMED(tm, KAllocate, s, launch_allocate(max_p, p, sc.num_cus, s));
     TIMED(tm, KFinalize, s, launch_finalize(max_p, p, g_grp, s));
     if (!tm.begin(KEmitDups, s)) return MPZCH_ERR_HIP;
     hipLaunchKernelGGL(k_emit_dups, dim3(g_grp), dim3(kBlock), 0, s, p);

@@ -82,6 +82,7 @@ struct Params {
     uint32_t *list;
     uint32_t *ent;                 // entry of the position's id in the scratch set
     uint32_t *first_of;            // position of the first occurrence of the position's id
+    uint8_t *hint;                 // round at which k_allocate placed the position's claim (lane form)
     uint32_t *seg_cnt;
     int32_t seg_chunks;
     int32_t num_segs;
@@ -283,19 +284,29 @@ __device__ __forceinline__ int probe_lines(const TableDesc &d, int64_t id, int64
     const int g = lane / G, r = lane % G;
     const int base_off = (int)(((uintptr_t)d.I >> 3) & (G - 1));
     int my_dist = -1;
+    // All 16 line loads are issued before the first result is looked at.  A lane that has no
+    // slot to look at re-reads the group's home slot (always a valid address, same line), so
+    // the loads carry no branch and stay in flight together.
+    int64_t v[G];
+    uint32_t act_bits = 0;
+#pragma unroll
+    for (int t = 0; t < G; ++t) {
+        const int src = t * IPI + g;
+        const int64_t ghome = shfl64(home, src);
+        const bool gon = __shfl((int)on, src);
+        const int round = r - (int)((ghome + base_off) & (G - 1));
+        const int64_t s = ghome + round;
+        const bool act = gon && round >= 0 && round < d.P && s < d.N;
+        v[t] = d.I[act ? s : ghome];
+        act_bits |= (uint32_t)act << t;
+    }
 #pragma unroll
     for (int t = 0; t < G; ++t) {
         const int src = t * IPI + g;
         const int64_t gid = shfl64(id, src);
-        const int64_t ghome = shfl64(home, src);
-        const bool gon = __shfl((int)on, src);
-        const int go = (int)((ghome + base_off) & (G - 1));     // slots between the line start and home
-        const int round = r - go;
-        const int64_t s = ghome + round;
-        const bool act = gon && round >= 0 && round < d.P && s < d.N;
-        int64_t v = -1;
-        if (act) v = d.I[s];
-        const int first = group_first<G>(__ballot(act && v == gid), g);
+        const int go = (int)((shfl64(home, src) + base_off) & (G - 1));   // slots between line start and home
+        const bool act = (act_bits >> t) & 1u;
+        const int first = group_first<G>(__ballot(act && v[t] == gid), g);
         const int got = __shfl(first >= 0 ? first - go : -1, (lane % IPI) * G);
         if (lane / IPI == t) my_dist = got;
     }
@@ -315,9 +326,8 @@ __device__ __forceinline__ int probe_lines(const TableDesc &d, int64_t id, int64
         for (int q0 = __shfl(covered, src); __any(gact && first < 0 && q0 < d.P); q0 += G) {
             const int round = q0 + r;
             const bool act = gact && first < 0 && round < d.P;
-            int64_t v = -1;
-            if (act) v = d.I[wrap(ghome + round, d.N)];
-            const int f = group_first<G>(__ballot(act && v == gid), g);
+            const int64_t v2 = d.I[act ? wrap(ghome + round, d.N) : ghome];
+            const int f = group_first<G>(__ballot(act && v2 == gid), g);
             if (first < 0 && f >= 0) first = q0 + f;
         }
 #pragma unroll
@@ -374,11 +384,14 @@ __global__ __launch_bounds__(kBlock) void k_discover(Params p)
         staged = 0;
     };
 
+    // the ids of the next chunk are requested while the current one is probed
+    int64_t id_next = (c_begin < c_end && c_begin * kWave + lane < p.n) ? p.ids[c_begin * kWave + lane] : -1;
     for (int64_t c = c_begin; c < c_end; ++c) {
         const int64_t base = c * kWave;
         const int64_t pos = base + lane;
         const bool in_range = pos < p.n;
-        const int64_t id = in_range ? p.ids[pos] : -1;
+        const int64_t id = id_next;
+        id_next = (c + 1 < c_end && pos + kWave < p.n) ? p.ids[pos + kWave] : -1;
         bool todo = in_range;
         // every pass handles the lanes that belong to one table (one pass unless the chunk
         // straddles a feature boundary)
@@ -512,24 +525,106 @@ __device__ __forceinline__ void claim_lane(const Params &p, const TableDesc &d, 
     }
 }
 
+// One workgroup = one wavefront.  The windows (identities and metadata) of up to 64 claimants
+// are read cooperatively -- G lanes read G consecutive slots of one claimant with one coalesced
+// access, all accesses in flight together -- and transposed through LDS so that every lane then
+// walks the window of its own claimant.  The lane records the round at which its claimant was
+// placed (hint) so that k_finalize can go straight to that slot.
+constexpr uint32_t kHintNone = 0xFF;       // not an elected position
+constexpr uint32_t kHintUnplaced = 0xFE;   // ran out of slots: falls back to home (final)
+
 template <int PMAX>
-__global__ __launch_bounds__(kBlock) void k_allocate_lane(Params p)
+__global__ __launch_bounds__(kWave) void k_allocate_lane(Params p)
 {
-    const int lane = lane_id();
-    const int64_t wave_global = ((int64_t)blockIdx.x * kBlock + threadIdx.x) / kWave;
-    const int64_t num_waves = (int64_t)gridDim.x * kWavesPerBlock;
+    constexpr int G = PMAX < kLine ? PMAX : kLine;   // lanes that read one claimant's window together
+    constexpr int APL = kWave / G;                   // claimants served by one load instruction
+    constexpr int CH = PMAX / G;                     // load instructions per claimant
+    constexpr int NT = kWave / APL;
+    __shared__ int64_t s_I[kWave][PMAX + 1];         // +1: rows fall into different banks
+    __shared__ int32_t s_M[kWave][PMAX + 1];
+
+    const int lane = threadIdx.x;
+    const int g = lane / G, r = lane % G;
     const bool multi = p.num_tables > 1;
-    for (int64_t seg = wave_global; seg < p.num_segs; seg += num_waves) {
+    for (int64_t seg = blockIdx.x; seg < p.num_segs; seg += gridDim.x) {
         const uint32_t cnt = p.seg_cnt[seg];
         const int64_t seg_base = seg * p.seg_chunks * kWave;
-        for (uint32_t j = lane; j < cnt; j += kWave) {
-            const uint32_t pos = p.list[seg_base + j];
-            const uint32_t first = p.set_minpos[p.ent[seg_base + j]];
-            p.first_of[seg_base + j] = first;
-            if (first != pos) continue;                       // a later copy of the id
+        for (uint32_t j0 = 0; j0 < cnt; j0 += kWave) {
+            const int64_t idx = seg_base + j0 + lane;
+            const bool have = j0 + lane < cnt;
+            bool agent = false;
+            uint32_t pos = 0;
+            int f = 0;
+            int64_t home = 0;
             TableDesc d = p.t0;
-            if (multi) d = p.descs[find_table(p.offsets, p.num_tables, (int64_t)pos)];
-            claim_lane<PMAX>(p, d, pos, home_slot(p.ids[pos], d.seed, d.N), 0);
+            if (have) {
+                pos = p.list[idx];
+                const uint32_t first = p.set_minpos[p.ent[idx]];
+                p.first_of[idx] = first;
+                agent = first == pos;                         // else: a later copy of the id
+                if (agent) {
+                    if (multi) { f = find_table(p.offsets, p.num_tables, (int64_t)pos); d = p.descs[f]; }
+                    home = home_slot(p.ids[pos], d.seed, d.N);
+                }
+            }
+            // cooperative loads; lanes without a slot to read use slot 0 / the home slot (valid addresses)
+            int64_t vi[NT * CH];
+            int32_t vm[NT * CH];
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                const int a = t * APL + g;
+                const int64_t ghome = shfl64(home, a);
+                int64_t *gI = p.t0.I;
+                int32_t *gM = p.t0.M;
+                int64_t gN = p.t0.N;
+                int gP = p.t0.P;
+                if (multi) {
+                    const TableDesc &gd = p.descs[__shfl(f, a)];
+                    gI = gd.I; gM = gd.M; gN = gd.N; gP = gd.P;
+                }
+#pragma unroll
+                for (int c = 0; c < CH; ++c) {
+                    const int k = c * G + r;
+                    const int64_t sl = k < gP ? wrap(ghome + k, gN) : ghome;
+                    vi[t * CH + c] = __hip_atomic_load(&gI[sl], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    vm[t * CH + c] = gM[sl];
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+                for (int c = 0; c < CH; ++c) {
+                    s_I[t * APL + g][c * G + r] = vi[t * CH + c];
+                    s_M[t * APL + g][c * G + r] = vm[t * CH + c];
+                }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            uint32_t hint = kHintNone;
+            if (agent) {
+                hint = kHintUnplaced;
+                for (int k = 0; k < d.P; ++k) {
+                    const int64_t v = s_I[lane][k];
+                    uint32_t occ = 0;
+                    bool cand;
+                    if (v == -1) cand = true;
+                    else if (v >= 0) { cand = d.evict && (int64_t)p.step - (int64_t)s_M[lane][k] > (int64_t)d.ttl; occ = 1; }
+                    else { occ = tag_occ(v); cand = v > make_tag((uint32_t)k, pos, occ); }
+                    if (!cand) continue;
+                    const int64_t mine = make_tag((uint32_t)k, pos, occ);
+                    const int64_t old = __hip_atomic_fetch_min(&d.I[wrap(home + k, d.N)], mine, __ATOMIC_RELAXED,
+                                                               __HIP_MEMORY_SCOPE_AGENT);
+                    if (is_tag(old) && old < mine) continue;      // a better claim got there first
+                    hint = (uint32_t)k;
+                    if (is_tag(old)) {
+                        // carry the displaced claimant on from its next round (same table: same slot)
+                        const uint32_t vpos = tag_pos(old);
+                        const int32_t vr = (int32_t)tag_round(old) + 1;
+                        if (vr < d.P) claim_lane<PMAX>(p, d, vpos, home_slot(p.ids[vpos], d.seed, d.N), vr);
+                    }
+                    break;
+                }
+            }
+            if (have) p.hint[idx] = (uint8_t)hint;
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         }
     }
 }
@@ -728,7 +823,6 @@ __device__ __forceinline__ void finalize_epilogue(const Params &p, FinalizeState
     }
 }
 
-template <int PMAX>
 __global__ __launch_bounds__(kBlock) void k_finalize_lane(Params p)
 {
     __shared__ int64_t s_ev[kWavesPerBlock][kEvBuf];
@@ -762,18 +856,21 @@ __global__ __launch_bounds__(kBlock) void k_finalize_lane(Params p)
                 if (multi) { f = find_table(p.offsets, p.num_tables, (int64_t)pos); d = p.descs[f]; }
                 const int64_t id = p.ids[pos];
                 const int64_t home = home_slot(id, d.seed, d.N);
-                // find the slot that carries this claimant's tag: whole window first, then walk it
-                int64_t v[PMAX];
-#pragma unroll
-                for (int k = 0; k < PMAX; ++k) {
-                    v[k] = 0;
-                    if (k < d.P) v[k] = d.I[wrap(home + k, d.N)];
-                }
+                // the slot that carries this claimant's tag: where k_allocate left it, unless the
+                // claimant was displaced afterwards -- then its window is searched
+                const uint32_t h = p.hint[seg_base + j0 + lane];
                 int at = -1;
                 uint32_t occ = 0;
-#pragma unroll
-                for (int k = 0; k < PMAX; ++k)
-                    if (at < 0 && k < d.P && is_tag(v[k]) && tag_pos(v[k]) == pos) { at = k; occ = tag_occ(v[k]); }
+                if (h < kHintUnplaced) {
+                    const int64_t v = d.I[wrap(home + (int)h, d.N)];
+                    if (is_tag(v) && tag_pos(v) == pos) { at = (int)h; occ = tag_occ(v); }
+                }
+                if (at < 0 && h != kHintUnplaced) {
+                    for (int k = 0; k < d.P && at < 0; ++k) {
+                        const int64_t v = d.I[wrap(home + k, d.N)];
+                        if (is_tag(v) && tag_pos(v) == pos) { at = k; occ = tag_occ(v); }
+                    }
+                }
                 if (at >= 0) {
                     // the claim becomes the id; metadata gets the step (Algorithm 1, Pass 2)
                     s_final = wrap(home + at, d.N);
