@@ -272,78 +272,55 @@ __device__ __forceinline__ void block_stat_row(const Params &p, StatRow *rows, i
 }
 
 // ------------------------------------------------------------------ Pass 1 (discovery)
-// Probes the windows of the 64 ids held one per lane.  d is wave-uniform.  `on` marks lanes
-// whose id is valid and belongs to table d.  Returns, per lane, the probe distance of the hit
-// or -1.  Phase 1: each 16-lane group reads the 128-byte line holding the home slot of one id
-// (4 ids per access, 16 accesses in flight).  Phase 2: ids that were not found and whose window
-// goes on beyond that line are compacted and scanned 16 slots at a time.
-__device__ __forceinline__ int probe_lines(const TableDesc &d, int64_t id, int64_t home, bool on)
+// One probe pass over the 64 ids held one per lane: the id of lane L is compared with the 16
+// slots of rounds [q, q + 16) of its window (q may be negative: rounds below 0 do not exist;
+// q >= d.P switches the lane off).  A 16-lane group serves one id per access, so with q chosen
+// such that home + q is a multiple of 16 slots every access reads exactly one 128-byte line.
+// All 16 accesses are issued before the first result is looked at; a lane without a slot to
+// look at re-reads the home slot (a valid address, same or neighbouring line; slot 0 if the
+// lane belongs to another table), so the loads carry no branch and stay in flight together.  d is wave-uniform.  Returns the round of
+// the match or -1.
+__device__ __forceinline__ int probe_pass(const TableDesc &d, int64_t id, int64_t home, int q)
 {
     constexpr int G = kLine, IPI = kWave / G;
     const int lane = lane_id();
     const int g = lane / G, r = lane % G;
-    const int base_off = (int)(((uintptr_t)d.I >> 3) & (G - 1));
-    int my_dist = -1;
-    // All 16 line loads are issued before the first result is looked at.  A lane that has no
-    // slot to look at re-reads the group's home slot (always a valid address, same line), so
-    // the loads carry no branch and stay in flight together.
     int64_t v[G];
     uint32_t act_bits = 0;
 #pragma unroll
     for (int t = 0; t < G; ++t) {
         const int src = t * IPI + g;
         const int64_t ghome = shfl64(home, src);
-        const bool gon = __shfl((int)on, src);
-        const int round = r - (int)((ghome + base_off) & (G - 1));
-        const int64_t s = ghome + round;
-        const bool act = gon && round >= 0 && round < d.P && s < d.N;
-        v[t] = d.I[act ? s : ghome];
+        const int round = __shfl(q, src) + r;
+        const bool act = round >= 0 && round < d.P;
+        // inactive lanes may carry the home slot of another (larger) table: keep the address inside d
+        v[t] = d.I[act ? wrap(ghome + round, d.N) : (ghome < d.N ? ghome : 0)];
         act_bits |= (uint32_t)act << t;
     }
+    int found = -1;
 #pragma unroll
     for (int t = 0; t < G; ++t) {
         const int src = t * IPI + g;
         const int64_t gid = shfl64(id, src);
-        const int go = (int)((shfl64(home, src) + base_off) & (G - 1));   // slots between line start and home
-        const bool act = (act_bits >> t) & 1u;
-        const int first = group_first<G>(__ballot(act && v[t] == gid), g);
-        const int got = __shfl(first >= 0 ? first - go : -1, (lane % IPI) * G);
-        if (lane / IPI == t) my_dist = got;
+        const int gq = __shfl(q, src);         // shuffles stay outside conditionals: every lane must take part
+        const int first = group_first<G>(__ballot(((act_bits >> t) & 1u) && v[t] == gid), g);
+        const int got = __shfl(first >= 0 ? gq + first : -1, (lane % IPI) * G);
+        if (lane / IPI == t) found = got;
     }
-    // rounds already looked at for this lane's own id
-    const int o = (int)((home + base_off) & (G - 1));
-    int covered = G - o;
-    if (covered > d.P) covered = d.P;
-    if ((int64_t)covered > d.N - home) covered = (int)(d.N - home);
-    uint64_t um = __ballot(on && my_dist < 0 && covered < d.P);
-    while (um) {
-        const int b = next_bits<G>(um, g);
-        const bool gact = b >= 0;
-        const int src = gact ? b : 0;
-        const int64_t gid = shfl64(id, src);
-        const int64_t ghome = shfl64(home, src);
-        int first = -1;
-        for (int q0 = __shfl(covered, src); __any(gact && first < 0 && q0 < d.P); q0 += G) {
-            const int round = q0 + r;
-            const bool act = gact && first < 0 && round < d.P;
-            const int64_t v2 = d.I[act ? wrap(ghome + round, d.N) : ghome];
-            const int f = group_first<G>(__ballot(act && v2 == gid), g);
-            if (first < 0 && f >= 0) first = q0 + f;
-        }
-#pragma unroll
-        for (int gg = 0; gg < IPI; ++gg) {
-            const int bsel = __shfl(b, gg * G);
-            const int fsel = __shfl(first, gg * G);
-            if (bsel == lane) my_dist = fsel;
-        }
-    }
-    return my_dist;
+    return found;
 }
 
+// Every wavefront owns one segment of positions.  Per 64-position chunk it probes the line that
+// holds each id's home slot.  Ids that were not found there but whose window goes on are parked
+// in LDS (position, home, next round) and resolved later, 64 at a time, so that the second
+// memory round trip is paid once per 64 parked ids instead of once per chunk.  What remains
+// unfound is the segment's miss list.
 template <bool TRAIN>
 __global__ __launch_bounds__(kBlock) void k_discover(Params p)
 {
-    __shared__ uint32_t s_stage[kWavesPerBlock][kStage];
+    __shared__ uint32_t s_pos[kWavesPerBlock][kStage];
+    __shared__ int64_t s_home[kWavesPerBlock][kStage];
+    __shared__ int32_t s_q[kWavesPerBlock][kStage];
     __shared__ unsigned long long s_red[kWavesPerBlock][kStatCount];
     __shared__ int s_tab[kWavesPerBlock];
 
@@ -366,21 +343,88 @@ __global__ __launch_bounds__(kBlock) void k_discover(Params p)
     // per-lane counters of the table currently being processed
     unsigned long long st_hit = 0, st_miss = 0, st_inv = 0, st_probe = 0;
     int st_table = 0;
-    int staged = 0, flushed = 0;                 // wave-uniform: missed positions in LDS / already entered
+    int staged = 0, flushed = 0;                 // wave-uniform: parked ids in LDS / misses already listed
 
-    // enters the staged positions into the scratch set and appends them to the segment's list
-    auto flush_stage = [&]() {
+    // counters are kept for one table at a time
+    auto stats_table = [&](int f) {
+        if (!want_stats || f == st_table) return;
+        // table changed inside this wavefront's range (rare): hand the counters over
+        const unsigned long long a = wave_sum(st_hit), b = wave_sum(st_miss), x = wave_sum(st_inv), y = wave_sum(st_probe);
+        if (lane == 0) {
+            if (a) atomicAdd(&p.ctl->stats[st_table][kHitPos], a);
+            if (b) atomicAdd(&p.ctl->stats[st_table][kMissPos], b);
+            if (x) atomicAdd(&p.ctl->stats[st_table][kInvalidPos], x);
+            if (y) atomicAdd(&p.ctl->stats[st_table][kHitProbeSum], y);
+        }
+        st_hit = st_miss = st_inv = st_probe = 0;
+        st_table = f;
+    };
+    // a position whose id is resident at `dist` probes from home
+    auto finish_hit = [&](const TableDesc &d, int64_t pos, int64_t home, int dist) {
+        const int64_t slot = wrap(home + dist, d.N);
+        if (TRAIN) {
+            d.M[slot] = p.step;                       // "Update": refresh the resident's metadata
+            st_hit++;
+            st_probe += (unsigned long long)(dist + 1);
+        } else if (p.out_found) {
+            p.out_found[pos] = 1;
+        }
+        p.out_slots[pos] = slot;
+    };
+
+    // probes the parked ids until found or their window ends; enters the rest into the scratch set
+    auto resolve_stage = [&]() {
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        for (int j = lane; j < staged; j += kWave) {
-            const uint32_t pos = s_stage[w][j];
-            uint64_t sb, ss;
-            set_region(p, (int64_t)pos, sb, ss);
-            const uint32_t e = set_insert(p, p.ids[pos], pos, sb, ss);
-            p.list[seg_base + flushed + j] = pos;
-            p.ent[seg_base + flushed + j] = e;
+        int nmiss = 0;
+        for (int e0 = 0; e0 < staged; e0 += kWave) {
+            const bool have = e0 + lane < staged;
+            const uint32_t pos = have ? s_pos[w][e0 + lane] : 0;
+            const int64_t home = have ? s_home[w][e0 + lane] : 0;
+            int q = have ? s_q[w][e0 + lane] : 0;
+            const int64_t id = have ? p.ids[pos] : -1;
+            const int f = (have && multi) ? find_table(p.offsets, p.num_tables, (int64_t)pos) : 0;
+            bool todo = have;
+            while (__any(todo)) {
+                const int f0 = __shfl(f, __ffsll((unsigned long long)__ballot(todo)) - 1);
+                const bool mine = todo && f == f0;
+                const TableDesc d = multi ? p.descs[f0] : p.t0;
+                stats_table(f0);
+                int dist = -1;
+                for (;;) {
+                    const bool need = mine && dist < 0 && q < d.P;
+                    if (!__any(need)) break;
+                    const int got = probe_pass(d, id, mine ? home : 0, need ? q : d.P);
+                    if (need) { if (got >= 0) dist = got; else q += kLine; }
+                }
+                if (mine && dist >= 0) finish_hit(d, (int64_t)pos, home, dist);
+                const bool miss = mine && dist < 0;
+                const uint64_t mb = __ballot(miss);
+                if (miss) {
+                    if (TRAIN) {
+                        s_pos[w][nmiss + __popcll(mb & ((1ull << lane) - 1ull))] = pos;   // slots already consumed
+                        st_miss++;
+                    } else {
+                        p.out_slots[pos] = home;
+                        if (p.out_found) p.out_found[pos] = 0;
+                    }
+                }
+                nmiss += __popcll(mb);
+                todo = todo && !mine;
+            }
+        }
+        if (TRAIN) {
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            for (int j = lane; j < nmiss; j += kWave) {
+                const uint32_t pos = s_pos[w][j];
+                uint64_t sb, ss;
+                set_region(p, (int64_t)pos, sb, ss);
+                const uint32_t e = set_insert(p, p.ids[pos], pos, sb, ss);
+                p.list[seg_base + flushed + j] = pos;
+                p.ent[seg_base + flushed + j] = e;
+            }
+            flushed += nmiss;
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        flushed += staged;
         staged = 0;
     };
 
@@ -413,57 +457,36 @@ __global__ __launch_bounds__(kBlock) void k_discover(Params p)
             } else {
                 d = p.t0;
             }
-            if (want_stats && f != st_table) {
-                // table changed inside this wavefront's range (rare): hand the counters over
-                const unsigned long long a = wave_sum(st_hit), b = wave_sum(st_miss), x = wave_sum(st_inv),
-                                         y = wave_sum(st_probe);
-                if (lane == 0) {
-                    if (a) atomicAdd(&p.ctl->stats[st_table][kHitPos], a);
-                    if (b) atomicAdd(&p.ctl->stats[st_table][kMissPos], b);
-                    if (x) atomicAdd(&p.ctl->stats[st_table][kInvalidPos], x);
-                    if (y) atomicAdd(&p.ctl->stats[st_table][kHitProbeSum], y);
-                }
-                st_hit = st_miss = st_inv = st_probe = 0;
-                st_table = f;
-            }
+            stats_table(f);
 
             const bool valid = mine && id >= 0;
             const int64_t home = mine ? home_slot(id, d.seed, d.N) : 0;
-            const int dist = probe_lines(d, id, home, valid);
-            const bool hit = valid && dist >= 0;
-            const int64_t slot = hit ? wrap(home + dist, d.N) : home;
-
-            if (TRAIN) {
-                if (hit) {
-                    d.M[slot] = p.step;                   // "Update": refresh the resident's metadata
-                    p.out_slots[pos] = slot;
-                    st_hit++;
-                    st_probe += (unsigned long long)(dist + 1);
-                } else if (mine && !valid) {
-                    p.out_slots[pos] = slot;               // negative id: home of its bit pattern
-                    st_inv++;
-                }
-                const bool miss = valid && !hit;
-                const uint64_t mb = __ballot(miss);
-                if (miss) {
-                    s_stage[w][staged + __popcll(mb & ((1ull << lane) - 1ull))] = (uint32_t)pos;
-                    st_miss++;
-                }
-                staged += __popcll(mb);
-            } else {
-                if (mine) {
-                    p.out_slots[pos] = slot;
-                    if (p.out_found) p.out_found[pos] = hit ? 1 : 0;
-                }
+            // first pass: the line that holds the home slot
+            const int o = (int)((home + (int64_t)(((uintptr_t)d.I >> 3) & (kLine - 1))) & (kLine - 1));
+            const int dist = probe_pass(d, id, home, valid ? -o : d.P);
+            if (valid && dist >= 0) {
+                finish_hit(d, pos, home, dist);
+            } else if (mine && !valid) {
+                p.out_slots[pos] = home;                   // negative id: home of its bit pattern
+                if (TRAIN) st_inv++;
+                else if (p.out_found) p.out_found[pos] = 0;
             }
+            // not found so far: parked (its window may go on, or it is a miss)
+            const bool park = valid && dist < 0;
+            const uint64_t pb = __ballot(park);
+            if (park) {
+                const int at = staged + __popcll(pb & ((1ull << lane) - 1ull));
+                s_pos[w][at] = (uint32_t)pos;
+                s_home[w][at] = home;
+                s_q[w][at] = kLine - o;
+            }
+            staged += __popcll(pb);
             todo = todo && !mine;
         }
-        if (TRAIN && staged > kStage - kWave) flush_stage();
+        if (staged > kStage - kWave) resolve_stage();
     }
-    if (TRAIN) {
-        flush_stage();
-        if (lane == 0 && seg < p.num_segs) p.seg_cnt[seg] = (uint32_t)flushed;
-    }
+    resolve_stage();
+    if (TRAIN && lane == 0 && seg < p.num_segs) p.seg_cnt[seg] = (uint32_t)flushed;
     if (want_stats) {
         const int idx[4] = {kHitPos, kMissPos, kInvalidPos, kHitProbeSum};
         const unsigned long long vals[4] = {st_hit, st_miss, st_inv, st_probe};
