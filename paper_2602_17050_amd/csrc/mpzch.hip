@@ -112,8 +112,7 @@ struct Scratch {
     uint32_t *first_of = nullptr;
     uint8_t *hint = nullptr;
     uint32_t *seg_cnt = nullptr;
-    long long *set_keys = nullptr;
-    uint32_t *set_minpos = nullptr;
+    uint32_t *set_slot = nullptr;
     StatRow *rows_a = nullptr;
     StatRow *rows_b = nullptr;
     Control *ctl[2] = {nullptr, nullptr};
@@ -132,7 +131,7 @@ struct Scratch {
         return MPZCH_OK;
     }
 
-    // 37 bytes per position and a few small fixed areas
+    // 21 bytes per position and a few small fixed areas
     mpzch_status_t ensure(int64_t n)
     {
         mpzch_status_t st = query_device();
@@ -152,9 +151,8 @@ struct Scratch {
         const size_t o_first = o_ent + align_up(per_pos);
         const size_t o_hint = o_first + align_up(per_pos);
         const size_t o_seg = o_hint + align_up((size_t)n + kWave);
-        const size_t o_keys = o_seg + align_up(4 * max_blocks * kWavesPerBlock);
-        const size_t o_min = o_keys + align_up(16 * (size_t)n);
-        const size_t o_rows = o_min + align_up(8 * (size_t)n);
+        const size_t o_set = o_seg + align_up(4 * max_blocks * kWavesPerBlock);
+        const size_t o_rows = o_set + align_up(8 * (size_t)n);
         const size_t o_ctl = o_rows + 2 * align_up(max_blocks * sizeof(StatRow));
         const size_t total = o_ctl + 2 * align_up(sizeof(Control));
         if (hipMalloc((void **)&base, total) != hipSuccess) { base = nullptr; return MPZCH_ERR_ALLOC; }
@@ -163,15 +161,14 @@ struct Scratch {
         first_of = (uint32_t *)(base + o_first);
         hint = (uint8_t *)(base + o_hint);
         seg_cnt = (uint32_t *)(base + o_seg);
-        set_keys = (long long *)(base + o_keys);
-        set_minpos = (uint32_t *)(base + o_min);
+        set_slot = (uint32_t *)(base + o_set);
         rows_a = (StatRow *)(base + o_rows);
         rows_b = (StatRow *)(base + o_rows + align_up(max_blocks * sizeof(StatRow)));
         ctl[0] = (Control *)(base + o_ctl);
         ctl[1] = (Control *)(base + o_ctl + align_up(sizeof(Control)));
-        // empty set (key -1, position 0xFFFFFFFF) and zero counters; set entries are re-emptied
-        // by every call, so this is the only full clear
-        if (hipMemset(base + o_keys, 0xFF, (o_rows - o_keys)) != hipSuccess) return MPZCH_ERR_HIP;
+        // empty set (0xFFFFFFFF) and zero counters; set entries are re-emptied by every call, so
+        // this is the only full clear
+        if (hipMemset(base + o_set, 0xFF, (o_rows - o_set)) != hipSuccess) return MPZCH_ERR_HIP;
         if (hipMemset(base + o_rows, 0, total - o_rows) != hipSuccess) return MPZCH_ERR_HIP;
         if (hipDeviceSynchronize() != hipSuccess) return MPZCH_ERR_HIP;
         cap_n = n;
@@ -270,8 +267,7 @@ mpzch_status_t run_remap(Scratch &sc, Timing &tm, Params p, int32_t max_p, hipSt
     p.first_of = sc.first_of;
     p.hint = sc.hint;
     p.seg_cnt = sc.seg_cnt;
-    p.set_keys = sc.set_keys;
-    p.set_minpos = sc.set_minpos;
+    p.set_slot = sc.set_slot;
     p.rows_a = sc.rows_a;
     p.rows_b = sc.rows_b;
     p.ctl = sc.ctl[sc.parity];

@@ -86,8 +86,7 @@ struct Params {
     uint32_t *seg_cnt;
     int32_t seg_chunks;
     int32_t num_segs;
-    long long *set_keys;           // scratch hash set: key = id, empty = -1
-    uint32_t *set_minpos;          // smallest position that inserted the key, empty = 0xFFFFFFFF
+    uint32_t *set_slot;            // scratch hash set of batch positions, empty = 0xFFFFFFFF
     StatRow *rows_a;               // per workgroup of k_discover
     StatRow *rows_b;               // per workgroup of k_finalize
     int32_t blocks_a, blocks_b;
@@ -174,27 +173,30 @@ __device__ __forceinline__ int64_t wrap(int64_t s, int64_t n) { return s >= n ? 
 
 // ------------------------------------------------------------------ scratch set
 constexpr uint64_t kSetSeed = 0x2545F4914F6CDD1Dull;
+constexpr uint32_t kSetEmpty = 0xFFFFFFFFu;
 
-// Inserts (id -> min position) into the region [base, base + size) of the scratch set and
-// returns the entry index.  size >= 2 * (number of inserts into the region), so the unbounded
-// probe always ends.
+// The scratch set elects, per distinct missed id, the smallest batch position holding it.  An
+// entry is one 32-bit word: a batch position (the id it stands for is ids[position]) or empty.
+// Inserting (id, pos) into the region [base, base + size): claim the first empty entry of the
+// probe sequence with one compare-and-swap, or, on meeting an entry of the same id, lower it to
+// min(entry, pos).  An entry never changes the id it stands for, so concurrent inserts agree.
+// size >= 2 * (number of inserts into the region), so the unbounded probe always ends.
+// Returns the entry index.
 __device__ __forceinline__ uint32_t set_insert(const Params &p, int64_t id, uint32_t pos, uint64_t base, uint64_t size)
 {
     uint64_t e = base + __umul64hi(mix64((uint64_t)id ^ kSetSeed), size);
     const uint64_t end = base + size;
     for (;;) {
-        long long k = __hip_atomic_load(&p.set_keys[e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (k == -1) {
-            long long expected = -1;
-            if (__hip_atomic_compare_exchange_strong(&p.set_keys[e], &expected, (long long)id, __ATOMIC_RELAXED,
-                                                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
-                break;
-            k = expected;
+        uint32_t expected = kSetEmpty;
+        if (__hip_atomic_compare_exchange_strong(&p.set_slot[e], &expected, pos, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                                 __HIP_MEMORY_SCOPE_AGENT))
+            break;                                            // first of its id so far
+        if (p.ids[expected] == id) {
+            if (pos < expected) __hip_atomic_fetch_min(&p.set_slot[e], pos, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            break;
         }
-        if (k == (long long)id) break;
         if (++e == end) e = base;
     }
-    __hip_atomic_fetch_min(&p.set_minpos[e], pos, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     return (uint32_t)e;
 }
 
@@ -582,7 +584,7 @@ __global__ __launch_bounds__(kWave) void k_allocate_lane(Params p)
             TableDesc d = p.t0;
             if (have) {
                 pos = p.list[idx];
-                const uint32_t first = p.set_minpos[p.ent[idx]];
+                const uint32_t first = p.set_slot[p.ent[idx]];
                 p.first_of[idx] = first;
                 agent = first == pos;                         // else: a later copy of the id
                 if (agent) {
@@ -668,7 +670,7 @@ __global__ __launch_bounds__(kBlock) void k_allocate_wave(Params p)
             bool agent = false;
             if (j0 + lane < cnt) {
                 lpos = p.list[seg_base + j0 + lane];
-                const uint32_t first = p.set_minpos[p.ent[seg_base + j0 + lane]];
+                const uint32_t first = p.set_slot[p.ent[seg_base + j0 + lane]];
                 p.first_of[seg_base + j0 + lane] = first;
                 agent = first == lpos;
             }
@@ -1003,8 +1005,7 @@ __global__ __launch_bounds__(kBlock) void k_emit_dups(Params p)
             const uint32_t e = p.ent[seg_base + j];
             if (first != pos) p.out_slots[pos] = p.out_slots[first];
             // empty the scratch set entry again (every copy of the id does; the stores agree)
-            p.set_keys[e] = -1;
-            p.set_minpos[e] = 0xFFFFFFFFu;
+            p.set_slot[e] = kSetEmpty;
         }
     }
 
