@@ -1,0 +1,176 @@
+"""Parity at the full sizes of the benchmark configurations, in the launch configuration
+bench.py times.  Tables are prefilled through the HIP path; the table state is then copied to
+the host, checked with the oracle's state checker on sampled slot ranges (every resident id
+must be found by a read-only lookup at exactly its own slot), and the following steps are
+replayed by the oracle from that state and compared bit for bit."""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2602_17050_amd import binding as mp
+from paper_2602_17050_amd import workloads as wl
+from gpu_common import say
+
+pytestmark = pytest.mark.gpu
+
+
+def _prefill_stream(g, spec, chunk=1 << 24):
+    out = torch.empty(chunk, dtype=torch.int64, device="cuda")
+    for lo in range(0, spec.prefill_ids, chunk):
+        hi = min(lo + chunk, spec.prefill_ids)
+        ids = torch.arange(lo, hi, dtype=torch.int64, device="cuda") + wl.PREFILL_ID_BASE
+        g.remap(ids, 0, out[: hi - lo])
+    torch.cuda.synchronize()
+
+
+def _sampled_state_check(o, rng, ranges=4, width=1_000_000):
+    for _ in range(ranges):
+        lo = int(rng.integers(0, max(o.num_slots - width, 1)))
+        bad, occ, first_bad = o.check_state(lo, min(lo + width, o.num_slots))
+        assert bad == 0, (lo, first_bad)
+    # the wrap-around region
+    bad, _, first_bad = o.check_state(max(o.num_slots - 100_000, 0), o.num_slots)
+    assert bad == 0, first_bad
+    bad, _, first_bad = o.check_state(0, min(100_000, o.num_slots))
+    assert bad == 0, first_bad
+
+
+def _stream_parity(spec, steps, emb_check_rows=0):
+    t = spec.table
+    g = mp.MpzchTable(t.num_slots, t.max_probe, mp.EVICT_TTL, t.ttl, t.hash_seed, max_batch=1 << 24)
+    t0 = time.time()
+    _prefill_stream(g, spec)
+    say(f"prefilled {spec.prefill_ids} ids in {time.time() - t0:.1f}s")
+    I = g.identities.cpu().numpy()
+    M = g.metadata.cpu().numpy()
+    occ = int(np.count_nonzero(I >= 0))
+    say(f"occupied {occ} of {t.num_slots} ({occ / t.num_slots:.3f})")
+    # bounded probing: at load 0.9 with P = 16 some 5 % of the ids end without a slot (cf. Table 1)
+    assert occ > 0.94 * spec.prefill_ids
+    assert (I >= -1).all()                                     # no claim tag left behind
+    o = oracle.Table(t.num_slots, t.max_probe, oracle.EVICT_TTL, t.ttl, t.hash_seed, I, M)
+    _sampled_state_check(o, np.random.default_rng(1))
+    emb = None
+    if emb_check_rows:
+        emb = torch.ones((t.emb_rows, t.emb_dim), dtype=torch.bfloat16, device="cuda")
+    reset_rows = []
+    for k in range(steps):
+        step = spec.first_step + k
+        ids = wl.stream_batch(spec, step)
+        out = g.remap(torch.from_numpy(ids).cuda(), step)
+        if emb is not None:
+            g.reset_rows(emb)
+        torch.cuda.synchronize()
+        r = o.remap(ids, step)
+        assert np.array_equal(out.cpu().numpy(), r.slots), f"out_slots differ at step {step}"
+        ev = g.evicted.cpu().numpy()
+        assert np.array_equal(np.sort(ev), np.sort(r.evicted)), f"evicted set differs at step {step}"
+        assert g.stats_dict() == r.stats, (g.stats_dict(), r.stats)
+        # state at every slot this step touched, and at a random sample of untouched ones
+        touched = torch.from_numpy(np.unique(r.slots)).cuda()
+        assert np.array_equal(g.identities[touched].cpu().numpy(), o.identities[touched.cpu().numpy()])
+        assert np.array_equal(g.metadata[touched].cpu().numpy(), o.metadata[touched.cpu().numpy()])
+        reset_rows.append(r.evicted % t.emb_rows)
+        say(f"step {step}: {r.stats}")
+        assert r.stats["evictions"] > 0 and r.stats["hit_pos"] > 0
+    # whole state, in blocks (keeps the host copy small)
+    blk = 1 << 27
+    for lo in range(0, t.num_slots, blk):
+        hi = min(lo + blk, t.num_slots)
+        assert np.array_equal(g.identities[lo:hi].cpu().numpy(), o.identities[lo:hi]), f"identities differ in [{lo},{hi})"
+        assert np.array_equal(g.metadata[lo:hi].cpu().numpy(), o.metadata[lo:hi]), f"metadata differ in [{lo},{hi})"
+    if emb is not None:
+        rows = torch.from_numpy(np.unique(np.concatenate(reset_rows))).cuda()
+        assert int((emb[rows] != 0).sum().item()) == 0               # reset rows hold the init value exactly
+        zero_rows = int((emb.view(torch.int16)[:, 0] == 0).sum().item())
+        assert zero_rows == rows.numel()                              # and no other row was touched
+    g.close()
+
+
+def test_headline_one_billion_slots_two_steps():
+    """1 B slots, P = 16, TTL 20, load 0.7, 4 M ids per step (the workload bench.py times)."""
+    _stream_parity(wl.headline_spec(), steps=2)
+
+
+def test_config4_500m_slots_with_row_reset():
+    """500 M slots at load 0.9, 2 M ids per step, rows of a 100 M x 128 bf16 embedding
+    addressed as slot mod rows."""
+    _stream_parity(wl.c4_spec(), steps=3, emb_check_rows=1)
+
+
+def test_config3_100m_slots_lookup():
+    """100 M slots, 80 M resident ids, P = 32: 1 M lookups per batch, 95 % resident."""
+    spec = wl.c3_spec()
+    n_res = 80_000_000
+    g = mp.MpzchTable(spec.num_slots, spec.max_probe, mp.EVICT_NONE, 0, spec.hash_seed, max_batch=1 << 23)
+    chunk = 1 << 23
+    out = torch.empty(chunk, dtype=torch.int64, device="cuda")
+    collisions = 0
+    for lo in range(0, n_res, chunk):
+        hi = min(lo + chunk, n_res)
+        g.remap(torch.from_numpy(wl.c3_prefill_ids(lo, hi)).cuda(), 0, out[: hi - lo])
+        collisions += g.stats_dict()["collisions"]
+    torch.cuda.synchronize()
+    I = g.identities.cpu().numpy()
+    occ = int(np.count_nonzero(I >= 0))
+    say(f"c3 prefill: occupied {occ}, collisions {collisions}")
+    assert occ + collisions == n_res
+    o = oracle.Table(spec.num_slots, spec.max_probe, oracle.EVICT_NONE, 0, spec.hash_seed, I,
+                     np.zeros(spec.num_slots, np.int32))
+    _sampled_state_check(o, np.random.default_rng(3))
+    before = int(g.identities.sum().item())
+    for s in range(3):
+        ids = wl.c3_batch(s, 1_000_000, n_res)
+        sg, fg = g.lookup(torch.from_numpy(ids).cuda())
+        so, fo = o.lookup(ids)
+        assert np.array_equal(sg.cpu().numpy(), so) and np.array_equal(fg.cpu().numpy(), fo)
+        assert 0.93 < fo.mean() <= 0.951
+    assert int(g.identities.sum().item()) == before                  # read-only
+    g.close()
+
+
+def test_config5_26_tables_full_jagged_batch():
+    """26 tables, slot counts log-uniform 1 K .. 1 B scaled to <= 1 B in total, 65 536 samples,
+    pooling 1..50: one mpzch_remap_jagged call per step, two steps."""
+    spec = wl.c5_spec()
+    total = sum(t.num_slots for t in spec.tables)
+    say("c5 tables:", [t.num_slots for t in spec.tables], "total", total)
+    assert total <= 1_000_000_000 + 26_000
+    handles = [mp.mpzch_create(t.num_slots, t.max_probe, (mp.EVICT_TTL, t.ttl), t.hash_seed) for t in spec.tables]
+    group = mp.mpzch_group_create(handles)
+    I = [torch.empty(t.num_slots, dtype=torch.int64, device="cuda") for t in spec.tables]
+    M = [torch.empty(t.num_slots, dtype=torch.int32, device="cuda") for t in spec.tables]
+    for h, i, m in zip(handles, I, M):
+        mp.mpzch_init_tensors(h, i, m)
+    os_ = [oracle.Table(t.num_slots, t.max_probe, oracle.EVICT_TTL, t.ttl, t.hash_seed) for t in spec.tables]
+    T = len(spec.tables)
+    for step in (1, 2):
+        values, lengths, offsets = wl.c5_batch(spec, step)
+        say(f"c5 step {step}: {len(values)} values")
+        v = torch.from_numpy(values).cuda()
+        off = torch.from_numpy(offsets).cuda()
+        out = torch.empty(len(values), dtype=torch.int64, device="cuda")
+        ev = torch.empty(len(values), dtype=torch.int64, device="cuda")
+        nev = torch.zeros(T, dtype=torch.int64, device="cuda")
+        stats = torch.zeros(T * mp.STAT_COUNT, dtype=torch.int64, device="cuda")
+        mp.mpzch_remap_jagged(group, I, M, v, off, step, out, ev, [int(x) for x in offsets], nev, stats)
+        torch.cuda.synchronize()
+        t0 = time.time()
+        so, evs, sts = oracle.remap_jagged(os_, values, offsets, step)
+        say(f"oracle {time.time() - t0:.1f}s")
+        assert np.array_equal(out.cpu().numpy(), so)
+        nev_h, ev_h = nev.cpu().numpy(), ev.cpu().numpy()
+        st_h = stats.cpu().numpy().reshape(T, mp.STAT_COUNT)
+        for f in range(T):
+            assert nev_h[f] == len(evs[f])
+            assert np.array_equal(np.sort(ev_h[offsets[f]: offsets[f] + nev_h[f]]), np.sort(evs[f]))
+            assert dict(zip(mp.STAT_NAMES, st_h[f].tolist())) == sts[f], f
+    for f in range(T):
+        assert np.array_equal(I[f].cpu().numpy(), os_[f].identities), f
+        assert np.array_equal(M[f].cpu().numpy(), os_[f].metadata), f
+    mp.mpzch_group_destroy(group)
+    for h in handles:
+        mp.mpzch_destroy(h)
