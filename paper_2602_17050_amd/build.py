@@ -10,6 +10,8 @@ SRC = os.path.join(HERE, "csrc", "mpzch.hip")
 DEPS = [SRC, os.path.join(HERE, "csrc", "mpzch_kernels.hpp"),
         os.path.join(os.path.dirname(HERE), "include", "mpzch.h")]
 LIB = os.path.join(HERE, "libmpzch.so")
+CEIL_SRC = os.path.join(HERE, "csrc", "memory_ceilings.hip")
+CEIL_BIN = os.path.join(HERE, "memory_ceilings.bin")
 
 
 def hipcc() -> str:
@@ -32,5 +34,18 @@ def build_library(verbose: bool = False) -> str:
     return LIB
 
 
+def build_memory_ceilings(verbose: bool = False) -> str:
+    """Stand-alone tool that measures the random-access ceilings of the GPU it runs on."""
+    cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-result",
+           CEIL_SRC, "-o", CEIL_BIN + ".tmp"]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    os.replace(CEIL_BIN + ".tmp", CEIL_BIN)
+    return CEIL_BIN
+
+
 if __name__ == "__main__":
     print(build_library(verbose="-v" in sys.argv))
+    print(build_memory_ceilings(verbose="-v" in sys.argv))

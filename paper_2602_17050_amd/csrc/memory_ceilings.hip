@@ -1,0 +1,137 @@
+// Measures, on the GPU it runs on, the memory-system ceilings that bound the MPZCH remap path:
+// the path is a hash-table probe, i.e. independent random accesses of 4..128 bytes, so what limits
+// it is the rate of random requests the memory system sustains, not streaming bandwidth.
+// Stand-alone tool (no dependency on the library): prints one line per access pattern.
+//
+//   memory_ceilings [slots]      slots: size of the int64 array that is probed (default 1e9 = 8 GB)
+#include <hip/hip_runtime.h>
+#include <cstdint>
+#include <cstdio>
+#include <cstdlib>
+
+#define CK(x)                                                                              \
+    do {                                                                                   \
+        hipError_t e_ = (x);                                                               \
+        if (e_ != hipSuccess) {                                                            \
+            std::printf("HIP error %s at line %d\n", hipGetErrorString(e_), __LINE__);   \
+            return 1;                                                                      \
+        }                                                                                  \
+    } while (0)
+
+__device__ __forceinline__ uint64_t mix64(uint64_t x)
+{
+    uint64_t z = x + 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+__global__ void k_copy(const uint4 *a, uint4 *b, uint64_t n)
+{
+    for (uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; i < n; i += (uint64_t)gridDim.x * blockDim.x) b[i] = a[i];
+}
+
+// one 8-byte load per thread at a uniformly random slot
+__global__ void k_gather8(const long long *t, uint64_t n, uint64_t ops, long long *sink)
+{
+    long long a = 0;
+    for (uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; i < ops; i += (uint64_t)gridDim.x * blockDim.x)
+        a += t[__umul64hi(mix64(i), n)];
+    if (a == 0x1234567) sink[0] = a;
+}
+
+// 16 lanes read one random 128-byte line (aligned) or 16 consecutive slots from a random slot (unaligned)
+template <bool ALIGNED>
+__global__ void k_line(const long long *t, uint64_t n, uint64_t ops, long long *sink)
+{
+    long long a = 0;
+    const uint64_t tid = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x;
+    const uint64_t groups = ((uint64_t)gridDim.x * blockDim.x) >> 4;
+    const int r = tid & 15;
+    for (uint64_t i = tid >> 4; i < ops; i += groups * 4) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint64_t j = i + u * groups;
+            if (j < ops) {
+                uint64_t s = __umul64hi(mix64(j), n - 32);
+                if (ALIGNED) s &= ~15ull;
+                a += t[s + r];
+            }
+        }
+    }
+    if (a == 0x1234567) sink[0] = a;
+}
+
+__global__ void k_store4(int *t, uint64_t n, uint64_t ops)
+{
+    for (uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; i < ops; i += (uint64_t)gridDim.x * blockDim.x)
+        t[__umul64hi(mix64(i), n)] = 7;
+}
+
+__global__ void k_atomic_min(long long *t, uint64_t n, uint64_t ops, long long *sink)
+{
+    long long a = 0;
+    for (uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; i < ops; i += (uint64_t)gridDim.x * blockDim.x)
+        a += __hip_atomic_fetch_min(&t[__umul64hi(mix64(i), n)], (long long)(i | 0x4000000000000000ull), __ATOMIC_RELAXED,
+                                    __HIP_MEMORY_SCOPE_AGENT);
+    if (a == 0x1234567) sink[0] = a;
+}
+
+// one atomic per wavefront, all on ONE address (what a shared list cursor costs)
+__global__ void k_same_address(unsigned long long *c, unsigned long long *sink)
+{
+    unsigned long long b = 0;
+    if ((threadIdx.x & 63) == 0) b = atomicAdd(c, 64ull);
+    if (b == 0x1234567) sink[0] = b;
+}
+
+int main(int argc, char **argv)
+{
+    const uint64_t n = argc > 1 ? std::strtoull(argv[1], nullptr, 10) : 1000000000ull;
+    hipEvent_t e0, e1;
+    CK(hipEventCreate(&e0));
+    CK(hipEventCreate(&e1));
+    long long *t;
+    int *m;
+    unsigned long long *c;
+    CK(hipMalloc(&t, n * 8));
+    CK(hipMalloc(&m, n * 4));
+    CK(hipMalloc(&c, 4096));
+    CK(hipMemset(t, 0x7f, n * 8));
+    CK(hipMemset(m, 0, n * 4));
+    CK(hipMemset(c, 0, 4096));
+    hipDeviceProp_t prop;
+    CK(hipGetDeviceProperties(&prop, 0));
+    std::printf("device: %s, %d compute units; probed array: %llu int64 slots (%.1f GB)\n", prop.name,
+                prop.multiProcessorCount, (unsigned long long)n, n * 8 / 1e9);
+    float ms = 0.f;
+    auto report = [&](const char *name, double ops, double bytes_per_op) {
+        std::printf("%-58s %8.3f ms %9.2f G ops/s %9.1f GB/s\n", name, ms, ops / ms / 1e6, ops * bytes_per_op / ms / 1e6);
+        std::fflush(stdout);
+    };
+#define TIME(launch)                          \
+    launch;                                   \
+    CK(hipDeviceSynchronize());               \
+    CK(hipEventRecord(e0));                   \
+    launch;                                   \
+    CK(hipEventRecord(e1));                   \
+    CK(hipEventSynchronize(e1));              \
+    CK(hipEventElapsedTime(&ms, e0, e1));
+    const uint64_t ops = 64000000ull;
+    const uint64_t cn = (1ull << 31) / 16;   // 2 GiB copied
+    TIME((k_copy<<<8192, 256>>>((const uint4 *)t, (uint4 *)(t + (n / 2)), cn)));
+    report("streaming copy, 2 GiB read + 2 GiB written", (double)cn, 32.0);
+    TIME((k_gather8<<<8192, 256>>>(t, n, ops, (long long *)c + 8)));
+    report("random 8-byte loads (one per lane)", (double)ops, 8.0);
+    TIME((k_line<true><<<8192, 256>>>(t, n, ops, (long long *)c + 8)));
+    report("random aligned 128-byte lines (16 lanes each)", (double)ops, 128.0);
+    TIME((k_line<false><<<8192, 256>>>(t, n, ops, (long long *)c + 8)));
+    report("random unaligned 128-byte windows (16 lanes each)", (double)ops, 128.0);
+    TIME((k_store4<<<8192, 256>>>(m, n, ops)));
+    report("random 4-byte stores (one per lane)", (double)ops, 4.0);
+    TIME((k_atomic_min<<<8192, 256>>>(t, n, ops / 4, (long long *)c + 8)));
+    report("random 64-bit atomic min with return (one per lane)", (double)ops / 4, 8.0);
+    TIME((k_same_address<<<16384, 256>>>(c, c + 8)));
+    report("atomic add on ONE address, one per wavefront (65536)", 65536.0, 8.0);
+    return 0;
+}
