@@ -23,6 +23,14 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# Random-access ceilings of MI355X measured with paper_2602_17050_amd/memory_ceilings.bin
+# (profiles/memory_ceilings_mi355x.txt): aligned 128-byte line reads and 4-byte stores per second.
+CEIL_LINES_PER_S = 38.1e9
+CEIL_STORES_PER_S = 22.9e9
+# HBM bytes per k_discover launch on the full-size headline workload, from rocprofv3 --pmc
+# FETCH_SIZE and WRITE_SIZE (KiB per dispatch x 1024, calibration factor 1.000); see
+# profiles/remap_headline_1Bslots_4Mids.txt.  Only valid for that workload at scale 1.
+HEADLINE_DISCOVER_TRAFFIC_BYTES = None
 
 
 def log(*a):
@@ -90,9 +98,14 @@ def main():
     evicted = torch.empty(spec.batch, dtype=torch.int64, device=dev)
     log(f"[bench] generated {W + K} batches in {time.perf_counter() - t0:.2f}s")
 
+    ev_a = [torch.cuda.Event(enable_timing=True) for _ in range(W + K)]
+    ev_b = [torch.cuda.Event(enable_timing=True) for _ in range(W + K)]
+
     def one_step(i):
         mp.mpzch_remap(g.handle, g.identities, g.metadata, batches[i], steps[i], outs[i], evicted, nev[i], stats[i])
+        ev_a[i].record()          # the binding launches on torch's current stream, so these events see it
         mp.mpzch_reset_rows(evicted, nev[i], emb)
+        ev_b[i].record()
 
     for i in range(W):
         one_step(i)
@@ -116,6 +129,8 @@ def main():
     elapsed = time.perf_counter() - t0
     ktimes = {} if args.no_kernel_timing else mp.mpzch_kernel_times(g.handle)
     mp.mpzch_set_kernel_timing(g.handle, False)
+    if ktimes:
+        ktimes["k_reset_rows"] = (sum(ev_a[i].elapsed_time(ev_b[i]) for i in range(W, W + K)), K)
 
     total_ids = spec.batch * K
     value = total_ids / elapsed
@@ -147,9 +162,16 @@ def main():
         }.get(dom)
         if alg is not None:
             ach = alg / (avg_ms * 1e-3) / 1e9
+            # what the random-access ceilings allow for this launch: one line read per position
+            # (plus the further lines of parked ids) and one metadata store per hit position
+            lines = total_ids / K + (miss_pos + max(probe_sum - hit_pos, 0) / 8.0) / K
+            floor_ms = (lines / CEIL_LINES_PER_S + (hit_pos / K) / CEIL_STORES_PER_S) * 1e3
+            traffic = HEADLINE_DISCOVER_TRAFFIC_BYTES if (args.workload == "headline" and args.scale == 1.0) else None
             roofline = {"bound": "hbm", "kernel": dom, "achieved": round(ach, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                        "frac": round(ach / HBM_PEAK_GBS, 5), "traffic": None,
-                        "avg_kernel_ms": round(avg_ms, 4), "alg_bytes_per_launch": round(alg)}
+                        "frac": round(ach / HBM_PEAK_GBS, 5), "traffic": traffic,
+                        "avg_kernel_ms": round(avg_ms, 4), "alg_bytes_per_launch": round(alg),
+                        "random_access_floor_ms": round(floor_ms, 4),
+                        "frac_of_random_access_ceiling": round(floor_ms / avg_ms, 3)}
         else:
             roofline = {"bound": "hbm", "kernel": dom, "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                         "frac": None, "traffic": None, "avg_kernel_ms": round(avg_ms, 4)}

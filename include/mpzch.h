@@ -97,7 +97,7 @@ mpzch_status_t mpzch_create(int64_t num_slots, int32_t max_probe, mpzch_eviction
 mpzch_status_t mpzch_destroy(mpzch_table_t *t);
 
 /*
- * Optional: allocate scratch for batches of up to max_n positions now (about 21 bytes per
+ * Optional: allocate scratch for batches of up to max_n positions now (about 29 bytes per
  * position) so that later remap calls allocate nothing.  Synchronises the device when it
  * has to grow the scratch.  Errors: INVALID_ARG (max_n < 0 or > MPZCH_MAX_BATCH), ALLOC.
  */

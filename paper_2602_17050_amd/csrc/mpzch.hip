@@ -110,6 +110,7 @@ struct Scratch {
     uint32_t *list = nullptr;
     uint32_t *ent = nullptr;
     uint32_t *first_of = nullptr;
+    int64_t *homes = nullptr;
     uint8_t *hint = nullptr;
     uint32_t *seg_cnt = nullptr;
     uint32_t *set_slot = nullptr;
@@ -131,7 +132,7 @@ struct Scratch {
         return MPZCH_OK;
     }
 
-    // 21 bytes per position and a few small fixed areas
+    // 29 bytes per position and a few small fixed areas
     mpzch_status_t ensure(int64_t n)
     {
         mpzch_status_t st = query_device();
@@ -145,11 +146,12 @@ struct Scratch {
             cap_n = 0;
         }
         const size_t max_blocks = (size_t)num_cus * kDiscoverBlocksPerCuMax;
-        const size_t per_pos = 4 * ((size_t)n + kWave);
+        const size_t per_pos = 4 * ((size_t)n + 2 * kWave);   // list-shaped arrays: n + 128 entries
         const size_t o_list = 0;
         const size_t o_ent = o_list + align_up(per_pos);
         const size_t o_first = o_ent + align_up(per_pos);
-        const size_t o_hint = o_first + align_up(per_pos);
+        const size_t o_homes = o_first + align_up(per_pos);
+        const size_t o_hint = o_homes + align_up(2 * per_pos);
         const size_t o_seg = o_hint + align_up((size_t)n + kWave);
         const size_t o_set = o_seg + align_up(4 * max_blocks * kWavesPerBlock);
         const size_t o_rows = o_set + align_up(8 * (size_t)n);
@@ -159,6 +161,7 @@ struct Scratch {
         list = (uint32_t *)(base + o_list);
         ent = (uint32_t *)(base + o_ent);
         first_of = (uint32_t *)(base + o_first);
+        homes = (int64_t *)(base + o_homes);
         hint = (uint8_t *)(base + o_hint);
         seg_cnt = (uint32_t *)(base + o_seg);
         set_slot = (uint32_t *)(base + o_set);
@@ -266,6 +269,7 @@ mpzch_status_t run_remap(Scratch &sc, Timing &tm, Params p, int32_t max_p, hipSt
     p.ent = sc.ent;
     p.first_of = sc.first_of;
     p.hint = sc.hint;
+    p.homes = sc.homes;
     p.seg_cnt = sc.seg_cnt;
     p.set_slot = sc.set_slot;
     p.rows_a = sc.rows_a;

@@ -17,8 +17,9 @@
 //                round-major / position-minor sweep produces.
 //   k_finalize   every elected id finds its tag in its window, replaces it by the id, sets
 //                metadata = step and reports evicted slots; ids without a tag fall back to home.
-//   k_emit_dups  the other copies of a missed id copy the slot of the elected position; the
-//                scratch set entries that were used are emptied again; counters are published.
+//                The scratch set entries that were used are emptied again.
+//   k_emit_dups  the other copies of a missed id copy the slot of the elected position; counters
+//                are published.
 // k_allocate / k_finalize exist in two forms: one lane per claimant with the whole window in
 // registers (max_probe <= 32) and one wavefront per claimant scanning 64 slots per access.
 //
@@ -81,6 +82,7 @@ struct Params {
     // for k < seg_cnt[s]; ent and first_of run parallel to list.
     uint32_t *list;
     uint32_t *ent;                 // entry of the position's id in the scratch set
+    int64_t *homes;                // home slot of the position's id
     uint32_t *first_of;            // position of the first occurrence of the position's id
     uint8_t *hint;                 // round at which k_allocate placed the position's claim (lane form)
     uint32_t *seg_cnt;
@@ -403,7 +405,9 @@ __global__ __launch_bounds__(kBlock) void k_discover(Params p)
                 const uint64_t mb = __ballot(miss);
                 if (miss) {
                     if (TRAIN) {
-                        s_pos[w][nmiss + __popcll(mb & ((1ull << lane) - 1ull))] = pos;   // slots already consumed
+                        const int at = nmiss + __popcll(mb & ((1ull << lane) - 1ull));      // slots already consumed
+                        s_pos[w][at] = pos;
+                        s_home[w][at] = home;
                         st_miss++;
                     } else {
                         p.out_slots[pos] = home;
@@ -423,6 +427,7 @@ __global__ __launch_bounds__(kBlock) void k_discover(Params p)
                 const uint32_t e = set_insert(p, p.ids[pos], pos, sb, ss);
                 p.list[seg_base + flushed + j] = pos;
                 p.ent[seg_base + flushed + j] = e;
+                p.homes[seg_base + flushed + j] = s_home[w][j];
             }
             flushed += nmiss;
         }
@@ -574,24 +579,27 @@ __global__ __launch_bounds__(kWave) void k_allocate_lane(Params p)
     for (int64_t seg = blockIdx.x; seg < p.num_segs; seg += gridDim.x) {
         const uint32_t cnt = p.seg_cnt[seg];
         const int64_t seg_base = seg * p.seg_chunks * kWave;
-        for (uint32_t j0 = 0; j0 < cnt; j0 += kWave) {
+        if (seg_base >= p.n) break;                           // segments past the batch hold nothing
+        for (uint32_t j0 = 0;; j0 += kWave) {
+            // the list entries are requested before the count is known: the count is at most the
+            // number of positions of the segment and the arrays have room for n + 128 entries, so
+            // the addresses are valid whatever the count turns out to be
             const int64_t idx = seg_base + j0 + lane;
+            const uint32_t pos = p.list[idx];
+            const uint32_t e = p.ent[idx];
+            int64_t home = p.homes[idx];
+            if (j0 >= cnt) break;
             const bool have = j0 + lane < cnt;
             bool agent = false;
-            uint32_t pos = 0;
             int f = 0;
-            int64_t home = 0;
             TableDesc d = p.t0;
             if (have) {
-                pos = p.list[idx];
-                const uint32_t first = p.set_slot[p.ent[idx]];
+                const uint32_t first = p.set_slot[e];
                 p.first_of[idx] = first;
                 agent = first == pos;                         // else: a later copy of the id
-                if (agent) {
-                    if (multi) { f = find_table(p.offsets, p.num_tables, (int64_t)pos); d = p.descs[f]; }
-                    home = home_slot(p.ids[pos], d.seed, d.N);
-                }
+                if (agent && multi) { f = find_table(p.offsets, p.num_tables, (int64_t)pos); d = p.descs[f]; }
             }
+            if (!agent) home = 0;
             // cooperative loads; lanes without a slot to read use slot 0 / the home slot (valid addresses)
             int64_t vi[NT * CH];
             int32_t vm[NT * CH];
@@ -873,6 +881,7 @@ __global__ __launch_bounds__(kBlock) void k_finalize_lane(Params p)
             if (j0 + lane < cnt) {
                 pos = p.list[seg_base + j0 + lane];
                 agent = p.first_of[seg_base + j0 + lane] == pos;
+                p.set_slot[p.ent[seg_base + j0 + lane]] = kSetEmpty;   // the scratch set is left empty again
             }
             int outcome = 2, f = 0;
             int64_t s_final = 0;
@@ -880,7 +889,7 @@ __global__ __launch_bounds__(kBlock) void k_finalize_lane(Params p)
                 TableDesc d = p.t0;
                 if (multi) { f = find_table(p.offsets, p.num_tables, (int64_t)pos); d = p.descs[f]; }
                 const int64_t id = p.ids[pos];
-                const int64_t home = home_slot(id, d.seed, d.N);
+                const int64_t home = p.homes[seg_base + j0 + lane];
                 // the slot that carries this claimant's tag: where k_allocate left it, unless the
                 // claimant was displaced afterwards -- then its window is searched
                 const uint32_t h = p.hint[seg_base + j0 + lane];
@@ -940,6 +949,7 @@ __global__ __launch_bounds__(kBlock) void k_finalize_wave(Params p)
             if (j0 + lane < cnt) {
                 lpos = p.list[seg_base + j0 + lane];
                 agent = p.first_of[seg_base + j0 + lane] == lpos;
+                p.set_slot[p.ent[seg_base + j0 + lane]] = kSetEmpty;   // the scratch set is left empty again
             }
             uint64_t amask = __ballot(agent);
             while (amask) {
@@ -1002,10 +1012,7 @@ __global__ __launch_bounds__(kBlock) void k_emit_dups(Params p)
         for (uint32_t j = lane; j < cnt; j += kWave) {
             const uint32_t pos = p.list[seg_base + j];
             const uint32_t first = p.first_of[seg_base + j];
-            const uint32_t e = p.ent[seg_base + j];
             if (first != pos) p.out_slots[pos] = p.out_slots[first];
-            // empty the scratch set entry again (every copy of the id does; the stores agree)
-            p.set_slot[e] = kSetEmpty;
         }
     }
 
