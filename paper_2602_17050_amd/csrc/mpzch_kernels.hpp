@@ -508,45 +508,29 @@ __device__ __forceinline__ bool expired(const TableDesc &d, int32_t step, int64_
     return d.evict && (int64_t)step - (int64_t)d.M[s] > (int64_t)d.ttl;
 }
 
-// Deferred acceptance for the claimant at batch position cpos, starting at round cr, by one lane.
-// The whole window is loaded first (PMAX independent loads), then walked in probe order.
-template <int PMAX>
+// Deferred acceptance for the claimant at batch position cpos, starting at round cr, by one lane,
+// slot by slot.  This is the rare continuation for a claimant that was displaced by a better
+// claim; the first attempt of every claimant goes through the cooperative window loads below.
 __device__ __forceinline__ void claim_lane(const Params &p, const TableDesc &d, uint32_t cpos, int64_t home, int32_t cr)
 {
     for (;;) {
-        int64_t v[PMAX];
-#pragma unroll
-        for (int k = 0; k < PMAX; ++k) {
-            v[k] = 0;                                         // not claimable
-            if (k >= cr && k < d.P)
-                v[k] = __hip_atomic_load(&d.I[wrap(home + k, d.N)], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        // expiry of the slots that hold an id (second batch of independent loads)
-        uint32_t exp_bits = 0;
-        if (d.evict) {
-#pragma unroll
-            for (int k = 0; k < PMAX; ++k)
-                if (k >= cr && k < d.P && v[k] >= 0 && expired(d, p.step, wrap(home + k, d.N))) exp_bits |= 1u << k;
-        }
         int64_t displaced = 0;
-        bool placed = false;
-#pragma unroll
-        for (int k = 0; k < PMAX; ++k) {
-            if (placed || k < cr || k >= d.P) continue;
+        for (int32_t k = cr; k < d.P; ++k) {
+            const int64_t s = wrap(home + k, d.N);
+            const int64_t v = __hip_atomic_load(&d.I[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             uint32_t occ = 0;
             bool cand;
-            if (v[k] == -1) cand = true;
-            else if (v[k] >= 0) { cand = (exp_bits >> k) & 1u; occ = 1; }
-            else { occ = tag_occ(v[k]); cand = v[k] > make_tag((uint32_t)k, cpos, occ); }
+            if (v == -1) cand = true;
+            else if (v >= 0) { cand = expired(d, p.step, s); occ = 1; }
+            else { occ = tag_occ(v); cand = v > make_tag((uint32_t)k, cpos, occ); }
             if (!cand) continue;
             const int64_t mine = make_tag((uint32_t)k, cpos, occ);
-            const int64_t old = __hip_atomic_fetch_min(&d.I[wrap(home + k, d.N)], mine, __ATOMIC_RELAXED,
-                                                       __HIP_MEMORY_SCOPE_AGENT);
+            const int64_t old = __hip_atomic_fetch_min(&d.I[s], mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (is_tag(old) && old < mine) continue;          // a better claim got there first
-            placed = true;
             displaced = is_tag(old) ? old : 0;
+            break;
         }
-        if (!placed || !displaced) return;                    // settled, or out of slots (falls back later)
+        if (!displaced) return;                               // settled, or out of slots (falls back later)
         // carry the displaced claimant on from its next round (same table: same slot)
         cpos = tag_pos(displaced);
         cr = (int32_t)tag_round(displaced) + 1;
@@ -570,8 +554,9 @@ __global__ __launch_bounds__(kWave) void k_allocate_lane(Params p)
     constexpr int APL = kWave / G;                   // claimants served by one load instruction
     constexpr int CH = PMAX / G;                     // load instructions per claimant
     constexpr int NT = kWave / APL;
+    // what a lane needs to know of a slot: -1 empty, a claim tag (<= -2), 1 = holds an expired id,
+    // 0 = holds a live id
     __shared__ int64_t s_I[kWave][PMAX + 1];         // +1: rows fall into different banks
-    __shared__ int32_t s_M[kWave][PMAX + 1];
 
     const int lane = threadIdx.x;
     const int g = lane / G, r = lane % G;
@@ -603,6 +588,7 @@ __global__ __launch_bounds__(kWave) void k_allocate_lane(Params p)
             // cooperative loads; lanes without a slot to read use slot 0 / the home slot (valid addresses)
             int64_t vi[NT * CH];
             int32_t vm[NT * CH];
+            uint32_t gmeta[NT];                               // the claimant's table: eviction on + ttl
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
                 const int a = t * APL + g;
@@ -611,10 +597,13 @@ __global__ __launch_bounds__(kWave) void k_allocate_lane(Params p)
                 int32_t *gM = p.t0.M;
                 int64_t gN = p.t0.N;
                 int gP = p.t0.P;
+                int gttl = p.t0.evict ? p.t0.ttl : -1;
                 if (multi) {
                     const TableDesc &gd = p.descs[__shfl(f, a)];
                     gI = gd.I; gM = gd.M; gN = gd.N; gP = gd.P;
+                    gttl = gd.evict ? gd.ttl : -1;
                 }
+                gmeta[t] = (uint32_t)gttl;
 #pragma unroll
                 for (int c = 0; c < CH; ++c) {
                     const int k = c * G + r;
@@ -627,8 +616,10 @@ __global__ __launch_bounds__(kWave) void k_allocate_lane(Params p)
             for (int t = 0; t < NT; ++t)
 #pragma unroll
                 for (int c = 0; c < CH; ++c) {
-                    s_I[t * APL + g][c * G + r] = vi[t * CH + c];
-                    s_M[t * APL + g][c * G + r] = vm[t * CH + c];
+                    int64_t w = vi[t * CH + c];
+                    const int32_t ttl = (int32_t)gmeta[t];
+                    if (w >= 0) w = (ttl >= 0 && (int64_t)p.step - (int64_t)vm[t * CH + c] > (int64_t)ttl) ? 1 : 0;
+                    s_I[t * APL + g][c * G + r] = w;
                 }
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             uint32_t hint = kHintNone;
@@ -639,7 +630,7 @@ __global__ __launch_bounds__(kWave) void k_allocate_lane(Params p)
                     uint32_t occ = 0;
                     bool cand;
                     if (v == -1) cand = true;
-                    else if (v >= 0) { cand = d.evict && (int64_t)p.step - (int64_t)s_M[lane][k] > (int64_t)d.ttl; occ = 1; }
+                    else if (v >= 0) { cand = v == 1; occ = 1; }
                     else { occ = tag_occ(v); cand = v > make_tag((uint32_t)k, pos, occ); }
                     if (!cand) continue;
                     const int64_t mine = make_tag((uint32_t)k, pos, occ);
@@ -651,7 +642,7 @@ __global__ __launch_bounds__(kWave) void k_allocate_lane(Params p)
                         // carry the displaced claimant on from its next round (same table: same slot)
                         const uint32_t vpos = tag_pos(old);
                         const int32_t vr = (int32_t)tag_round(old) + 1;
-                        if (vr < d.P) claim_lane<PMAX>(p, d, vpos, home_slot(p.ids[vpos], d.seed, d.N), vr);
+                        if (vr < d.P) claim_lane(p, d, vpos, home_slot(p.ids[vpos], d.seed, d.N), vr);
                     }
                     break;
                 }
