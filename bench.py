@@ -30,7 +30,7 @@ CEIL_STORES_PER_S = 22.9e9
 # HBM bytes per k_discover launch on the full-size headline workload, from rocprofv3 --pmc
 # FETCH_SIZE and WRITE_SIZE (KiB per dispatch x 1024, calibration factor 1.000); see
 # profiles/remap_headline_1Bslots_4Mids.txt.  Only valid for that workload at scale 1.
-HEADLINE_DISCOVER_TRAFFIC_BYTES = None
+HEADLINE_DISCOVER_TRAFFIC_BYTES = int((352813.0 + 180308.4) * 1024)
 
 
 def log(*a):
@@ -42,7 +42,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="headline", choices=["headline", "c4", "c3"])
+    ap.add_argument("--workload", default="headline", choices=["headline", "c4", "c3", "c1", "c2", "c5"])
     ap.add_argument("--scale", type=float, default=1.0, help="shrink slots and batch (quick checks only)")
     ap.add_argument("--cpu-steps", type=int, default=2, help="steps the oracle replays for cpu_baseline (0 = skip)")
     ap.add_argument("--no-kernel-timing", action="store_true")
@@ -64,6 +64,10 @@ def main():
 
     if args.workload == "c3":
         return bench_lookup(args, np, torch, mp, wl, dev)
+    if args.workload in ("c1", "c2"):
+        return bench_small_table(args, np, torch, mp, wl, dev)
+    if args.workload == "c5":
+        return bench_jagged(args, np, torch, mp, wl, dev)
 
     spec = wl.headline_spec(args.scale) if args.workload == "headline" else wl.c4_spec(args.scale)
     t = spec.table
@@ -284,6 +288,117 @@ def bench_lookup(args, np, torch, mp, wl, dev):
         "cpu_baseline": cpu,
     }
     print(json.dumps(result), flush=True)
+
+
+def _emit(metric, value, K, W, elapsed, workload, ktimes, cpu, extra=None):
+    dom = max(ktimes, key=lambda k: ktimes[k][0]) if ktimes else None
+    result = {
+        "metric": metric, "value": round(value, 1), "unit": "ids/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": round(elapsed / K * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int64", "data": "synthetic", "config": {"workload": workload},
+        "kernel_ms_per_step": {k: round(v[0] / K, 4) for k, v in ktimes.items()},
+        "roofline": {"bound": "hbm", "kernel": dom, "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None,
+                     "traffic": None, "avg_kernel_ms": round(ktimes[dom][0] / ktimes[dom][1], 4) if dom else None},
+        "cpu_baseline": cpu,
+    }
+    if extra:
+        result.update(extra)
+    print(json.dumps(result), flush=True)
+
+
+def bench_small_table(args, np, torch, mp, wl, dev):
+    """Configs 1 and 2: tables that live in L2 / Infinity Cache; every step is launch-bound."""
+    if args.workload == "c1":
+        spec, batches_np = wl.c1_spec(), [(s, b) for s, b in wl.c1_batches()]
+        name = "c1: 4096 slots, P=8, TTL=3, 8 batches of 1024 Zipf(1.1) ids, fp32 4096x16 rows"
+        W = 0
+    else:
+        spec = wl.c2_spec()
+        batches_np = [wl.c2_prefill()] + [(s, wl.c2_batch(s)) for s in range(1, 51)]
+        name = "c2: 1M slots, P=16, TTL=10, prefill 0.3 then 50 batches of 65536 Zipf(1.05) ids, fp32 1Mx64 rows"
+        W = 1                                                    # the prefill call is not timed
+    g = mp.MpzchTable(spec.num_slots, spec.max_probe, mp.EVICT_TTL, spec.ttl, spec.hash_seed, max_batch=1 << 19)
+    emb = torch.ones((spec.emb_rows, spec.emb_dim), dtype=torch.float32, device=dev)
+    batches = [(s, torch.from_numpy(b).to(dev)) for s, b in batches_np]
+    outs = [torch.empty(b.numel(), dtype=torch.int64, device=dev) for _, b in batches]
+    # one untimed pass on a scratch table warms the code paths; the timed pass starts from an empty table
+    g2 = mp.MpzchTable(spec.num_slots, spec.max_probe, mp.EVICT_TTL, spec.ttl, spec.hash_seed, max_batch=1 << 19)
+    for (s, b), o in zip(batches, outs):
+        g2.remap(b, s, o)
+        g2.reset_rows(emb)
+    torch.cuda.synchronize()
+    g2.close()
+    for (s, b), o in list(zip(batches, outs))[:W]:
+        g.remap(b, s, o)
+    torch.cuda.synchronize()
+    mp.mpzch_set_kernel_timing(g.handle, True)
+    t0 = time.perf_counter()
+    for (s, b), o in list(zip(batches, outs))[W:]:
+        g.remap(b, s, o)
+        g.reset_rows(emb)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ktimes = mp.mpzch_kernel_times(g.handle)
+    K = len(batches) - W
+    total = sum(b.numel() for _, b in batches[W:])
+    cpu = None
+    if args.cpu_steps > 0:
+        import oracle
+        o = oracle.Table(spec.num_slots, spec.max_probe, oracle.EVICT_TTL, spec.ttl, spec.hash_seed)
+        for s, b in batches_np[:W]:
+            o.remap(b, s)
+        c0 = time.perf_counter()
+        same = True
+        for (s, b), og in list(zip(batches_np, outs))[W:]:
+            r = o.remap(b, s)
+            same = same and bool(np.array_equal(r.slots, og.cpu().numpy()))
+        cpu = {"value": round(total / (time.perf_counter() - c0), 1), "unit": "ids/s", "cores": 1, "kind": "oracle",
+               "sample": "all timed steps", "matches_gpu_out_slots": same}
+    occ = int((g.identities >= 0).sum().item())
+    _emit("remapped IDs/sec (train insert+evict) at 1 GPU", total / elapsed, K, W, elapsed, name, ktimes, cpu,
+          {"final_load": round(occ / spec.num_slots, 4)})
+
+
+def bench_jagged(args, np, torch, mp, wl, dev):
+    """Config 5: 26 tables, one mpzch_remap_jagged call per step."""
+    spec = wl.c5_spec(total_slots_cap=int(1_000_000_000 * args.scale), samples=max(int(65536 * args.scale), 64))
+    K, W = min(args.steps, 5), min(args.warmup, 2)
+    handles = [mp.mpzch_create(t.num_slots, t.max_probe, (mp.EVICT_TTL, t.ttl), t.hash_seed) for t in spec.tables]
+    group = mp.mpzch_group_create(handles)
+    I = [torch.empty(t.num_slots, dtype=torch.int64, device=dev) for t in spec.tables]
+    M = [torch.empty(t.num_slots, dtype=torch.int32, device=dev) for t in spec.tables]
+    for h, i, m in zip(handles, I, M):
+        mp.mpzch_init_tensors(h, i, m)
+    T = len(spec.tables)
+    data = [wl.c5_batch(spec, s) for s in range(1, W + K + 1)]
+    dev_b = [(torch.from_numpy(v).to(dev), torch.from_numpy(o).to(dev), [int(x) for x in o]) for v, _, o in data]
+    nmax = max(v.numel() for v, _, _ in dev_b)
+    mp.mpzch_group_reserve(group, nmax)
+    out = torch.empty(nmax, dtype=torch.int64, device=dev)
+    ev = torch.empty(nmax, dtype=torch.int64, device=dev)
+    nev = torch.zeros(T, dtype=torch.int64, device=dev)
+    stats = torch.zeros((W + K, T * mp.STAT_COUNT), dtype=torch.int64, device=dev)
+
+    def one(i):
+        v, o, eo = dev_b[i]
+        mp.mpzch_remap_jagged(group, I, M, v, o, i + 1, out[: v.numel()], ev, eo, nev, stats[i])
+
+    for i in range(W):
+        one(i)
+    torch.cuda.synchronize()
+    mp.mpzch_group_set_kernel_timing(group, True)
+    t0 = time.perf_counter()
+    for i in range(W, W + K):
+        one(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ktimes = mp.mpzch_group_kernel_times(group)
+    total = sum(dev_b[i][0].numel() for i in range(W, W + K))
+    st = stats[W:].cpu().numpy().reshape(K, T, mp.STAT_COUNT).sum(axis=(0, 1))
+    _emit("remapped IDs/sec (train insert+evict) at 1 GPU", total / elapsed, K, W, elapsed,
+          f"c5: 26 tables ({sum(t.num_slots for t in spec.tables)} slots in all), P=16, TTL=5, {spec.samples} samples, "
+          f"pooling 1..50, about {total // K} values per step, one mpzch_remap_jagged call per step", ktimes, None,
+          {"totals_over_timed_steps": dict(zip(mp.STAT_NAMES, [int(x) for x in st]))})
 
 
 if __name__ == "__main__":
