@@ -42,7 +42,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="headline", choices=["headline", "c4", "c3", "c1", "c2", "c5"])
+    ap.add_argument("--workload", default="headline", choices=["headline", "c4", "c3", "c1", "c2", "c5", "table1"])
     ap.add_argument("--scale", type=float, default=1.0, help="shrink slots and batch (quick checks only)")
     ap.add_argument("--cpu-steps", type=int, default=2, help="steps the oracle replays for cpu_baseline (0 = skip)")
     ap.add_argument("--no-kernel-timing", action="store_true")
@@ -68,6 +68,8 @@ def main():
         return bench_small_table(args, np, torch, mp, wl, dev)
     if args.workload == "c5":
         return bench_jagged(args, np, torch, mp, wl, dev)
+    if args.workload == "table1":
+        return bench_table1(args, np, torch, mp, wl, dev)
 
     spec = wl.headline_spec(args.scale) if args.workload == "headline" else wl.c4_spec(args.scale)
     t = spec.table
@@ -399,6 +401,60 @@ def bench_jagged(args, np, torch, mp, wl, dev):
           f"c5: 26 tables ({sum(t.num_slots for t in spec.tables)} slots in all), P=16, TTL=5, {spec.samples} samples, "
           f"pooling 1..50, about {total // K} values per step, one mpzch_remap_jagged call per step", ktimes, None,
           {"totals_over_timed_steps": dict(zip(mp.STAT_NAMES, [int(x) for x in st]))})
+
+
+def bench_table1(args, np, torch, mp, wl, dev):
+    """The collision-rate experiment of the paper's Table 1 as a workload: 150 M distinct ids are
+    inserted (eviction off) into tables of 100 M .. 500 M slots at max_probe 8 .. 512; reports the
+    collision rate of every cell next to the paper's and the insertion throughput against P."""
+    n_ids = int(150_000_000 * args.scale)
+    sizes_m = [100, 150, 200, 250, 300, 350, 400, 450, 500]
+    probes = [8, 16, 32, 64, 128, 256, 512]
+    golden = {}
+    with open(os.path.join(ROOT, "tests", "golden", "table1_collision_rate.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                v = line.split()
+                golden[int(v[0])] = dict(zip(probes, map(float, v[3:])))
+    batch = max(int(262144 * args.scale), 1024)
+    calls = (n_ids + batch - 1) // batch
+    out = torch.empty(batch, dtype=torch.int64, device=dev)
+    nev = torch.zeros(1, dtype=torch.int64, device=dev)
+    stats = torch.zeros((calls, mp.STAT_COUNT), dtype=torch.int64, device=dev)
+    ids_all = [wl.distinct_ids_device(lo, min(lo + batch, n_ids), dev) for lo in range(0, n_ids, batch)]
+    rows, total_s, total_ids = [], 0.0, 0
+    for sm in sizes_m:
+        n_slots = int(sm * 1_000_000 * args.scale)
+        I = torch.empty(n_slots, dtype=torch.int64, device=dev)
+        M = torch.empty(n_slots, dtype=torch.int32, device=dev)
+        for P in probes:
+            h = mp.mpzch_create(n_slots, P, (mp.EVICT_NONE, 0), wl.HASH_SEED_BASE)
+            mp.mpzch_reserve(h, batch)
+            mp.mpzch_init_tensors(h, I, M)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for k, ids in enumerate(ids_all):
+                mp.mpzch_remap(h, I, M, ids, k, out[: ids.numel()], None, nev, stats[k])
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+            coll = int(stats[:, mp.STAT_NAMES.index("collisions")].sum().item())
+            rows.append({"table_millions": sm, "max_probe": P, "collision_pct": round(100.0 * coll / n_ids, 4),
+                         "paper_pct": golden[sm][P], "ids_per_s": round(n_ids / dt, 1), "seconds": round(dt, 4)})
+            log(f"[table1] {sm}M slots P={P}: {rows[-1]['collision_pct']:.4f}% (paper {golden[sm][P]:.4f}%) "
+                f"{n_ids / dt / 1e9:.2f} G ids/s")
+            total_s += dt
+            total_ids += n_ids
+            mp.mpzch_destroy(h)
+        del I, M
+    result = {
+        "metric": "remapped IDs/sec (train insert, eviction off) at 1 GPU", "value": round(total_ids / total_s, 1),
+        "unit": "ids/s", "n_gpus": 1, "steps": len(rows), "warmup": 0, "ms_per_step": round(total_s / len(rows) * 1e3, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int64", "data": "synthetic",
+        "config": {"workload": f"table1: {n_ids} distinct ids into 9 table sizes x 7 probe depths, {batch} ids per call, "
+                               "eviction off", "scale": args.scale},
+        "cells": rows, "roofline": None, "cpu_baseline": None,
+    }
+    print(json.dumps(result), flush=True)
 
 
 if __name__ == "__main__":

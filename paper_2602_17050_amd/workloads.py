@@ -250,6 +250,13 @@ def distinct_ids(n: int, salt: int = 0) -> np.ndarray:
     return rank_to_id(np.arange(1, n + 1, dtype=np.int64) + (salt << 44))
 
 
+def distinct_ids_device(lo: int, hi: int, device, salt: int = 0):
+    """distinct_ids(n)[lo:hi] drawn on the device (same integers: the multiplication wraps mod 2^64)."""
+    import torch
+    r = torch.arange(lo + 1, hi + 1, dtype=torch.int64, device=device) + (salt << 44)
+    return (r * torch.tensor(-7046029254386353131, dtype=torch.int64, device=device)) & ((1 << 63) - 1)
+
+
 def embedding_pattern(rows: int, dim: int, dtype=np.float32) -> np.ndarray:
     """Non-zero closed-form fill so that a reset row is observable: integers 1..251."""
     r = np.arange(rows, dtype=np.int64)[:, None]
