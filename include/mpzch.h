@@ -31,6 +31,10 @@
  *   expired    : policy TTL and  step - metadata > ttl     (Sec. 3.4)
  *   valid ids  : 0 <= id <= 2^63 - 1.  Negative ids are never stored and never
  *                match; their output is home(id) of their bit pattern.
+ * Precondition on identities: it was initialised by mpzch_init_tensors and since then written
+ * only by this library (or is a copy of such a tensor).  Such a table never has an empty slot
+ * between an id's home and the slot that holds it -- an occupied slot never becomes empty again --
+ * and the lookups use that: a search ends at the first empty slot of the probe range.
  * While mpzch_remap / mpzch_remap_jagged run, identities may transiently hold
  * values <= -2; they are gone when the call's work on the stream has finished.
  */

@@ -270,7 +270,8 @@ int oracle_reset_rows(const int64_t *slots, int64_t count,
  * State checker over slots [lo, hi): every resident id must be found by a
  * read-only lookup at exactly the slot that holds it.  That single condition
  * implies that no id is stored twice and that every resident lies within
- * min(P, N) probes of its home.  Also counts occupied slots and slots holding
+ * min(P, N) probes of its home.  It also checks that no empty slot lies between
+ * a resident's home and its slot.  Also counts occupied slots and slots holding
  * values that are neither -1 nor a valid id.  Returns the number of
  * violations; *first_bad is the first offending slot (or -1).
  */
@@ -286,7 +287,10 @@ int64_t oracle_check_state(const oracle_cfg *c, const int64_t *I,
         occ++;
         int64_t h = oracle_home(x, c->hash_seed, c->num_slots);
         int64_t r = discover(c, I, x, h);
-        if (r < 0 || probe_slot(h, r, c->num_slots) != s) { if (fb < 0) fb = s; bad++; }
+        if (r < 0 || probe_slot(h, r, c->num_slots) != s) { if (fb < 0) fb = s; bad++; continue; }
+        /* a slot never becomes empty again, so no empty slot may precede a resident in its window */
+        for (int64_t k = 0; k < r; ++k)
+            if (I[probe_slot(h, k, c->num_slots)] == -1) { if (fb < 0) fb = s; bad++; break; }
     }
     if (out_occupied) *out_occupied = occ;
     if (first_bad) *first_bad = fb;

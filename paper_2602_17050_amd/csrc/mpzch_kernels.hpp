@@ -282,8 +282,14 @@ __device__ __forceinline__ void block_stat_row(const Params &p, StatRow *rows, i
 // such that home + q is a multiple of 16 slots every access reads exactly one 128-byte line.
 // All 16 accesses are issued before the first result is looked at; a lane without a slot to
 // look at re-reads the home slot (a valid address, same or neighbouring line; slot 0 if the
-// lane belongs to another table), so the loads carry no branch and stay in flight together.  d is wave-uniform.  Returns the round of
-// the match or -1.
+// lane belongs to another table), so the loads carry no branch and stay in flight together.
+// d is wave-uniform.  Returns the round of the match, kProbeGoOn when the id is not among these
+// slots, or kProbeAbsent when in addition one of them is empty: a slot never becomes empty again
+// once it was occupied, so no resident id lies beyond an empty slot of its window and the search
+// can end there.
+constexpr int kProbeGoOn = -1;
+constexpr int kProbeAbsent = -2;
+
 __device__ __forceinline__ int probe_pass(const TableDesc &d, int64_t id, int64_t home, int q)
 {
     constexpr int G = kLine, IPI = kWave / G;
@@ -301,14 +307,16 @@ __device__ __forceinline__ int probe_pass(const TableDesc &d, int64_t id, int64_
         v[t] = d.I[act ? wrap(ghome + round, d.N) : (ghome < d.N ? ghome : 0)];
         act_bits |= (uint32_t)act << t;
     }
-    int found = -1;
+    int found = kProbeGoOn;
 #pragma unroll
     for (int t = 0; t < G; ++t) {
         const int src = t * IPI + g;
         const int64_t gid = shfl64(id, src);
         const int gq = __shfl(q, src);         // shuffles stay outside conditionals: every lane must take part
-        const int first = group_first<G>(__ballot(((act_bits >> t) & 1u) && v[t] == gid), g);
-        const int got = __shfl(first >= 0 ? gq + first : -1, (lane % IPI) * G);
+        const bool act = (act_bits >> t) & 1u;
+        const int first = group_first<G>(__ballot(act && v[t] == gid), g);
+        const bool empty = group_first<G>(__ballot(act && v[t] == -1), g) >= 0;
+        const int got = __shfl(first >= 0 ? gq + first : (empty ? kProbeAbsent : kProbeGoOn), (lane % IPI) * G);
         if (lane / IPI == t) found = got;
     }
     return found;
@@ -398,7 +406,11 @@ __global__ __launch_bounds__(kBlock) void k_discover(Params p)
                     const bool need = mine && dist < 0 && q < d.P;
                     if (!__any(need)) break;
                     const int got = probe_pass(d, id, mine ? home : 0, need ? q : d.P);
-                    if (need) { if (got >= 0) dist = got; else q += kLine; }
+                    if (need) {
+                        if (got >= 0) dist = got;
+                        else if (got == kProbeAbsent) q = d.P;      // an empty slot ends the search
+                        else q += kLine;
+                    }
                 }
                 if (mine && dist >= 0) finish_hit(d, (int64_t)pos, home, dist);
                 const bool miss = mine && dist < 0;
@@ -485,7 +497,7 @@ __global__ __launch_bounds__(kBlock) void k_discover(Params p)
                 const int at = staged + __popcll(pb & ((1ull << lane) - 1ull));
                 s_pos[w][at] = (uint32_t)pos;
                 s_home[w][at] = home;
-                s_q[w][at] = kLine - o;
+                s_q[w][at] = dist == kProbeAbsent ? d.P : kLine - o;    // d.P: nothing left to look at
             }
             staged += __popcll(pb);
             todo = todo && !mine;
