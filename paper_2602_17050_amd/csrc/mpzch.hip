@@ -228,24 +228,18 @@ mpzch_status_t launch_discover(const Params &p, int grid, hipStream_t s)
 // max_p: largest min(max_probe, num_slots) of the tables involved
 mpzch_status_t launch_allocate(int32_t max_p, const Params &p, int num_cus, hipStream_t s)
 {
-    if (max_p <= 32) {
-        // one wavefront per workgroup, one segment per workgroup pass
-        const int grid = grid_for((int64_t)p.num_segs, 1, num_cus, 4 * group_blocks_per_cu());
-        if (max_p <= 8) hipLaunchKernelGGL((k_allocate_lane<8>), dim3(grid), dim3(kWave), 0, s, p);
-        else if (max_p <= 16) hipLaunchKernelGGL((k_allocate_lane<16>), dim3(grid), dim3(kWave), 0, s, p);
-        else hipLaunchKernelGGL((k_allocate_lane<32>), dim3(grid), dim3(kWave), 0, s, p);
-    } else {
-        const int grid = grid_for((int64_t)p.num_segs, kWavesPerBlock, num_cus, group_blocks_per_cu());
-        hipLaunchKernelGGL(k_allocate_wave, dim3(grid), dim3(kBlock), 0, s, p);
-    }
+    // one wavefront per workgroup, one segment per workgroup pass; the lane phase covers the first
+    // 8 or 16 slots of every window, longer windows continue in the wave phase
+    const int grid = grid_for((int64_t)p.num_segs, 1, num_cus, 4 * group_blocks_per_cu());
+    if (max_p <= 8) hipLaunchKernelGGL((k_allocate<8>), dim3(grid), dim3(kWave), 0, s, p);
+    else hipLaunchKernelGGL((k_allocate<16>), dim3(grid), dim3(kWave), 0, s, p);
     LAUNCH_CHECK();
     return MPZCH_OK;
 }
 
-mpzch_status_t launch_finalize(int32_t max_p, const Params &p, int grid, hipStream_t s)
+mpzch_status_t launch_finalize(const Params &p, int grid, hipStream_t s)
 {
-    if (max_p <= 32) hipLaunchKernelGGL(k_finalize_lane, dim3(grid), dim3(kBlock), 0, s, p);
-    else hipLaunchKernelGGL(k_finalize_wave, dim3(grid), dim3(kBlock), 0, s, p);
+    hipLaunchKernelGGL(k_finalize, dim3(grid), dim3(kBlock), 0, s, p);
     LAUNCH_CHECK();
     return MPZCH_OK;
 }
@@ -290,7 +284,7 @@ mpzch_status_t run_remap(Scratch &sc, Timing &tm, Params p, int32_t max_p, hipSt
 
     TIMED(tm, KDiscover, s, (launch_discover<true>(p, g_disc, s)));
     TIMED(tm, KAllocate, s, launch_allocate(max_p, p, sc.num_cus, s));
-    TIMED(tm, KFinalize, s, launch_finalize(max_p, p, g_grp, s));
+    TIMED(tm, KFinalize, s, launch_finalize(p, g_grp, s));
     if (!tm.begin(KEmitDups, s)) return MPZCH_ERR_HIP;
     hipLaunchKernelGGL(k_emit_dups, dim3(g_grp), dim3(kBlock), 0, s, p);
     LAUNCH_CHECK();

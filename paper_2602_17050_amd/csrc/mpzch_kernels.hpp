@@ -20,8 +20,8 @@
 //                The scratch set entries that were used are emptied again.
 //   k_emit_dups  the other copies of a missed id copy the slot of the elected position; counters
 //                are published.
-// k_allocate / k_finalize exist in two forms: one lane per claimant with the whole window in
-// registers (max_probe <= 32) and one wavefront per claimant scanning 64 slots per access.
+// k_allocate / k_finalize work with one lane per claimant on the first slots of the window and
+// hand the few claimants that need more to the whole wavefront (64 slots per access).
 //
 // No kernel funnels work through one hot address: an atomic on a single address costs about
 // 12 ns on this GPU however many lanes it serves, so miss lists are per wavefront (no shared
@@ -513,54 +513,87 @@ __global__ __launch_bounds__(kBlock) void k_discover(Params p)
     }
 }
 
-// ------------------------------------------------------------------ allocation, one lane per claimant
+// ------------------------------------------------------------------ allocation
 // TTL test of Sec. 3.4 on a slot that holds an id
 __device__ __forceinline__ bool expired(const TableDesc &d, int32_t step, int64_t s)
 {
     return d.evict && (int64_t)step - (int64_t)d.M[s] > (int64_t)d.ttl;
 }
 
-// Deferred acceptance for the claimant at batch position cpos, starting at round cr, by one lane,
-// slot by slot.  This is the rare continuation for a claimant that was displaced by a better
-// claim; the first attempt of every claimant goes through the cooperative window loads below.
-__device__ __forceinline__ void claim_lane(const Params &p, const TableDesc &d, uint32_t cpos, int64_t home, int32_t cr)
-{
-    for (;;) {
-        int64_t displaced = 0;
-        for (int32_t k = cr; k < d.P; ++k) {
-            const int64_t s = wrap(home + k, d.N);
-            const int64_t v = __hip_atomic_load(&d.I[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            uint32_t occ = 0;
-            bool cand;
-            if (v == -1) cand = true;
-            else if (v >= 0) { cand = expired(d, p.step, s); occ = 1; }
-            else { occ = tag_occ(v); cand = v > make_tag((uint32_t)k, cpos, occ); }
-            if (!cand) continue;
-            const int64_t mine = make_tag((uint32_t)k, cpos, occ);
-            const int64_t old = __hip_atomic_fetch_min(&d.I[s], mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (is_tag(old) && old < mine) continue;          // a better claim got there first
-            displaced = is_tag(old) ? old : 0;
-            break;
-        }
-        if (!displaced) return;                               // settled, or out of slots (falls back later)
-        // carry the displaced claimant on from its next round (same table: same slot)
-        cpos = tag_pos(displaced);
-        cr = (int32_t)tag_round(displaced) + 1;
-        if (cr >= d.P) return;
-        home = home_slot(p.ids[cpos], d.seed, d.N);
-    }
-}
-
-// One workgroup = one wavefront.  The windows (identities and metadata) of up to 64 claimants
-// are read cooperatively -- G lanes read G consecutive slots of one claimant with one coalesced
-// access, all accesses in flight together -- and transposed through LDS so that every lane then
-// walks the window of its own claimant.  The lane records the round at which its claimant was
-// placed (hint) so that k_finalize can go straight to that slot.
+// One workgroup = one wavefront.  Lane phase: the first PMAX slots of the windows (identities and
+// metadata) of up to 64 claimants are read cooperatively -- G lanes read G consecutive slots of
+// one claimant with one coalesced access, all accesses in flight together -- and transposed
+// through LDS so that every lane then walks the window of its own claimant.  Wave phase: the few
+// claimants that go on -- displaced by a better claim, or without a claimable slot among their
+// first PMAX -- are served one after the other by the whole wavefront, 64 slots per access.
+// The round at which a lane's own claimant was placed is left as a hint for k_finalize.
 constexpr uint32_t kHintNone = 0xFF;       // not an elected position
 constexpr uint32_t kHintUnplaced = 0xFE;   // ran out of slots: falls back to home (final)
+constexpr uint32_t kHintUnknown = 0xFD;    // placed, but not at a round that fits the hint: search the window
+
+// Deferred acceptance by the whole wavefront for the claimant at batch position cpos from round
+// cr on (all arguments wave-uniform).  A claimant it displaces is carried on in turn.  Returns
+// the round at which the FIRST claimant was placed, or -1 if it ran out of slots.
+__device__ __forceinline__ int32_t claim_wave(const Params &p, const TableDesc &d, uint32_t cpos, int32_t cr)
+{
+    const int lane = lane_id();
+    int64_t home = home_slot(p.ids[cpos], d.seed, d.N);
+    int32_t first_round = -1;
+    bool is_first = true, active = cr < d.P;
+    while (active) {
+        // lanes look at rounds cr .. cr + 63
+        const int32_t round = cr + lane;
+        bool cand = false;
+        uint32_t occ = 0;
+        int64_t s = 0;
+        if (round < d.P) {
+            s = wrap(home + round, d.N);
+            const int64_t v = __hip_atomic_load(&d.I[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (v == -1) cand = true;
+            else if (v >= 0) { cand = expired(d, p.step, s); occ = 1; }
+            else { occ = tag_occ(v); cand = v > make_tag((uint32_t)round, cpos, occ); }
+        }
+        uint64_t cmask = __ballot(cand);
+        bool placed = false;
+        int64_t displaced = 0;
+        int32_t placed_round = -1;
+        while (cmask && !placed) {
+            const int first = __ffsll((unsigned long long)cmask) - 1;
+            cmask &= cmask - 1;
+            int64_t old = 0, mine = 0;
+            if (lane == first) {
+                mine = make_tag((uint32_t)round, cpos, occ);
+                old = __hip_atomic_fetch_min(&d.I[s], mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            old = shfl64(old, first);
+            mine = shfl64(mine, first);
+            if (is_tag(old) && old < mine) continue;          // a better claim got there first
+            placed = true;
+            placed_round = cr + first;
+            displaced = is_tag(old) ? old : 0;
+        }
+        if (placed) {
+            if (is_first) first_round = placed_round;
+            is_first = false;
+            if (displaced) {
+                // carry the displaced claimant on from its next round (same table: same slot)
+                cpos = tag_pos(displaced);
+                cr = (int32_t)tag_round(displaced) + 1;
+                home = home_slot(p.ids[cpos], d.seed, d.N);
+                if (cr >= d.P) active = false;                // out of rounds: falls back at finalize
+            } else {
+                active = false;
+            }
+        } else {
+            cr += kWave;
+            if (cr >= d.P) active = false;                    // window exhausted: falls back at finalize
+        }
+    }
+    return first_round;
+}
 
 template <int PMAX>
-__global__ __launch_bounds__(kWave) void k_allocate_lane(Params p)
+__global__ __launch_bounds__(kWave) void k_allocate(Params p)
 {
     constexpr int G = PMAX < kLine ? PMAX : kLine;   // lanes that read one claimant's window together
     constexpr int APL = kWave / G;                   // claimants served by one load instruction
@@ -634,10 +667,16 @@ __global__ __launch_bounds__(kWave) void k_allocate_lane(Params p)
                     s_I[t * APL + g][c * G + r] = w;
                 }
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            // lane phase
             uint32_t hint = kHintNone;
+            bool more = false;           // a claimant of this lane goes on in the wave phase
+            uint32_t mpos = 0;
+            int32_t mr = 0;
             if (agent) {
                 hint = kHintUnplaced;
-                for (int k = 0; k < d.P; ++k) {
+                const int lim = d.P < PMAX ? d.P : PMAX;
+                bool placed = false;
+                for (int k = 0; k < lim; ++k) {
                     const int64_t v = s_I[lane][k];
                     uint32_t occ = 0;
                     bool cand;
@@ -650,96 +689,32 @@ __global__ __launch_bounds__(kWave) void k_allocate_lane(Params p)
                                                                __HIP_MEMORY_SCOPE_AGENT);
                     if (is_tag(old) && old < mine) continue;      // a better claim got there first
                     hint = (uint32_t)k;
-                    if (is_tag(old)) {
-                        // carry the displaced claimant on from its next round (same table: same slot)
-                        const uint32_t vpos = tag_pos(old);
-                        const int32_t vr = (int32_t)tag_round(old) + 1;
-                        if (vr < d.P) claim_lane(p, d, vpos, home_slot(p.ids[vpos], d.seed, d.N), vr);
+                    placed = true;
+                    if (is_tag(old) && (int32_t)tag_round(old) + 1 < d.P) {
+                        // the displaced claimant goes on from its next round (same table: same slot)
+                        more = true;
+                        mpos = tag_pos(old);
+                        mr = (int32_t)tag_round(old) + 1;
                     }
                     break;
                 }
+                if (!placed && d.P > PMAX) { more = true; mpos = pos; mr = PMAX; }
+            }
+            // wave phase
+            uint64_t lm = __ballot(more);
+            while (lm) {
+                const int src = __ffsll((unsigned long long)lm) - 1;
+                lm &= lm - 1;
+                const uint32_t cpos = __shfl(mpos, src);
+                const int32_t cr = __shfl(mr, src);
+                const uint32_t own = __shfl(pos, src);
+                const TableDesc dw = multi ? p.descs[__shfl(f, src)] : p.t0;
+                const int32_t fr = claim_wave(p, dw, cpos, cr);
+                if (lane == src && cpos == own)
+                    hint = fr < 0 ? kHintUnplaced : (fr < (int32_t)kHintUnknown ? (uint32_t)fr : kHintUnknown);
             }
             if (have) p.hint[idx] = (uint8_t)hint;
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        }
-    }
-}
-
-// ------------------------------------------------------------------ allocation, one wavefront per claimant
-__global__ __launch_bounds__(kBlock) void k_allocate_wave(Params p)
-{
-    const int lane = lane_id();
-    const int64_t wave_global = ((int64_t)blockIdx.x * kBlock + threadIdx.x) / kWave;
-    const int64_t num_waves = (int64_t)gridDim.x * kWavesPerBlock;
-    const bool multi = p.num_tables > 1;
-    for (int64_t seg = wave_global; seg < p.num_segs; seg += num_waves) {
-        const uint32_t cnt = p.seg_cnt[seg];
-        const int64_t seg_base = seg * p.seg_chunks * kWave;
-        for (uint32_t j0 = 0; j0 < cnt; j0 += kWave) {
-            // one list entry per lane; the elected ones are then served one after the other
-            uint32_t lpos = 0;
-            bool agent = false;
-            if (j0 + lane < cnt) {
-                lpos = p.list[seg_base + j0 + lane];
-                const uint32_t first = p.set_slot[p.ent[seg_base + j0 + lane]];
-                p.first_of[seg_base + j0 + lane] = first;
-                agent = first == lpos;
-            }
-            uint64_t amask = __ballot(agent);
-            while (amask) {
-                const int src = __ffsll((unsigned long long)amask) - 1;
-                amask &= amask - 1;
-                uint32_t cpos = __shfl(lpos, src);                // claimant carried by the wavefront
-                TableDesc d = p.t0;
-                if (multi) d = p.descs[find_table(p.offsets, p.num_tables, (int64_t)cpos)];
-                int64_t home = home_slot(p.ids[cpos], d.seed, d.N);
-                int32_t cr = 0;
-                bool active = true;
-                while (active) {
-                    // lanes look at rounds cr .. cr + 63
-                    const int32_t round = cr + lane;
-                    bool cand = false;
-                    uint32_t occ = 0;
-                    int64_t s = 0;
-                    if (round < d.P) {
-                        s = wrap(home + round, d.N);
-                        const int64_t v = __hip_atomic_load(&d.I[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        if (v == -1) cand = true;
-                        else if (v >= 0) { cand = expired(d, p.step, s); occ = 1; }
-                        else { occ = tag_occ(v); cand = v > make_tag((uint32_t)round, cpos, occ); }
-                    }
-                    uint64_t cmask = __ballot(cand);
-                    bool placed = false;
-                    int64_t displaced = 0;
-                    while (cmask && !placed) {
-                        const int first = __ffsll((unsigned long long)cmask) - 1;
-                        cmask &= cmask - 1;
-                        int64_t old = 0, mine = 0;
-                        if (lane == first) {
-                            mine = make_tag((uint32_t)round, cpos, occ);
-                            old = __hip_atomic_fetch_min(&d.I[s], mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        }
-                        old = shfl64(old, first);
-                        mine = shfl64(mine, first);
-                        if (is_tag(old) && old < mine) continue;  // a better claim got there first
-                        placed = true;
-                        displaced = is_tag(old) ? old : 0;
-                    }
-                    if (placed) {
-                        if (displaced) {
-                            cpos = tag_pos(displaced);
-                            cr = (int32_t)tag_round(displaced) + 1;
-                            home = home_slot(p.ids[cpos], d.seed, d.N);
-                            if (cr >= d.P) active = false;        // out of rounds: falls back at finalize
-                        } else {
-                            active = false;
-                        }
-                    } else {
-                        cr += kWave;
-                        if (cr >= d.P) active = false;            // window exhausted: falls back at finalize
-                    }
-                }
-            }
         }
     }
 }
@@ -859,7 +834,7 @@ __device__ __forceinline__ void finalize_epilogue(const Params &p, FinalizeState
     }
 }
 
-__global__ __launch_bounds__(kBlock) void k_finalize_lane(Params p)
+__global__ __launch_bounds__(kBlock) void k_finalize(Params p)
 {
     __shared__ int64_t s_ev[kWavesPerBlock][kEvBuf];
     __shared__ unsigned long long s_red[kWavesPerBlock][kStatCount];
@@ -887,27 +862,53 @@ __global__ __launch_bounds__(kBlock) void k_finalize_lane(Params p)
                 p.set_slot[p.ent[seg_base + j0 + lane]] = kSetEmpty;   // the scratch set is left empty again
             }
             int outcome = 2, f = 0;
-            int64_t s_final = 0;
+            int64_t s_final = 0, home = 0, id = 0;
+            TableDesc d = p.t0;
+            bool search = false;         // the hint did not lead to the tag: the window is searched
+            int at = -1;
+            uint32_t occ = 0;
             if (agent) {
-                TableDesc d = p.t0;
                 if (multi) { f = find_table(p.offsets, p.num_tables, (int64_t)pos); d = p.descs[f]; }
-                const int64_t id = p.ids[pos];
-                const int64_t home = p.homes[seg_base + j0 + lane];
+                id = p.ids[pos];
+                home = p.homes[seg_base + j0 + lane];
                 // the slot that carries this claimant's tag: where k_allocate left it, unless the
-                // claimant was displaced afterwards -- then its window is searched
+                // claimant was displaced afterwards
                 const uint32_t h = p.hint[seg_base + j0 + lane];
-                int at = -1;
-                uint32_t occ = 0;
-                if (h < kHintUnplaced) {
+                if (h < kHintUnknown) {
                     const int64_t v = d.I[wrap(home + (int)h, d.N)];
                     if (is_tag(v) && tag_pos(v) == pos) { at = (int)h; occ = tag_occ(v); }
                 }
-                if (at < 0 && h != kHintUnplaced) {
-                    for (int k = 0; k < d.P && at < 0; ++k) {
-                        const int64_t v = d.I[wrap(home + k, d.N)];
-                        if (is_tag(v) && tag_pos(v) == pos) { at = k; occ = tag_occ(v); }
+                search = at < 0 && h != kHintUnplaced;
+            }
+            // searches are served one after the other by the whole wavefront, 64 slots per access
+            uint64_t sm = __ballot(search);
+            while (sm) {
+                const int src = __ffsll((unsigned long long)sm) - 1;
+                sm &= sm - 1;
+                const uint32_t cpos = __shfl(pos, src);
+                const int64_t chome = shfl64(home, src);
+                const TableDesc dw = multi ? p.descs[__shfl(f, src)] : p.t0;
+                int found_round = -1;
+                uint32_t found_occ = 0;
+                for (int32_t c0 = 0; c0 < dw.P && found_round < 0; c0 += kWave) {
+                    const int32_t round = c0 + lane;
+                    bool mine = false;
+                    uint32_t o = 0;
+                    if (round < dw.P) {
+                        const int64_t v = dw.I[wrap(chome + round, dw.N)];
+                        mine = is_tag(v) && tag_pos(v) == cpos;
+                        o = tag_occ(v);
+                    }
+                    const uint64_t mb = __ballot(mine);
+                    if (mb) {
+                        const int ml = __ffsll((unsigned long long)mb) - 1;
+                        found_round = c0 + ml;
+                        found_occ = __shfl(o, ml);
                     }
                 }
+                if (lane == src) { at = found_round; occ = found_occ; }
+            }
+            if (agent) {
                 if (at >= 0) {
                     // the claim becomes the id; metadata gets the step (Algorithm 1, Pass 2)
                     s_final = wrap(home + at, d.N);
@@ -922,80 +923,6 @@ __global__ __launch_bounds__(kBlock) void k_finalize_lane(Params p)
                 p.out_slots[pos] = s_final;
             }
             finalize_account(p, fs, s_ev[w], agent, outcome, s_final, f, want_stats);
-        }
-    }
-    finalize_epilogue(p, fs, s_ev, s_cnt, s_tab, &s_base, s_red, want_stats);
-}
-
-__global__ __launch_bounds__(kBlock) void k_finalize_wave(Params p)
-{
-    __shared__ int64_t s_ev[kWavesPerBlock][kEvBuf];
-    __shared__ unsigned long long s_red[kWavesPerBlock][kStatCount];
-    __shared__ int s_cnt[kWavesPerBlock];
-    __shared__ int s_tab[kWavesPerBlock];
-    __shared__ unsigned long long s_base;
-
-    const int lane = lane_id();
-    const int w = threadIdx.x / kWave;
-    const int64_t wave_global = ((int64_t)blockIdx.x * kBlock + threadIdx.x) / kWave;
-    const int64_t num_waves = (int64_t)gridDim.x * kWavesPerBlock;
-    const bool multi = p.num_tables > 1;
-    const bool want_stats = p.out_stats != nullptr;
-    FinalizeState fs;
-
-    for (int64_t seg = wave_global; seg < p.num_segs; seg += num_waves) {
-        const uint32_t cnt = p.seg_cnt[seg];
-        const int64_t seg_base = seg * p.seg_chunks * kWave;
-        for (uint32_t j0 = 0; j0 < cnt; j0 += kWave) {
-            uint32_t lpos = 0;
-            bool agent = false;
-            if (j0 + lane < cnt) {
-                lpos = p.list[seg_base + j0 + lane];
-                agent = p.first_of[seg_base + j0 + lane] == lpos;
-                p.set_slot[p.ent[seg_base + j0 + lane]] = kSetEmpty;   // the scratch set is left empty again
-            }
-            uint64_t amask = __ballot(agent);
-            while (amask) {
-                const int src = __ffsll((unsigned long long)amask) - 1;
-                amask &= amask - 1;
-                const uint32_t cpos = __shfl(lpos, src);
-                int f = 0;
-                TableDesc d = p.t0;
-                if (multi) { f = find_table(p.offsets, p.num_tables, (int64_t)cpos); d = p.descs[f]; }
-                const int64_t id = p.ids[cpos];
-                const int64_t home = home_slot(id, d.seed, d.N);
-                // lanes look at 64 slots of the window per pass until the tag is found
-                bool found = false, mine = false;
-                uint32_t occ = 0;
-                int64_t s = 0;
-                for (int32_t c0 = 0; c0 < d.P && !found; c0 += kWave) {
-                    const int32_t round = c0 + lane;
-                    mine = false;
-                    if (round < d.P) {
-                        s = wrap(home + round, d.N);
-                        const int64_t v = d.I[s];
-                        mine = is_tag(v) && tag_pos(v) == cpos;
-                        occ = tag_occ(v);
-                    }
-                    found = __any(mine);
-                }
-                int outcome = 2;
-                int64_t s_final = home;
-                if (found) {
-                    if (mine) {
-                        d.I[s] = id;
-                        d.M[s] = p.step;
-                        p.out_slots[cpos] = s;
-                    }
-                    const int at = __ffsll((unsigned long long)__ballot(mine)) - 1;
-                    s_final = shfl64(s, at);
-                    outcome = (int)__shfl(occ, at);
-                } else if (lane == 0) {
-                    d.M[home] = p.step;
-                    p.out_slots[cpos] = home;
-                }
-                finalize_account(p, fs, s_ev[w], lane == 0, outcome, s_final, f, want_stats);
-            }
         }
     }
     finalize_epilogue(p, fs, s_ev, s_cnt, s_tab, &s_base, s_red, want_stats);
