@@ -174,3 +174,45 @@ def test_config5_26_tables_full_jagged_batch():
     mp.mpzch_group_destroy(group)
     for h in handles:
         mp.mpzch_destroy(h)
+
+
+@pytest.mark.parametrize("size_m,max_probe", [(150, 16), (200, 8), (200, 64), (300, 64)])
+def test_table1_cells_at_full_scale(size_m, max_probe):
+    """Sec. 3.3, Table 1 at the paper's own scale: 150 M distinct ids, eviction off.  The fraction
+    of ids left without a slot must match the printed cell (3 % relative or four standard
+    deviations of the count); 2.0x capacity with P = 64 must give zero collisions."""
+    import math
+    import os
+    golden = {}
+    with open(os.path.join(os.path.dirname(__file__), "golden", "table1_collision_rate.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                v = line.split()
+                golden[int(v[0])] = dict(zip((8, 16, 32, 64, 128, 256, 512), map(float, v[3:])))
+    n_ids, batch = 150_000_000, 262144
+    n_slots = size_m * 1_000_000
+    h = mp.mpzch_create(n_slots, max_probe, (mp.EVICT_NONE, 0), wl.HASH_SEED_BASE)
+    I = torch.empty(n_slots, dtype=torch.int64, device="cuda")
+    M = torch.empty(n_slots, dtype=torch.int32, device="cuda")
+    mp.mpzch_init_tensors(h, I, M)
+    mp.mpzch_reserve(h, batch)
+    calls = (n_ids + batch - 1) // batch
+    stats = torch.zeros((calls, mp.STAT_COUNT), dtype=torch.int64, device="cuda")
+    out = torch.empty(batch, dtype=torch.int64, device="cuda")
+    nev = torch.zeros(1, dtype=torch.int64, device="cuda")
+    for k, lo in enumerate(range(0, n_ids, batch)):
+        ids = wl.distinct_ids_device(lo, min(lo + batch, n_ids), "cuda")
+        mp.mpzch_remap(h, I, M, ids, k, out[: ids.numel()], None, nev, stats[k])
+    torch.cuda.synchronize()
+    tot = dict(zip(mp.STAT_NAMES, stats.sum(dim=0).tolist()))
+    assert tot["hit_pos"] == 0 and tot["miss_pos"] == n_ids and tot["evictions"] == 0
+    assert tot["inserts"] + tot["collisions"] == n_ids
+    assert int((I >= 0).sum().item()) == tot["inserts"]            # every placed id owns exactly one slot
+    got = 100.0 * tot["collisions"] / n_ids
+    want = golden[size_m][max_probe]
+    sigma = 100.0 * math.sqrt(max(want / 100.0 * n_ids, 1.0)) / n_ids
+    say(f"table1 {size_m}M P={max_probe}: {got:.4f}% (paper {want:.4f}%)")
+    assert abs(got - want) <= max(0.03 * want, 4 * sigma)
+    if size_m == 300 and max_probe == 64:
+        assert tot["collisions"] == 0
+    mp.mpzch_destroy(h)
