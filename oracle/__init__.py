@@ -20,6 +20,7 @@ _LIB = os.path.join(_HERE, "libmpzch_oracle.so")
 
 EVICT_NONE = 0
 EVICT_TTL = 1
+EVICT_LRU = 2
 
 STAT_NAMES = (
     "hit_pos", "miss_pos", "distinct_miss", "inserts",

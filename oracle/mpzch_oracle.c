@@ -28,7 +28,11 @@
  *                 every probe round the lowest first-occurrence batch index
  *                 wins a contended slot;
  *   invalid ids = negative ids: never stored, never match, map to the home
- *                 slot of their bit pattern.
+ *                 slot of their bit pattern;
+ *   LRU policy  = first empty slot of the range, else the entry with the oldest
+ *                 time stamp (ties: earlier round), never one seen at this step;
+ *                 contended slots go to the lower choice number, then to the
+ *                 lower first-occurrence batch index.
  *
  * Pins (tests/test_oracle_*.py): published SplitMix64 vectors; Table 1 of
  * the paper at reduced scale; the balls-in-bins closed form for P = 1;
@@ -40,7 +44,7 @@
 #include <stdlib.h>
 #include <string.h>
 
-enum { ORACLE_EVICT_NONE = 0, ORACLE_EVICT_TTL = 1 };
+enum { ORACLE_EVICT_NONE = 0, ORACLE_EVICT_TTL = 1, ORACLE_EVICT_LRU = 2 };
 
 typedef struct {
     int64_t  num_slots;   /* N */
@@ -190,10 +194,60 @@ int oracle_remap(const oracle_cfg *c, int64_t *I, int32_t *M,
         }
         st[ST_DISTINCT_MISS] = n_miss;
 
-        /* Stage 2 (Pass 2 "Allocation", outcomes 1 and 2): round-major,
-         * position-minor.  A claim writes M = step, so the slot is no longer
+        if (c->policy == ORACLE_EVICT_LRU) {
+            /* Stage 2, LRU policy (Sec. 3.4, last paragraph): a missed id takes the first
+             * empty slot of its range; if there is none it evicts the entry with the oldest
+             * time stamp (ties: the earlier probe round).  Entries seen at this very step are
+             * never evicted.  Every missed id therefore has a preference list -- empty slots
+             * in probe order, then evictable slots oldest first -- fixed by the state after
+             * Stage 1.  Choice-major, position-minor sweep: in sweep k every id still
+             * without a slot asks for its k-th choice, lowest batch position first. */
+            int32_t *pref = (int32_t *)malloc((size_t)(n_miss > 0 ? n_miss : 1) * (size_t)P * sizeof *pref);
+            int32_t *plen = (int32_t *)malloc((size_t)(n_miss > 0 ? n_miss : 1) * sizeof *plen);
+            if (!pref || !plen) { free(pref); free(plen); free(first); free(result); free(miss); return -1; }
+            for (int64_t k = 0; k < n_miss; ++k) {
+                int64_t h = oracle_home(ids[miss[k]], c->hash_seed, N);
+                int32_t *pl = pref + k * P;
+                int32_t len = 0;
+                for (int64_t r = 0; r < P; ++r)
+                    if (I[probe_slot(h, r, N)] == -1) pl[len++] = (int32_t)r;
+                int32_t start = len;
+                for (int64_t r = 0; r < P; ++r) {
+                    int64_t s = probe_slot(h, r, N);
+                    if (I[s] < 0 || M[s] == step) continue;
+                    int32_t at = len;                    /* insertion keeps (M, round) ascending */
+                    while (at > start && M[probe_slot(h, pl[at - 1], N)] > M[s]) { pl[at] = pl[at - 1]; --at; }
+                    pl[at] = (int32_t)r;
+                    ++len;
+                }
+                plen[k] = len;
+            }
+            for (int64_t choice = 0; choice < P; ++choice) {
+                for (int64_t k = 0; k < n_miss; ++k) {
+                    int64_t j = miss[k];
+                    if (result[j] >= 0 || choice >= plen[k]) continue;
+                    int64_t s = probe_slot(oracle_home(ids[j], c->hash_seed, N), pref[k * P + choice], N);
+                    if (I[s] != -1 && M[s] == step) continue;        /* taken earlier in this batch */
+                    int was_occupied = (I[s] != -1);
+                    I[s] = ids[j];
+                    M[s] = step;
+                    result[j] = s;
+                    if (was_occupied) {
+                        if (out_evicted && n_evicted < evicted_cap) out_evicted[n_evicted] = s;
+                        n_evicted++;
+                        st[ST_EVICTIONS]++;
+                    } else {
+                        st[ST_INSERTS]++;
+                    }
+                }
+            }
+            free(pref); free(plen);
+        }
+
+        /* Stage 2 (Pass 2 "Allocation", outcomes 1 and 2), TTL policy or eviction off:
+         * round-major, position-minor.  A claim writes M = step, so the slot is no longer
          * claimable for anyone visiting it later in this batch. */
-        for (int64_t r = 0; r < P; ++r) {
+        for (int64_t r = 0; r < P && c->policy != ORACLE_EVICT_LRU; ++r) {
             for (int64_t k = 0; k < n_miss; ++k) {
                 int64_t j = miss[k];
                 if (result[j] >= 0) continue;
