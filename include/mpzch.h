@@ -55,13 +55,17 @@ typedef enum {
     MPZCH_ERR_INVALID_ARG = 1,
     MPZCH_ERR_ALLOC = 2,       /* device or host allocation failed */
     MPZCH_ERR_HIP = 3,         /* a HIP runtime call failed        */
-    MPZCH_ERR_UNSUPPORTED = 4  /* e.g. MPZCH_EVICT_LRU             */
+    MPZCH_ERR_UNSUPPORTED = 4  /* e.g. MPZCH_EVICT_LRU in a group  */
 } mpzch_status_t;
 
 typedef enum {
     MPZCH_EVICT_NONE = 0, /* lookup + insert only (Sec. 3.3, eviction disabled)           */
     MPZCH_EVICT_TTL = 1,  /* lazy TTL eviction (Sec. 3.4)                                 */
-    MPZCH_EVICT_LRU = 2   /* Sec. 3.4 last paragraph; not implemented: MPZCH_ERR_UNSUPPORTED */
+    MPZCH_EVICT_LRU = 2   /* Sec. 3.4 last paragraph: first empty slot of the range, else evict the entry
+                             with the oldest metadata (ties: earlier probe round), never one whose metadata
+                             equals the current step; contended slots go to the lower choice number, then
+                             to the id whose first occurrence comes first.  Single tables with
+                             max_probe <= MPZCH_MAX_PROBE_LRU only (else MPZCH_ERR_UNSUPPORTED). */
 } mpzch_evict_kind_t;
 
 typedef struct {
@@ -85,13 +89,14 @@ enum {
 #define MPZCH_MAX_BATCH ((int64_t)1 << 30) /* positions per remap / lookup call          */
 #define MPZCH_MAX_PROBE (1 << 20)          /* upper bound accepted for max_probe          */
 #define MPZCH_MAX_GROUP_TABLES 64          /* tables per mpzch_group_t                    */
+#define MPZCH_MAX_PROBE_LRU 64             /* largest max_probe with MPZCH_EVICT_LRU      */
 
 /*
  * Creates a table handle (Algorithm 1's globals: P = max_probe; Sec. 3.4: policy).
  * Allocates no tensor and touches no GPU: scratch is allocated by the first remap
  * (or by mpzch_reserve) on the device that is current then.
  * Errors: INVALID_ARG for num_slots < 1, max_probe < 1 or > MPZCH_MAX_PROBE, ttl < 0,
- * unknown policy kind, out == NULL; UNSUPPORTED for MPZCH_EVICT_LRU.
+ * unknown policy kind, out == NULL; UNSUPPORTED for MPZCH_EVICT_LRU with max_probe > 64.
  * max_probe > num_slots is accepted and behaves as max_probe == num_slots.
  */
 mpzch_status_t mpzch_create(int64_t num_slots, int32_t max_probe, mpzch_eviction_policy_t policy,

@@ -205,7 +205,7 @@ TableDesc make_desc(const TableCfg &c, int64_t *I, int32_t *M, int64_t ev_begin,
     d.seed = c.seed;
     d.P = p_eff(c);
     d.ttl = c.ttl;
-    d.evict = c.kind == MPZCH_EVICT_TTL ? 1 : 0;
+    d.evict = c.kind == MPZCH_EVICT_TTL ? 1 : c.kind == MPZCH_EVICT_LRU ? 2 : 0;
     d.pad_ = 0;
     d.ev_begin = ev_begin;
     d.ev_cap = ev_cap;
@@ -231,7 +231,8 @@ mpzch_status_t launch_allocate(int32_t max_p, const Params &p, int num_cus, hipS
     // one wavefront per workgroup, one segment per workgroup pass; the lane phase covers the first
     // 8 or 16 slots of every window, longer windows continue in the wave phase
     const int grid = grid_for((int64_t)p.num_segs, 1, num_cus, 4 * group_blocks_per_cu());
-    if (max_p <= 8) hipLaunchKernelGGL((k_allocate<8>), dim3(grid), dim3(kWave), 0, s, p);
+    if (p.t0.evict == 2) hipLaunchKernelGGL(k_allocate_lru, dim3(grid), dim3(kWave), 0, s, p);
+    else if (max_p <= 8) hipLaunchKernelGGL((k_allocate<8>), dim3(grid), dim3(kWave), 0, s, p);
     else hipLaunchKernelGGL((k_allocate<16>), dim3(grid), dim3(kWave), 0, s, p);
     LAUNCH_CHECK();
     return MPZCH_OK;
@@ -313,7 +314,7 @@ mpzch_status_t fill32(int32_t *dst, int64_t count, int32_t value, hipStream_t s)
 bool valid_cfg(int64_t num_slots, int32_t max_probe, mpzch_eviction_policy_t policy)
 {
     if (num_slots < 1 || max_probe < 1 || max_probe > MPZCH_MAX_PROBE) return false;
-    if (policy.kind != MPZCH_EVICT_NONE && policy.kind != MPZCH_EVICT_TTL) return false;
+    if (policy.kind != MPZCH_EVICT_NONE && policy.kind != MPZCH_EVICT_TTL && policy.kind != MPZCH_EVICT_LRU) return false;
     if (policy.ttl < 0) return false;
     return true;
 }
@@ -342,8 +343,8 @@ mpzch_status_t mpzch_create(int64_t num_slots, int32_t max_probe, mpzch_eviction
 {
     if (!out) return MPZCH_ERR_INVALID_ARG;
     *out = nullptr;
-    if (policy.kind == MPZCH_EVICT_LRU) return MPZCH_ERR_UNSUPPORTED;
     if (!valid_cfg(num_slots, max_probe, policy)) return MPZCH_ERR_INVALID_ARG;
+    if (policy.kind == MPZCH_EVICT_LRU && max_probe > MPZCH_MAX_PROBE_LRU) return MPZCH_ERR_UNSUPPORTED;
     mpzch_table *t = new (std::nothrow) mpzch_table();
     if (!t) return MPZCH_ERR_ALLOC;
     t->cfg = {num_slots, max_probe, policy.kind, policy.ttl, hash_seed};
@@ -467,8 +468,10 @@ mpzch_status_t mpzch_group_create(mpzch_table_t *const *tables, int32_t num_tabl
     if (!out) return MPZCH_ERR_INVALID_ARG;
     *out = nullptr;
     if (!tables || num_tables < 1 || num_tables > MPZCH_MAX_GROUP_TABLES) return MPZCH_ERR_INVALID_ARG;
-    for (int i = 0; i < num_tables; ++i)
+    for (int i = 0; i < num_tables; ++i) {
         if (!tables[i]) return MPZCH_ERR_INVALID_ARG;
+        if (tables[i]->cfg.kind == MPZCH_EVICT_LRU) return MPZCH_ERR_UNSUPPORTED;   // groups: TTL / none only
+    }
     mpzch_group *g = new (std::nothrow) mpzch_group();
     if (!g) return MPZCH_ERR_ALLOC;
     for (int i = 0; i < num_tables; ++i) g->cfgs.push_back(tables[i]->cfg);

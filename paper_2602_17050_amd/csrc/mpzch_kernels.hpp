@@ -719,6 +719,105 @@ __global__ __launch_bounds__(kWave) void k_allocate(Params p)
     }
 }
 
+// ------------------------------------------------------------------ allocation, LRU policy
+// LRU (Sec. 3.4, last paragraph): a missed id takes the first empty slot of its range, else it
+// evicts the entry with the oldest time stamp (ties: the earlier probe round), never one seen at
+// the current step.  Its preference list -- empty slots in probe order, then evictable slots
+// oldest first -- follows from the state at the start of allocation, which stays readable while
+// claims are in flight: a tag keeps the was-occupied bit and metadata is not written before
+// k_finalize.  The tag's round field carries the CHOICE number, so a slot ends with the claimant
+// of the lowest (choice, position).  One wavefront serves one claimant, one lane per slot of its
+// window (max_probe <= 64); a displaced claimant is carried on from its next choice.
+// Returns the probe round at which the first claimant was placed, or -1.
+__device__ __forceinline__ int32_t claim_wave_lru(const Params &p, const TableDesc &d, uint32_t cpos, int32_t choice)
+{
+    const int lane = lane_id();
+    int32_t first_round = -1;
+    bool is_first = true;
+    for (;;) {
+        const int64_t home = home_slot(p.ids[cpos], d.seed, d.N);
+        const bool in = lane < d.P;
+        int64_t s = 0, v = 0;
+        int32_t m = 0;
+        if (in) {
+            s = wrap(home + lane, d.N);
+            v = __hip_atomic_load(&d.I[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            m = d.M[s];
+        }
+        const bool base_empty = in && (v == -1 || (is_tag(v) && !tag_occ(v)));
+        const bool evictable = in && (v >= 0 || (is_tag(v) && tag_occ(v))) && m != p.step;
+        const uint64_t emask = __ballot(base_empty);
+        const int n_empty = __popcll(emask);
+        // rank of this lane's slot in the claimant's preference list
+        int older = 0;
+        for (int l = 0; l < d.P; ++l) {
+            const int32_t ml = __shfl(m, l);
+            const bool el = __shfl((int)evictable, l);
+            if (el && (ml < m || (ml == m && l < lane))) ++older;
+        }
+        int rank = 0x7FFFFFFF;
+        if (base_empty) rank = __popcll(emask & ((1ull << lane) - 1ull));
+        else if (evictable) rank = n_empty + older;
+        const int n_choices = n_empty + __popcll(__ballot(evictable));
+        bool placed = false;
+        int64_t displaced = 0;
+        for (; choice < n_choices && !placed; ++choice) {
+            const uint64_t wb = __ballot(rank == choice);
+            const int who = __ffsll((unsigned long long)wb) - 1;      // exactly one lane has this rank
+            int64_t old = 0, mine = 0;
+            if (lane == who) {
+                mine = make_tag((uint32_t)choice, cpos, base_empty ? 0u : 1u);
+                old = __hip_atomic_fetch_min(&d.I[s], mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            old = shfl64(old, who);
+            mine = shfl64(mine, who);
+            if (is_tag(old) && old < mine) continue;                    // a better claim holds this slot
+            placed = true;
+            displaced = is_tag(old) ? old : 0;
+            if (is_first) first_round = who;
+        }
+        is_first = false;
+        if (!placed || !displaced) break;
+        cpos = tag_pos(displaced);                                       // same table: same slot
+        choice = (int32_t)tag_round(displaced) + 1;
+    }
+    return first_round;
+}
+
+__global__ __launch_bounds__(kWave) void k_allocate_lru(Params p)
+{
+    const int lane = threadIdx.x;
+    const bool multi = p.num_tables > 1;
+    for (int64_t seg = blockIdx.x; seg < p.num_segs; seg += gridDim.x) {
+        const uint32_t cnt = p.seg_cnt[seg];
+        const int64_t seg_base = seg * p.seg_chunks * kWave;
+        if (seg_base >= p.n) break;
+        for (uint32_t j0 = 0; j0 < cnt; j0 += kWave) {
+            const int64_t idx = seg_base + j0 + lane;
+            const bool have = j0 + lane < cnt;
+            uint32_t pos = 0;
+            bool agent = false;
+            if (have) {
+                pos = p.list[idx];
+                const uint32_t first = p.set_slot[p.ent[idx]];
+                p.first_of[idx] = first;
+                agent = first == pos;
+            }
+            uint32_t hint = kHintNone;
+            uint64_t am = __ballot(agent);
+            while (am) {
+                const int src = __ffsll((unsigned long long)am) - 1;
+                am &= am - 1;
+                const uint32_t cpos = __shfl(pos, src);
+                const TableDesc dw = multi ? p.descs[find_table(p.offsets, p.num_tables, (int64_t)cpos)] : p.t0;
+                const int32_t fr = claim_wave_lru(p, dw, cpos, 0);
+                if (lane == src) hint = fr < 0 ? kHintUnplaced : (uint32_t)fr;
+            }
+            if (have) p.hint[idx] = (uint8_t)hint;
+        }
+    }
+}
+
 // ------------------------------------------------------------------ finalize
 // Appends the staged evicted slots of one wavefront to table `table`'s list.
 __device__ __forceinline__ void flush_evicted(const Params &p, const int64_t *buf, int &count, int table)

@@ -16,8 +16,9 @@ class Pair:
     """One table on both sides."""
 
     def __init__(self, num_slots, max_probe, ttl, evict=True, hash_seed=0, emb=None):
-        kind_g = mp.EVICT_TTL if evict else mp.EVICT_NONE
-        kind_o = oracle.EVICT_TTL if evict else oracle.EVICT_NONE
+        # evict: True = TTL, False = off, "lru" = LRU
+        kind_g = mp.EVICT_LRU if evict == "lru" else mp.EVICT_TTL if evict else mp.EVICT_NONE
+        kind_o = oracle.EVICT_LRU if evict == "lru" else oracle.EVICT_TTL if evict else oracle.EVICT_NONE
         self.g = mp.MpzchTable(num_slots, max_probe, kind_g, ttl, hash_seed)
         self.o = oracle.Table(num_slots, max_probe, kind_o, ttl, hash_seed)
         self.emb_o = None

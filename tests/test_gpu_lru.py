@@ -1,0 +1,63 @@
+"""GPU parity of the LRU eviction policy against the oracle, bit for bit."""
+import numpy as np
+import pytest
+
+from paper_2602_17050_amd import workloads as wl
+from gpu_common import Pair, say
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    # (slots, max_probe, universe, batch, steps)
+    (1, 1, 4, 9, 6),
+    (7, 3, 20, 64, 10),
+    (50, 8, 300, 257, 12),
+    (100, 16, 400, 1000, 12),
+    (257, 33, 2000, 4096, 10),
+    (1000, 64, 5000, 8191, 8),
+    (64, 64, 300, 500, 8),
+    (4099, 4, 30000, 20000, 10),
+]
+
+
+@pytest.mark.parametrize("case", CASES, ids=[f"N{c[0]}_P{c[1]}" for c in CASES])
+def test_lru_contended_small_tables(case):
+    n_slots, max_probe, universe, batch, steps = case
+    rng = np.random.Generator(np.random.Philox(key=(hash(case) ^ 0x1234) & 0xFFFFFFFF))
+    p = Pair(n_slots, max_probe, 0, "lru", hash_seed=0xBEE0 + n_slots)
+    step = 0
+    evictions = 0
+    for k in range(steps):
+        step += int(rng.integers(0, 3))
+        kind = k % 3
+        if kind == 0:
+            ids = wl.zipf_ids(rng, batch, 1.1, universe)
+        elif kind == 1:
+            ids = rng.integers(-2, universe, size=batch // 2 + 1)
+        else:
+            ids = wl.rank_to_id(rng.integers(universe, 3 * universe, size=batch))
+        say("lru case", case, "step", step, "n", len(ids))
+        evictions += p.step(ids, step).stats["evictions"]
+        assert p.o.check_state()[0] == 0
+    assert evictions > 0 or n_slots == 1
+    p.close()
+
+
+def test_lru_one_million_slots_with_row_reset():
+    """Config-2 shaped stream under LRU: the table fills up, then every new id evicts the oldest
+    entry of its range; rows of evicted slots are reset."""
+    spec = wl.c2_spec()
+    emb = wl.embedding_pattern(spec.emb_rows, 8, np.float32)
+    p = Pair(spec.num_slots, spec.max_probe, 0, "lru", spec.hash_seed, emb)
+    step0, pre = wl.c2_prefill()
+    p.step(pre, step0, check_state=False)
+    p.step(wl.scattered_prefill_ids(20_000_000, 20_650_000), 0, check_state=False)   # load ~0.95
+    tot = 0
+    for step in range(1, 21):
+        r = p.step(wl.c2_batch(step), step, check_state=(step % 10 == 0))
+        tot += r.stats["evictions"]
+    say("lru c2-shaped: evictions", tot, "load", float((p.o.identities >= 0).mean()))
+    assert tot > 10000
+    p.check_state()
+    assert p.o.check_state()[0] == 0
+    p.close()

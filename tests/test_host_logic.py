@@ -53,8 +53,9 @@ def test_create_validates_arguments_without_a_gpu(binding):
         with pytest.raises(b.MpzchError) as e:
             b.mpzch_create(args[0], args[1], args[2], 0)
         assert e.value.status == 1
+    b.mpzch_destroy(b.mpzch_create(16, 8, (b.EVICT_LRU, 0), 0))
     with pytest.raises(b.MpzchError) as e:
-        b.mpzch_create(16, 8, (b.EVICT_LRU, 0), 0)
+        b.mpzch_create(1000, 65, (b.EVICT_LRU, 0), 0)        # LRU: max_probe <= 64
     assert e.value.status == 4
     assert b.mpzch_status_string(0) == "ok"
     assert b.mpzch_status_string(1) == "invalid argument"
@@ -69,6 +70,11 @@ def test_group_create_validates_arguments(binding):
     b.mpzch_group_destroy(g)
     with pytest.raises(b.MpzchError):
         b.mpzch_group_create([])
+    h = b.mpzch_create(100, 4, (b.EVICT_LRU, 0), 0)
+    with pytest.raises(b.MpzchError) as e:
+        b.mpzch_group_create([h])                             # groups take TTL / no-eviction tables only
+    assert e.value.status == 4
+    b.mpzch_destroy(h)
 
 
 def test_missing_library_fails_loudly(binding, tmp_path):
