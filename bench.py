@@ -46,6 +46,7 @@ def main():
     ap.add_argument("--scale", type=float, default=1.0, help="shrink slots and batch (quick checks only)")
     ap.add_argument("--cpu-steps", type=int, default=2, help="steps the oracle replays for cpu_baseline (0 = skip)")
     ap.add_argument("--no-kernel-timing", action="store_true")
+    ap.add_argument("--policy", default="ttl", choices=["ttl", "lru"], help="eviction policy (headline / c4 workloads)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build runs on ONE GPU (a table shard is local to its GPU; see DESIGN.md on sharding). "
@@ -77,7 +78,8 @@ def main():
     log(f"[bench] workload={args.workload} slots={t.num_slots} P={t.max_probe} ttl={t.ttl} batch={spec.batch} "
         f"prefill={spec.prefill_ids} emb={t.emb_rows}x{t.emb_dim} {t.emb_dtype}")
 
-    g = mp.MpzchTable(t.num_slots, t.max_probe, mp.EVICT_TTL, t.ttl, t.hash_seed, max_batch=max(spec.batch, 1 << 24))
+    kind = mp.EVICT_LRU if args.policy == "lru" else mp.EVICT_TTL
+    g = mp.MpzchTable(t.num_slots, t.max_probe, kind, t.ttl, t.hash_seed, max_batch=max(spec.batch, 1 << 24))
     emb = torch.ones((t.emb_rows, t.emb_dim), dtype=torch.bfloat16, device=dev)
 
     # ---- prefill at step 0 (ids PREFILL_ID_BASE + k, generated on the device in chunks)
@@ -186,7 +188,8 @@ def main():
     cpu = None
     if args.cpu_steps > 0:
         import oracle
-        o = oracle.Table(t.num_slots, t.max_probe, oracle.EVICT_TTL, t.ttl, t.hash_seed, host_I, host_M)
+        o = oracle.Table(t.num_slots, t.max_probe, oracle.EVICT_LRU if args.policy == "lru" else oracle.EVICT_TTL,
+                         t.ttl, t.hash_seed, host_I, host_M)
         n_cpu = min(args.cpu_steps, K)
         cpu_t = 0.0
         same = True
@@ -214,7 +217,8 @@ def main():
         "dtype": "int64",
         "data": "synthetic",
         "config": {
-            "workload": f"{args.workload}: {t.num_slots}-slot table, P={t.max_probe}, TTL={t.ttl}, load "
+            "workload": f"{args.workload}: {t.num_slots}-slot table, P={t.max_probe}, "
+                        f"{'LRU' if args.policy == 'lru' else 'TTL=' + str(t.ttl)}, load "
                         f"{spec.prefill_ids / t.num_slots:.2f}, {spec.batch} ids/step, "
                         f"{int(spec.new_fraction * 100)}% new ids/step, reset rows of {t.emb_rows}x{t.emb_dim} bf16",
             "num_slots": t.num_slots, "max_probe": t.max_probe, "ttl": t.ttl, "batch": spec.batch, "scale": args.scale,
