@@ -181,6 +181,59 @@ mpzch_status_t mpzch_reset_rows(const int64_t *slots, const int64_t *num_slots_d
                                 const void *init_row, void *stream);
 
 /*
+ * Reset of several tensors in one launch (Sec. 3.4: "both the embedding weights and the optimizer
+ * state (e.g., momentum) are reset"): as mpzch_reset_rows for each of tensors[0 .. num_tensors).
+ * tensors [host] array of 1..4 descriptions; every field as in mpzch_reset_rows.
+ */
+typedef struct {
+    void *rows;               /* [dev] */
+    int64_t num_rows;
+    int64_t row_bytes;
+    int64_t row_stride_bytes;
+    const void *init_row;     /* [dev] row_bytes bytes, or NULL for zeros */
+} mpzch_rows_t;
+mpzch_status_t mpzch_reset_rows_multi(const int64_t *slots, const int64_t *num_slots_dev, int64_t slots_cap,
+                                      const mpzch_rows_t *tensors, int32_t num_tensors, void *stream);
+
+/*
+ * Inference lookup fused with the embedding gather (Sec. 3.7): out_rows[j, :] = rows[slot_j mod num_rows, :]
+ * where slot_j is what mpzch_lookup returns for ids[j] (the home slot's row when the id is not resident).
+ * out_rows [dev] n x row_bytes bytes, dense.  scratch_slots [dev] int64[n]: the looked-up slots (also an
+ * output).  out_found [dev] uint8[n] or NULL.
+ */
+mpzch_status_t mpzch_lookup_gather(const mpzch_table_t *t, const int64_t *identities,
+                                   const int64_t *ids, int64_t n,
+                                   const void *rows, int64_t num_rows, int64_t row_bytes, int64_t row_stride_bytes,
+                                   void *out_rows, int64_t *scratch_slots, uint8_t *out_found, void *stream);
+
+/*
+ * Streaming delta (Sec. 3.8: sparse delta publishing; "the corresponding entries in the identities tensor
+ * are updated in conjunction with the embedding rows").
+ *
+ * mpzch_collect_delta (training side): every occupied slot whose metadata is >= since_step -- the slots
+ * whose id was seen, inserted or refreshed since then -- goes to the list (out_slots[k], out_ids[k]), order
+ * unspecified.  out_count [dev] int64[1] receives the number found; when it exceeds cap the lists hold the
+ * first cap that were written.  Needs metadata that holds last-seen steps (TTL, LRU or no eviction).
+ *
+ * mpzch_gather_rows: out_rows[k, :] = rows[slots[k] mod num_rows, :] for k < min(*count_dev, cap)
+ * (count_dev may be NULL: then cap rows) -- the payload of a delta.
+ *
+ * mpzch_apply_delta (inference side): for k < min(*count_dev, cap): first
+ * rows[slots[k] mod num_rows, :] = delta_rows[k, :], then identities[slots[k]] = ids[k].  rows may be NULL
+ * (identities only).  Slots outside [0, num_slots) are skipped.
+ */
+mpzch_status_t mpzch_collect_delta(const mpzch_table_t *t, const int64_t *identities, const int32_t *metadata,
+                                   int32_t since_step, int64_t *out_slots, int64_t *out_ids, int64_t cap,
+                                   int64_t *out_count, void *stream);
+mpzch_status_t mpzch_gather_rows(const int64_t *slots, const int64_t *count_dev, int64_t cap,
+                                 const void *rows, int64_t num_rows, int64_t row_bytes, int64_t row_stride_bytes,
+                                 void *out_rows, void *stream);
+mpzch_status_t mpzch_apply_delta(int64_t *identities, int64_t num_slots,
+                                 const int64_t *slots, const int64_t *ids, const int64_t *count_dev, int64_t cap,
+                                 void *rows, int64_t num_rows, int64_t row_bytes, int64_t row_stride_bytes,
+                                 const void *delta_rows, void *stream);
+
+/*
  * Several tables remapped by one launch sequence (Sec. 3.4: one kernel serving tables of
  * several features; Sec. 3.6: a keyed jagged batch of an embedding collection).
  * tables [host] array of num_tables handles (1..MPZCH_MAX_GROUP_TABLES); the group keeps

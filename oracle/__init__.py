@@ -191,3 +191,21 @@ def reset_rows(slots, rows: np.ndarray, init_row: np.ndarray | None = None):
                                    row_bytes, init_p)
     if rc != 0:
         raise RuntimeError("oracle_reset_rows failed")
+
+
+def collect_delta(table: Table, since_step: int):
+    """Sec. 3.8 sparse delta: (slots, ids) of every occupied slot seen at or after since_step, ascending slot."""
+    slots = np.nonzero((table.identities >= 0) & (table.metadata >= since_step))[0].astype(np.int64)
+    return slots, table.identities[slots].copy()
+
+
+def gather_rows(slots, rows: np.ndarray) -> np.ndarray:
+    return rows[_i64(slots) % rows.shape[0]].copy()
+
+
+def apply_delta(identities: np.ndarray, slots, ids, rows: np.ndarray | None = None, delta_rows=None):
+    """Sec. 3.8: identities entries are updated together with the embedding rows they belong to."""
+    slots = _i64(slots)
+    if rows is not None:
+        rows[slots % rows.shape[0]] = delta_rows
+    identities[slots] = _i64(ids)

@@ -24,6 +24,7 @@ EXPORTED = (
     "mpzch_lookup", "mpzch_reset_rows", "mpzch_group_create", "mpzch_group_destroy",
     "mpzch_group_reserve", "mpzch_remap_jagged", "mpzch_set_kernel_timing", "mpzch_kernel_times",
     "mpzch_group_set_kernel_timing", "mpzch_group_kernel_times", "mpzch_status_string",
+    "mpzch_reset_rows_multi", "mpzch_lookup_gather", "mpzch_collect_delta", "mpzch_gather_rows", "mpzch_apply_delta",
 )
 
 
@@ -35,6 +36,11 @@ class MpzchError(RuntimeError):
 
 class _Policy(ctypes.Structure):
     _fields_ = [("kind", ctypes.c_int32), ("ttl", ctypes.c_int32)]
+
+
+class _Rows(ctypes.Structure):
+    _fields_ = [("rows", ctypes.c_void_p), ("num_rows", ctypes.c_int64), ("row_bytes", ctypes.c_int64),
+                ("row_stride_bytes", ctypes.c_int64), ("init_row", ctypes.c_void_p)]
 
 
 _lib = None
@@ -59,6 +65,11 @@ def load_library(path: str | None = None):
     lib.mpzch_remap.argtypes = [vp, vp, vp, vp, i64, i32, vp, vp, i64, vp, vp, vp]
     lib.mpzch_lookup.argtypes = [vp, vp, vp, i64, vp, vp, vp]
     lib.mpzch_reset_rows.argtypes = [vp, vp, i64, vp, i64, i64, i64, vp, vp]
+    lib.mpzch_reset_rows_multi.argtypes = [vp, vp, i64, ctypes.POINTER(_Rows), i32, vp]
+    lib.mpzch_lookup_gather.argtypes = [vp, vp, vp, i64, vp, i64, i64, i64, vp, vp, vp, vp]
+    lib.mpzch_collect_delta.argtypes = [vp, vp, vp, i32, vp, vp, i64, vp, vp]
+    lib.mpzch_gather_rows.argtypes = [vp, vp, i64, vp, i64, i64, i64, vp, vp]
+    lib.mpzch_apply_delta.argtypes = [vp, i64, vp, vp, vp, i64, vp, i64, i64, i64, vp, vp]
     lib.mpzch_group_create.argtypes = [ctypes.POINTER(vp), i32, ctypes.POINTER(vp)]
     lib.mpzch_group_destroy.argtypes = [vp]
     lib.mpzch_group_reserve.argtypes = [vp, i64]
@@ -152,6 +163,57 @@ def mpzch_reset_rows(slots, num_slots_dev, rows, init_row=None, num_rows: int | 
                                            ctypes.c_void_p(rows.data_ptr()), nrows, row_bytes, stride,
                                            None if init_row is None else ctypes.c_void_p(init_row.data_ptr()),
                                            _stream()), "mpzch_reset_rows")
+
+
+def _row_geometry(rows):
+    assert rows.dim() == 2 and rows.stride(1) == 1 and rows.is_cuda
+    return rows.shape[0], rows.shape[1] * rows.element_size(), rows.stride(0) * rows.element_size()
+
+
+def mpzch_reset_rows_multi(slots, num_slots_dev, tensors, init_rows=None):
+    """tensors: list of 2-D device tensors (weights, optimizer state, ...), reset in one launch."""
+    init_rows = init_rows or [None] * len(tensors)
+    arr = (_Rows * len(tensors))()
+    for k, (t, init) in enumerate(zip(tensors, init_rows)):
+        n, rb, st = _row_geometry(t)
+        arr[k] = _Rows(t.data_ptr(), n, rb, st, None if init is None else init.data_ptr())
+    _check(load_library().mpzch_reset_rows_multi(_ptr(slots, torch.int64), _ptr(num_slots_dev, torch.int64),
+                                                 slots.numel(), arr, len(tensors), _stream()), "mpzch_reset_rows_multi")
+
+
+def mpzch_lookup_gather(handle, identities, ids, rows, out_rows, scratch_slots, out_found=None):
+    n, rb, st = _row_geometry(rows)
+    assert out_rows.is_contiguous() and out_rows.numel() * out_rows.element_size() == ids.numel() * rb
+    _check(load_library().mpzch_lookup_gather(handle, _ptr(identities, torch.int64), _ptr(ids, torch.int64), ids.numel(),
+                                              ctypes.c_void_p(rows.data_ptr()), n, rb, st,
+                                              ctypes.c_void_p(out_rows.data_ptr()), _ptr(scratch_slots, torch.int64),
+                                              _ptr(out_found, torch.uint8), _stream()), "mpzch_lookup_gather")
+
+
+def mpzch_collect_delta(handle, identities, metadata, since_step: int, out_slots, out_ids, out_count):
+    _check(load_library().mpzch_collect_delta(handle, _ptr(identities, torch.int64), _ptr(metadata, torch.int32),
+                                              since_step, _ptr(out_slots, torch.int64), _ptr(out_ids, torch.int64),
+                                              out_slots.numel(), _ptr(out_count, torch.int64), _stream()),
+           "mpzch_collect_delta")
+
+
+def mpzch_gather_rows(slots, count_dev, rows, out_rows):
+    n, rb, st = _row_geometry(rows)
+    assert out_rows.is_contiguous()
+    _check(load_library().mpzch_gather_rows(_ptr(slots, torch.int64), _ptr(count_dev, torch.int64), slots.numel(),
+                                            ctypes.c_void_p(rows.data_ptr()), n, rb, st,
+                                            ctypes.c_void_p(out_rows.data_ptr()), _stream()), "mpzch_gather_rows")
+
+
+def mpzch_apply_delta(identities, slots, ids, count_dev, rows=None, delta_rows=None):
+    if rows is not None:
+        n, rb, st = _row_geometry(rows)
+        rp, dp = ctypes.c_void_p(rows.data_ptr()), ctypes.c_void_p(delta_rows.data_ptr())
+    else:
+        n, rb, st, rp, dp = 0, 0, 0, None, None
+    _check(load_library().mpzch_apply_delta(_ptr(identities, torch.int64), identities.numel(), _ptr(slots, torch.int64),
+                                            _ptr(ids, torch.int64), _ptr(count_dev, torch.int64), slots.numel(),
+                                            rp, n, rb, st, dp, _stream()), "mpzch_apply_delta")
 
 
 def mpzch_group_create(handles):

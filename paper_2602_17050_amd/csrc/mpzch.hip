@@ -463,6 +463,143 @@ mpzch_status_t mpzch_reset_rows(const int64_t *slots, const int64_t *num_slots_d
     return MPZCH_OK;
 }
 
+namespace {
+// geometry shared by the row movers: 16-byte chunks when everything is 16-byte aligned, else 4-byte
+struct RowGeom { bool ok; bool wide; int64_t chunks; };
+RowGeom row_geom(const void *rows, int64_t row_bytes, int64_t row_stride_bytes, const void *other)
+{
+    RowGeom g{false, false, 0};
+    if (row_bytes < 4 || row_stride_bytes < row_bytes || (row_bytes & 3) || (row_stride_bytes & 3)) return g;
+    if (((uintptr_t)rows & 3) || ((uintptr_t)other & 3)) return g;
+    g.wide = !(row_bytes & 15) && !(row_stride_bytes & 15) && !((uintptr_t)rows & 15) && !((uintptr_t)other & 15);
+    g.chunks = g.wide ? row_bytes / 16 : row_bytes / 4;
+    g.ok = g.chunks <= 0x7FFFFFFF;
+    return g;
+}
+int row_grid(int64_t items)
+{
+    int64_t want = (items + kBlock - 1) / kBlock;
+    if (want > 8192) want = 8192;
+    if (want < 1) want = 1;
+    return (int)want;
+}
+}  // namespace
+
+mpzch_status_t mpzch_reset_rows_multi(const int64_t *slots, const int64_t *num_slots_dev, int64_t slots_cap,
+                                      const mpzch_rows_t *tensors, int32_t num_tensors, void *stream)
+{
+    if (!num_slots_dev || slots_cap < 0 || !tensors || num_tensors < 1 || num_tensors > kMaxResetTensors)
+        return MPZCH_ERR_INVALID_ARG;
+    RowsDescs ds;
+    std::memset(&ds, 0, sizeof ds);
+    bool wide = true;
+    for (int i = 0; i < num_tensors; ++i) {
+        const mpzch_rows_t &t = tensors[i];
+        if (!t.rows || t.num_rows < 1) return MPZCH_ERR_INVALID_ARG;
+        const RowGeom g = row_geom(t.rows, t.row_bytes, t.row_stride_bytes, t.init_row);
+        if (!g.ok) return MPZCH_ERR_INVALID_ARG;
+        wide = wide && g.wide;
+    }
+    int64_t total = 0;
+    for (int i = 0; i < num_tensors; ++i) {
+        const mpzch_rows_t &t = tensors[i];
+        ds.t[i].rows = (char *)t.rows;
+        ds.t[i].init_row = t.init_row;
+        ds.t[i].num_rows = t.num_rows;
+        ds.t[i].row_stride_bytes = t.row_stride_bytes;
+        ds.t[i].chunks = (int32_t)(wide ? t.row_bytes / 16 : t.row_bytes / 4);
+        total += ds.t[i].chunks;
+    }
+    if (total > 0x7FFFFFFF) return MPZCH_ERR_INVALID_ARG;
+    ds.count = num_tensors;
+    ds.total_chunks = (int32_t)total;
+    if (slots_cap == 0) return MPZCH_OK;
+    if (!slots) return MPZCH_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    const int grid = row_grid(slots_cap * total);
+    if (wide) hipLaunchKernelGGL((k_reset_rows_multi<u32x4>), dim3(grid), dim3(kBlock), 0, s, slots, num_slots_dev, slots_cap, ds);
+    else hipLaunchKernelGGL((k_reset_rows_multi<uint32_t>), dim3(grid), dim3(kBlock), 0, s, slots, num_slots_dev, slots_cap, ds);
+    LAUNCH_CHECK();
+    return MPZCH_OK;
+}
+
+mpzch_status_t mpzch_gather_rows(const int64_t *slots, const int64_t *count_dev, int64_t cap,
+                                 const void *rows, int64_t num_rows, int64_t row_bytes, int64_t row_stride_bytes,
+                                 void *out_rows, void *stream)
+{
+    if (cap < 0 || !rows || num_rows < 1 || !out_rows) return MPZCH_ERR_INVALID_ARG;
+    const RowGeom g = row_geom(rows, row_bytes, row_stride_bytes, out_rows);
+    if (!g.ok) return MPZCH_ERR_INVALID_ARG;
+    if (cap == 0) return MPZCH_OK;
+    if (!slots) return MPZCH_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    const int grid = row_grid(cap * g.chunks);
+    if (g.wide)
+        hipLaunchKernelGGL((k_gather_rows<u32x4>), dim3(grid), dim3(kBlock), 0, s, slots, count_dev, cap, (const char *)rows,
+                           num_rows, (int32_t)g.chunks, row_stride_bytes, (u32x4 *)out_rows);
+    else
+        hipLaunchKernelGGL((k_gather_rows<uint32_t>), dim3(grid), dim3(kBlock), 0, s, slots, count_dev, cap,
+                           (const char *)rows, num_rows, (int32_t)g.chunks, row_stride_bytes, (uint32_t *)out_rows);
+    LAUNCH_CHECK();
+    return MPZCH_OK;
+}
+
+mpzch_status_t mpzch_lookup_gather(const mpzch_table_t *t, const int64_t *identities,
+                                   const int64_t *ids, int64_t n,
+                                   const void *rows, int64_t num_rows, int64_t row_bytes, int64_t row_stride_bytes,
+                                   void *out_rows, int64_t *scratch_slots, uint8_t *out_found, void *stream)
+{
+    if (n > 0 && !scratch_slots) return MPZCH_ERR_INVALID_ARG;
+    mpzch_status_t st = mpzch_lookup(t, identities, ids, n, scratch_slots, out_found, stream);
+    if (st != MPZCH_OK) return st;
+    return mpzch_gather_rows(scratch_slots, nullptr, n, rows, num_rows, row_bytes, row_stride_bytes, out_rows, stream);
+}
+
+mpzch_status_t mpzch_collect_delta(const mpzch_table_t *t, const int64_t *identities, const int32_t *metadata,
+                                   int32_t since_step, int64_t *out_slots, int64_t *out_ids, int64_t cap,
+                                   int64_t *out_count, void *stream)
+{
+    if (!t || !identities || !metadata || !out_count || cap < 0) return MPZCH_ERR_INVALID_ARG;
+    if (cap > 0 && (!out_slots || !out_ids)) return MPZCH_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    mpzch_table *mt = const_cast<mpzch_table *>(t);
+    TRY(mt->sc.query_device());
+    TRY(fill64(out_count, 1, 0, s));
+    const int grid = grid_for(t->cfg.num_slots, 4 * kBlock, mt->sc.num_cus, 8);
+    hipLaunchKernelGGL(k_collect_delta, dim3(grid), dim3(kBlock), 0, s, identities, metadata, t->cfg.num_slots,
+                       since_step, out_slots, out_ids, cap, (unsigned long long *)out_count);
+    LAUNCH_CHECK();
+    return MPZCH_OK;
+}
+
+mpzch_status_t mpzch_apply_delta(int64_t *identities, int64_t num_slots,
+                                 const int64_t *slots, const int64_t *ids, const int64_t *count_dev, int64_t cap,
+                                 void *rows, int64_t num_rows, int64_t row_bytes, int64_t row_stride_bytes,
+                                 const void *delta_rows, void *stream)
+{
+    if (!identities || num_slots < 1 || cap < 0) return MPZCH_ERR_INVALID_ARG;
+    RowGeom g{true, false, 1};
+    if (rows) {
+        if (num_rows < 1 || !delta_rows) return MPZCH_ERR_INVALID_ARG;
+        g = row_geom(rows, row_bytes, row_stride_bytes, delta_rows);
+        if (!g.ok) return MPZCH_ERR_INVALID_ARG;
+    }
+    if (cap == 0) return MPZCH_OK;
+    if (!slots || !ids) return MPZCH_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    const int grid = row_grid(cap * g.chunks);
+    if (g.wide)
+        hipLaunchKernelGGL((k_apply_delta<u32x4>), dim3(grid), dim3(kBlock), 0, s, identities, num_slots, slots, ids,
+                           count_dev, cap, (char *)rows, num_rows, (int32_t)g.chunks, row_stride_bytes,
+                           (const u32x4 *)delta_rows);
+    else
+        hipLaunchKernelGGL((k_apply_delta<uint32_t>), dim3(grid), dim3(kBlock), 0, s, identities, num_slots, slots, ids,
+                           count_dev, cap, (char *)rows, num_rows, (int32_t)g.chunks, row_stride_bytes,
+                           (const uint32_t *)delta_rows);
+    LAUNCH_CHECK();
+    return MPZCH_OK;
+}
+
 mpzch_status_t mpzch_group_create(mpzch_table_t *const *tables, int32_t num_tables, mpzch_group_t **out)
 {
     if (!out) return MPZCH_ERR_INVALID_ARG;

@@ -1110,4 +1110,134 @@ __global__ __launch_bounds__(kBlock) void k_reset_rows(const int64_t *slots, con
     }
 }
 
+// rows[(slots[k] mod num_rows)] <- init for several tensors at once (embedding weights and
+// optimizer state, Sec. 3.4): one thread per VEC-byte chunk of a row of one tensor.
+struct RowsDesc {
+    char *rows;
+    const void *init_row;
+    int64_t num_rows;
+    int64_t row_stride_bytes;
+    int32_t chunks;          // VEC-sized chunks per row
+    int32_t pad_;
+};
+constexpr int kMaxResetTensors = 4;
+struct RowsDescs {
+    RowsDesc t[kMaxResetTensors];
+    int32_t count;
+    int32_t total_chunks;
+};
+
+template <typename VEC>
+__global__ __launch_bounds__(kBlock) void k_reset_rows_multi(const int64_t *slots, const int64_t *count_dev, int64_t cap,
+                                                              RowsDescs ds)
+{
+    int64_t count = *count_dev;
+    if (count > cap) count = cap;
+    if (count < 0) count = 0;
+    const int64_t total = count * ds.total_chunks;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < total; i += (int64_t)gridDim.x * kBlock) {
+        const int64_t k = i / ds.total_chunks;
+        int32_t c = (int32_t)(i - k * ds.total_chunks);
+        int which = 0;
+        while (which + 1 < ds.count && c >= ds.t[which].chunks) { c -= ds.t[which].chunks; ++which; }
+        const RowsDesc &t = ds.t[which];
+        int64_t s = slots[k];
+        if (s < 0) continue;
+        if (s >= t.num_rows) s %= t.num_rows;
+        VEC v = VEC(0);
+        if (t.init_row) v = reinterpret_cast<const VEC *>(t.init_row)[c];
+        __builtin_nontemporal_store(v, reinterpret_cast<VEC *>(t.rows + s * t.row_stride_bytes) + c);
+    }
+}
+
+// out[k, :] <- rows[slots[k] mod num_rows, :]   (dense output rows of chunks * sizeof(VEC) bytes)
+template <typename VEC>
+__global__ __launch_bounds__(kBlock) void k_gather_rows(const int64_t *slots, const int64_t *count_dev, int64_t cap,
+                                                         const char *rows, int64_t num_rows, int32_t chunks,
+                                                         int64_t row_stride_bytes, VEC *out)
+{
+    int64_t count = count_dev ? *count_dev : cap;
+    if (count > cap) count = cap;
+    if (count < 0) count = 0;
+    const int64_t total = count * chunks;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < total; i += (int64_t)gridDim.x * kBlock) {
+        const int64_t k = i / chunks;
+        const int32_t c = (int32_t)(i - k * chunks);
+        int64_t s = slots[k];
+        VEC v = VEC(0);
+        if (s >= 0) {
+            if (s >= num_rows) s %= num_rows;
+            v = reinterpret_cast<const VEC *>(rows + s * row_stride_bytes)[c];
+        }
+        out[i] = v;
+    }
+}
+
+// Streaming delta, receiving side (Sec. 3.8): rows[slots[k] mod num_rows, :] <- delta_rows[k, :] and then
+// identities[slots[k]] <- ids[k], so that an identity never points at a row that is older than it.
+template <typename VEC>
+__global__ __launch_bounds__(kBlock) void k_apply_delta(int64_t *identities, int64_t num_slots, const int64_t *slots,
+                                                         const int64_t *ids, const int64_t *count_dev, int64_t cap,
+                                                         char *rows, int64_t num_rows, int32_t chunks,
+                                                         int64_t row_stride_bytes, const VEC *delta_rows)
+{
+    int64_t count = count_dev ? *count_dev : cap;
+    if (count > cap) count = cap;
+    if (count < 0) count = 0;
+    const int64_t total = count * chunks;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < total; i += (int64_t)gridDim.x * kBlock) {
+        const int64_t k = i / chunks;
+        const int32_t c = (int32_t)(i - k * chunks);
+        const int64_t s = slots[k];
+        if (s < 0 || s >= num_slots) continue;
+        if (rows) {
+            const int64_t r = s >= num_rows ? s % num_rows : s;
+            reinterpret_cast<VEC *>(rows + r * row_stride_bytes)[c] = delta_rows[i];
+        }
+        if (c == chunks - 1) {
+            __threadfence();
+            __hip_atomic_store(&identities[s], ids[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
+// Streaming delta, sending side (Sec. 3.8): every occupied slot whose metadata is >= since goes to the
+// list (slot, id), order unspecified.  A workgroup scans a contiguous range of slots, stages its finds in
+// LDS and appends them with one reservation per kDeltaStage finds.
+constexpr int kDeltaStage = 1024;
+
+__global__ __launch_bounds__(kBlock) void k_collect_delta(const int64_t *identities, const int32_t *metadata,
+                                                          int64_t num_slots, int32_t since, int64_t *out_slots,
+                                                          int64_t *out_ids, int64_t cap, unsigned long long *out_count)
+{
+    __shared__ int64_t s_slot[kDeltaStage + kBlock];
+    __shared__ int s_n;
+    __shared__ unsigned long long s_base;
+    const int64_t per_block = (num_slots + gridDim.x - 1) / gridDim.x;
+    const int64_t lo = (int64_t)blockIdx.x * per_block;
+    const int64_t hi = lo + per_block < num_slots ? lo + per_block : num_slots;
+    if (threadIdx.x == 0) s_n = 0;
+    __syncthreads();
+    auto flush = [&]() {       // reached by all threads
+        __syncthreads();
+        const int n = s_n;
+        if (threadIdx.x == 0 && n) s_base = atomicAdd(out_count, (unsigned long long)n);
+        __syncthreads();
+        for (int i = threadIdx.x; i < n; i += kBlock) {
+            const int64_t at = (int64_t)s_base + i;
+            if (at < cap) { out_slots[at] = s_slot[i]; out_ids[at] = identities[s_slot[i]]; }
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) s_n = 0;
+        __syncthreads();
+    };
+    for (int64_t base = lo; base < hi; base += kBlock) {
+        const int64_t s = base + threadIdx.x;
+        if (s < hi && identities[s] >= 0 && metadata[s] >= since) s_slot[atomicAdd(&s_n, 1)] = s;
+        __syncthreads();
+        if (s_n > kDeltaStage) flush();
+    }
+    flush();
+}
+
 }  // namespace mpzch

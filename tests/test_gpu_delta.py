@@ -1,0 +1,114 @@
+"""Row movers and the streaming delta (Sec. 3.4 reset of weights + optimizer state, Sec. 3.7 lookup
+followed by the embedding gather, Sec. 3.8 sparse delta publishing) against plain numpy statements."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2602_17050_amd import binding as mp
+from paper_2602_17050_amd import workloads as wl
+from gpu_common import Pair, say
+
+pytestmark = pytest.mark.gpu
+
+
+def test_reset_rows_multi_resets_weights_and_optimizer_state_in_one_launch():
+    dev = "cuda"
+    w_np = wl.embedding_pattern(1000, 64, np.float32)
+    m_np = wl.embedding_pattern(1000, 1, np.float32) + 3          # row-wise momentum, 4-byte rows
+    v_np = wl.embedding_pattern(500, 32, np.float32)              # a tensor with fewer rows: slot mod rows
+    w, m, v = (torch.from_numpy(a).to(dev) for a in (w_np, m_np, v_np))
+    v = v.to(torch.bfloat16)
+    v_np = v.float().cpu().numpy()
+    slots_np = np.array([3, 999, 1500, 42, 7, 100000], dtype=np.int64)
+    slots = torch.from_numpy(slots_np).to(dev)
+    cnt = torch.tensor([5], dtype=torch.int64, device=dev)
+    init_m = torch.full((1,), 0.25, dtype=torch.float32, device=dev)
+    mp.mpzch_reset_rows_multi(slots, cnt, [w, m, v], [None, init_m, None])
+    torch.cuda.synchronize()
+    oracle.reset_rows(slots_np[:5], w_np)
+    oracle.reset_rows(slots_np[:5], m_np, np.array([0.25], np.float32))
+    oracle.reset_rows(slots_np[:5], v_np)
+    assert np.array_equal(w.cpu().numpy(), w_np)
+    assert np.array_equal(m.cpu().numpy(), m_np)
+    assert np.array_equal(v.float().cpu().numpy(), v_np)
+
+
+def test_lookup_gather_returns_the_rows_of_the_looked_up_slots():
+    p = Pair(50_000, 16, 3, True, 77)
+    rng = np.random.Generator(np.random.Philox(key=11))
+    for step in range(4):
+        p.step(wl.zipf_ids(rng, 20_000, 1.05, 60_000), step, check_state=False)
+    for dim, dtype in ((32, torch.float32), (128, torch.bfloat16), (3, torch.float32)):
+        rows_np = wl.embedding_pattern(20_000, dim, np.float32)           # fewer rows than slots
+        rows = torch.from_numpy(rows_np).cuda().to(dtype)
+        q = np.concatenate([wl.zipf_ids(rng, 5000, 1.05, 60_000), rng.integers(-3, 1 << 40, size=500)])
+        ids = torch.from_numpy(q).cuda()
+        out = torch.empty((len(q), dim), dtype=dtype, device="cuda")
+        slots = torch.empty(len(q), dtype=torch.int64, device="cuda")
+        found = torch.empty(len(q), dtype=torch.uint8, device="cuda")
+        mp.mpzch_lookup_gather(p.g.handle, p.g.identities, ids, rows, out, slots, found)
+        torch.cuda.synchronize()
+        so, fo = p.o.lookup(q)
+        assert np.array_equal(slots.cpu().numpy(), so) and np.array_equal(found.cpu().numpy(), fo)
+        want = oracle.gather_rows(so, rows.float().cpu().numpy())
+        assert np.array_equal(out.float().cpu().numpy(), want)
+    p.close()
+
+
+def test_streaming_delta_brings_an_inference_copy_up_to_date():
+    """Train for a while, publish a full snapshot (identities + rows), train on, publish a delta of
+    what was touched since: the inference copy must equal the training state wherever it matters."""
+    spec = wl.c4_spec(1 / 2000)                                          # 250 K slots
+    t = spec.table
+    dim = 16
+    p = Pair(t.num_slots, t.max_probe, t.ttl, True, t.hash_seed)
+    rows = torch.from_numpy(wl.embedding_pattern(t.num_slots, dim, np.float32)).cuda()
+    for lo in range(0, spec.prefill_ids, 50_000):
+        p.step(wl.stream_prefill_ids(lo, min(lo + 50_000, spec.prefill_ids)), 0, check_state=False)
+    step = spec.first_step
+    for _ in range(3):
+        p.step(wl.stream_batch(spec, step), step, check_state=False)
+        step += 1
+    # full snapshot: identities only (metadata is not published, Sec. 3.7) + rows
+    inf_I = p.g.identities.clone()
+    inf_rows = rows.clone()
+    since = step
+    touched_rows = []
+    for _ in range(4):
+        ids = wl.stream_batch(spec, step)
+        r = p.step(ids, step, check_state=False)
+        # "training": every row that was looked up changes, evicted rows are reset first
+        p.g.reset_rows(rows)
+        sl = torch.from_numpy(np.unique(r.slots)).cuda()
+        rows[sl] += float(step)
+        touched_rows.append(np.unique(r.slots))
+        step += 1
+    cap = t.num_slots
+    d_slots = torch.empty(cap, dtype=torch.int64, device="cuda")
+    d_ids = torch.empty(cap, dtype=torch.int64, device="cuda")
+    d_cnt = torch.zeros(1, dtype=torch.int64, device="cuda")
+    mp.mpzch_collect_delta(p.g.handle, p.g.identities, p.g.metadata, since, d_slots, d_ids, d_cnt)
+    n = int(d_cnt.item())
+    so, io = oracle.collect_delta(p.o, since)
+    got = d_slots[:n].cpu().numpy()
+    order = np.argsort(got)
+    assert np.array_equal(got[order], so) and np.array_equal(d_ids[:n].cpu().numpy()[order], io)
+    assert set(np.concatenate(touched_rows).tolist()) <= set(so.tolist())     # every touched slot is in the delta
+    say("delta entries", n, "of", t.num_slots)
+    payload = torch.empty((cap, dim), dtype=torch.float32, device="cuda")
+    mp.mpzch_gather_rows(d_slots, d_cnt, rows, payload)
+    mp.mpzch_apply_delta(inf_I, d_slots, d_ids, d_cnt, inf_rows, payload)
+    torch.cuda.synchronize()
+    assert torch.equal(inf_I, p.g.identities)
+    assert torch.equal(inf_rows, rows)
+    # truncated output: the count is still the true one
+    small = torch.empty(10, dtype=torch.int64, device="cuda")
+    mp.mpzch_collect_delta(p.g.handle, p.g.identities, p.g.metadata, since, small, small.clone(), d_cnt)
+    assert int(d_cnt.item()) == n
+    # identities-only delta
+    inf2 = torch.full_like(inf_I, -1)
+    mp.mpzch_apply_delta(inf2, d_slots, d_ids, torch.tensor([n], dtype=torch.int64, device="cuda"))
+    torch.cuda.synchronize()
+    assert torch.equal(inf2[d_slots[:n]], d_ids[:n]) and int((inf2 >= 0).sum().item()) == n
+    p.close()
