@@ -21,6 +21,7 @@ _LIB = os.path.join(_HERE, "libmpzch_oracle.so")
 EVICT_NONE = 0
 EVICT_TTL = 1
 EVICT_LRU = 2
+EVICT_TTL_EXPIRY = 3
 
 STAT_NAMES = (
     "hit_pos", "miss_pos", "distinct_miss", "inserts",
@@ -66,6 +67,9 @@ def _load():
         lib.oracle_remap.restype = ctypes.c_int
         lib.oracle_remap.argtypes = [ctypes.POINTER(_Cfg), p, p, p, ctypes.c_int64, ctypes.c_int32,
                                      p, p, ctypes.c_int64, p, p]
+        lib.oracle_remap_ttls.restype = ctypes.c_int
+        lib.oracle_remap_ttls.argtypes = [ctypes.POINTER(_Cfg), p, p, p, p, ctypes.c_int64, ctypes.c_int32,
+                                          p, p, ctypes.c_int64, p, p]
         lib.oracle_lookup.restype = ctypes.c_int
         lib.oracle_lookup.argtypes = [ctypes.POINTER(_Cfg), p, p, ctypes.c_int64, p, p]
         lib.oracle_reset_rows.restype = ctypes.c_int
@@ -122,15 +126,20 @@ class Table:
         assert self.metadata.dtype == np.int32 and self.metadata.shape == (num_slots,)
         assert self.identities.flags.c_contiguous and self.metadata.flags.c_contiguous
 
-    def remap(self, ids, step: int) -> RemapResult:
+    def remap(self, ids, step: int, ttls=None) -> RemapResult:
+        """ttls: with EVICT_TTL_EXPIRY, int32 retention per position (per-feature TTL, Sec. 3.4)."""
         ids = _i64(ids)
         n = ids.shape[0]
+        if ttls is not None:
+            ttls = np.ascontiguousarray(ttls, dtype=np.int32)
+            assert ttls.shape == (n,) and self.policy == EVICT_TTL_EXPIRY
         out = np.empty(n, dtype=np.int64)
         ev = np.empty(max(n, 1), dtype=np.int64)
         nev = np.zeros(1, dtype=np.int64)
         st = np.zeros(len(STAT_NAMES), dtype=np.int64)
-        rc = _load().oracle_remap(ctypes.byref(self.cfg), _ptr(self.identities), _ptr(self.metadata),
-                                  _ptr(ids), n, step, _ptr(out), _ptr(ev), ev.shape[0], _ptr(nev), _ptr(st))
+        rc = _load().oracle_remap_ttls(ctypes.byref(self.cfg), _ptr(self.identities), _ptr(self.metadata),
+                                       _ptr(ids), None if ttls is None else _ptr(ttls), n, step, _ptr(out),
+                                       _ptr(ev), ev.shape[0], _ptr(nev), _ptr(st))
         if rc != 0:
             raise RuntimeError("oracle_remap failed")
         return RemapResult(out, ev[: int(nev[0])].copy(), dict(zip(STAT_NAMES, st.tolist())))

@@ -44,7 +44,7 @@
 #include <stdlib.h>
 #include <string.h>
 
-enum { ORACLE_EVICT_NONE = 0, ORACLE_EVICT_TTL = 1, ORACLE_EVICT_LRU = 2 };
+enum { ORACLE_EVICT_NONE = 0, ORACLE_EVICT_TTL = 1, ORACLE_EVICT_LRU = 2, ORACLE_EVICT_TTL_EXPIRY = 3 };
 
 typedef struct {
     int64_t  num_slots;   /* N */
@@ -102,6 +102,9 @@ static int claimable(const oracle_cfg *c, const int64_t *I, const int32_t *M,
     if (I[s] == -1) return 1;
     if (c->policy == ORACLE_EVICT_TTL && I[s] >= 0 &&
         (int64_t)step - (int64_t)M[s] > (int64_t)c->ttl) return 1;
+    /* Sec. 3.4 as written: the stored value is "now + duration" of the id's feature, and a slot
+     * whose value lies before the current time stamp is expired */
+    if (c->policy == ORACLE_EVICT_TTL_EXPIRY && I[s] >= 0 && M[s] < step) return 1;
     return 0;
 }
 
@@ -129,11 +132,21 @@ static int cmp_id_pos(const void *a, const void *b)
  * out of memory.  out_evicted receives at most evicted_cap slots (in claim
  * order); *out_num_evicted is the true count.  stats may be NULL.
  */
-int oracle_remap(const oracle_cfg *c, int64_t *I, int32_t *M,
-                 const int64_t *ids, int64_t n, int32_t step,
-                 int64_t *out_slots,
-                 int64_t *out_evicted, int64_t evicted_cap, int64_t *out_num_evicted,
-                 int64_t *stats)
+/* value written to the metadata of a slot touched for the id at batch position j */
+static int32_t meta_value(const oracle_cfg *c, const int32_t *ttls, int64_t j, int32_t step)
+{
+    if (c->policy != ORACLE_EVICT_TTL_EXPIRY) return step;          /* last-seen step */
+    return step + (ttls ? ttls[j] : c->ttl);                        /* per-feature TTL: expiry time */
+}
+
+/* ttls: with ORACLE_EVICT_TTL_EXPIRY, the retention (in steps) of the feature each position
+ * belongs to (Sec. 3.4, per-feature TTL); NULL = the table's ttl for every position.  All copies
+ * of an id carry the same value; the first occurrence's is used. */
+int oracle_remap_ttls(const oracle_cfg *c, int64_t *I, int32_t *M,
+                      const int64_t *ids, const int32_t *ttls, int64_t n, int32_t step,
+                      int64_t *out_slots,
+                      int64_t *out_evicted, int64_t evicted_cap, int64_t *out_num_evicted,
+                      int64_t *stats)
 {
     if (!c || c->num_slots < 1 || c->max_probe < 1 || n < 0) return -1;
     int64_t st[ST_COUNT];
@@ -173,7 +186,7 @@ int oracle_remap(const oracle_cfg *c, int64_t *I, int32_t *M,
             int64_t r = discover(c, I, id, h);
             if (r >= 0) {
                 int64_t s = probe_slot(h, r, N);
-                M[s] = step;
+                M[s] = meta_value(c, ttls, j, step);
                 result[j] = s;
             } else {
                 result[j] = -1;
@@ -256,7 +269,7 @@ int oracle_remap(const oracle_cfg *c, int64_t *I, int32_t *M,
                 if (!claimable(c, I, M, s, step)) continue;
                 int was_occupied = (I[s] != -1);
                 I[s] = id;
-                M[s] = step;
+                M[s] = meta_value(c, ttls, j, step);
                 result[j] = s;
                 if (was_occupied) {
                     if (out_evicted && n_evicted < evicted_cap) out_evicted[n_evicted] = s;
@@ -274,7 +287,7 @@ int oracle_remap(const oracle_cfg *c, int64_t *I, int32_t *M,
             if (result[j] >= 0) continue;
             int64_t h = oracle_home(ids[j], c->hash_seed, N);
             result[j] = h;
-            M[h] = step;
+            M[h] = meta_value(c, ttls, j, step);
             st[ST_COLLISIONS]++;
         }
 
@@ -286,6 +299,16 @@ int oracle_remap(const oracle_cfg *c, int64_t *I, int32_t *M,
     if (out_num_evicted) *out_num_evicted = n_evicted;
     if (stats) memcpy(stats, st, sizeof st);
     return 0;
+}
+
+int oracle_remap(const oracle_cfg *c, int64_t *I, int32_t *M,
+                 const int64_t *ids, int64_t n, int32_t step,
+                 int64_t *out_slots,
+                 int64_t *out_evicted, int64_t evicted_cap, int64_t *out_num_evicted,
+                 int64_t *stats)
+{
+    return oracle_remap_ttls(c, I, M, ids, NULL, n, step, out_slots, out_evicted, evicted_cap,
+                             out_num_evicted, stats);
 }
 
 /* Sec. 3.7: read-only lookup.  Miss -> home slot, found flag 0. */
