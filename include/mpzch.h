@@ -66,6 +66,10 @@ typedef enum {
                              equals the current step; contended slots go to the lower choice number, then
                              to the id whose first occurrence comes first.  Single tables with
                              max_probe <= MPZCH_MAX_PROBE_LRU only (else MPZCH_ERR_UNSUPPORTED). */
+    , MPZCH_EVICT_TTL_EXPIRY = 3 /* Sec. 3.4 as written, for tables shared by features with different
+                             retention ("per-feature TTL"): metadata holds the step after which the id is
+                             expired, step + ttl of its feature; a slot is expired when metadata < step.
+                             With one ttl for all ids this is MPZCH_EVICT_TTL with metadata shifted by ttl. */
 } mpzch_evict_kind_t;
 
 typedef struct {
@@ -152,6 +156,18 @@ mpzch_status_t mpzch_remap(mpzch_table_t *t, int64_t *identities, int32_t *metad
                            int64_t *out_slots,
                            int64_t *out_evicted_slots, int64_t evicted_cap, int64_t *out_num_evicted,
                            int64_t *out_stats, void *stream);
+
+/*
+ * mpzch_remap for a table of kind MPZCH_EVICT_TTL_EXPIRY whose ids come from features with different
+ * retention (Sec. 3.4, second paragraph).  ttls [dev] int32[n]: retention in steps (>= 0) of the feature
+ * each position belongs to; all copies of an id must carry the same value; NULL = policy.ttl for all
+ * (then any table kind is accepted and the call is mpzch_remap).  step + ttl must fit int32.
+ */
+mpzch_status_t mpzch_remap_feature_ttl(mpzch_table_t *t, int64_t *identities, int32_t *metadata,
+                                       const int64_t *ids, const int32_t *ttls, int64_t n, int32_t step,
+                                       int64_t *out_slots,
+                                       int64_t *out_evicted_slots, int64_t evicted_cap, int64_t *out_num_evicted,
+                                       int64_t *out_stats, void *stream);
 
 /*
  * Inference lookup (Sec. 3.7): read-only, Pass 1 of Algorithm 1 for every position

@@ -287,7 +287,9 @@ int oracle_remap_ttls(const oracle_cfg *c, int64_t *I, int32_t *M,
             if (result[j] >= 0) continue;
             int64_t h = oracle_home(ids[j], c->hash_seed, N);
             result[j] = h;
-            M[h] = meta_value(c, ttls, j, step);
+            /* never lowers the stored value: with last-seen steps this is M[h] = step; with
+             * per-feature expiry times a short-lived id must not shorten the resident's retention */
+            if (meta_value(c, ttls, j, step) > M[h]) M[h] = meta_value(c, ttls, j, step);
             st[ST_COLLISIONS]++;
         }
 

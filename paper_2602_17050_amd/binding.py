@@ -14,7 +14,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libmpzch.so")
 
-EVICT_NONE, EVICT_TTL, EVICT_LRU = 0, 1, 2
+EVICT_NONE, EVICT_TTL, EVICT_LRU, EVICT_TTL_EXPIRY = 0, 1, 2, 3
 STAT_NAMES = ("hit_pos", "miss_pos", "distinct_miss", "inserts",
               "evictions", "collisions", "invalid_pos", "hit_probe_sum")
 STAT_COUNT = len(STAT_NAMES)
@@ -24,7 +24,7 @@ EXPORTED = (
     "mpzch_lookup", "mpzch_reset_rows", "mpzch_group_create", "mpzch_group_destroy",
     "mpzch_group_reserve", "mpzch_remap_jagged", "mpzch_set_kernel_timing", "mpzch_kernel_times",
     "mpzch_group_set_kernel_timing", "mpzch_group_kernel_times", "mpzch_status_string",
-    "mpzch_reset_rows_multi", "mpzch_lookup_gather", "mpzch_collect_delta", "mpzch_gather_rows", "mpzch_apply_delta",
+    "mpzch_remap_feature_ttl", "mpzch_reset_rows_multi", "mpzch_lookup_gather", "mpzch_collect_delta", "mpzch_gather_rows", "mpzch_apply_delta",
 )
 
 
@@ -63,6 +63,7 @@ def load_library(path: str | None = None):
     lib.mpzch_reserve.argtypes = [vp, i64]
     lib.mpzch_init_tensors.argtypes = [vp, vp, vp, vp]
     lib.mpzch_remap.argtypes = [vp, vp, vp, vp, i64, i32, vp, vp, i64, vp, vp, vp]
+    lib.mpzch_remap_feature_ttl.argtypes = [vp, vp, vp, vp, vp, i64, i32, vp, vp, i64, vp, vp, vp]
     lib.mpzch_lookup.argtypes = [vp, vp, vp, i64, vp, vp, vp]
     lib.mpzch_reset_rows.argtypes = [vp, vp, i64, vp, i64, i64, i64, vp, vp]
     lib.mpzch_reset_rows_multi.argtypes = [vp, vp, i64, ctypes.POINTER(_Rows), i32, vp]
@@ -143,6 +144,18 @@ def mpzch_remap(handle, identities, metadata, ids, step: int, out_slots, out_evi
                                       _ptr(ids, torch.int64), n, step, _ptr(out_slots, torch.int64),
                                       _ptr(out_evicted_slots, torch.int64), cap, _ptr(out_num_evicted, torch.int64),
                                       _ptr(out_stats, torch.int64), _stream()), "mpzch_remap")
+
+
+def mpzch_remap_feature_ttl(handle, identities, metadata, ids, ttls, step: int, out_slots, out_evicted_slots,
+                            out_num_evicted, out_stats=None):
+    n = ids.numel()
+    cap = 0 if out_evicted_slots is None else out_evicted_slots.numel()
+    assert ttls is None or ttls.numel() == n
+    _check(load_library().mpzch_remap_feature_ttl(handle, _ptr(identities, torch.int64), _ptr(metadata, torch.int32),
+                                                  _ptr(ids, torch.int64), _ptr(ttls, torch.int32), n, step,
+                                                  _ptr(out_slots, torch.int64), _ptr(out_evicted_slots, torch.int64),
+                                                  cap, _ptr(out_num_evicted, torch.int64),
+                                                  _ptr(out_stats, torch.int64), _stream()), "mpzch_remap_feature_ttl")
 
 
 def mpzch_lookup(handle, identities, ids, out_slots, out_found=None):
@@ -289,14 +302,14 @@ class MpzchTable:
             mpzch_reserve(self.handle, max_batch)
             self._evicted = torch.empty(max_batch, dtype=torch.int64, device=device)
 
-    def remap(self, ids, step, out_slots=None):
+    def remap(self, ids, step, out_slots=None, ttls=None):
         n = ids.numel()
         if out_slots is None:
             out_slots = torch.empty(n, dtype=torch.int64, device=ids.device)
         if self._evicted is None or self._evicted.numel() < n:
             self._evicted = torch.empty(max(n, 1), dtype=torch.int64, device=ids.device)
-        mpzch_remap(self.handle, self.identities, self.metadata, ids, step, out_slots, self._evicted,
-                    self.num_evicted, self.stats)
+        mpzch_remap_feature_ttl(self.handle, self.identities, self.metadata, ids, ttls, step, out_slots,
+                                self._evicted, self.num_evicted, self.stats)
         return out_slots
 
     @property

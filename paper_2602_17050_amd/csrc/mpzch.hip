@@ -205,7 +205,7 @@ TableDesc make_desc(const TableCfg &c, int64_t *I, int32_t *M, int64_t ev_begin,
     d.seed = c.seed;
     d.P = p_eff(c);
     d.ttl = c.ttl;
-    d.evict = c.kind == MPZCH_EVICT_TTL ? 1 : c.kind == MPZCH_EVICT_LRU ? 2 : 0;
+    d.evict = c.kind == MPZCH_EVICT_TTL ? 1 : c.kind == MPZCH_EVICT_LRU ? 2 : c.kind == MPZCH_EVICT_TTL_EXPIRY ? 3 : 0;
     d.pad_ = 0;
     d.ev_begin = ev_begin;
     d.ev_cap = ev_cap;
@@ -314,7 +314,9 @@ mpzch_status_t fill32(int32_t *dst, int64_t count, int32_t value, hipStream_t s)
 bool valid_cfg(int64_t num_slots, int32_t max_probe, mpzch_eviction_policy_t policy)
 {
     if (num_slots < 1 || max_probe < 1 || max_probe > MPZCH_MAX_PROBE) return false;
-    if (policy.kind != MPZCH_EVICT_NONE && policy.kind != MPZCH_EVICT_TTL && policy.kind != MPZCH_EVICT_LRU) return false;
+    if (policy.kind != MPZCH_EVICT_NONE && policy.kind != MPZCH_EVICT_TTL && policy.kind != MPZCH_EVICT_LRU &&
+        policy.kind != MPZCH_EVICT_TTL_EXPIRY)
+        return false;
     if (policy.ttl < 0) return false;
     return true;
 }
@@ -376,14 +378,15 @@ mpzch_status_t mpzch_init_tensors(const mpzch_table_t *t, int64_t *identities, i
     return MPZCH_OK;
 }
 
-mpzch_status_t mpzch_remap(mpzch_table_t *t, int64_t *identities, int32_t *metadata,
-                           const int64_t *ids, int64_t n, int32_t step,
+mpzch_status_t mpzch_remap_feature_ttl(mpzch_table_t *t, int64_t *identities, int32_t *metadata,
+                                       const int64_t *ids, const int32_t *ttls, int64_t n, int32_t step,
                            int64_t *out_slots,
                            int64_t *out_evicted_slots, int64_t evicted_cap, int64_t *out_num_evicted,
                            int64_t *out_stats, void *stream)
 {
     if (!t || !identities || !metadata || !out_num_evicted) return MPZCH_ERR_INVALID_ARG;
     if (n < 0 || n > MPZCH_MAX_BATCH || step < 0 || evicted_cap < 0) return MPZCH_ERR_INVALID_ARG;
+    if (ttls && t->cfg.kind != MPZCH_EVICT_TTL_EXPIRY) return MPZCH_ERR_INVALID_ARG;
     if (n > 0 && (!ids || !out_slots)) return MPZCH_ERR_INVALID_ARG;
     if (evicted_cap > 0 && !out_evicted_slots) return MPZCH_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)stream;
@@ -396,6 +399,7 @@ mpzch_status_t mpzch_remap(mpzch_table_t *t, int64_t *identities, int32_t *metad
     Params p;
     std::memset(&p, 0, sizeof p);
     p.ids = ids;
+    p.ttls = ttls;
     p.n = n;
     p.step = step;
     p.num_tables = 1;
@@ -405,6 +409,16 @@ mpzch_status_t mpzch_remap(mpzch_table_t *t, int64_t *identities, int32_t *metad
     p.out_num_evicted = out_num_evicted;
     p.out_stats = out_stats;
     return run_remap(t->sc, t->tm, p, p.t0.P, s);
+}
+
+mpzch_status_t mpzch_remap(mpzch_table_t *t, int64_t *identities, int32_t *metadata,
+                           const int64_t *ids, int64_t n, int32_t step,
+                           int64_t *out_slots,
+                           int64_t *out_evicted_slots, int64_t evicted_cap, int64_t *out_num_evicted,
+                           int64_t *out_stats, void *stream)
+{
+    return mpzch_remap_feature_ttl(t, identities, metadata, ids, nullptr, n, step, out_slots, out_evicted_slots,
+                                   evicted_cap, out_num_evicted, out_stats, stream);
 }
 
 mpzch_status_t mpzch_lookup(const mpzch_table_t *t, const int64_t *identities,

@@ -51,7 +51,7 @@ struct TableDesc {
     uint64_t seed;
     int32_t P;             // min(max_probe, N)
     int32_t ttl;
-    int32_t evict;         // 0 = off, 1 = TTL
+    int32_t evict;         // 0 = off, 1 = TTL (metadata = last-seen step), 2 = LRU, 3 = TTL with metadata = expiry step
     int32_t pad_;
     int64_t ev_begin;      // where this table's evicted list starts in out_evicted
     int64_t ev_cap;
@@ -72,6 +72,7 @@ struct StatRow {
 
 struct Params {
     const int64_t *ids;
+    const int32_t *ttls;           // evict == 3: retention of every position's feature, or null (= the table's ttl)
     int64_t n;
     int32_t step;
     int32_t num_tables;            // 1 => t0 is used and offsets/descs are ignored
@@ -172,6 +173,32 @@ __device__ __forceinline__ int find_table(const int64_t *offsets, int num_tables
 }
 
 __device__ __forceinline__ int64_t wrap(int64_t s, int64_t n) { return s >= n ? s - n : s; }
+
+// Metadata written for the id at batch position pos: the step (last seen), or with per-feature TTL
+// (Sec. 3.4) the step after which the id is expired: now + duration of its feature.
+__device__ __forceinline__ int32_t meta_value(const Params &p, const TableDesc &d, int64_t pos)
+{
+    if (d.evict != 3) return p.step;
+    return p.step + (p.ttls ? p.ttls[pos] : d.ttl);
+}
+
+// Metadata write of k_finalize.  With last-seen metadata every writer of a call stores the same step.
+// With per-feature expiry times the writers of one slot -- the id placed there and the ids that fall
+// back to it as their home -- carry different values; the slot keeps the maximum (a refresh never
+// lowers the stored value), which also makes the result independent of their order.
+__device__ __forceinline__ void store_meta(const TableDesc &d, int64_t s, int32_t value)
+{
+    if (d.evict == 3) atomicMax(&d.M[s], value);
+    else d.M[s] = value;
+}
+
+// TTL test of Sec. 3.4 on metadata m of a slot that holds an id
+__device__ __forceinline__ bool is_expired(int32_t evict, int32_t ttl, int32_t step, int32_t m)
+{
+    if (evict == 1) return (int64_t)step - (int64_t)m > (int64_t)ttl;
+    if (evict == 3) return m < step;
+    return false;
+}
 
 // ------------------------------------------------------------------ scratch set
 constexpr uint64_t kSetSeed = 0x2545F4914F6CDD1Dull;
@@ -375,7 +402,7 @@ __global__ __launch_bounds__(kBlock) void k_discover(Params p)
     auto finish_hit = [&](const TableDesc &d, int64_t pos, int64_t home, int dist) {
         const int64_t slot = wrap(home + dist, d.N);
         if (TRAIN) {
-            d.M[slot] = p.step;                       // "Update": refresh the resident's metadata
+            d.M[slot] = meta_value(p, d, pos);        // "Update": refresh the resident's metadata
             st_hit++;
             st_probe += (unsigned long long)(dist + 1);
         } else if (p.out_found) {
@@ -517,7 +544,7 @@ __global__ __launch_bounds__(kBlock) void k_discover(Params p)
 // TTL test of Sec. 3.4 on a slot that holds an id
 __device__ __forceinline__ bool expired(const TableDesc &d, int32_t step, int64_t s)
 {
-    return d.evict && (int64_t)step - (int64_t)d.M[s] > (int64_t)d.ttl;
+    return is_expired(d.evict, d.ttl, step, d.M[s]);
 }
 
 // One workgroup = one wavefront.  Lane phase: the first PMAX slots of the windows (identities and
@@ -633,7 +660,8 @@ __global__ __launch_bounds__(kWave) void k_allocate(Params p)
             // cooperative loads; lanes without a slot to read use slot 0 / the home slot (valid addresses)
             int64_t vi[NT * CH];
             int32_t vm[NT * CH];
-            uint32_t gmeta[NT];                               // the claimant's table: eviction on + ttl
+            uint32_t gmeta[NT];                               // the claimant's table: ttl
+            int32_t gmode[NT];                                // ... and eviction mode
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
                 const int a = t * APL + g;
@@ -642,13 +670,14 @@ __global__ __launch_bounds__(kWave) void k_allocate(Params p)
                 int32_t *gM = p.t0.M;
                 int64_t gN = p.t0.N;
                 int gP = p.t0.P;
-                int gttl = p.t0.evict ? p.t0.ttl : -1;
+                int gttl = p.t0.ttl, gev = p.t0.evict;
                 if (multi) {
                     const TableDesc &gd = p.descs[__shfl(f, a)];
                     gI = gd.I; gM = gd.M; gN = gd.N; gP = gd.P;
-                    gttl = gd.evict ? gd.ttl : -1;
+                    gttl = gd.ttl; gev = gd.evict;
                 }
                 gmeta[t] = (uint32_t)gttl;
+                gmode[t] = gev;
 #pragma unroll
                 for (int c = 0; c < CH; ++c) {
                     const int k = c * G + r;
@@ -662,8 +691,7 @@ __global__ __launch_bounds__(kWave) void k_allocate(Params p)
 #pragma unroll
                 for (int c = 0; c < CH; ++c) {
                     int64_t w = vi[t * CH + c];
-                    const int32_t ttl = (int32_t)gmeta[t];
-                    if (w >= 0) w = (ttl >= 0 && (int64_t)p.step - (int64_t)vm[t * CH + c] > (int64_t)ttl) ? 1 : 0;
+                    if (w >= 0) w = is_expired(gmode[t], (int32_t)gmeta[t], p.step, vm[t * CH + c]) ? 1 : 0;
                     s_I[t * APL + g][c * G + r] = w;
                 }
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -1012,12 +1040,12 @@ __global__ __launch_bounds__(kBlock) void k_finalize(Params p)
                     // the claim becomes the id; metadata gets the step (Algorithm 1, Pass 2)
                     s_final = wrap(home + at, d.N);
                     d.I[s_final] = id;
-                    d.M[s_final] = p.step;
+                    store_meta(d, s_final, meta_value(p, d, pos));
                     outcome = (int)occ;
                 } else {
                     // Case 3: no empty or evictable slot -> home slot, its metadata refreshed
                     s_final = home;
-                    d.M[home] = p.step;
+                    store_meta(d, home, meta_value(p, d, pos));
                 }
                 p.out_slots[pos] = s_final;
             }

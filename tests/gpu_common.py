@@ -16,9 +16,10 @@ class Pair:
     """One table on both sides."""
 
     def __init__(self, num_slots, max_probe, ttl, evict=True, hash_seed=0, emb=None):
-        # evict: True = TTL, False = off, "lru" = LRU
-        kind_g = mp.EVICT_LRU if evict == "lru" else mp.EVICT_TTL if evict else mp.EVICT_NONE
-        kind_o = oracle.EVICT_LRU if evict == "lru" else oracle.EVICT_TTL if evict else oracle.EVICT_NONE
+        # evict: True = TTL, False = off, "lru" = LRU, "expiry" = per-feature TTL (metadata = expiry step)
+        kind_g = {"lru": mp.EVICT_LRU, "expiry": mp.EVICT_TTL_EXPIRY}.get(evict, mp.EVICT_TTL if evict else mp.EVICT_NONE)
+        kind_o = {"lru": oracle.EVICT_LRU, "expiry": oracle.EVICT_TTL_EXPIRY}.get(
+            evict, oracle.EVICT_TTL if evict else oracle.EVICT_NONE)
         self.g = mp.MpzchTable(num_slots, max_probe, kind_g, ttl, hash_seed)
         self.o = oracle.Table(num_slots, max_probe, kind_o, ttl, hash_seed)
         self.emb_o = None
@@ -34,14 +35,15 @@ class Pair:
             emb = wl.embedding_pattern(spec.emb_rows, spec.emb_dim, np.float32)
         return cls(spec.num_slots, spec.max_probe, spec.ttl, spec.evict, spec.hash_seed, emb)
 
-    def step(self, ids_np, step, check_state=True, init_row=None):
+    def step(self, ids_np, step, check_state=True, init_row=None, ttls=None):
         ids_np = np.ascontiguousarray(ids_np, dtype=np.int64)
         ids_g = torch.from_numpy(ids_np).cuda()
-        out_g = self.g.remap(ids_g, step)
+        ttls_g = None if ttls is None else torch.from_numpy(np.ascontiguousarray(ttls, dtype=np.int32)).cuda()
+        out_g = self.g.remap(ids_g, step, ttls=ttls_g)
         if self.emb_g is not None and ids_np.size:
             self.g.reset_rows(self.emb_g, None if init_row is None else torch.from_numpy(init_row).cuda())
         torch.cuda.synchronize()
-        r = self.o.remap(ids_np, step)
+        r = self.o.remap(ids_np, step, ttls)
         if self.emb_o is not None:
             oracle.reset_rows(r.evicted, self.emb_o, init_row)
         got = out_g.cpu().numpy()

@@ -29,7 +29,7 @@ class ExpiryAlg1:
             if not exists and self.I[s] != -1 and self.M[s] < step:
                 self.I[s], self.M[s] = id_, meta
                 return s, True
-        self.M[h] = meta
+        self.M[h] = max(self.M[h], meta)        # Case 3 refreshes, it never shortens the resident's retention
         return h, False
 
 
