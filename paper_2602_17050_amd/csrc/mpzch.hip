@@ -232,8 +232,13 @@ mpzch_status_t launch_allocate(int32_t max_p, const Params &p, int num_cus, hipS
     // 8 or 16 slots of every window, longer windows continue in the wave phase
     const int grid = grid_for((int64_t)p.num_segs, 1, num_cus, 4 * group_blocks_per_cu());
     if (p.t0.evict == 2) hipLaunchKernelGGL(k_allocate_lru, dim3(grid), dim3(kWave), 0, s, p);
-    else if (max_p <= 8) hipLaunchKernelGGL((k_allocate<8>), dim3(grid), dim3(kWave), 0, s, p);
-    else hipLaunchKernelGGL((k_allocate<16>), dim3(grid), dim3(kWave), 0, s, p);
+    else if (p.num_tables > 1) {
+        if (max_p <= 8) hipLaunchKernelGGL((k_allocate<8, true>), dim3(grid), dim3(kWave), 0, s, p);
+        else hipLaunchKernelGGL((k_allocate<16, true>), dim3(grid), dim3(kWave), 0, s, p);
+    } else {
+        if (max_p <= 8) hipLaunchKernelGGL((k_allocate<8, false>), dim3(grid), dim3(kWave), 0, s, p);
+        else hipLaunchKernelGGL((k_allocate<16, false>), dim3(grid), dim3(kWave), 0, s, p);
+    }
     LAUNCH_CHECK();
     return MPZCH_OK;
 }

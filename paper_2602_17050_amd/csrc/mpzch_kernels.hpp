@@ -174,9 +174,39 @@ __device__ __forceinline__ int find_table(const int64_t *offsets, int num_tables
 
 __device__ __forceinline__ int64_t wrap(int64_t s, int64_t n) { return s >= n ? s - n : s; }
 
+// Device-side view of a TableDesc.  A pointer read from a descriptor in memory has lost the
+// "global" address space that kernel arguments carry, and accesses through it become flat_
+// instructions, which also count against the LDS wait counter.  All table state is device memory,
+// and the view's pointer types say so.
+template <typename T>
+using global_ptr = T __attribute__((address_space(1))) *;
+
+struct Tab {
+    global_ptr<int64_t> I;
+    global_ptr<int32_t> M;
+    int64_t N;
+    uint64_t seed;
+    int32_t P;
+    int32_t ttl;
+    int32_t evict;
+};
+
+__device__ __forceinline__ Tab view(const TableDesc &d)
+{
+    Tab t;
+    t.I = (global_ptr<int64_t>)d.I;
+    t.M = (global_ptr<int32_t>)d.M;
+    t.N = d.N;
+    t.seed = d.seed;
+    t.P = d.P;
+    t.ttl = d.ttl;
+    t.evict = d.evict;
+    return t;
+}
+
 // Metadata written for the id at batch position pos: the step (last seen), or with per-feature TTL
 // (Sec. 3.4) the step after which the id is expired: now + duration of its feature.
-__device__ __forceinline__ int32_t meta_value(const Params &p, const TableDesc &d, int64_t pos)
+__device__ __forceinline__ int32_t meta_value(const Params &p, const Tab &d, int64_t pos)
 {
     if (d.evict != 3) return p.step;
     return p.step + (p.ttls ? p.ttls[pos] : d.ttl);
@@ -186,9 +216,9 @@ __device__ __forceinline__ int32_t meta_value(const Params &p, const TableDesc &
 // With per-feature expiry times the writers of one slot -- the id placed there and the ids that fall
 // back to it as their home -- carry different values; the slot keeps the maximum (a refresh never
 // lowers the stored value), which also makes the result independent of their order.
-__device__ __forceinline__ void store_meta(const TableDesc &d, int64_t s, int32_t value)
+__device__ __forceinline__ void store_meta(const Tab &d, int64_t s, int32_t value)
 {
-    if (d.evict == 3) atomicMax(&d.M[s], value);
+    if (d.evict == 3) __hip_atomic_fetch_max(&d.M[s], value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     else d.M[s] = value;
 }
 
@@ -317,7 +347,7 @@ __device__ __forceinline__ void block_stat_row(const Params &p, StatRow *rows, i
 constexpr int kProbeGoOn = -1;
 constexpr int kProbeAbsent = -2;
 
-__device__ __forceinline__ int probe_pass(const TableDesc &d, int64_t id, int64_t home, int q)
+__device__ __forceinline__ int probe_pass(const Tab &d, int64_t id, int64_t home, int q)
 {
     constexpr int G = kLine, IPI = kWave / G;
     const int lane = lane_id();
@@ -399,7 +429,7 @@ __global__ __launch_bounds__(kBlock) void k_discover(Params p)
         st_table = f;
     };
     // a position whose id is resident at `dist` probes from home
-    auto finish_hit = [&](const TableDesc &d, int64_t pos, int64_t home, int dist) {
+    auto finish_hit = [&](const Tab &d, int64_t pos, int64_t home, int dist) {
         const int64_t slot = wrap(home + dist, d.N);
         if (TRAIN) {
             d.M[slot] = meta_value(p, d, pos);        // "Update": refresh the resident's metadata
@@ -426,7 +456,7 @@ __global__ __launch_bounds__(kBlock) void k_discover(Params p)
             while (__any(todo)) {
                 const int f0 = __shfl(f, __ffsll((unsigned long long)__ballot(todo)) - 1);
                 const bool mine = todo && f == f0;
-                const TableDesc d = multi ? p.descs[f0] : p.t0;
+                const Tab d = view(multi ? p.descs[f0] : p.t0);
                 stats_table(f0);
                 int dist = -1;
                 for (;;) {
@@ -486,7 +516,7 @@ __global__ __launch_bounds__(kBlock) void k_discover(Params p)
         // every pass handles the lanes that belong to one table (one pass unless the chunk
         // straddles a feature boundary)
         while (__any(todo)) {
-            TableDesc d;
+            Tab d;
             int f = 0;
             bool mine = todo;
             if (multi) {
@@ -498,10 +528,10 @@ __global__ __launch_bounds__(kBlock) void k_discover(Params p)
                 int64_t seg_hi = p.offsets[f + 1];
                 if (f == p.num_tables - 1 || seg_hi > p.n) seg_hi = p.n;
                 if (seg_hi <= first_pos) seg_hi = first_pos + 1;
-                d = p.descs[f];
+                d = view(p.descs[f]);
                 mine = todo && pos < seg_hi;
             } else {
-                d = p.t0;
+                d = view(p.t0);
             }
             stats_table(f);
 
@@ -542,7 +572,7 @@ __global__ __launch_bounds__(kBlock) void k_discover(Params p)
 
 // ------------------------------------------------------------------ allocation
 // TTL test of Sec. 3.4 on a slot that holds an id
-__device__ __forceinline__ bool expired(const TableDesc &d, int32_t step, int64_t s)
+__device__ __forceinline__ bool expired(const Tab &d, int32_t step, int64_t s)
 {
     return is_expired(d.evict, d.ttl, step, d.M[s]);
 }
@@ -561,7 +591,7 @@ constexpr uint32_t kHintUnknown = 0xFD;    // placed, but not at a round that fi
 // Deferred acceptance by the whole wavefront for the claimant at batch position cpos from round
 // cr on (all arguments wave-uniform).  A claimant it displaces is carried on in turn.  Returns
 // the round at which the FIRST claimant was placed, or -1 if it ran out of slots.
-__device__ __forceinline__ int32_t claim_wave(const Params &p, const TableDesc &d, uint32_t cpos, int32_t cr)
+__device__ __forceinline__ int32_t claim_wave(const Params &p, const Tab &d, uint32_t cpos, int32_t cr)
 {
     const int lane = lane_id();
     int64_t home = home_slot(p.ids[cpos], d.seed, d.N);
@@ -619,7 +649,13 @@ __device__ __forceinline__ int32_t claim_wave(const Params &p, const TableDesc &
     return first_round;
 }
 
-template <int PMAX>
+// What the lanes that load a claimant's window need of the claimant's table (several tables only)
+struct TabWords {
+    int64_t I, M, N;
+    int32_t P, ttl, evict, pad_;
+};
+
+template <int PMAX, bool MULTI>
 __global__ __launch_bounds__(kWave) void k_allocate(Params p)
 {
     constexpr int G = PMAX < kLine ? PMAX : kLine;   // lanes that read one claimant's window together
@@ -629,10 +665,11 @@ __global__ __launch_bounds__(kWave) void k_allocate(Params p)
     // what a lane needs to know of a slot: -1 empty, a claim tag (<= -2), 1 = holds an expired id,
     // 0 = holds a live id
     __shared__ int64_t s_I[kWave][PMAX + 1];         // +1: rows fall into different banks
+    __shared__ TabWords s_d[MULTI ? kWave : 1];      // every lane's table, for the lanes that load for it
 
     const int lane = threadIdx.x;
     const int g = lane / G, r = lane % G;
-    const bool multi = p.num_tables > 1;
+    const Tab d0 = view(p.t0);
     for (int64_t seg = blockIdx.x; seg < p.num_segs; seg += gridDim.x) {
         const uint32_t cnt = p.seg_cnt[seg];
         const int64_t seg_base = seg * p.seg_chunks * kWave;
@@ -649,35 +686,36 @@ __global__ __launch_bounds__(kWave) void k_allocate(Params p)
             const bool have = j0 + lane < cnt;
             bool agent = false;
             int f = 0;
-            TableDesc d = p.t0;
+            Tab d = d0;
             if (have) {
                 const uint32_t first = p.set_slot[e];
                 p.first_of[idx] = first;
                 agent = first == pos;                         // else: a later copy of the id
-                if (agent && multi) { f = find_table(p.offsets, p.num_tables, (int64_t)pos); d = p.descs[f]; }
+                if (MULTI && agent) { f = find_table(p.offsets, p.num_tables, (int64_t)pos); d = view(p.descs[f]); }
             }
             if (!agent) home = 0;
+            if constexpr (MULTI) {
+                s_d[lane] = TabWords{(int64_t)d.I, (int64_t)d.M, d.N, d.P, d.ttl, d.evict, 0};
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            }
             // cooperative loads; lanes without a slot to read use slot 0 / the home slot (valid addresses)
             int64_t vi[NT * CH];
             int32_t vm[NT * CH];
-            uint32_t gmeta[NT];                               // the claimant's table: ttl
-            int32_t gmode[NT];                                // ... and eviction mode
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
                 const int a = t * APL + g;
                 const int64_t ghome = shfl64(home, a);
-                int64_t *gI = p.t0.I;
-                int32_t *gM = p.t0.M;
-                int64_t gN = p.t0.N;
-                int gP = p.t0.P;
-                int gttl = p.t0.ttl, gev = p.t0.evict;
-                if (multi) {
-                    const TableDesc &gd = p.descs[__shfl(f, a)];
-                    gI = gd.I; gM = gd.M; gN = gd.N; gP = gd.P;
-                    gttl = gd.ttl; gev = gd.evict;
+                global_ptr<int64_t> gI = d0.I;
+                global_ptr<int32_t> gM = d0.M;
+                int64_t gN = d0.N;
+                int gP = d0.P;
+                if constexpr (MULTI) {
+                    const TabWords &gd = s_d[a];
+                    gI = (global_ptr<int64_t>)gd.I;
+                    gM = (global_ptr<int32_t>)gd.M;
+                    gN = gd.N;
+                    gP = gd.P;
                 }
-                gmeta[t] = (uint32_t)gttl;
-                gmode[t] = gev;
 #pragma unroll
                 for (int c = 0; c < CH; ++c) {
                     const int k = c * G + r;
@@ -687,13 +725,19 @@ __global__ __launch_bounds__(kWave) void k_allocate(Params p)
                 }
             }
 #pragma unroll
-            for (int t = 0; t < NT; ++t)
+            for (int t = 0; t < NT; ++t) {
+                int32_t gttl = d0.ttl, gev = d0.evict;        // the claimant's table: ttl and eviction mode
+                if constexpr (MULTI) {
+                    gttl = s_d[t * APL + g].ttl;
+                    gev = s_d[t * APL + g].evict;
+                }
 #pragma unroll
                 for (int c = 0; c < CH; ++c) {
                     int64_t w = vi[t * CH + c];
-                    if (w >= 0) w = is_expired(gmode[t], (int32_t)gmeta[t], p.step, vm[t * CH + c]) ? 1 : 0;
+                    if (w >= 0) w = is_expired(gev, gttl, p.step, vm[t * CH + c]) ? 1 : 0;
                     s_I[t * APL + g][c * G + r] = w;
                 }
+            }
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             // lane phase
             uint32_t hint = kHintNone;
@@ -736,7 +780,7 @@ __global__ __launch_bounds__(kWave) void k_allocate(Params p)
                 const uint32_t cpos = __shfl(mpos, src);
                 const int32_t cr = __shfl(mr, src);
                 const uint32_t own = __shfl(pos, src);
-                const TableDesc dw = multi ? p.descs[__shfl(f, src)] : p.t0;
+                const Tab dw = MULTI ? view(p.descs[__shfl(f, src)]) : d0;
                 const int32_t fr = claim_wave(p, dw, cpos, cr);
                 if (lane == src && cpos == own)
                     hint = fr < 0 ? kHintUnplaced : (fr < (int32_t)kHintUnknown ? (uint32_t)fr : kHintUnknown);
@@ -757,7 +801,7 @@ __global__ __launch_bounds__(kWave) void k_allocate(Params p)
 // of the lowest (choice, position).  One wavefront serves one claimant, one lane per slot of its
 // window (max_probe <= 64); a displaced claimant is carried on from its next choice.
 // Returns the probe round at which the first claimant was placed, or -1.
-__device__ __forceinline__ int32_t claim_wave_lru(const Params &p, const TableDesc &d, uint32_t cpos, int32_t choice)
+__device__ __forceinline__ int32_t claim_wave_lru(const Params &p, const Tab &d, uint32_t cpos, int32_t choice)
 {
     const int lane = lane_id();
     int32_t first_round = -1;
@@ -837,7 +881,7 @@ __global__ __launch_bounds__(kWave) void k_allocate_lru(Params p)
                 const int src = __ffsll((unsigned long long)am) - 1;
                 am &= am - 1;
                 const uint32_t cpos = __shfl(pos, src);
-                const TableDesc dw = multi ? p.descs[find_table(p.offsets, p.num_tables, (int64_t)cpos)] : p.t0;
+                const Tab dw = view(multi ? p.descs[find_table(p.offsets, p.num_tables, (int64_t)cpos)] : p.t0);
                 const int32_t fr = claim_wave_lru(p, dw, cpos, 0);
                 if (lane == src) hint = fr < 0 ? kHintUnplaced : (uint32_t)fr;
             }
@@ -990,12 +1034,12 @@ __global__ __launch_bounds__(kBlock) void k_finalize(Params p)
             }
             int outcome = 2, f = 0;
             int64_t s_final = 0, home = 0, id = 0;
-            TableDesc d = p.t0;
+            Tab d = view(p.t0);
             bool search = false;         // the hint did not lead to the tag: the window is searched
             int at = -1;
             uint32_t occ = 0;
             if (agent) {
-                if (multi) { f = find_table(p.offsets, p.num_tables, (int64_t)pos); d = p.descs[f]; }
+                if (multi) { f = find_table(p.offsets, p.num_tables, (int64_t)pos); d = view(p.descs[f]); }
                 id = p.ids[pos];
                 home = p.homes[seg_base + j0 + lane];
                 // the slot that carries this claimant's tag: where k_allocate left it, unless the
@@ -1014,7 +1058,7 @@ __global__ __launch_bounds__(kBlock) void k_finalize(Params p)
                 sm &= sm - 1;
                 const uint32_t cpos = __shfl(pos, src);
                 const int64_t chome = shfl64(home, src);
-                const TableDesc dw = multi ? p.descs[__shfl(f, src)] : p.t0;
+                const Tab dw = view(multi ? p.descs[__shfl(f, src)] : p.t0);
                 int found_round = -1;
                 uint32_t found_occ = 0;
                 for (int32_t c0 = 0; c0 < dw.P && found_round < 0; c0 += kWave) {
