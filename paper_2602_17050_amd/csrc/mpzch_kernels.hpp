@@ -62,6 +62,7 @@ struct TableDesc {
 struct Control {
     unsigned long long num_evicted[kMaxTables];
     unsigned long long stats[kMaxTables][kStatCount];
+    unsigned long long done;       // workgroups of k_emit_dups that have added their share of the rows
 };
 
 // Per-workgroup partial counters, written once with plain stores and summed by k_emit_dups.
@@ -1103,6 +1104,7 @@ __global__ __launch_bounds__(kBlock) void k_finalize(Params p)
 __global__ __launch_bounds__(kBlock) void k_emit_dups(Params p)
 {
     __shared__ unsigned long long s_bins[kMaxTables][kStatCount];
+    __shared__ bool s_last;
     const int lane = lane_id();
     const int64_t wave_global = ((int64_t)blockIdx.x * kBlock + threadIdx.x) / kWave;
     const int64_t num_waves = (int64_t)gridDim.x * kWavesPerBlock;
@@ -1120,27 +1122,47 @@ __global__ __launch_bounds__(kBlock) void k_emit_dups(Params p)
     if (blockIdx.x == 0) {
         for (int i = threadIdx.x; i < p.num_tables; i += kBlock)
             p.out_num_evicted[i] = (int64_t)p.ctl->num_evicted[i];
-        if (p.out_stats) {
-            const int nbins = p.num_tables * kStatCount;
-            for (int i = threadIdx.x; i < nbins; i += kBlock)
-                s_bins[i / kStatCount][i % kStatCount] = p.ctl->stats[i / kStatCount][i % kStatCount];
-            __syncthreads();
-            for (int i = threadIdx.x; i < p.blocks_a + p.blocks_b; i += kBlock) {
-                const StatRow *row = i < p.blocks_a ? &p.rows_a[i] : &p.rows_b[i - p.blocks_a];
-                const int t = (int)row->table;
-                for (int k = 0; k < kStatCount; ++k) {
-                    const unsigned long long v = row->v[k];
-                    if (v) atomicAdd(&s_bins[t][k], v);
-                }
-            }
-            __syncthreads();
-            for (int t = threadIdx.x; t < p.num_tables; t += kBlock)
-                s_bins[t][kDistinctMiss] = s_bins[t][kInserts] + s_bins[t][kEvictions] + s_bins[t][kCollisions];
-            __syncthreads();
-            for (int i = threadIdx.x; i < nbins; i += kBlock)
-                p.out_stats[i] = (int64_t)s_bins[i / kStatCount][i % kStatCount];
+    }
+    if (!p.out_stats) return;
+
+    // Counters: the per-workgroup rows of k_discover and k_finalize are summed by the first
+    // workgroups of this grid, kBlock rows each, into the call's counter block; the workgroup
+    // that finishes last reads the totals back and publishes them.
+    const int rows = p.blocks_a + p.blocks_b;
+    int helpers = (rows + kBlock - 1) / kBlock;
+    if (helpers > (int)gridDim.x) helpers = (int)gridDim.x;
+    if ((int)blockIdx.x >= helpers) return;
+    const int nbins = p.num_tables * kStatCount;
+    for (int i = threadIdx.x; i < nbins; i += kBlock) s_bins[i / kStatCount][i % kStatCount] = 0ull;
+    __syncthreads();
+    for (int i = blockIdx.x * kBlock + threadIdx.x; i < rows; i += helpers * kBlock) {
+        const StatRow *row = i < p.blocks_a ? &p.rows_a[i] : &p.rows_b[i - p.blocks_a];
+        const int t = (int)row->table;
+        for (int k = 0; k < kStatCount; ++k) {
+            const unsigned long long v = row->v[k];
+            if (v) atomicAdd(&s_bins[t][k], v);
         }
     }
+    __syncthreads();
+    for (int i = threadIdx.x; i < nbins; i += kBlock) {
+        const unsigned long long v = s_bins[i / kStatCount][i % kStatCount];
+        if (v) atomicAdd(&p.ctl->stats[i / kStatCount][i % kStatCount], v);
+    }
+    __threadfence();                     // this workgroup's additions are visible before it counts as done
+    __syncthreads();
+    if (threadIdx.x == 0) s_last = atomicAdd(&p.ctl->done, 1ull) == (unsigned long long)(helpers - 1);
+    __syncthreads();
+    if (!s_last) return;
+    __threadfence();
+    for (int i = threadIdx.x; i < nbins; i += kBlock)
+        s_bins[i / kStatCount][i % kStatCount] =
+            __hip_atomic_load(&p.ctl->stats[i / kStatCount][i % kStatCount], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    for (int t = threadIdx.x; t < p.num_tables; t += kBlock)
+        s_bins[t][kDistinctMiss] = s_bins[t][kInserts] + s_bins[t][kEvictions] + s_bins[t][kCollisions];
+    __syncthreads();
+    for (int i = threadIdx.x; i < nbins; i += kBlock)
+        p.out_stats[i] = (int64_t)s_bins[i / kStatCount][i % kStatCount];
 }
 
 // ------------------------------------------------------------------ fills and row reset
