@@ -231,7 +231,13 @@ mpzch_status_t launch_allocate(int32_t max_p, const Params &p, int num_cus, hipS
     // one wavefront per workgroup, one segment per workgroup pass; the lane phase covers the first
     // 8 or 16 slots of every window, longer windows continue in the wave phase
     const int grid = grid_for((int64_t)p.num_segs, 1, num_cus, 4 * group_blocks_per_cu());
-    if (p.t0.evict == 2) hipLaunchKernelGGL(k_allocate_lru, dim3(grid), dim3(kWave), 0, s, p);
+    if (p.t0.evict == 2) {
+        // a group of 8, 16, 32 or 64 lanes per claimant, whichever holds its window
+        if (max_p <= 8) hipLaunchKernelGGL((k_allocate_lru<8>), dim3(grid), dim3(kWave), 0, s, p);
+        else if (max_p <= 16) hipLaunchKernelGGL((k_allocate_lru<16>), dim3(grid), dim3(kWave), 0, s, p);
+        else if (max_p <= 32) hipLaunchKernelGGL((k_allocate_lru<32>), dim3(grid), dim3(kWave), 0, s, p);
+        else hipLaunchKernelGGL((k_allocate_lru<64>), dim3(grid), dim3(kWave), 0, s, p);
+    }
     else if (p.num_tables > 1) {
         if (max_p <= 8) hipLaunchKernelGGL((k_allocate<8, true>), dim3(grid), dim3(kWave), 0, s, p);
         else hipLaunchKernelGGL((k_allocate<16, true>), dim3(grid), dim3(kWave), 0, s, p);

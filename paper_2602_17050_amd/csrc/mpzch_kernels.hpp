@@ -799,68 +799,93 @@ __global__ __launch_bounds__(kWave) void k_allocate(Params p)
 // oldest first -- follows from the state at the start of allocation, which stays readable while
 // claims are in flight: a tag keeps the was-occupied bit and metadata is not written before
 // k_finalize.  The tag's round field carries the CHOICE number, so a slot ends with the claimant
-// of the lowest (choice, position).  One wavefront serves one claimant, one lane per slot of its
-// window (max_probe <= 64); a displaced claimant is carried on from its next choice.
-// Returns the probe round at which the first claimant was placed, or -1.
-__device__ __forceinline__ int32_t claim_wave_lru(const Params &p, const Tab &d, uint32_t cpos, int32_t choice)
+// of the lowest (choice, position).  A group of G lanes serves one claimant, one lane per slot of
+// its window (max_probe <= G <= 64), so a wavefront works on 64 / G claimants at a time; a
+// displaced claimant is carried on by the group that displaced it, from its next choice.
+// active, cpos and choice are uniform within a group.  Returns the probe round at which the
+// group's first claimant was placed, or -1.
+template <int G>
+__device__ __forceinline__ int32_t claim_group_lru(const Params &p, const Tab &d, bool active, uint32_t cpos,
+                                                   int32_t choice)
 {
     const int lane = lane_id();
+    const int r = lane % G, gbase = lane - r;
+    const uint64_t gmask = G == kWave ? ~0ull : ((1ull << (G % kWave)) - 1ull) << gbase;
+    const uint64_t below = (1ull << lane) - 1ull;
     int32_t first_round = -1;
     bool is_first = true;
-    for (;;) {
-        const int64_t home = home_slot(p.ids[cpos], d.seed, d.N);
-        const bool in = lane < d.P;
+    while (__any(active)) {
+        const bool in = active && r < d.P;
         int64_t s = 0, v = 0;
         int32_t m = 0;
         if (in) {
-            s = wrap(home + lane, d.N);
+            s = wrap(home_slot(p.ids[cpos], d.seed, d.N) + r, d.N);
             v = __hip_atomic_load(&d.I[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             m = d.M[s];
         }
         const bool base_empty = in && (v == -1 || (is_tag(v) && !tag_occ(v)));
         const bool evictable = in && (v >= 0 || (is_tag(v) && tag_occ(v))) && m != p.step;
-        const uint64_t emask = __ballot(base_empty);
+        const uint64_t emask = __ballot(base_empty) & gmask;
+        const uint64_t vmask = __ballot(evictable) & gmask;
         const int n_empty = __popcll(emask);
         // rank of this lane's slot in the claimant's preference list
         int older = 0;
-        for (int l = 0; l < d.P; ++l) {
-            const int32_t ml = __shfl(m, l);
-            const bool el = __shfl((int)evictable, l);
-            if (el && (ml < m || (ml == m && l < lane))) ++older;
+        for (int l = 0; l < G; ++l) {
+            const int32_t ml = __shfl(m, gbase + l);
+            const bool el = (vmask >> (gbase + l)) & 1ull;
+            if (el && (ml < m || (ml == m && l < r))) ++older;
         }
         int rank = 0x7FFFFFFF;
-        if (base_empty) rank = __popcll(emask & ((1ull << lane) - 1ull));
+        if (base_empty) rank = __popcll(emask & below);
         else if (evictable) rank = n_empty + older;
-        const int n_choices = n_empty + __popcll(__ballot(evictable));
+        const int n_choices = n_empty + __popcll(vmask);
         bool placed = false;
         int64_t displaced = 0;
-        for (; choice < n_choices && !placed; ++choice) {
-            const uint64_t wb = __ballot(rank == choice);
-            const int who = __ffsll((unsigned long long)wb) - 1;      // exactly one lane has this rank
+        bool trying = active && choice < n_choices;
+        while (__any(trying)) {
+            const uint64_t wb = __ballot(trying && rank == choice) & gmask;
+            const int who = __ffsll((unsigned long long)wb) - 1;      // exactly one lane of a trying group has this rank
             int64_t old = 0, mine = 0;
             if (lane == who) {
                 mine = make_tag((uint32_t)choice, cpos, base_empty ? 0u : 1u);
                 old = __hip_atomic_fetch_min(&d.I[s], mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
-            old = shfl64(old, who);
-            mine = shfl64(mine, who);
-            if (is_tag(old) && old < mine) continue;                    // a better claim holds this slot
-            placed = true;
-            displaced = is_tag(old) ? old : 0;
-            if (is_first) first_round = who;
+            const int from = who >= 0 ? who : lane;
+            old = shfl64(old, from);
+            mine = shfl64(mine, from);
+            if (trying) {
+                if (is_tag(old) && old < mine) {
+                    ++choice;                                           // a better claim holds this slot
+                    trying = choice < n_choices;
+                } else {
+                    placed = true;
+                    displaced = is_tag(old) ? old : 0;
+                    if (is_first) first_round = who - gbase;
+                    trying = false;
+                }
+            }
         }
         is_first = false;
-        if (!placed || !displaced) break;
-        cpos = tag_pos(displaced);                                       // same table: same slot
-        choice = (int32_t)tag_round(displaced) + 1;
+        if (active) {
+            if (!placed || !displaced) {
+                active = false;
+            } else {
+                cpos = tag_pos(displaced);                               // same table: same slot
+                choice = (int32_t)tag_round(displaced) + 1;
+            }
+        }
     }
     return first_round;
 }
 
+// One workgroup = one wavefront; single tables only.
+template <int G>
 __global__ __launch_bounds__(kWave) void k_allocate_lru(Params p)
 {
+    constexpr int NG = kWave / G;
     const int lane = threadIdx.x;
-    const bool multi = p.num_tables > 1;
+    const int g = lane / G;
+    const Tab d = view(p.t0);
     for (int64_t seg = blockIdx.x; seg < p.num_segs; seg += gridDim.x) {
         const uint32_t cnt = p.seg_cnt[seg];
         const int64_t seg_base = seg * p.seg_chunks * kWave;
@@ -879,12 +904,23 @@ __global__ __launch_bounds__(kWave) void k_allocate_lru(Params p)
             uint32_t hint = kHintNone;
             uint64_t am = __ballot(agent);
             while (am) {
-                const int src = __ffsll((unsigned long long)am) - 1;
-                am &= am - 1;
-                const uint32_t cpos = __shfl(pos, src);
-                const Tab dw = view(multi ? p.descs[find_table(p.offsets, p.num_tables, (int64_t)cpos)] : p.t0);
-                const int32_t fr = claim_wave_lru(p, dw, cpos, 0);
-                if (lane == src) hint = fr < 0 ? kHintUnplaced : (uint32_t)fr;
+                // the next NG claimants, one per group of lanes
+                int src = -1;
+#pragma unroll
+                for (int k = 0; k < NG; ++k) {
+                    const int sk = am ? __ffsll((unsigned long long)am) - 1 : -1;
+                    am &= am - 1;                                         // 0 stays 0
+                    if (k == g) src = sk;
+                }
+                const uint32_t cpos = __shfl(pos, src >= 0 ? src : lane);
+                const int32_t fr = claim_group_lru<G>(p, d, src >= 0, cpos, 0);
+                // the outcome goes to the lane that holds the claimant's list entry
+#pragma unroll
+                for (int k = 0; k < NG; ++k) {
+                    const int sk = __shfl(src, k * G);
+                    const int32_t frk = __shfl(fr, k * G);
+                    if (lane == sk) hint = frk < 0 ? kHintUnplaced : (uint32_t)frk;
+                }
             }
             if (have) p.hint[idx] = (uint8_t)hint;
         }
