@@ -13,6 +13,8 @@ CASES = [
     (7, 3, 20, 64, 10),
     (50, 8, 300, 257, 12),
     (100, 16, 400, 1000, 12),
+    (300, 24, 1500, 3000, 10),
+    (513, 32, 3000, 5000, 8),
     (257, 33, 2000, 4096, 10),
     (1000, 64, 5000, 8191, 8),
     (64, 64, 300, 500, 8),
