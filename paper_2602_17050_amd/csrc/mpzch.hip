@@ -225,22 +225,32 @@ mpzch_status_t launch_discover(const Params &p, int grid, hipStream_t s)
     return MPZCH_OK;
 }
 
-// max_p: largest min(max_probe, num_slots) of the tables involved
-mpzch_status_t launch_allocate(int32_t max_p, const Params &p, int num_cus, hipStream_t s)
+// max_p: largest min(max_probe, num_slots) of the tables involved; max_p_lru: the same over the LRU
+// tables, 0 when there is none
+template <bool MULTI>
+void launch_allocate_lru(int32_t max_p_lru, const Params &p, int grid, hipStream_t s)
+{
+    // a group of 8, 16, 32 or 64 lanes per claimant, whichever holds its window
+    if (max_p_lru <= 8) hipLaunchKernelGGL((k_allocate_lru<8, MULTI>), dim3(grid), dim3(kWave), 0, s, p);
+    else if (max_p_lru <= 16) hipLaunchKernelGGL((k_allocate_lru<16, MULTI>), dim3(grid), dim3(kWave), 0, s, p);
+    else if (max_p_lru <= 32) hipLaunchKernelGGL((k_allocate_lru<32, MULTI>), dim3(grid), dim3(kWave), 0, s, p);
+    else hipLaunchKernelGGL((k_allocate_lru<64, MULTI>), dim3(grid), dim3(kWave), 0, s, p);
+}
+
+mpzch_status_t launch_allocate(int32_t max_p, int32_t max_p_lru, const Params &p, int num_cus, hipStream_t s)
 {
     // one wavefront per workgroup, one segment per workgroup pass; the lane phase covers the first
     // 8 or 16 slots of every window, longer windows continue in the wave phase
     const int grid = grid_for((int64_t)p.num_segs, 1, num_cus, 4 * group_blocks_per_cu());
-    if (p.t0.evict == 2) {
-        // a group of 8, 16, 32 or 64 lanes per claimant, whichever holds its window
-        if (max_p <= 8) hipLaunchKernelGGL((k_allocate_lru<8>), dim3(grid), dim3(kWave), 0, s, p);
-        else if (max_p <= 16) hipLaunchKernelGGL((k_allocate_lru<16>), dim3(grid), dim3(kWave), 0, s, p);
-        else if (max_p <= 32) hipLaunchKernelGGL((k_allocate_lru<32>), dim3(grid), dim3(kWave), 0, s, p);
-        else hipLaunchKernelGGL((k_allocate_lru<64>), dim3(grid), dim3(kWave), 0, s, p);
-    }
-    else if (p.num_tables > 1) {
+    if (p.num_tables > 1) {
+        // several tables: TTL / no-eviction claimants first (this also writes every hint), then
+        // the claimants of LRU tables
         if (max_p <= 8) hipLaunchKernelGGL((k_allocate<8, true>), dim3(grid), dim3(kWave), 0, s, p);
         else hipLaunchKernelGGL((k_allocate<16, true>), dim3(grid), dim3(kWave), 0, s, p);
+        LAUNCH_CHECK();
+        if (max_p_lru > 0) launch_allocate_lru<true>(max_p_lru, p, grid, s);
+    } else if (max_p_lru > 0) {
+        launch_allocate_lru<false>(max_p_lru, p, grid, s);
     } else {
         if (max_p <= 8) hipLaunchKernelGGL((k_allocate<8, false>), dim3(grid), dim3(kWave), 0, s, p);
         else hipLaunchKernelGGL((k_allocate<16, false>), dim3(grid), dim3(kWave), 0, s, p);
@@ -269,7 +279,7 @@ mpzch_status_t launch_finalize(const Params &p, int grid, hipStream_t s)
     } while (0)
 
 // The launch sequence of one training remap (single table or group).
-mpzch_status_t run_remap(Scratch &sc, Timing &tm, Params p, int32_t max_p, hipStream_t s)
+mpzch_status_t run_remap(Scratch &sc, Timing &tm, Params p, int32_t max_p, int32_t max_p_lru, hipStream_t s)
 {
     p.list = sc.list;
     p.ent = sc.ent;
@@ -295,7 +305,7 @@ mpzch_status_t run_remap(Scratch &sc, Timing &tm, Params p, int32_t max_p, hipSt
     p.blocks_b = g_grp;
 
     TIMED(tm, KDiscover, s, (launch_discover<true>(p, g_disc, s)));
-    TIMED(tm, KAllocate, s, launch_allocate(max_p, p, sc.num_cus, s));
+    TIMED(tm, KAllocate, s, launch_allocate(max_p, max_p_lru, p, sc.num_cus, s));
     TIMED(tm, KFinalize, s, launch_finalize(p, g_grp, s));
     if (!tm.begin(KEmitDups, s)) return MPZCH_ERR_HIP;
     hipLaunchKernelGGL(k_emit_dups, dim3(g_grp), dim3(kBlock), 0, s, p);
@@ -419,7 +429,7 @@ mpzch_status_t mpzch_remap_feature_ttl(mpzch_table_t *t, int64_t *identities, in
     p.out_evicted = out_evicted_slots;
     p.out_num_evicted = out_num_evicted;
     p.out_stats = out_stats;
-    return run_remap(t->sc, t->tm, p, p.t0.P, s);
+    return run_remap(t->sc, t->tm, p, p.t0.P, p.t0.evict == 2 ? p.t0.P : 0, s);
 }
 
 mpzch_status_t mpzch_remap(mpzch_table_t *t, int64_t *identities, int32_t *metadata,
@@ -632,7 +642,6 @@ mpzch_status_t mpzch_group_create(mpzch_table_t *const *tables, int32_t num_tabl
     if (!tables || num_tables < 1 || num_tables > MPZCH_MAX_GROUP_TABLES) return MPZCH_ERR_INVALID_ARG;
     for (int i = 0; i < num_tables; ++i) {
         if (!tables[i]) return MPZCH_ERR_INVALID_ARG;
-        if (tables[i]->cfg.kind == MPZCH_EVICT_LRU) return MPZCH_ERR_UNSUPPORTED;   // groups: TTL / none only
     }
     mpzch_group *g = new (std::nothrow) mpzch_group();
     if (!g) return MPZCH_ERR_ALLOC;
@@ -669,7 +678,7 @@ mpzch_status_t mpzch_remap_jagged(mpzch_group_t *g, int64_t *const *identities, 
     if (total_values < 0 || total_values > MPZCH_MAX_BATCH || step < 0) return MPZCH_ERR_INVALID_ARG;
     if (total_values > 0 && (!values || !out_slots)) return MPZCH_ERR_INVALID_ARG;
     const int T = (int)g->cfgs.size();
-    int32_t max_p = 1;
+    int32_t max_p = 1, max_p_lru = 0;
     std::vector<TableDesc> descs((size_t)T);
     for (int f = 0; f < T; ++f) {
         if (!identities[f] || !metadata[f]) return MPZCH_ERR_INVALID_ARG;
@@ -678,6 +687,7 @@ mpzch_status_t mpzch_remap_jagged(mpzch_group_t *g, int64_t *const *identities, 
         if (cap > 0 && !out_evicted_slots) return MPZCH_ERR_INVALID_ARG;
         descs[f] = make_desc(g->cfgs[f], identities[f], metadata[f], evicted_offsets[f], cap);
         if (descs[f].P > max_p) max_p = descs[f].P;
+        if (descs[f].evict == 2 && descs[f].P > max_p_lru) max_p_lru = descs[f].P;
     }
     hipStream_t s = (hipStream_t)stream;
     if (total_values == 0) {
@@ -715,7 +725,7 @@ mpzch_status_t mpzch_remap_jagged(mpzch_group_t *g, int64_t *const *identities, 
     p.out_stats = out_stats;
     // a group of one table still goes through the descriptor path
     if (T == 1) p.num_tables = 1;
-    return run_remap(g->sc, g->tm, p, max_p, s);
+    return run_remap(g->sc, g->tm, p, max_p, max_p_lru, s);
 }
 
 mpzch_status_t mpzch_set_kernel_timing(mpzch_table_t *t, int32_t enable)

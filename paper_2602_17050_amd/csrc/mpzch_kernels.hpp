@@ -692,7 +692,11 @@ __global__ __launch_bounds__(kWave) void k_allocate(Params p)
                 const uint32_t first = p.set_slot[e];
                 p.first_of[idx] = first;
                 agent = first == pos;                         // else: a later copy of the id
-                if (MULTI && agent) { f = find_table(p.offsets, p.num_tables, (int64_t)pos); d = view(p.descs[f]); }
+                if (MULTI && agent) {
+                    f = find_table(p.offsets, p.num_tables, (int64_t)pos);
+                    d = view(p.descs[f]);
+                    if (d.evict == 2) agent = false;          // claimants of LRU tables are served by k_allocate_lru
+                }
             }
             if (!agent) home = 0;
             if constexpr (MULTI) {
@@ -878,14 +882,16 @@ __device__ __forceinline__ int32_t claim_group_lru(const Params &p, const Tab &d
     return first_round;
 }
 
-// One workgroup = one wavefront; single tables only.
-template <int G>
+// One workgroup = one wavefront.  With several tables this kernel runs after k_allocate, which has
+// written the hints of every list entry and skipped the claimants of LRU tables; here only those
+// claimants are served and only their hints are written.
+template <int G, bool MULTI>
 __global__ __launch_bounds__(kWave) void k_allocate_lru(Params p)
 {
     constexpr int NG = kWave / G;
     const int lane = threadIdx.x;
     const int g = lane / G;
-    const Tab d = view(p.t0);
+    const Tab d0 = view(MULTI ? p.descs[0] : p.t0);
     for (int64_t seg = blockIdx.x; seg < p.num_segs; seg += gridDim.x) {
         const uint32_t cnt = p.seg_cnt[seg];
         const int64_t seg_base = seg * p.seg_chunks * kWave;
@@ -895,11 +901,16 @@ __global__ __launch_bounds__(kWave) void k_allocate_lru(Params p)
             const bool have = j0 + lane < cnt;
             uint32_t pos = 0;
             bool agent = false;
+            int f = 0;
             if (have) {
                 pos = p.list[idx];
                 const uint32_t first = p.set_slot[p.ent[idx]];
                 p.first_of[idx] = first;
                 agent = first == pos;
+                if (MULTI && agent) {
+                    f = find_table(p.offsets, p.num_tables, (int64_t)pos);
+                    agent = p.descs[f].evict == 2;
+                }
             }
             uint32_t hint = kHintNone;
             uint64_t am = __ballot(agent);
@@ -913,6 +924,8 @@ __global__ __launch_bounds__(kWave) void k_allocate_lru(Params p)
                     if (k == g) src = sk;
                 }
                 const uint32_t cpos = __shfl(pos, src >= 0 ? src : lane);
+                const int fs = __shfl(f, src >= 0 ? src : lane);
+                const Tab d = (MULTI && src >= 0) ? view(p.descs[fs]) : d0;
                 const int32_t fr = claim_group_lru<G>(p, d, src >= 0, cpos, 0);
                 // the outcome goes to the lane that holds the claimant's list entry
 #pragma unroll
@@ -922,7 +935,7 @@ __global__ __launch_bounds__(kWave) void k_allocate_lru(Params p)
                     if (lane == sk) hint = frk < 0 ? kHintUnplaced : (uint32_t)frk;
                 }
             }
-            if (have) p.hint[idx] = (uint8_t)hint;
+            if (MULTI ? agent : have) p.hint[idx] = (uint8_t)hint;
         }
     }
 }

@@ -76,7 +76,7 @@ class TableSpec:
     num_slots: int
     max_probe: int
     ttl: int               # steps; ignored when evict is False
-    evict: bool = True     # TTL eviction on / off
+    evict: object = True   # True = TTL eviction, False = off; tests also pass "lru" / "expiry"
     hash_seed: int = HASH_SEED_BASE
     emb_rows: int = 0      # rows of the embedding the reset targets (row = slot mod emb_rows)
     emb_dim: int = 0

@@ -14,15 +14,16 @@ pytestmark = pytest.mark.gpu
 class JaggedPair:
     def __init__(self, specs):
         self.specs = specs
-        self.handles = [mp.mpzch_create(t.num_slots, t.max_probe, (mp.EVICT_TTL if t.evict else mp.EVICT_NONE, t.ttl),
-                                        t.hash_seed) for t in specs]
+        kg = lambda e: {"lru": mp.EVICT_LRU, "expiry": mp.EVICT_TTL_EXPIRY}.get(e, mp.EVICT_TTL if e else mp.EVICT_NONE)
+        ko = lambda e: {"lru": oracle.EVICT_LRU, "expiry": oracle.EVICT_TTL_EXPIRY}.get(
+            e, oracle.EVICT_TTL if e else oracle.EVICT_NONE)
+        self.handles = [mp.mpzch_create(t.num_slots, t.max_probe, (kg(t.evict), t.ttl), t.hash_seed) for t in specs]
         self.group = mp.mpzch_group_create(self.handles)
         self.I = [torch.empty(t.num_slots, dtype=torch.int64, device="cuda") for t in specs]
         self.M = [torch.empty(t.num_slots, dtype=torch.int32, device="cuda") for t in specs]
         for h, i, m in zip(self.handles, self.I, self.M):
             mp.mpzch_init_tensors(h, i, m)
-        self.o = [oracle.Table(t.num_slots, t.max_probe, oracle.EVICT_TTL if t.evict else oracle.EVICT_NONE, t.ttl,
-                               t.hash_seed) for t in specs]
+        self.o = [oracle.Table(t.num_slots, t.max_probe, ko(t.evict), t.ttl, t.hash_seed) for t in specs]
 
     def step(self, values, offsets, step):
         T = len(self.specs)
@@ -105,4 +106,31 @@ def test_group_of_one_table_equals_plain_remap():
         values = rng.integers(0, 2000, size=1500).astype(np.int64)
         jp.step(values, np.array([0, len(values)], np.int64), step)
     jp.check_state()
+    jp.close()
+
+
+@pytest.mark.parametrize("kinds", [("lru",) * 4, (True, "lru", False, "expiry", "lru", True)],
+                         ids=["all_lru", "mixed_policies"])
+def test_jagged_group_with_every_policy(kinds):
+    """Tables of different eviction policies in one group: TTL, off, LRU and expiry-step TTL
+    (each table its own retention, i.e. per-feature TTL with one table per feature)."""
+    shapes = [(60, 5), (300, 16), (1000, 24), (40, 40), (2000, 9), (500, 64)]
+    specs = [wl.TableSpec(n, p, 1 + i % 3, k, 100 + i) for i, ((n, p), k) in enumerate(zip(shapes, kinds))]
+    jp = JaggedPair(specs)
+    rng = np.random.Generator(np.random.Philox(key=1234 + len(kinds)))
+    tot = 0
+    step = 0
+    for it in range(12):
+        step += int(rng.integers(0, 3))
+        counts = [int(rng.integers(0, 3 * s.num_slots)) if rng.random() > 0.15 else 0 for s in specs]
+        vals = [rng.integers(-1, 5 * s.num_slots, size=c) for s, c in zip(specs, counts)]
+        values = np.concatenate(vals).astype(np.int64)
+        offsets = np.concatenate([[0], np.cumsum(counts)]).astype(np.int64)
+        say("policies", kinds, "step", step, counts)
+        sts = jp.step(values, offsets, step)
+        tot += sum(s["evictions"] for s in sts)
+        jp.check_state()
+        for o in jp.o:
+            assert o.check_state()[0] == 0
+    assert tot > 0
     jp.close()
