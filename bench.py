@@ -44,7 +44,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="headline", choices=["headline", "c4", "c3", "c1", "c2", "c5", "table1"])
     ap.add_argument("--scale", type=float, default=1.0, help="shrink slots and batch (quick checks only)")
-    ap.add_argument("--cpu-steps", type=int, default=2, help="steps the oracle replays for cpu_baseline (0 = skip)")
+    ap.add_argument("--cpu-steps", type=int, default=12,
+                    help="steps the oracle replays for cpu_baseline (0 = skip); 12 headline steps are about 10 s of CPU work")
     ap.add_argument("--no-kernel-timing", action="store_true")
     ap.add_argument("--policy", default="ttl", choices=["ttl", "lru"], help="eviction policy (headline / c4 workloads)")
     args = ap.parse_args()
