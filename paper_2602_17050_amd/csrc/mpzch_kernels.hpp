@@ -345,12 +345,14 @@ __device__ __forceinline__ void block_stat_row(const Params &p, StatRow *rows, i
 // slots, or kProbeAbsent when in addition one of them is empty: a slot never becomes empty again
 // once it was occupied, so no resident id lies beyond an empty slot of its window and the search
 // can end there.
+constexpr int kFirstG = 8;             // slots looked at by the first pass: the aligned 64 bytes that hold the home slot
 constexpr int kProbeGoOn = -1;
 constexpr int kProbeAbsent = -2;
 
+template <int G>
 __device__ __forceinline__ int probe_pass(const Tab &d, int64_t id, int64_t home, int q)
 {
-    constexpr int G = kLine, IPI = kWave / G;
+    constexpr int IPI = kWave / G;
     const int lane = lane_id();
     const int g = lane / G, r = lane % G;
     int64_t v[G];
@@ -463,7 +465,7 @@ __global__ __launch_bounds__(kBlock) void k_discover(Params p)
                 for (;;) {
                     const bool need = mine && dist < 0 && q < d.P;
                     if (!__any(need)) break;
-                    const int got = probe_pass(d, id, mine ? home : 0, need ? q : d.P);
+                    const int got = probe_pass<kLine>(d, id, mine ? home : 0, need ? q : d.P);
                     if (need) {
                         if (got >= 0) dist = got;
                         else if (got == kProbeAbsent) q = d.P;      // an empty slot ends the search
@@ -539,8 +541,8 @@ __global__ __launch_bounds__(kBlock) void k_discover(Params p)
             const bool valid = mine && id >= 0;
             const int64_t home = mine ? home_slot(id, d.seed, d.N) : 0;
             // first pass: the line that holds the home slot
-            const int o = (int)((home + (int64_t)(((uintptr_t)d.I >> 3) & (kLine - 1))) & (kLine - 1));
-            const int dist = probe_pass(d, id, home, valid ? -o : d.P);
+            const int o = (int)((home + (int64_t)(((uintptr_t)d.I >> 3) & (kFirstG - 1))) & (kFirstG - 1));
+            const int dist = probe_pass<kFirstG>(d, id, home, valid ? -o : d.P);
             if (valid && dist >= 0) {
                 finish_hit(d, pos, home, dist);
             } else if (mine && !valid) {
@@ -555,7 +557,7 @@ __global__ __launch_bounds__(kBlock) void k_discover(Params p)
                 const int at = staged + __popcll(pb & ((1ull << lane) - 1ull));
                 s_pos[w][at] = (uint32_t)pos;
                 s_home[w][at] = home;
-                s_q[w][at] = dist == kProbeAbsent ? d.P : kLine - o;    // d.P: nothing left to look at
+                s_q[w][at] = dist == kProbeAbsent ? d.P : kFirstG - o;  // d.P: nothing left to look at
             }
             staged += __popcll(pb);
             todo = todo && !mine;
