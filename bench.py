@@ -30,7 +30,7 @@ CEIL_STORES_PER_S = 22.9e9
 # HBM bytes per k_discover launch on the full-size headline workload, from rocprofv3 --pmc
 # FETCH_SIZE and WRITE_SIZE (KiB per dispatch x 1024, calibration factor 1.000); see
 # profiles/remap_headline_1Bslots_4Mids.txt.  Only valid for that workload at scale 1.
-HEADLINE_DISCOVER_TRAFFIC_BYTES = int((333696.0 + 180402.5) * 1024)
+HEADLINE_DISCOVER_TRAFFIC_BYTES = int((348763.8 + 182932.1) * 1024)
 
 
 def log(*a):
