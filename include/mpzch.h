@@ -113,6 +113,10 @@ mpzch_status_t mpzch_destroy(mpzch_table_t *t);
  * Optional: allocate scratch for batches of up to max_n positions now (about 29 bytes per
  * position) so that later remap calls allocate nothing.  Synchronises the device when it
  * has to grow the scratch.  Errors: INVALID_ARG (max_n < 0 or > MPZCH_MAX_BATCH), ALLOC.
+ * With enough scratch reserved and kernel timing off, mpzch_remap, mpzch_remap_feature_ttl,
+ * mpzch_lookup and the row movers only launch kernels on the given stream (no allocation, no
+ * synchronisation, no memset) and leave their counters zeroed for the next call, so a step may
+ * be captured into a HIP graph and replayed (step and pointers are then those of the capture).
  */
 mpzch_status_t mpzch_reserve(mpzch_table_t *t, int64_t max_n);
 
@@ -160,7 +164,8 @@ mpzch_status_t mpzch_remap(mpzch_table_t *t, int64_t *identities, int32_t *metad
 /*
  * mpzch_remap for a table of kind MPZCH_EVICT_TTL_EXPIRY whose ids come from features with different
  * retention (Sec. 3.4, second paragraph).  ttls [dev] int32[n]: retention in steps (>= 0) of the feature
- * each position belongs to; all copies of an id must carry the same value; NULL = policy.ttl for all
+ * each position belongs to; all copies of an id must carry the same value (else the stored value is
+ * that of one of the copies, unspecified which); NULL = policy.ttl for all
  * (then any table kind is accepted and the call is mpzch_remap).  step + ttl must fit int32.
  */
 mpzch_status_t mpzch_remap_feature_ttl(mpzch_table_t *t, int64_t *identities, int32_t *metadata,

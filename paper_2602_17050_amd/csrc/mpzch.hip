@@ -116,8 +116,7 @@ struct Scratch {
     uint32_t *set_slot = nullptr;
     StatRow *rows_a = nullptr;
     StatRow *rows_b = nullptr;
-    Control *ctl[2] = {nullptr, nullptr};
-    int parity = 0;
+    Control *ctl = nullptr;
     int num_cus = 0;
 
     static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -156,7 +155,7 @@ struct Scratch {
         const size_t o_set = o_seg + align_up(4 * max_blocks * kWavesPerBlock);
         const size_t o_rows = o_set + align_up(8 * (size_t)n);
         const size_t o_ctl = o_rows + 2 * align_up(max_blocks * sizeof(StatRow));
-        const size_t total = o_ctl + 2 * align_up(sizeof(Control));
+        const size_t total = o_ctl + align_up(sizeof(Control));
         if (hipMalloc((void **)&base, total) != hipSuccess) { base = nullptr; return MPZCH_ERR_ALLOC; }
         list = (uint32_t *)(base + o_list);
         ent = (uint32_t *)(base + o_ent);
@@ -167,15 +166,13 @@ struct Scratch {
         set_slot = (uint32_t *)(base + o_set);
         rows_a = (StatRow *)(base + o_rows);
         rows_b = (StatRow *)(base + o_rows + align_up(max_blocks * sizeof(StatRow)));
-        ctl[0] = (Control *)(base + o_ctl);
-        ctl[1] = (Control *)(base + o_ctl + align_up(sizeof(Control)));
+        ctl = (Control *)(base + o_ctl);
         // empty set (0xFFFFFFFF) and zero counters; set entries are re-emptied by every call, so
         // this is the only full clear
         if (hipMemset(base + o_set, 0xFF, (o_rows - o_set)) != hipSuccess) return MPZCH_ERR_HIP;
         if (hipMemset(base + o_rows, 0, total - o_rows) != hipSuccess) return MPZCH_ERR_HIP;
         if (hipDeviceSynchronize() != hipSuccess) return MPZCH_ERR_HIP;
         cap_n = n;
-        parity = 0;
         return MPZCH_OK;
     }
     void release()
@@ -290,9 +287,7 @@ mpzch_status_t run_remap(Scratch &sc, Timing &tm, Params p, int32_t max_p, int32
     p.set_slot = sc.set_slot;
     p.rows_a = sc.rows_a;
     p.rows_b = sc.rows_b;
-    p.ctl = sc.ctl[sc.parity];
-    p.ctl_next = sc.ctl[sc.parity ^ 1];
-    sc.parity ^= 1;
+    p.ctl = sc.ctl;
 
     // k_discover: every wavefront owns one segment of seg_chunks 64-position chunks
     const int g_disc = grid_for(p.n, kBlock, sc.num_cus, discover_blocks_per_cu());

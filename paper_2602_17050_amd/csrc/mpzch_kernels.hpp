@@ -57,8 +57,8 @@ struct TableDesc {
     int64_t ev_cap;
 };
 
-// Counters of one call that do go through atomics (few per call).  Two copies exist; a call
-// uses one and zeroes the other for the next call.
+// Counters of one call that do go through atomics (few per call).  The block is all zero between
+// calls: the workgroup of k_emit_dups that publishes the counters clears it again.
 struct Control {
     unsigned long long num_evicted[kMaxTables];
     unsigned long long stats[kMaxTables][kStatCount];
@@ -95,7 +95,6 @@ struct Params {
     StatRow *rows_b;               // per workgroup of k_finalize
     int32_t blocks_a, blocks_b;
     Control *ctl;
-    Control *ctl_next;
     // several tables
     const TableDesc *descs;        // device array [num_tables]
     const int64_t *offsets;        // device array [num_tables + 1]
@@ -405,12 +404,6 @@ __global__ __launch_bounds__(kBlock) void k_discover(Params p)
     const int64_t seg_base = c_begin * kWave;
     const bool multi = p.num_tables > 1;
     const bool want_stats = TRAIN && p.out_stats != nullptr;
-
-    if (TRAIN && blockIdx.x == 0) {
-        // zero the other counter block for the next call
-        unsigned long long *z = reinterpret_cast<unsigned long long *>(p.ctl_next);
-        for (int i = threadIdx.x; i < (int)(sizeof(Control) / sizeof(unsigned long long)); i += kBlock) z[i] = 0ull;
-    }
 
     // per-lane counters of the table currently being processed
     unsigned long long st_hit = 0, st_miss = 0, st_inv = 0, st_probe = 0;
@@ -1170,34 +1163,32 @@ __global__ __launch_bounds__(kBlock) void k_emit_dups(Params p)
         }
     }
 
-    if (blockIdx.x == 0) {
-        for (int i = threadIdx.x; i < p.num_tables; i += kBlock)
-            p.out_num_evicted[i] = (int64_t)p.ctl->num_evicted[i];
-    }
-    if (!p.out_stats) return;
-
     // Counters: the per-workgroup rows of k_discover and k_finalize are summed by the first
     // workgroups of this grid, kBlock rows each, into the call's counter block; the workgroup
-    // that finishes last reads the totals back and publishes them.
-    const int rows = p.blocks_a + p.blocks_b;
+    // that finishes last reads the totals back, publishes them and leaves the block zeroed for
+    // the next call (so a captured launch sequence can be replayed).
+    const int rows = p.out_stats ? p.blocks_a + p.blocks_b : 0;
     int helpers = (rows + kBlock - 1) / kBlock;
     if (helpers > (int)gridDim.x) helpers = (int)gridDim.x;
+    if (helpers < 1) helpers = 1;
     if ((int)blockIdx.x >= helpers) return;
     const int nbins = p.num_tables * kStatCount;
-    for (int i = threadIdx.x; i < nbins; i += kBlock) s_bins[i / kStatCount][i % kStatCount] = 0ull;
-    __syncthreads();
-    for (int i = blockIdx.x * kBlock + threadIdx.x; i < rows; i += helpers * kBlock) {
-        const StatRow *row = i < p.blocks_a ? &p.rows_a[i] : &p.rows_b[i - p.blocks_a];
-        const int t = (int)row->table;
-        for (int k = 0; k < kStatCount; ++k) {
-            const unsigned long long v = row->v[k];
-            if (v) atomicAdd(&s_bins[t][k], v);
+    if (p.out_stats) {
+        for (int i = threadIdx.x; i < nbins; i += kBlock) s_bins[i / kStatCount][i % kStatCount] = 0ull;
+        __syncthreads();
+        for (int i = blockIdx.x * kBlock + threadIdx.x; i < rows; i += helpers * kBlock) {
+            const StatRow *row = i < p.blocks_a ? &p.rows_a[i] : &p.rows_b[i - p.blocks_a];
+            const int t = (int)row->table;
+            for (int k = 0; k < kStatCount; ++k) {
+                const unsigned long long v = row->v[k];
+                if (v) atomicAdd(&s_bins[t][k], v);
+            }
         }
-    }
-    __syncthreads();
-    for (int i = threadIdx.x; i < nbins; i += kBlock) {
-        const unsigned long long v = s_bins[i / kStatCount][i % kStatCount];
-        if (v) atomicAdd(&p.ctl->stats[i / kStatCount][i % kStatCount], v);
+        __syncthreads();
+        for (int i = threadIdx.x; i < nbins; i += kBlock) {
+            const unsigned long long v = s_bins[i / kStatCount][i % kStatCount];
+            if (v) atomicAdd(&p.ctl->stats[i / kStatCount][i % kStatCount], v);
+        }
     }
     __threadfence();                     // this workgroup's additions are visible before it counts as done
     __syncthreads();
@@ -1205,15 +1196,23 @@ __global__ __launch_bounds__(kBlock) void k_emit_dups(Params p)
     __syncthreads();
     if (!s_last) return;
     __threadfence();
-    for (int i = threadIdx.x; i < nbins; i += kBlock)
-        s_bins[i / kStatCount][i % kStatCount] =
-            __hip_atomic_load(&p.ctl->stats[i / kStatCount][i % kStatCount], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (int i = threadIdx.x; i < p.num_tables; i += kBlock)
+        p.out_num_evicted[i] =
+            (int64_t)__hip_atomic_load(&p.ctl->num_evicted[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (p.out_stats) {
+        for (int i = threadIdx.x; i < nbins; i += kBlock)
+            s_bins[i / kStatCount][i % kStatCount] =
+                __hip_atomic_load(&p.ctl->stats[i / kStatCount][i % kStatCount], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        for (int t = threadIdx.x; t < p.num_tables; t += kBlock)
+            s_bins[t][kDistinctMiss] = s_bins[t][kInserts] + s_bins[t][kEvictions] + s_bins[t][kCollisions];
+        __syncthreads();
+        for (int i = threadIdx.x; i < nbins; i += kBlock)
+            p.out_stats[i] = (int64_t)s_bins[i / kStatCount][i % kStatCount];
+    }
     __syncthreads();
-    for (int t = threadIdx.x; t < p.num_tables; t += kBlock)
-        s_bins[t][kDistinctMiss] = s_bins[t][kInserts] + s_bins[t][kEvictions] + s_bins[t][kCollisions];
-    __syncthreads();
-    for (int i = threadIdx.x; i < nbins; i += kBlock)
-        p.out_stats[i] = (int64_t)s_bins[i / kStatCount][i % kStatCount];
+    unsigned long long *z = reinterpret_cast<unsigned long long *>(p.ctl);
+    for (int i = threadIdx.x; i < (int)(sizeof(Control) / sizeof(unsigned long long)); i += kBlock) z[i] = 0ull;
 }
 
 // ------------------------------------------------------------------ fills and row reset
