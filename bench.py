@@ -37,6 +37,24 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def host_cpu():
+    """(model name, logical cores the process may use) of the host the oracle is timed on."""
+    model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as fh:
+            for line in fh:
+                if line.startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    try:
+        cores = len(os.sched_getaffinity(0))
+    except AttributeError:
+        cores = os.cpu_count() or 1
+    return model, cores
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -199,10 +217,14 @@ def main():
             r = o.remap(batches_np[i], steps[i])
             cpu_t += time.perf_counter() - c0
             same = same and bool(np.array_equal(r.slots, outs[i].cpu().numpy()))
+        model, host_cores = host_cpu()
         cpu = {"value": round(spec.batch * n_cpu / cpu_t, 1), "unit": "ids/s", "cores": 1, "kind": "oracle",
                "sample": f"first {n_cpu} timed steps ({spec.batch} ids each) replayed from a host copy of the table state",
-               "matches_gpu_out_slots": same}
-        log(f"[bench] oracle: {cpu['value']:.3e} ids/s on 1 core; out_slots identical to GPU: {same}")
+               "matches_gpu_out_slots": same, "host_cpu": model, "host_cores": host_cores,
+               "ideal_scaling_extrapolation_not_measured": round(spec.batch * n_cpu / cpu_t * host_cores, 1)}
+        log(f"[bench] oracle: {cpu['value']:.3e} ids/s on 1 core of {host_cores} ({model}); x{host_cores} = "
+            f"{cpu['ideal_scaling_extrapolation_not_measured']:.3e} ids/s (ideal-scaling extrapolation, not measured); "
+            f"out_slots identical to GPU: {same}")
 
     result = {
         "metric": "remapped IDs/sec (train insert+evict) at 1 GPU",
