@@ -38,9 +38,10 @@ def _sampled_state_check(o, rng, ranges=4, width=1_000_000):
     assert bad == 0, first_bad
 
 
-def _stream_parity(spec, steps, emb_check_rows=0):
+def _stream_parity(spec, steps, emb_check_rows=0, lru=False):
     t = spec.table
-    g = mp.MpzchTable(t.num_slots, t.max_probe, mp.EVICT_TTL, t.ttl, t.hash_seed, max_batch=1 << 24)
+    kind_g, kind_o = (mp.EVICT_LRU, oracle.EVICT_LRU) if lru else (mp.EVICT_TTL, oracle.EVICT_TTL)
+    g = mp.MpzchTable(t.num_slots, t.max_probe, kind_g, t.ttl, t.hash_seed, max_batch=1 << 24)
     t0 = time.time()
     _prefill_stream(g, spec)
     say(f"prefilled {spec.prefill_ids} ids in {time.time() - t0:.1f}s")
@@ -51,7 +52,7 @@ def _stream_parity(spec, steps, emb_check_rows=0):
     # bounded probing: at load 0.9 with P = 16 some 5 % of the ids end without a slot (cf. Table 1)
     assert occ > 0.94 * spec.prefill_ids
     assert (I >= -1).all()                                     # no claim tag left behind
-    o = oracle.Table(t.num_slots, t.max_probe, oracle.EVICT_TTL, t.ttl, t.hash_seed, I, M)
+    o = oracle.Table(t.num_slots, t.max_probe, kind_o, t.ttl, t.hash_seed, I, M)
     _sampled_state_check(o, np.random.default_rng(1))
     emb = None
     if emb_check_rows:
@@ -99,6 +100,11 @@ def test_config4_500m_slots_with_row_reset():
     """500 M slots at load 0.9, 2 M ids per step, rows of a 100 M x 128 bf16 embedding
     addressed as slot mod rows."""
     _stream_parity(wl.c4_spec(), steps=3, emb_check_rows=1)
+
+
+def test_config4_500m_slots_lru():
+    """The same stream under the LRU policy (16-lane groups per claimant at P = 16)."""
+    _stream_parity(wl.c4_spec(), steps=2, lru=True)
 
 
 def test_config3_100m_slots_lookup():
