@@ -217,7 +217,13 @@ TableDesc make_desc(const TableCfg &c, int64_t *I, int32_t *M, int64_t ev_begin,
 template <bool TRAIN>
 mpzch_status_t launch_discover(const Params &p, int grid, hipStream_t s)
 {
-    hipLaunchKernelGGL((k_discover<TRAIN>), dim3(grid), dim3(kBlock), 0, s, p);
+    if (TRAIN) {
+        if (p.num_tables > 1) hipLaunchKernelGGL(k_discover_tables, dim3(grid), dim3(kBlock), 0, s, p);
+        else hipLaunchKernelGGL(k_discover, dim3(grid), dim3(kBlock), 0, s, p);
+    } else {
+        if (p.num_tables > 1) hipLaunchKernelGGL(k_lookup_tables, dim3(grid), dim3(kBlock), 0, s, p);
+        else hipLaunchKernelGGL(k_lookup, dim3(grid), dim3(kBlock), 0, s, p);
+    }
     LAUNCH_CHECK();
     return MPZCH_OK;
 }

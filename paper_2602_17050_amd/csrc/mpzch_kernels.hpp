@@ -386,8 +386,8 @@ __device__ __forceinline__ int probe_pass(const Tab &d, int64_t id, int64_t home
 // in LDS (position, home, next round) and resolved later, 64 at a time, so that the second
 // memory round trip is paid once per 64 parked ids instead of once per chunk.  What remains
 // unfound is the segment's miss list.
-template <bool TRAIN>
-__global__ __launch_bounds__(kBlock) void k_discover(Params p)
+template <bool TRAIN, bool MULTI>
+__device__ __forceinline__ void discover_body(const Params &p)
 {
     __shared__ uint32_t s_pos[kWavesPerBlock][kStage];
     __shared__ int64_t s_home[kWavesPerBlock][kStage];
@@ -402,7 +402,7 @@ __global__ __launch_bounds__(kBlock) void k_discover(Params p)
     const int64_t c_begin = seg * p.seg_chunks;
     const int64_t c_end = c_begin + p.seg_chunks < num_chunks ? c_begin + p.seg_chunks : num_chunks;
     const int64_t seg_base = c_begin * kWave;
-    const bool multi = p.num_tables > 1;
+    constexpr bool multi = MULTI;
     const bool want_stats = TRAIN && p.out_stats != nullptr;
 
     // per-lane counters of the table currently being processed
@@ -564,6 +564,31 @@ __global__ __launch_bounds__(kBlock) void k_discover(Params p)
         const unsigned long long vals[4] = {st_hit, st_miss, st_inv, st_probe};
         block_stat_row(p, p.rows_a, p.blocks_a, idx, vals, 4, st_table, s_red, s_tab);
     }
+}
+
+// Four kernels around the one body, each compiled for the number of wavefronts per SIMD that
+// measured best: the training pass over one table is bound by its metadata stores and does not
+// gain from more wavefronts than two; the read-only lookup hides its load latency with four; with
+// several tables the chunk's table is looked up before its ids can be hashed (a chain of
+// dependent loads), which three wavefronts (training) or four (lookup) hide better.
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_discover(Params p)
+{
+    discover_body<true, false>(p);
+}
+
+__global__ __launch_bounds__(kBlock, 4) void k_lookup(Params p)
+{
+    discover_body<false, false>(p);
+}
+
+__global__ __launch_bounds__(kBlock, 3) void k_discover_tables(Params p)
+{
+    discover_body<true, true>(p);
+}
+
+__global__ __launch_bounds__(kBlock, 4) void k_lookup_tables(Params p)
+{
+    discover_body<false, true>(p);
 }
 
 // ------------------------------------------------------------------ allocation
