@@ -68,6 +68,42 @@ __global__ void k_store4(int *t, uint64_t n, uint64_t ops)
         t[__umul64hi(mix64(i), n)] = 7;
 }
 
+// LANES consecutive lanes write one random aligned chunk of LANES * 16 bytes (16 .. 128 bytes)
+template <int LANES>
+__global__ void k_store_chunk(uint4 *t, uint64_t n16, uint64_t ops)
+{
+    const uint64_t tid = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x;
+    const uint64_t groups = ((uint64_t)gridDim.x * blockDim.x) / LANES;
+    const int r = tid % LANES;
+    for (uint64_t i = tid / LANES; i < ops; i += groups) {
+        const uint64_t c = __umul64hi(mix64(i), n16 / LANES);
+        t[c * LANES + r] = make_uint4(7u, 7u, 7u, 7u);
+    }
+}
+
+// a 4-byte atomic max whose result is not used, at a random slot
+__global__ void k_atomic_max4(int *t, uint64_t n, uint64_t ops)
+{
+    for (uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; i < ops; i += (uint64_t)gridDim.x * blockDim.x)
+        (void)__hip_atomic_fetch_max(&t[__umul64hi(mix64(i), n)], 7, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// the word is read first, then written (the line is in the cache when the store arrives)
+__global__ void k_load_store4(int *t, uint64_t n, uint64_t ops)
+{
+    for (uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; i < ops; i += (uint64_t)gridDim.x * blockDim.x) {
+        int *p = &t[__umul64hi(mix64(i), n)];
+        const int v = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *p = v | 7;
+    }
+}
+
+__global__ void k_store4_nt(int *t, uint64_t n, uint64_t ops)
+{
+    for (uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; i < ops; i += (uint64_t)gridDim.x * blockDim.x)
+        __builtin_nontemporal_store(7, &t[__umul64hi(mix64(i), n)]);
+}
+
 __global__ void k_atomic_min(long long *t, uint64_t n, uint64_t ops, long long *sink)
 {
     long long a = 0;
@@ -129,6 +165,20 @@ int main(int argc, char **argv)
     report("random unaligned 128-byte windows (16 lanes each)", (double)ops, 128.0);
     TIME((k_store4<<<8192, 256>>>(m, n, ops)));
     report("random 4-byte stores (one per lane)", (double)ops, 4.0);
+    TIME((k_store4_nt<<<8192, 256>>>(m, n, ops)));
+    report("random 4-byte non-temporal stores (one per lane)", (double)ops, 4.0);
+    TIME((k_load_store4<<<8192, 256>>>(m, n, ops)));
+    report("random 4-byte load, then store to the same word", (double)ops, 4.0);
+    TIME((k_atomic_max4<<<8192, 256>>>(m, n, ops)));
+    report("random 4-byte atomic max, result unused (one per lane)", (double)ops, 4.0);
+    TIME((k_store_chunk<1><<<8192, 256>>>((uint4 *)m, n / 4, ops)));
+    report("random aligned 16-byte stores (one lane each)", (double)ops, 16.0);
+    TIME((k_store_chunk<2><<<8192, 256>>>((uint4 *)m, n / 4, ops)));
+    report("random aligned 32-byte stores (2 lanes each)", (double)ops, 32.0);
+    TIME((k_store_chunk<4><<<8192, 256>>>((uint4 *)m, n / 4, ops)));
+    report("random aligned 64-byte stores (4 lanes each)", (double)ops, 64.0);
+    TIME((k_store_chunk<8><<<8192, 256>>>((uint4 *)m, n / 4, ops)));
+    report("random aligned 128-byte stores (8 lanes each)", (double)ops, 128.0);
     TIME((k_atomic_min<<<8192, 256>>>(t, n, ops / 4, (long long *)c + 8)));
     report("random 64-bit atomic min with return (one per lane)", (double)ops / 4, 8.0);
     TIME((k_same_address<<<16384, 256>>>(c, c + 8)));
