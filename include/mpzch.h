@@ -54,7 +54,8 @@ typedef enum {
     MPZCH_OK = 0,
     MPZCH_ERR_INVALID_ARG = 1,
     MPZCH_ERR_ALLOC = 2,       /* device or host allocation failed */
-    MPZCH_ERR_HIP = 3,         /* a HIP runtime call failed        */
+    MPZCH_ERR_HIP = 3,         /* a HIP runtime call failed; when a remap returns it, the tensors may be
+                                  left mid-update (their state is undefined), the handle stays usable */
     MPZCH_ERR_UNSUPPORTED = 4  /* e.g. MPZCH_EVICT_LRU with max_probe > 64 */
 } mpzch_status_t;
 

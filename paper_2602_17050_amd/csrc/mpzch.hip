@@ -117,6 +117,7 @@ struct Scratch {
     StatRow *rows_a = nullptr;
     StatRow *rows_b = nullptr;
     Control *ctl = nullptr;
+    bool dirty = false;            // a launch sequence was cut short: set and counters must be cleared before use
     int num_cus = 0;
 
     static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -281,8 +282,27 @@ mpzch_status_t launch_finalize(const Params &p, int grid, hipStream_t s)
         if (!(tm).end((s))) return MPZCH_ERR_HIP;   \
     } while (0)
 
+mpzch_status_t fill64(int64_t *dst, int64_t count, long long value, hipStream_t s);
+mpzch_status_t fill32(int32_t *dst, int64_t count, int32_t value, hipStream_t s);
+
 // The launch sequence of one training remap (single table or group).
-mpzch_status_t run_remap(Scratch &sc, Timing &tm, Params p, int32_t max_p, int32_t max_p_lru, hipStream_t s)
+mpzch_status_t launch_remap(Scratch &sc, Timing &tm, Params p, int32_t max_p, int32_t max_p_lru, hipStream_t s);
+
+// Every call leaves the scratch set empty and the counter block zeroed -- unless its launch
+// sequence was cut short by a HIP error; the next call then clears both before it starts.
+mpzch_status_t run_remap(Scratch &sc, Timing &tm, const Params &p, int32_t max_p, int32_t max_p_lru, hipStream_t s)
+{
+    if (sc.dirty) {
+        TRY(fill32((int32_t *)sc.set_slot, 2 * sc.cap_n, -1, s));
+        TRY(fill64((int64_t *)sc.ctl, (int64_t)(sizeof(Control) / sizeof(int64_t)), 0, s));
+    }
+    sc.dirty = true;
+    const mpzch_status_t st = launch_remap(sc, tm, p, max_p, max_p_lru, s);
+    if (st == MPZCH_OK) sc.dirty = false;
+    return st;
+}
+
+mpzch_status_t launch_remap(Scratch &sc, Timing &tm, Params p, int32_t max_p, int32_t max_p_lru, hipStream_t s)
 {
     p.list = sc.list;
     p.ent = sc.ent;

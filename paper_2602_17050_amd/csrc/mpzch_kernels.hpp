@@ -250,7 +250,7 @@ __device__ __forceinline__ uint32_t set_insert(const Params &p, int64_t id, uint
         if (__hip_atomic_compare_exchange_strong(&p.set_slot[e], &expected, pos, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
                                                  __HIP_MEMORY_SCOPE_AGENT))
             break;                                            // first of its id so far
-        if (p.ids[expected] == id) {
+        if ((int64_t)expected < p.n && p.ids[expected] == id) {   // (an entry is always a position of this batch)
             if (pos < expected) __hip_atomic_fetch_min(&p.set_slot[e], pos, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             break;
         }
