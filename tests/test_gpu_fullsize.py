@@ -224,3 +224,65 @@ def test_table1_cells_at_full_scale(size_m, max_probe):
     if size_m == 300 and max_probe == 64:
         assert got < 0.00005                              # prints as the paper's 0.0000 %
     mp.mpzch_destroy(h)
+
+
+def test_maximum_batch_in_one_call():
+    """MPZCH_MAX_BATCH = 2^30 positions in ONE remap call (32-bit positions, claim tags, set
+    indices and segment arithmetic at their limits): 805 M distinct ids, of which the first
+    268 M occur twice, 805 M positions apart, into an empty table of 1.2 B slots, P = 16.
+    The oracle cannot replay 2^30 ids in seconds; it checks the resulting table (sampled slot
+    ranges: every resident findable at its own slot, no empty slot before a resident) and looks
+    up a sample of the ids on a host copy of the table; counters and duplicates are checked
+    with identities that hold at any size."""
+    n = 1 << 30
+    distinct = 805_306_368                                    # 0.75 * 2^30
+    num_slots, max_probe, seed = 1_200_000_000, 16, 0x5EED0099
+    dev = torch.device("cuda")
+    g = mp.MpzchTable(num_slots, max_probe, mp.EVICT_NONE, 0, seed)
+    ids = torch.empty(n, dtype=torch.int64, device=dev)
+    chunk = 1 << 26
+    for lo in range(0, distinct, chunk):
+        hi = min(lo + chunk, distinct)
+        ids[lo:hi] = wl.distinct_ids_device(lo, hi, dev, salt=9)
+    ids[distinct:] = ids[: n - distinct]
+    out = torch.empty(n, dtype=torch.int64, device=dev)
+    say("max batch: remap of", n, "positions")
+    t0 = time.time()
+    mp.mpzch_reserve(g.handle, n)
+    g.remap(ids, 1, out)
+    torch.cuda.synchronize()
+    say(f"max batch: done in {time.time() - t0:.2f}s (scratch allocation included)")
+    st = g.stats_dict()
+    say("max batch:", st)
+    assert st["hit_pos"] == 0 and st["invalid_pos"] == 0 and st["miss_pos"] == n
+    assert st["distinct_miss"] == distinct and st["evictions"] == 0
+    assert st["inserts"] + st["collisions"] == distinct
+    assert 0 < st["collisions"] < 0.02 * distinct            # load 0.67 at P = 16 (cf. Table 1)
+    assert int(g.num_evicted.item()) == 0
+    # both copies of an id carry one slot; every slot is inside the table
+    assert bool((out[distinct:] == out[: n - distinct]).all())
+    assert int(out.min().item()) >= 0 and int(out.max().item()) < num_slots
+    # the table: one resident per inserted id, no claim tag left, metadata = step where occupied
+    occ_mask = g.identities >= 0
+    assert int(occ_mask.sum().item()) == st["inserts"]
+    assert int((g.identities < -1).sum().item()) == 0
+    assert bool((g.metadata[occ_mask] == 1).all())
+    del occ_mask
+    # a read-only lookup of all 2^30 positions returns the same slots (found or home alike)
+    sl, found = g.lookup(ids)
+    assert bool((sl == out).all())
+    n_found = int(found.sum().item())
+    say("max batch: found positions", n_found)
+    assert n_found >= st["inserts"]
+    del sl, found
+    # the oracle on a host copy of the table
+    I = g.identities.cpu().numpy()
+    o = oracle.Table(num_slots, max_probe, oracle.EVICT_NONE, 0, seed, I, np.zeros(num_slots, np.int32))
+    _sampled_state_check(o, np.random.default_rng(11))
+    rng = np.random.default_rng(12)
+    pos = np.sort(rng.integers(0, n, size=2_000_000))
+    pos_t = torch.from_numpy(pos).to(dev)
+    so, fo = o.lookup(ids[pos_t].cpu().numpy())
+    assert np.array_equal(out[pos_t].cpu().numpy(), so)
+    assert fo.mean() > 0.97
+    g.close()
