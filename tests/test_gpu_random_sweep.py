@@ -1,6 +1,8 @@
 """Seeded random sweep: table shape, probe depth, policy, retention, batch size and id mix drawn
 at random; every call compared with the oracle bit for bit (out_slots, evicted set, counters,
 identities, metadata)."""
+import os
+
 import numpy as np
 import pytest
 
@@ -27,7 +29,8 @@ def draw_ids(rng, n, universe):
     return np.repeat(rng.integers(0, universe, size=max(n // 7, 1)), 7)[:n]  # runs of equal ids
 
 
-@pytest.mark.parametrize("block", range(12))
+# MPZCH_SWEEP_BLOCKS widens the sweep for an occasional long run (16 tables per block)
+@pytest.mark.parametrize("block", range(int(os.environ.get("MPZCH_SWEEP_BLOCKS", "12"))))
 def test_random_tables_every_policy(block):
     rng = np.random.Generator(np.random.Philox(key=0x5EED + block))
     for case in range(16):
@@ -53,3 +56,34 @@ def test_random_tables_every_policy(block):
             step += int(rng.integers(0, 3))
         p.lookup(rng.integers(-2, 2 * universe, size=300))
         p.close()
+
+
+@pytest.mark.parametrize("block", range(int(os.environ.get("MPZCH_SWEEP_BLOCKS", "12"))))
+def test_random_groups_of_tables(block):
+    """Keyed jagged batches over 1..8 tables of random shape and policy, through one group."""
+    from test_gpu_jagged import JaggedPair
+
+    rng = np.random.Generator(np.random.Philox(key=0xFACE + block))
+    for case in range(6):
+        T = int(rng.integers(1, 9))
+        specs = []
+        for f in range(T):
+            policy = POLICIES[int(rng.integers(0, 4))]
+            n_slots = int(rng.choice([1, 2, 17, 64, 65, 300, 2000]))
+            max_probe = int(rng.choice([1, 3, 8, 9, 16, 17, 32, 33, 64, 64 if policy == "lru" else 150]))
+            specs.append(wl.TableSpec(n_slots, max_probe, int(rng.integers(0, 4)), policy, int(rng.integers(0, 1 << 40))))
+        jp = JaggedPair(specs)
+        step = int(rng.integers(0, 4))
+        for k in range(int(rng.integers(2, 6))):
+            counts = [0 if rng.random() < 0.2 else int(rng.integers(0, 5 * s.num_slots + 3)) for s in specs]
+            vals = [draw_ids(rng, c, max(2, 3 * s.num_slots)) if c else np.empty(0, np.int64) for s, c in zip(specs, counts)]
+            values = np.concatenate(vals).astype(np.int64)
+            offsets = np.concatenate([[0], np.cumsum(counts)]).astype(np.int64)
+            say("group sweep block", block, "case", case, "step", step, "tables",
+                [(s.num_slots, s.max_probe, s.evict) for s in specs], "counts", counts)
+            jp.step(values, offsets, step)
+            jp.check_state()
+            step += int(rng.integers(0, 3))
+        for o in jp.o:
+            assert o.check_state()[0] == 0
+        jp.close()
