@@ -123,7 +123,12 @@ __global__ void k_same_address(unsigned long long *c, unsigned long long *sink)
 
 int main(int argc, char **argv)
 {
-    const uint64_t n = argc > 1 ? std::strtoull(argv[1], nullptr, 10) : 1000000000ull;
+    // a multiple of 1024 slots keeps both halves of the array 16-byte aligned
+    const uint64_t n = (argc > 1 ? std::strtoull(argv[1], nullptr, 10) : 1000000000ull) & ~1023ull;
+    if (n < 65536 || n > (1ull << 34)) {
+        std::printf("slots must lie in [65536, 2^34]\n");
+        return 1;
+    }
     hipEvent_t e0, e1;
     CK(hipEventCreate(&e0));
     CK(hipEventCreate(&e1));
@@ -154,9 +159,13 @@ int main(int argc, char **argv)
     CK(hipEventSynchronize(e1));              \
     CK(hipEventElapsedTime(&ms, e0, e1));
     const uint64_t ops = 64000000ull;
-    const uint64_t cn = (1ull << 31) / 16;   // 2 GiB copied
+    // the copy reads the first half of the array and writes the second: at most 2 GiB, never more than half
+    uint64_t copy_bytes = n * 4 < (1ull << 31) ? n * 4 : (1ull << 31);
+    copy_bytes &= ~15ull;
+    const uint64_t cn = copy_bytes / 16;
     TIME((k_copy<<<8192, 256>>>((const uint4 *)t, (uint4 *)(t + (n / 2)), cn)));
-    report("streaming copy, 2 GiB read + 2 GiB written", (double)cn, 32.0);
+    std::printf("streaming copy moves %.3f GiB each way\n", copy_bytes / 1073741824.0);
+    report("streaming copy (read + written)", (double)cn, 32.0);
     TIME((k_gather8<<<8192, 256>>>(t, n, ops, (long long *)c + 8)));
     report("random 8-byte loads (one per lane)", (double)ops, 8.0);
     TIME((k_line<true><<<8192, 256>>>(t, n, ops, (long long *)c + 8)));
