@@ -28,9 +28,11 @@ HBM_PEAK_GBS = 8000.0
 CEIL_LINES_PER_S = 38.1e9
 CEIL_STORES_PER_S = 22.9e9
 # HBM bytes per k_discover launch on the full-size headline workload, from rocprofv3 --pmc
-# FETCH_SIZE and WRITE_SIZE (KiB per dispatch x 1024, calibration factor 1.000); see
-# profiles/remap_headline_1Bslots_4Mids.txt.  Only valid for that workload at scale 1.
-HEADLINE_DISCOVER_TRAFFIC_BYTES = int((348763.8 + 182932.1) * 1024)
+# FETCH_SIZE and WRITE_SIZE (KiB per dispatch x 1024).  Calibrated against a copy kernel of known
+# size, FETCH_SIZE reads half the bytes on this GPU (every read request is 128 bytes and is priced
+# as 64) and WRITE_SIZE reads them all: factors 2.000 and 1.000, profiles/counter_calibration_mi355x.txt;
+# figures from profiles/remap_headline_1Bslots_4Mids.txt.  Only valid for that workload at scale 1.
+HEADLINE_DISCOVER_TRAFFIC_BYTES = int((2.0 * 348763.8 + 1.0 * 182932.1) * 1024)
 
 
 def log(*a):
