@@ -425,21 +425,24 @@ __device__ __forceinline__ void discover_body(const Params &p)
         st_table = f;
     };
     // a position whose id is resident at `dist` probes from home
-    auto finish_hit = [&](const Tab &d, int64_t pos, int64_t home, int dist) {
+    // (the first pass stores the outputs of its whole chunk itself: emit = false)
+    auto finish_hit = [&](const Tab &d, int64_t pos, int64_t home, int dist, bool emit) {
         const int64_t slot = wrap(home + dist, d.N);
         if (TRAIN) {
             d.M[slot] = meta_value(p, d, pos);        // "Update": refresh the resident's metadata
             st_hit++;
             st_probe += (unsigned long long)(dist + 1);
-        } else if (p.out_found) {
-            p.out_found[pos] = 1;
         }
-        p.out_slots[pos] = slot;
+        if (emit) {
+            p.out_slots[pos] = slot;
+            if (!TRAIN && p.out_found) p.out_found[pos] = 1;
+        }
     };
 
     // probes the parked ids until found or their window ends; enters the rest into the scratch set
     auto resolve_stage = [&]() {
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        // the outputs stored by the first pass are performed before any lane rewrites them below
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
         int nmiss = 0;
         for (int e0 = 0; e0 < staged; e0 += kWave) {
             const bool have = e0 + lane < staged;
@@ -465,7 +468,7 @@ __device__ __forceinline__ void discover_body(const Params &p)
                         else q += kLine;
                     }
                 }
-                if (mine && dist >= 0) finish_hit(d, (int64_t)pos, home, dist);
+                if (mine && dist >= 0) finish_hit(d, (int64_t)pos, home, dist, true);
                 const bool miss = mine && dist < 0;
                 const uint64_t mb = __ballot(miss);
                 if (miss) {
@@ -474,10 +477,8 @@ __device__ __forceinline__ void discover_body(const Params &p)
                         s_pos[w][at] = pos;
                         s_home[w][at] = home;
                         st_miss++;
-                    } else {
-                        p.out_slots[pos] = home;
-                        if (p.out_found) p.out_found[pos] = 0;
                     }
+                    // lookup: the first pass has already stored home and "not found"
                 }
                 nmiss += __popcll(mb);
                 todo = todo && !mine;
@@ -536,12 +537,16 @@ __device__ __forceinline__ void discover_body(const Params &p)
             // first pass: the line that holds the home slot
             const int o = (int)((home + (int64_t)(((uintptr_t)d.I >> 3) & (kFirstG - 1))) & (kFirstG - 1));
             const int dist = probe_pass<kFirstG>(d, id, home, valid ? -o : d.P);
-            if (valid && dist >= 0) {
-                finish_hit(d, pos, home, dist);
-            } else if (mine && !valid) {
-                p.out_slots[pos] = home;                   // negative id: home of its bit pattern
-                if (TRAIN) st_inv++;
-                else if (p.out_found) p.out_found[pos] = 0;
+            const bool hit = valid && dist >= 0;
+            if (hit) finish_hit(d, pos, home, dist, false);
+            else if (TRAIN && mine && !valid) st_inv++;
+            // One store for the whole chunk keeps the 64-byte sectors of the outputs complete (a
+            // sector written with holes leaves the cache as narrow writes).  A position that is
+            // not decided yet gets its home slot: final for a negative id (home of its bit
+            // pattern) and for a lookup miss, rewritten later otherwise.
+            if (mine) {
+                p.out_slots[pos] = hit ? wrap(home + dist, d.N) : home;
+                if (!TRAIN && p.out_found) p.out_found[pos] = hit ? 1 : 0;
             }
             // not found so far: parked (its window may go on, or it is a miss)
             const bool park = valid && dist < 0;
