@@ -70,7 +70,7 @@ def main():
     ap.add_argument("--policy", default="ttl", choices=["ttl", "lru"], help="eviction policy (headline / c4 workloads)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        log("bench.py: this build runs on ONE GPU (a table shard is local to its GPU; see DESIGN.md on sharding). "
+        log("bench.py: this build runs on ONE GPU (a table shard and every operation on it are local to its GPU). "
             "Run with --gpus 1.")
         sys.exit(2)
 
