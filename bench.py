@@ -32,7 +32,7 @@ CEIL_STORES_PER_S = 22.9e9
 # size, FETCH_SIZE reads half the bytes on this GPU (every read request is 128 bytes and is priced
 # as 64) and WRITE_SIZE reads them all: factors 2.000 and 1.000, profiles/counter_calibration_mi355x.txt;
 # figures from profiles/remap_headline_1Bslots_4Mids.txt.  Only valid for that workload at scale 1.
-HEADLINE_DISCOVER_TRAFFIC_BYTES = int((2.0 * 348763.8 + 1.0 * 182932.1) * 1024)
+HEADLINE_DISCOVER_TRAFFIC_BYTES = int((2.0 * 347449.5 + 1.0 * 182988.6) * 1024)
 
 
 def log(*a):
