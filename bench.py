@@ -200,7 +200,10 @@ def main():
                         "frac": round(ach / HBM_PEAK_GBS, 5), "traffic": traffic,
                         "avg_kernel_ms": round(avg_ms, 4), "alg_bytes_per_launch": round(alg),
                         "random_access_floor_ms": round(floor_ms, 4),
-                        "frac_of_random_access_ceiling": round(floor_ms / avg_ms, 3)}
+                        "frac_of_random_access_ceiling": round(floor_ms / avg_ms, 3),
+                        # all HBM bytes the kernel moves (useful or not) against the same peak
+                        "traffic_frac_of_peak": None if traffic is None else
+                        round(traffic / (avg_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         else:
             roofline = {"bound": "hbm", "kernel": dom, "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                         "frac": None, "traffic": None, "avg_kernel_ms": round(avg_ms, 4)}
