@@ -292,6 +292,22 @@ mpzch_status_t mpzch_remap_jagged(mpzch_group_t *g, int64_t *const *identities, 
                                   int64_t *out_num_evicted, int64_t *out_stats, void *stream);
 
 /*
+ * mpzch_remap_jagged for groups with tables of kind MPZCH_EVICT_TTL_EXPIRY whose region of the
+ * batch mixes features of different retention (Sec. 3.4, second paragraph: several features share
+ * one table).  ttls [dev] int32[total_values]: retention in steps (>= 0) of the feature each value
+ * belongs to, read for the values of MPZCH_EVICT_TTL_EXPIRY tables only; all copies of an id inside
+ * one table's region must carry the same value; NULL = every table's own policy.ttl.
+ * INVALID_ARG when ttls is given and no table of the group has that kind.
+ */
+mpzch_status_t mpzch_remap_jagged_feature_ttl(mpzch_group_t *g, int64_t *const *identities, int32_t *const *metadata,
+                                              const int64_t *values, const int32_t *ttls,
+                                              const int64_t *feature_offsets,
+                                              int64_t total_values, int32_t step,
+                                              int64_t *out_slots,
+                                              int64_t *out_evicted_slots, const int64_t *evicted_offsets,
+                                              int64_t *out_num_evicted, int64_t *out_stats, void *stream);
+
+/*
  * Per-kernel timing for benchmarks.  While enabled, every kernel launched through the
  * handle is bracketed by HIP events on the call's stream.  mpzch_kernel_times
  * synchronises those events, adds up the durations per kernel and clears the record.

@@ -165,11 +165,12 @@ class Table:
         return int(bad), int(occ[0]), int(fb[0])
 
 
-def remap_jagged(tables, values, feature_offsets, step: int):
+def remap_jagged(tables, values, feature_offsets, step: int, ttls=None):
     """Keyed-jagged batch: feature f owns values[offsets[f]:offsets[f+1]] and table f.
 
     Tables are independent (Sec. 3.6: operations stay local to a table's shard),
     so the batch is the per-table remap applied to each slice.
+    ttls: optional per-value retention (Sec. 3.4, per-feature TTL) for the expiry-step tables.
     Returns (slots int64[total], [evicted arrays per table], [stats per table]).
     """
     values = _i64(values)
@@ -178,7 +179,9 @@ def remap_jagged(tables, values, feature_offsets, step: int):
     evs, sts = [], []
     for f, t in enumerate(tables):
         lo, hi = int(offs[f]), int(offs[f + 1])
-        r = t.remap(values[lo:hi], step)
+        # per-value retention applies to tables that store expiry steps; the others have their own ttl
+        use = ttls is not None and t.policy == EVICT_TTL_EXPIRY
+        r = t.remap(values[lo:hi], step, np.asarray(ttls)[lo:hi] if use else None)
         out[lo:hi] = r.slots
         evs.append(r.evicted)
         sts.append(r.stats)

@@ -25,6 +25,7 @@ EXPORTED = (
     "mpzch_group_reserve", "mpzch_remap_jagged", "mpzch_set_kernel_timing", "mpzch_kernel_times",
     "mpzch_group_set_kernel_timing", "mpzch_group_kernel_times", "mpzch_status_string",
     "mpzch_remap_feature_ttl", "mpzch_reset_rows_multi", "mpzch_lookup_gather", "mpzch_collect_delta", "mpzch_gather_rows", "mpzch_apply_delta",
+    "mpzch_remap_jagged_feature_ttl",
 )
 
 
@@ -76,6 +77,8 @@ def load_library(path: str | None = None):
     lib.mpzch_group_reserve.argtypes = [vp, i64]
     lib.mpzch_remap_jagged.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), vp, vp, i64, i32, vp, vp,
                                        ctypes.POINTER(i64), vp, vp, vp]
+    lib.mpzch_remap_jagged_feature_ttl.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), vp, vp, vp, i64, i32, vp,
+                                                   vp, ctypes.POINTER(i64), vp, vp, vp]
     for name in ("mpzch_kernel_times", "mpzch_group_kernel_times"):
         getattr(lib, name).argtypes = [vp, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_double),
                                        ctypes.POINTER(i64), i32, ctypes.POINTER(i32)]
@@ -242,6 +245,20 @@ def mpzch_group_destroy(group):
 
 def mpzch_group_reserve(group, max_total_values: int):
     _check(load_library().mpzch_group_reserve(group, max_total_values), "mpzch_group_reserve")
+
+
+def mpzch_remap_jagged_feature_ttl(group, identities, metadata, values, ttls, feature_offsets, step: int, out_slots,
+                                   out_evicted_slots, evicted_offsets, out_num_evicted, out_stats=None):
+    """identities / metadata: lists of device tensors; ttls: int32 per value or None;
+    evicted_offsets: host list of ints."""
+    T = len(identities)
+    ip = (ctypes.c_void_p * T)(*[t.data_ptr() for t in identities])
+    mp = (ctypes.c_void_p * T)(*[t.data_ptr() for t in metadata])
+    eo = (ctypes.c_int64 * (T + 1))(*[int(x) for x in evicted_offsets])
+    _check(load_library().mpzch_remap_jagged_feature_ttl(
+        group, ip, mp, _ptr(values, torch.int64), _ptr(ttls, torch.int32), _ptr(feature_offsets, torch.int64),
+        values.numel(), step, _ptr(out_slots, torch.int64), _ptr(out_evicted_slots, torch.int64), eo,
+        _ptr(out_num_evicted, torch.int64), _ptr(out_stats, torch.int64), _stream()), "mpzch_remap_jagged_feature_ttl")
 
 
 def mpzch_remap_jagged(group, identities, metadata, values, feature_offsets, step: int, out_slots,

@@ -687,18 +687,24 @@ mpzch_status_t mpzch_group_reserve(mpzch_group_t *g, int64_t max_total_values)
     return g->sc.ensure(max_total_values);
 }
 
-mpzch_status_t mpzch_remap_jagged(mpzch_group_t *g, int64_t *const *identities, int32_t *const *metadata,
-                                  const int64_t *values, const int64_t *feature_offsets,
-                                  int64_t total_values, int32_t step,
-                                  int64_t *out_slots,
-                                  int64_t *out_evicted_slots, const int64_t *evicted_offsets,
-                                  int64_t *out_num_evicted, int64_t *out_stats, void *stream)
+mpzch_status_t mpzch_remap_jagged_feature_ttl(mpzch_group_t *g, int64_t *const *identities, int32_t *const *metadata,
+                                              const int64_t *values, const int32_t *ttls,
+                                              const int64_t *feature_offsets,
+                                              int64_t total_values, int32_t step,
+                                              int64_t *out_slots,
+                                              int64_t *out_evicted_slots, const int64_t *evicted_offsets,
+                                              int64_t *out_num_evicted, int64_t *out_stats, void *stream)
 {
     if (!g || !identities || !metadata || !feature_offsets || !evicted_offsets || !out_num_evicted)
         return MPZCH_ERR_INVALID_ARG;
     if (total_values < 0 || total_values > MPZCH_MAX_BATCH || step < 0) return MPZCH_ERR_INVALID_ARG;
     if (total_values > 0 && (!values || !out_slots)) return MPZCH_ERR_INVALID_ARG;
     const int T = (int)g->cfgs.size();
+    if (ttls) {
+        bool any = false;
+        for (int f = 0; f < T; ++f) any = any || g->cfgs[f].kind == MPZCH_EVICT_TTL_EXPIRY;
+        if (!any) return MPZCH_ERR_INVALID_ARG;          // no table of the group uses retention times
+    }
     int32_t max_p = 1, max_p_lru = 0;
     std::vector<TableDesc> descs((size_t)T);
     for (int f = 0; f < T; ++f) {
@@ -734,6 +740,7 @@ mpzch_status_t mpzch_remap_jagged(mpzch_group_t *g, int64_t *const *identities, 
     Params p;
     std::memset(&p, 0, sizeof p);
     p.ids = values;
+    p.ttls = ttls;
     p.n = total_values;
     p.step = step;
     p.num_tables = T;
@@ -747,6 +754,18 @@ mpzch_status_t mpzch_remap_jagged(mpzch_group_t *g, int64_t *const *identities, 
     // a group of one table still goes through the descriptor path
     if (T == 1) p.num_tables = 1;
     return run_remap(g->sc, g->tm, p, max_p, max_p_lru, s);
+}
+
+mpzch_status_t mpzch_remap_jagged(mpzch_group_t *g, int64_t *const *identities, int32_t *const *metadata,
+                                  const int64_t *values, const int64_t *feature_offsets,
+                                  int64_t total_values, int32_t step,
+                                  int64_t *out_slots,
+                                  int64_t *out_evicted_slots, const int64_t *evicted_offsets,
+                                  int64_t *out_num_evicted, int64_t *out_stats, void *stream)
+{
+    return mpzch_remap_jagged_feature_ttl(g, identities, metadata, values, nullptr, feature_offsets, total_values, step,
+                                          out_slots, out_evicted_slots, evicted_offsets, out_num_evicted, out_stats,
+                                          stream);
 }
 
 mpzch_status_t mpzch_set_kernel_timing(mpzch_table_t *t, int32_t enable)

@@ -25,7 +25,7 @@ class JaggedPair:
             mp.mpzch_init_tensors(h, i, m)
         self.o = [oracle.Table(t.num_slots, t.max_probe, ko(t.evict), t.ttl, t.hash_seed) for t in specs]
 
-    def step(self, values, offsets, step):
+    def step(self, values, offsets, step, ttls=None):
         T = len(self.specs)
         v = torch.from_numpy(values).cuda()
         off = torch.from_numpy(offsets).cuda()
@@ -34,9 +34,13 @@ class JaggedPair:
         ev = torch.empty(max(len(values), 1), dtype=torch.int64, device="cuda")
         nev = torch.zeros(T, dtype=torch.int64, device="cuda")
         stats = torch.zeros(T * mp.STAT_COUNT, dtype=torch.int64, device="cuda")
-        mp.mpzch_remap_jagged(self.group, self.I, self.M, v, off, step, out, ev, ev_off, nev, stats)
+        if ttls is None:
+            mp.mpzch_remap_jagged(self.group, self.I, self.M, v, off, step, out, ev, ev_off, nev, stats)
+        else:
+            mp.mpzch_remap_jagged_feature_ttl(self.group, self.I, self.M, v, torch.from_numpy(ttls).cuda(), off, step,
+                                              out, ev, ev_off, nev, stats)
         torch.cuda.synchronize()
-        so, evs, sts = oracle.remap_jagged(self.o, values, offsets, step)
+        so, evs, sts = oracle.remap_jagged(self.o, values, offsets, step, ttls)
         assert np.array_equal(out.cpu().numpy(), so)
         nev_h = nev.cpu().numpy()
         ev_h = ev.cpu().numpy()
@@ -133,4 +137,40 @@ def test_jagged_group_with_every_policy(kinds):
         for o in jp.o:
             assert o.check_state()[0] == 0
     assert tot > 0
+    jp.close()
+
+
+def test_jagged_regions_that_mix_features_of_different_retention():
+    """Tables of the expiry-step kind whose region of the batch holds values of several features,
+    each value with the retention of its feature (per-feature TTL, Sec. 3.4), next to a plain TTL
+    table and an LRU table that ignore the per-value retention."""
+    specs = [wl.TableSpec(400, 8, 1, "expiry", 11), wl.TableSpec(1000, 16, 2, True, 12),
+             wl.TableSpec(64, 20, 0, "expiry", 13), wl.TableSpec(300, 16, 0, "lru", 14)]
+    jp = JaggedPair(specs)
+    rng = np.random.Generator(np.random.Philox(key=2024))
+    step, tot = 0, 0
+    for it in range(14):
+        step += int(rng.integers(0, 3))
+        counts = [int(rng.integers(0, 4 * s.num_slots)) for s in specs]
+        vals = [rng.integers(0, 4 * s.num_slots, size=c) for s, c in zip(specs, counts)]
+        values = np.concatenate(vals).astype(np.int64)
+        offsets = np.concatenate([[0], np.cumsum(counts)]).astype(np.int64)
+        ttls = ((values >> 2) % 6).astype(np.int32)          # the id's feature decides: equal ids, equal value
+        say("feature-ttl group step", step, counts)
+        sts = jp.step(values, offsets, step, ttls)
+        tot += sum(s["evictions"] for s in sts)
+        jp.check_state()
+    assert tot > 0
+    # metadata of the expiry-step tables holds step + retention, i.e. values beyond the last step
+    assert int(jp.M[0].max().item()) > step and int(jp.M[2].max().item()) > step
+    assert int(jp.M[1].max().item()) <= step
+    jp.close()
+
+
+def test_per_value_retention_needs_a_table_that_uses_it():
+    specs = [wl.TableSpec(50, 4, 1, True, 1)]
+    jp = JaggedPair(specs)
+    values = np.arange(10, dtype=np.int64)
+    with pytest.raises(mp.MpzchError):
+        jp.step(values, np.array([0, 10], np.int64), 1, np.ones(10, np.int32))
     jp.close()
