@@ -56,7 +56,7 @@ typedef enum {
     MPZCH_ERR_ALLOC = 2,       /* device or host allocation failed */
     MPZCH_ERR_HIP = 3,         /* a HIP runtime call failed; when a remap returns it, the tensors may be
                                   left mid-update (their state is undefined), the handle stays usable */
-    MPZCH_ERR_UNSUPPORTED = 4  /* e.g. MPZCH_EVICT_LRU with max_probe > 64 */
+    MPZCH_ERR_UNSUPPORTED = 4  /* e.g. MPZCH_EVICT_LRU with max_probe > MPZCH_MAX_PROBE_LRU */
 } mpzch_status_t;
 
 typedef enum {
@@ -65,7 +65,7 @@ typedef enum {
     MPZCH_EVICT_LRU = 2   /* Sec. 3.4 last paragraph: first empty slot of the range, else evict the entry
                              with the oldest metadata (ties: earlier probe round), never one whose metadata
                              equals the current step; contended slots go to the lower choice number, then
-                             to the id whose first occurrence comes first.  Single tables with
+                             to the id whose first occurrence comes first.
                              max_probe <= MPZCH_MAX_PROBE_LRU only (else MPZCH_ERR_UNSUPPORTED). */
     , MPZCH_EVICT_TTL_EXPIRY = 3 /* Sec. 3.4 as written, for tables shared by features with different
                              retention ("per-feature TTL"): metadata holds the step after which the id is
@@ -94,14 +94,14 @@ enum {
 #define MPZCH_MAX_BATCH ((int64_t)1 << 30) /* positions per remap / lookup call          */
 #define MPZCH_MAX_PROBE (1 << 20)          /* upper bound accepted for max_probe          */
 #define MPZCH_MAX_GROUP_TABLES 64          /* tables per mpzch_group_t                    */
-#define MPZCH_MAX_PROBE_LRU 64             /* largest max_probe with MPZCH_EVICT_LRU      */
+#define MPZCH_MAX_PROBE_LRU 1024           /* largest max_probe with MPZCH_EVICT_LRU      */
 
 /*
  * Creates a table handle (Algorithm 1's globals: P = max_probe; Sec. 3.4: policy).
  * Allocates no tensor and touches no GPU: scratch is allocated by the first remap
  * (or by mpzch_reserve) on the device that is current then.
  * Errors: INVALID_ARG for num_slots < 1, max_probe < 1 or > MPZCH_MAX_PROBE, ttl < 0,
- * unknown policy kind, out == NULL; UNSUPPORTED for MPZCH_EVICT_LRU with max_probe > 64.
+ * unknown policy kind, out == NULL; UNSUPPORTED for MPZCH_EVICT_LRU with max_probe > MPZCH_MAX_PROBE_LRU.
  * max_probe > num_slots is accepted and behaves as max_probe == num_slots.
  */
 mpzch_status_t mpzch_create(int64_t num_slots, int32_t max_probe, mpzch_eviction_policy_t policy,

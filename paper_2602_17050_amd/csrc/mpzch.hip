@@ -192,6 +192,8 @@ int grid_for(int64_t items, int64_t items_per_block, int num_cus, int blocks_per
     return (int)b;
 }
 
+static_assert(kLruLongProbe == MPZCH_MAX_PROBE_LRU, "the LRU kernels hold max_probe / 64 slots per lane");
+
 int32_t p_eff(const TableCfg &c) { return (int64_t)c.max_probe < c.num_slots ? c.max_probe : (int32_t)c.num_slots; }
 
 TableDesc make_desc(const TableCfg &c, int64_t *I, int32_t *M, int64_t ev_begin, int64_t ev_cap)
@@ -234,8 +236,10 @@ mpzch_status_t launch_discover(const Params &p, int grid, hipStream_t s)
 template <bool MULTI>
 void launch_allocate_lru(int32_t max_p_lru, const Params &p, int grid, hipStream_t s)
 {
-    // a group of 8, 16, 32 or 64 lanes per claimant, whichever holds its window
-    if (max_p_lru <= 8) hipLaunchKernelGGL((k_allocate_lru<8, MULTI>), dim3(grid), dim3(kWave), 0, s, p);
+    // a group of 8, 16, 32 or 64 lanes per claimant, whichever holds its window; the whole wavefront
+    // with several slots per lane for longer probe ranges
+    if (max_p_lru > kWave) hipLaunchKernelGGL((k_allocate_lru_long<MULTI>), dim3(grid), dim3(kWave), 0, s, p);
+    else if (max_p_lru <= 8) hipLaunchKernelGGL((k_allocate_lru<8, MULTI>), dim3(grid), dim3(kWave), 0, s, p);
     else if (max_p_lru <= 16) hipLaunchKernelGGL((k_allocate_lru<16, MULTI>), dim3(grid), dim3(kWave), 0, s, p);
     else if (max_p_lru <= 32) hipLaunchKernelGGL((k_allocate_lru<32, MULTI>), dim3(grid), dim3(kWave), 0, s, p);
     else hipLaunchKernelGGL((k_allocate_lru<64, MULTI>), dim3(grid), dim3(kWave), 0, s, p);

@@ -829,7 +829,8 @@ __global__ __launch_bounds__(kWave) void k_allocate(Params p)
 // claims are in flight: a tag keeps the was-occupied bit and metadata is not written before
 // k_finalize.  The tag's round field carries the CHOICE number, so a slot ends with the claimant
 // of the lowest (choice, position).  A group of G lanes serves one claimant, one lane per slot of
-// its window (max_probe <= G <= 64), so a wavefront works on 64 / G claimants at a time; a
+// its window (max_probe <= G <= 64; longer ranges: claim_wave_lru_long), so a wavefront works on
+// 64 / G claimants at a time; a
 // displaced claimant is carried on by the group that displaced it, from its next choice.
 // active, cpos and choice are uniform within a group.  Returns the probe round at which the
 // group's first claimant was placed, or -1.
@@ -959,6 +960,152 @@ __global__ __launch_bounds__(kWave) void k_allocate_lru(Params p)
                     const int32_t frk = __shfl(fr, k * G);
                     if (lane == sk) hint = frk < 0 ? kHintUnplaced : (uint32_t)frk;
                 }
+            }
+            if (MULTI ? agent : have) p.hint[idx] = (uint8_t)hint;
+        }
+    }
+}
+
+// LRU for probe ranges of 65 .. 1 024 slots: the whole wavefront serves one claimant, a lane holds
+// the slots of rounds lane, lane + 64, ...  The preference list is not materialised: choice k is
+// the k-th empty slot in probe order while k < number of empty slots, else the (k - empties)-th
+// evictable slot in (time stamp, round) order, drawn by repeated wavefront-wide minimum of the
+// keys above the previous draw.  Same outcome rule as claim_group_lru.
+constexpr int kLruLongSlots = 16;          // slots per lane
+constexpr int kLruLongProbe = kLruLongSlots * kWave;
+
+__device__ __forceinline__ uint64_t wave_min64(uint64_t x)
+{
+    const int lane = lane_id();
+    for (int o = 32; o > 0; o >>= 1) {
+        const uint64_t y = (uint64_t)shfl64((int64_t)x, (lane + o) & 63);
+        x = y < x ? y : x;
+    }
+    return x;
+}
+
+__device__ __forceinline__ int32_t claim_wave_lru_long(const Params &p, const Tab &d, uint32_t cpos, int32_t choice)
+{
+    const int lane = lane_id();
+    const int C = (d.P + kWave - 1) / kWave;             // <= kLruLongSlots (checked when the table is created)
+    int32_t first_round = -1;
+    bool is_first = true;
+    for (;;) {
+        const int64_t home = home_slot(p.ids[cpos], d.seed, d.N);
+        uint32_t emp = 0, evi = 0;                        // bit c: the slot of round c * 64 + lane is empty / evictable
+        int32_t m[kLruLongSlots];
+#pragma unroll
+        for (int c = 0; c < kLruLongSlots; ++c) {
+            const int round = c * kWave + lane;
+            const bool in = c < C && round < d.P;
+            const int64_t s = in ? wrap(home + round, d.N) : home;      // a valid address either way
+            const int64_t v = __hip_atomic_load(&d.I[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            m[c] = d.M[s];
+            const bool be = v == -1 || (is_tag(v) && !tag_occ(v));
+            const bool oc = v >= 0 || (is_tag(v) && tag_occ(v));
+            if (in && be) emp |= 1u << c;
+            if (in && oc && m[c] != p.step) evi |= 1u << c;
+        }
+        int n_empty = 0, n_evict = 0;
+        for (int c = 0; c < C; ++c) {
+            n_empty += __popcll(__ballot((emp >> c) & 1u));
+            n_evict += __popcll(__ballot((evi >> c) & 1u));
+        }
+        const int n_choices = n_empty + n_evict;
+        bool placed = false;
+        int64_t displaced = 0;
+        uint64_t prev_key = 0;                            // key of the last evictable slot drawn (keys are >= 1)
+        int drawn = 0;                                    // evictable slots drawn so far
+        for (; choice < n_choices && !placed; ++choice) {
+            int round = -1;
+            uint32_t occ = 0;
+            if (choice < n_empty) {
+                int k = choice;
+                for (int c = 0; c < C && round < 0; ++c) {
+                    uint64_t mask = __ballot((emp >> c) & 1u);
+                    const int pc = __popcll(mask);
+                    if (k < pc) {
+                        for (int i = 0; i < k; ++i) mask &= mask - 1;
+                        round = c * kWave + __ffsll((unsigned long long)mask) - 1;
+                    } else {
+                        k -= pc;
+                    }
+                }
+            } else {
+                const int j = choice - n_empty;
+                while (drawn <= j) {
+                    uint64_t best = ~0ull;
+#pragma unroll
+                    for (int c = 0; c < kLruLongSlots; ++c) {
+                        const uint64_t key =
+                            (((uint64_t)((uint32_t)m[c] ^ 0x80000000u) << 32) | (uint32_t)(c * kWave + lane)) + 1ull;
+                        if (((evi >> c) & 1u) && key > prev_key && key < best) best = key;
+                    }
+                    prev_key = wave_min64(best);
+                    ++drawn;
+                }
+                round = (int)(uint32_t)((prev_key - 1ull) & 0xFFFFFFFFull);
+                occ = 1;
+            }
+            if (round < 0) break;                                        // (cannot happen: choice < n_choices)
+            const int who = round % kWave;
+            int64_t old = 0, mine = 0;
+            if (lane == who) {
+                mine = make_tag((uint32_t)choice, cpos, occ);
+                old = __hip_atomic_fetch_min(&d.I[wrap(home + round, d.N)], mine, __ATOMIC_RELAXED,
+                                             __HIP_MEMORY_SCOPE_AGENT);
+            }
+            old = shfl64(old, who);
+            mine = shfl64(mine, who);
+            if (is_tag(old) && old < mine) continue;                    // a better claim holds this slot
+            placed = true;
+            displaced = is_tag(old) ? old : 0;
+            if (is_first) first_round = round;
+        }
+        is_first = false;
+        if (!placed || !displaced) break;
+        cpos = tag_pos(displaced);                                       // same table: same slot
+        choice = (int32_t)tag_round(displaced) + 1;
+    }
+    return first_round;
+}
+
+template <bool MULTI>
+__global__ __launch_bounds__(kWave) void k_allocate_lru_long(Params p)
+{
+    const int lane = threadIdx.x;
+    const Tab d0 = view(MULTI ? p.descs[0] : p.t0);
+    for (int64_t seg = blockIdx.x; seg < p.num_segs; seg += gridDim.x) {
+        const uint32_t cnt = p.seg_cnt[seg];
+        const int64_t seg_base = seg * p.seg_chunks * kWave;
+        if (seg_base >= p.n) break;
+        for (uint32_t j0 = 0; j0 < cnt; j0 += kWave) {
+            const int64_t idx = seg_base + j0 + lane;
+            const bool have = j0 + lane < cnt;
+            uint32_t pos = 0;
+            bool agent = false;
+            int f = 0;
+            if (have) {
+                pos = p.list[idx];
+                const uint32_t first = p.set_slot[p.ent[idx]];
+                p.first_of[idx] = first;
+                agent = first == pos;
+                if (MULTI && agent) {
+                    f = find_table(p.offsets, p.num_tables, (int64_t)pos);
+                    agent = p.descs[f].evict == 2;
+                }
+            }
+            uint32_t hint = kHintNone;
+            uint64_t am = __ballot(agent);
+            while (am) {
+                const int src = __ffsll((unsigned long long)am) - 1;
+                am &= am - 1;
+                const uint32_t cpos = __shfl(pos, src);
+                const int fs = __shfl(f, src);
+                const Tab d = MULTI ? view(p.descs[fs]) : d0;
+                const int32_t fr = claim_wave_lru_long(p, d, cpos, 0);
+                if (lane == src)
+                    hint = fr < 0 ? kHintUnplaced : (fr < (int32_t)kHintUnknown ? (uint32_t)fr : kHintUnknown);
             }
             if (MULTI ? agent : have) p.hint[idx] = (uint8_t)hint;
         }

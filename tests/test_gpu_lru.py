@@ -19,6 +19,10 @@ CASES = [
     (1000, 64, 5000, 8191, 8),
     (64, 64, 300, 500, 8),
     (4099, 4, 30000, 20000, 10),
+    (700, 65, 3000, 4000, 8),
+    (2000, 200, 9000, 6000, 6),
+    (1500, 1024, 6000, 2500, 4),
+    (300, 1024, 1500, 1200, 4),
 ]
 
 

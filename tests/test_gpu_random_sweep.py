@@ -36,7 +36,7 @@ def test_random_tables_every_policy(block):
     for case in range(16):
         policy = POLICIES[int(rng.integers(0, 4))]
         n_slots = int(rng.choice([1, 2, 3, 15, 16, 17, 63, 64, 65, 200, 1000, 5000]))
-        p_hi = 64 if policy == "lru" else 300
+        p_hi = 300
         max_probe = int(rng.choice([1, 2, 7, 8, 9, 15, 16, 17, 31, 32, 33, 63, 64, p_hi]))
         ttl = int(rng.integers(0, 4))
         universe = max(2, int(n_slots * float(rng.choice([0.5, 1.5, 4.0]))))
@@ -70,7 +70,7 @@ def test_random_groups_of_tables(block):
         for f in range(T):
             policy = POLICIES[int(rng.integers(0, 4))]
             n_slots = int(rng.choice([1, 2, 17, 64, 65, 300, 2000]))
-            max_probe = int(rng.choice([1, 3, 8, 9, 16, 17, 32, 33, 64, 64 if policy == "lru" else 150]))
+            max_probe = int(rng.choice([1, 3, 8, 9, 16, 17, 32, 33, 64, 150]))
             specs.append(wl.TableSpec(n_slots, max_probe, int(rng.integers(0, 4)), policy, int(rng.integers(0, 1 << 40))))
         jp = JaggedPair(specs)
         step = int(rng.integers(0, 4))

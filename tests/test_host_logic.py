@@ -55,7 +55,7 @@ def test_create_validates_arguments_without_a_gpu(binding):
         assert e.value.status == 1
     b.mpzch_destroy(b.mpzch_create(16, 8, (b.EVICT_LRU, 0), 0))
     with pytest.raises(b.MpzchError) as e:
-        b.mpzch_create(1000, 65, (b.EVICT_LRU, 0), 0)        # LRU: max_probe <= 64
+        b.mpzch_create(5000, 1025, (b.EVICT_LRU, 0), 0)      # LRU: max_probe <= 1024
     assert e.value.status == 4
     assert b.mpzch_status_string(0) == "ok"
     assert b.mpzch_status_string(1) == "invalid argument"
