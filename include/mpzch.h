@@ -308,8 +308,10 @@ mpzch_status_t mpzch_remap_jagged_feature_ttl(mpzch_group_t *g, int64_t *const *
                                               int64_t *out_num_evicted, int64_t *out_stats, void *stream);
 
 /*
- * Per-kernel timing for benchmarks.  While enabled, every kernel launched through the
- * handle is bracketed by HIP events on the call's stream.  mpzch_kernel_times
+ * Per-kernel timing for benchmarks.  enable = 1: every kernel launched through the handle is
+ * bracketed by HIP events on the call's stream; enable = 2: only the Pass-1 kernel of each call
+ * (k_discover / k_lookup), which costs the call a few microseconds instead of some thirty;
+ * enable = 0: off.  mpzch_kernel_times
  * synchronises those events, adds up the durations per kernel and clears the record.
  * names [host] receives up to cap pointers to static strings, ms [host] the summed
  * milliseconds, launches [host] the number of launches; *count the number of kernels.

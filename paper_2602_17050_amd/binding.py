@@ -285,7 +285,8 @@ def _times(fn, handle):
     return {names[i].decode(): (ms[i], cnt[i]) for i in range(k.value)}
 
 
-def mpzch_set_kernel_timing(handle, enable: bool):
+def mpzch_set_kernel_timing(handle, enable):
+    """enable: 0 / False = off, 1 / True = every kernel, 2 = the Pass-1 kernel only."""
     _check(load_library().mpzch_set_kernel_timing(handle, int(enable)), "mpzch_set_kernel_timing")
 
 
@@ -294,7 +295,7 @@ def mpzch_kernel_times(handle):
     return _times(load_library().mpzch_kernel_times, handle)
 
 
-def mpzch_group_set_kernel_timing(group, enable: bool):
+def mpzch_group_set_kernel_timing(group, enable):
     _check(load_library().mpzch_group_set_kernel_timing(group, int(enable)), "mpzch_group_set_kernel_timing")
 
 

@@ -27,13 +27,16 @@ const char *const kKernelNames[KernelCount] = {"k_discover", "k_allocate", "k_fi
 
 struct Timing {
     bool enabled = false;
+    bool pass1_only = false;       // bracket k_discover / k_lookup only (two events per call instead of eight)
+    bool skipped = false;          // the launch between the last begin and end is not bracketed
     struct Rec { int kernel; hipEvent_t a, b; };
     std::vector<Rec> used;
     std::vector<std::pair<hipEvent_t, hipEvent_t>> pool;
 
     bool begin(int kernel, hipStream_t s)
     {
-        if (!enabled) return true;
+        skipped = !enabled || (pass1_only && kernel != KDiscover && kernel != KLookup);
+        if (skipped) return true;
         std::pair<hipEvent_t, hipEvent_t> ev;
         if (!pool.empty()) {
             ev = pool.back();
@@ -47,7 +50,7 @@ struct Timing {
     }
     bool end(hipStream_t s)
     {
-        if (!enabled) return true;
+        if (skipped) return true;
         return hipEventRecord(used.back().b, s) == hipSuccess;
     }
     mpzch_status_t collect(const char **names, double *ms, int64_t *launches, int32_t cap, int32_t *count)
@@ -776,6 +779,7 @@ mpzch_status_t mpzch_set_kernel_timing(mpzch_table_t *t, int32_t enable)
 {
     if (!t) return MPZCH_ERR_INVALID_ARG;
     t->tm.enabled = enable != 0;
+    t->tm.pass1_only = enable == 2;
     return MPZCH_OK;
 }
 
@@ -790,6 +794,7 @@ mpzch_status_t mpzch_group_set_kernel_timing(mpzch_group_t *g, int32_t enable)
 {
     if (!g) return MPZCH_ERR_INVALID_ARG;
     g->tm.enabled = enable != 0;
+    g->tm.pass1_only = enable == 2;
     return MPZCH_OK;
 }
 
