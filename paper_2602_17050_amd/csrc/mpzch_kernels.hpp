@@ -1,10 +1,12 @@
 // Device code of the MPZCH batched remap for gfx950 (wave64).
 //
 // Kernel sequence of one training remap (paper Sec. 3.2 / Algorithm 1, Sec. 3.4, Sec. 3.6):
-//   k_discover   Pass 1 for every position.  A 16-lane group reads the 128-byte line that holds
+//   k_discover   Pass 1 for every position.  An 8-lane group reads the aligned 64 bytes that hold
 //                the id's home slot with one coalesced access and finds the id by ballot + ffs;
-//                the few ids whose window continues into further lines are compacted and
-//                scanned line by line.  Hits store metadata = step and the output slot.  Each
+//                the few ids whose window continues are parked in LDS and scanned 16 slots at
+//                a time.  Hits store metadata = step and the output slot.  (k_lookup is the
+//                same body without writes, k_discover_tables / k_lookup_tables the bodies for
+//                several tables.)  Each
 //                wavefront owns a contiguous range of positions (a segment) and appends the
 //                positions that missed to its segment's list; at the end it enters them into a
 //                scratch hash set that elects, per distinct missed id, the position of its first
@@ -21,7 +23,9 @@
 //   k_emit_dups  the other copies of a missed id copy the slot of the elected position; counters
 //                are published.
 // k_allocate / k_finalize work with one lane per claimant on the first slots of the window and
-// hand the few claimants that need more to the whole wavefront (64 slots per access).
+// hand the few claimants that need more to the whole wavefront (64 slots per access).  Tables
+// under the LRU policy allocate in k_allocate_lru (a group of lanes per claimant) or
+// k_allocate_lru_long (probe ranges beyond 64 slots).
 //
 // No kernel funnels work through one hot address: an atomic on a single address costs about
 // 12 ns on this GPU however many lanes it serves, so miss lists are per wavefront (no shared
