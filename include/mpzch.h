@@ -308,6 +308,17 @@ mpzch_status_t mpzch_remap_jagged_feature_ttl(mpzch_group_t *g, int64_t *const *
                                               int64_t *out_num_evicted, int64_t *out_stats, void *stream);
 
 /*
+ * Inference lookup (Sec. 3.7) for a feature-major keyed jagged batch: value k of feature f is looked
+ * up in table f exactly as mpzch_lookup would, in one launch for all tables.  Read-only.
+ * identities [host] array of num_tables [dev] const int64 pointers (a change of pointers synchronises
+ *            `stream` once to upload them); values, feature_offsets, out_slots as in mpzch_remap_jagged;
+ * out_found [dev] uint8[total_values] or NULL.
+ */
+mpzch_status_t mpzch_lookup_jagged(mpzch_group_t *g, const int64_t *const *identities,
+                                   const int64_t *values, const int64_t *feature_offsets, int64_t total_values,
+                                   int64_t *out_slots, uint8_t *out_found, void *stream);
+
+/*
  * Per-kernel timing for benchmarks.  enable = 1: every kernel launched through the handle is
  * bracketed by HIP events on the call's stream; enable = 2: only the Pass-1 kernel of each call
  * (k_discover / k_lookup), which costs the call a few microseconds instead of some thirty;

@@ -25,7 +25,7 @@ EXPORTED = (
     "mpzch_group_reserve", "mpzch_remap_jagged", "mpzch_set_kernel_timing", "mpzch_kernel_times",
     "mpzch_group_set_kernel_timing", "mpzch_group_kernel_times", "mpzch_status_string",
     "mpzch_remap_feature_ttl", "mpzch_reset_rows_multi", "mpzch_lookup_gather", "mpzch_collect_delta", "mpzch_gather_rows", "mpzch_apply_delta",
-    "mpzch_remap_jagged_feature_ttl",
+    "mpzch_remap_jagged_feature_ttl", "mpzch_lookup_jagged",
 )
 
 
@@ -79,6 +79,7 @@ def load_library(path: str | None = None):
                                        ctypes.POINTER(i64), vp, vp, vp]
     lib.mpzch_remap_jagged_feature_ttl.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), vp, vp, vp, i64, i32, vp,
                                                    vp, ctypes.POINTER(i64), vp, vp, vp]
+    lib.mpzch_lookup_jagged.argtypes = [vp, ctypes.POINTER(vp), vp, vp, i64, vp, vp, vp]
     for name in ("mpzch_kernel_times", "mpzch_group_kernel_times"):
         getattr(lib, name).argtypes = [vp, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_double),
                                        ctypes.POINTER(i64), i32, ctypes.POINTER(i32)]
@@ -273,6 +274,15 @@ def mpzch_remap_jagged(group, identities, metadata, values, feature_offsets, ste
                                              _ptr(out_slots, torch.int64), _ptr(out_evicted_slots, torch.int64), eo,
                                              _ptr(out_num_evicted, torch.int64), _ptr(out_stats, torch.int64),
                                              _stream()), "mpzch_remap_jagged")
+
+
+def mpzch_lookup_jagged(group, identities, values, feature_offsets, out_slots, out_found=None):
+    """identities: list of device tensors, one per table of the group."""
+    T = len(identities)
+    ip = (ctypes.c_void_p * T)(*[t.data_ptr() for t in identities])
+    _check(load_library().mpzch_lookup_jagged(group, ip, _ptr(values, torch.int64), _ptr(feature_offsets, torch.int64),
+                                              values.numel(), _ptr(out_slots, torch.int64), _ptr(out_found, torch.uint8),
+                                              _stream()), "mpzch_lookup_jagged")
 
 
 def _times(fn, handle):

@@ -378,13 +378,42 @@ struct mpzch_table {
     Timing tm;
 };
 
+// A device copy of the table descriptors of a group, re-uploaded only when a pointer changes.
+struct DescCache {
+    TableDesc *dev = nullptr;
+    std::vector<TableDesc> host;         // what dev holds
+    bool uploaded = false;
+
+    mpzch_status_t put(const std::vector<TableDesc> &descs, hipStream_t s)
+    {
+        if (!dev && hipMalloc((void **)&dev, sizeof(TableDesc) * MPZCH_MAX_GROUP_TABLES) != hipSuccess) {
+            dev = nullptr;
+            return MPZCH_ERR_ALLOC;
+        }
+        const size_t bytes = sizeof(TableDesc) * descs.size();
+        if (!uploaded || host.size() != descs.size() || std::memcmp(host.data(), descs.data(), bytes) != 0) {
+            // earlier calls on this stream may still read the old descriptors
+            if (hipStreamSynchronize(s) != hipSuccess) return MPZCH_ERR_HIP;
+            if (hipMemcpy(dev, descs.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) return MPZCH_ERR_HIP;
+            host = descs;
+            uploaded = true;
+        }
+        return MPZCH_OK;
+    }
+    void release()
+    {
+        if (dev) (void)hipFree(dev);
+        dev = nullptr;
+        uploaded = false;
+    }
+};
+
 struct mpzch_group {
     std::vector<TableCfg> cfgs;
     Scratch sc;
     Timing tm;
-    TableDesc *descs_dev = nullptr;
-    std::vector<TableDesc> descs_host;   // what descs_dev holds
-    bool uploaded = false;
+    DescCache train;                     // descriptors of mpzch_remap_jagged (identities + metadata)
+    DescCache infer;                     // descriptors of mpzch_lookup_jagged (identities only)
 };
 
 extern "C" {
@@ -683,7 +712,8 @@ mpzch_status_t mpzch_group_destroy(mpzch_group_t *g)
     if (!g) return MPZCH_OK;
     g->sc.release();
     g->tm.destroy();
-    if (g->descs_dev) (void)hipFree(g->descs_dev);
+    g->train.release();
+    g->infer.release();
     delete g;
     return MPZCH_OK;
 }
@@ -730,20 +760,7 @@ mpzch_status_t mpzch_remap_jagged_feature_ttl(mpzch_group_t *g, int64_t *const *
         return MPZCH_OK;
     }
     TRY(g->sc.ensure(total_values));
-    if (!g->descs_dev) {
-        if (hipMalloc((void **)&g->descs_dev, sizeof(TableDesc) * MPZCH_MAX_GROUP_TABLES) != hipSuccess) {
-            g->descs_dev = nullptr;
-            return MPZCH_ERR_ALLOC;
-        }
-    }
-    if (!g->uploaded || std::memcmp(g->descs_host.data(), descs.data(), sizeof(TableDesc) * (size_t)T) != 0) {
-        // earlier calls on this stream may still read the old descriptors
-        if (hipStreamSynchronize(s) != hipSuccess) return MPZCH_ERR_HIP;
-        if (hipMemcpy(g->descs_dev, descs.data(), sizeof(TableDesc) * (size_t)T, hipMemcpyHostToDevice) != hipSuccess)
-            return MPZCH_ERR_HIP;
-        g->descs_host = descs;
-        g->uploaded = true;
-    }
+    TRY(g->train.put(descs, s));
     Params p;
     std::memset(&p, 0, sizeof p);
     p.ids = values;
@@ -752,7 +769,7 @@ mpzch_status_t mpzch_remap_jagged_feature_ttl(mpzch_group_t *g, int64_t *const *
     p.step = step;
     p.num_tables = T;
     p.out_slots = out_slots;
-    p.descs = g->descs_dev;
+    p.descs = g->train.dev;
     p.offsets = feature_offsets;
     p.t0 = descs[0];
     p.out_evicted = out_evicted_slots;
@@ -773,6 +790,41 @@ mpzch_status_t mpzch_remap_jagged(mpzch_group_t *g, int64_t *const *identities, 
     return mpzch_remap_jagged_feature_ttl(g, identities, metadata, values, nullptr, feature_offsets, total_values, step,
                                           out_slots, out_evicted_slots, evicted_offsets, out_num_evicted, out_stats,
                                           stream);
+}
+
+mpzch_status_t mpzch_lookup_jagged(mpzch_group_t *g, const int64_t *const *identities,
+                                   const int64_t *values, const int64_t *feature_offsets, int64_t total_values,
+                                   int64_t *out_slots, uint8_t *out_found, void *stream)
+{
+    if (!g || !identities || !feature_offsets) return MPZCH_ERR_INVALID_ARG;
+    if (total_values < 0 || total_values > MPZCH_MAX_BATCH) return MPZCH_ERR_INVALID_ARG;
+    const int T = (int)g->cfgs.size();
+    std::vector<TableDesc> descs((size_t)T);
+    for (int f = 0; f < T; ++f) {
+        if (!identities[f]) return MPZCH_ERR_INVALID_ARG;
+        descs[f] = make_desc(g->cfgs[f], const_cast<int64_t *>(identities[f]), nullptr, 0, 0);
+    }
+    if (total_values == 0) return MPZCH_OK;
+    if (!values || !out_slots) return MPZCH_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    TRY(g->sc.query_device());
+    TRY(g->infer.put(descs, s));
+    Params p;
+    std::memset(&p, 0, sizeof p);
+    p.ids = values;
+    p.n = total_values;
+    p.num_tables = T;
+    p.out_slots = out_slots;
+    p.out_found = out_found;
+    p.descs = g->infer.dev;
+    p.offsets = feature_offsets;
+    p.t0 = descs[0];
+    if (T == 1) p.num_tables = 1;            // a group of one table: the single-table kernel, offsets unused
+    const int grid = grid_for(total_values, kBlock, g->sc.num_cus, discover_blocks_per_cu());
+    p.num_segs = grid * kWavesPerBlock;
+    p.seg_chunks = (int32_t)(((total_values + kWave - 1) / kWave + p.num_segs - 1) / p.num_segs);
+    TIMED(g->tm, KLookup, s, (launch_discover<false>(p, grid, s)));
+    return MPZCH_OK;
 }
 
 mpzch_status_t mpzch_set_kernel_timing(mpzch_table_t *t, int32_t enable)

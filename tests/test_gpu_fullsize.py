@@ -177,6 +177,21 @@ def test_config5_26_tables_full_jagged_batch():
     for f in range(T):
         assert np.array_equal(I[f].cpu().numpy(), os_[f].identities), f
         assert np.array_equal(M[f].cpu().numpy(), os_[f].metadata), f
+    # inference over the same 26 tables: one read-only launch for a whole jagged batch
+    values, lengths, offsets = wl.c5_batch(spec, 3)
+    v = torch.from_numpy(values).cuda()
+    out = torch.empty(len(values), dtype=torch.int64, device="cuda")
+    found = torch.empty(len(values), dtype=torch.uint8, device="cuda")
+    mp.mpzch_lookup_jagged(group, I, v, torch.from_numpy(offsets).cuda(), out, found)
+    torch.cuda.synchronize()
+    out_h, found_h = out.cpu().numpy(), found.cpu().numpy()
+    for f in range(T):
+        lo, hi = int(offsets[f]), int(offsets[f + 1])
+        so, fo = os_[f].lookup(values[lo:hi])
+        assert np.array_equal(out_h[lo:hi], so) and np.array_equal(found_h[lo:hi], fo), f
+    say(f"c5 jagged lookup: {len(values)} values, found {found_h.mean():.3f}")
+    for f in range(T):
+        assert np.array_equal(I[f].cpu().numpy(), os_[f].identities), f      # read-only
     mp.mpzch_group_destroy(group)
     for h in handles:
         mp.mpzch_destroy(h)

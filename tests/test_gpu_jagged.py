@@ -52,6 +52,29 @@ class JaggedPair:
             assert dict(zip(mp.STAT_NAMES, st_h[f].tolist())) == sts[f], f
         return sts
 
+    def lookup(self, values, offsets):
+        """Read-only lookup of a jagged batch through the group, against per-table oracle lookups."""
+        v = torch.from_numpy(values).cuda()
+        off = torch.from_numpy(offsets).cuda()
+        out = torch.empty(len(values), dtype=torch.int64, device="cuda")
+        found = torch.empty(len(values), dtype=torch.uint8, device="cuda")
+        before = [int(i.sum().item()) for i in self.I]
+        mp.mpzch_lookup_jagged(self.group, self.I, v, off, out, found)
+        torch.cuda.synchronize()
+        so = np.empty(len(values), np.int64)
+        fo = np.empty(len(values), np.uint8)
+        for f, o in enumerate(self.o):
+            lo, hi = int(offsets[f]), int(offsets[f + 1])
+            so[lo:hi], fo[lo:hi] = o.lookup(values[lo:hi])
+        assert np.array_equal(out.cpu().numpy(), so)
+        assert np.array_equal(found.cpu().numpy(), fo)
+        assert [int(i.sum().item()) for i in self.I] == before      # nothing written
+        out2 = torch.empty(len(values), dtype=torch.int64, device="cuda")
+        mp.mpzch_lookup_jagged(self.group, self.I, v, off, out2, None)
+        torch.cuda.synchronize()
+        assert np.array_equal(out2.cpu().numpy(), so)
+        return fo
+
     def check_state(self):
         for f, o in enumerate(self.o):
             assert np.array_equal(self.I[f].cpu().numpy(), o.identities), f
@@ -77,6 +100,10 @@ def test_config5_jagged_scaled():
             for k in tot:
                 tot[k] += s[k]
     jp.check_state()
+    values, lengths, offsets = wl.c5_batch(spec, 13)
+    fo = jp.lookup(values, offsets)
+    say("c5 lookup of an unseen batch: found fraction", float(fo.mean()))
+    assert 0.3 < fo.mean() < 1.0
     say("c5 totals", tot)
     assert all(v > 0 for v in tot.values())
     jp.close()
@@ -97,8 +124,13 @@ def test_jagged_boundaries_and_empty_features():
         say("jagged step", step, counts)
         jp.step(values, offsets, step)
         jp.check_state()
+        fo = jp.lookup(values, offsets)                             # the batch just remapped: mostly resident
+        probe = [rng.integers(-2, 6 * s.num_slots, size=int(rng.integers(0, 500))) for s in specs]
+        jp.lookup(np.concatenate(probe).astype(np.int64),
+                  np.concatenate([[0], np.cumsum([len(x) for x in probe])]).astype(np.int64))
     # an entirely empty batch
     jp.step(np.empty(0, np.int64), np.zeros(len(specs) + 1, np.int64), 11)
+    jp.lookup(np.empty(0, np.int64), np.zeros(len(specs) + 1, np.int64))
     jp.close()
 
 

@@ -83,6 +83,7 @@ def test_random_groups_of_tables(block):
                 [(s.num_slots, s.max_probe, s.evict) for s in specs], "counts", counts)
             jp.step(values, offsets, step)
             jp.check_state()
+            jp.lookup(values, offsets)
             step += int(rng.integers(0, 3))
         for o in jp.o:
             assert o.check_state()[0] == 0
