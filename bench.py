@@ -421,9 +421,13 @@ def bench_jagged(args, np, torch, mp, wl, dev):
     nev = torch.zeros(T, dtype=torch.int64, device=dev)
     stats = torch.zeros((W + K, T * mp.STAT_COUNT), dtype=torch.int64, device=dev)
 
+    # reset target of every table: bf16 rows of 16 values, one row per slot (32 GB for 1 B slots)
+    emb = [torch.ones((t.num_slots, 16), dtype=torch.bfloat16, device=dev) for t in spec.tables]
+
     def one(i):
         v, o, eo = dev_b[i]
         mp.mpzch_remap_jagged(group, I, M, v, o, i + 1, out[: v.numel()], ev, eo, nev, stats[i])
+        mp.mpzch_reset_rows_jagged(group, ev, eo, nev, emb)
 
     for i in range(W):
         one(i)
@@ -439,7 +443,8 @@ def bench_jagged(args, np, torch, mp, wl, dev):
     st = stats[W:].cpu().numpy().reshape(K, T, mp.STAT_COUNT).sum(axis=(0, 1))
     _emit("remapped IDs/sec (train insert+evict) at 1 GPU", total / elapsed, K, W, elapsed,
           f"c5: 26 tables ({sum(t.num_slots for t in spec.tables)} slots in all), P=16, TTL=5, {spec.samples} samples, "
-          f"pooling 1..50, about {total // K} values per step, one mpzch_remap_jagged call per step", ktimes, None,
+          f"pooling 1..50, about {total // K} values per step, one mpzch_remap_jagged + one mpzch_reset_rows_jagged call "
+          f"per step (bf16 x16 rows per slot)", ktimes, None,
           {"totals_over_timed_steps": dict(zip(mp.STAT_NAMES, [int(x) for x in st]))})
 
 

@@ -308,6 +308,18 @@ mpzch_status_t mpzch_remap_jagged_feature_ttl(mpzch_group_t *g, int64_t *const *
                                               int64_t *out_num_evicted, int64_t *out_stats, void *stream);
 
 /*
+ * Row reset (Sec. 3.4) after mpzch_remap_jagged, for all tables of the group in one launch: for table f
+ * and every k < min(num_evicted[f], evicted_offsets[f+1] - evicted_offsets[f]) the row
+ * (evicted_slots[evicted_offsets[f] + k] mod tensors[f].num_rows) of tensors[f] receives tensors[f].init_row
+ * (zeros when NULL), as mpzch_reset_rows does for one table.
+ * evicted_slots, num_evicted [dev]: the outputs of mpzch_remap_jagged; evicted_offsets [host] int64[T + 1]: the
+ * same array; tensors [host] array of T row tensors (rows == NULL: nothing to reset for that table).
+ * A change of pointers synchronises `stream` once to upload them.
+ */
+mpzch_status_t mpzch_reset_rows_jagged(mpzch_group_t *g, const int64_t *evicted_slots, const int64_t *evicted_offsets,
+                                       const int64_t *num_evicted, const mpzch_rows_t *tensors, void *stream);
+
+/*
  * Inference lookup (Sec. 3.7) for a feature-major keyed jagged batch: value k of feature f is looked
  * up in table f exactly as mpzch_lookup would, in one launch for all tables.  Read-only.
  * identities [host] array of num_tables [dev] const int64 pointers (a change of pointers synchronises

@@ -25,7 +25,7 @@ EXPORTED = (
     "mpzch_group_reserve", "mpzch_remap_jagged", "mpzch_set_kernel_timing", "mpzch_kernel_times",
     "mpzch_group_set_kernel_timing", "mpzch_group_kernel_times", "mpzch_status_string",
     "mpzch_remap_feature_ttl", "mpzch_reset_rows_multi", "mpzch_lookup_gather", "mpzch_collect_delta", "mpzch_gather_rows", "mpzch_apply_delta",
-    "mpzch_remap_jagged_feature_ttl", "mpzch_lookup_jagged",
+    "mpzch_remap_jagged_feature_ttl", "mpzch_lookup_jagged", "mpzch_reset_rows_jagged",
 )
 
 
@@ -79,6 +79,7 @@ def load_library(path: str | None = None):
                                        ctypes.POINTER(i64), vp, vp, vp]
     lib.mpzch_remap_jagged_feature_ttl.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), vp, vp, vp, i64, i32, vp,
                                                    vp, ctypes.POINTER(i64), vp, vp, vp]
+    lib.mpzch_reset_rows_jagged.argtypes = [vp, vp, ctypes.POINTER(i64), vp, ctypes.POINTER(_Rows), vp]
     lib.mpzch_lookup_jagged.argtypes = [vp, ctypes.POINTER(vp), vp, vp, i64, vp, vp, vp]
     for name in ("mpzch_kernel_times", "mpzch_group_kernel_times"):
         getattr(lib, name).argtypes = [vp, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_double),
@@ -274,6 +275,23 @@ def mpzch_remap_jagged(group, identities, metadata, values, feature_offsets, ste
                                              _ptr(out_slots, torch.int64), _ptr(out_evicted_slots, torch.int64), eo,
                                              _ptr(out_num_evicted, torch.int64), _ptr(out_stats, torch.int64),
                                              _stream()), "mpzch_remap_jagged")
+
+
+def mpzch_reset_rows_jagged(group, evicted_slots, evicted_offsets, num_evicted, tensors, init_rows=None):
+    """tensors: one 2-D device tensor (or None) per table of the group; evicted_offsets: host list of ints."""
+    T = len(tensors)
+    init_rows = init_rows or [None] * T
+    arr = (_Rows * T)()
+    for k, (t, init) in enumerate(zip(tensors, init_rows)):
+        if t is None:
+            arr[k] = _Rows(None, 0, 0, 0, None)
+        else:
+            n, rb, st = _row_geometry(t)
+            arr[k] = _Rows(t.data_ptr(), n, rb, st, None if init is None else init.data_ptr())
+    eo = (ctypes.c_int64 * (T + 1))(*[int(x) for x in evicted_offsets])
+    _check(load_library().mpzch_reset_rows_jagged(group, _ptr(evicted_slots, torch.int64), eo,
+                                                  _ptr(num_evicted, torch.int64), arr, _stream()),
+           "mpzch_reset_rows_jagged")
 
 
 def mpzch_lookup_jagged(group, identities, values, feature_offsets, out_slots, out_found=None):

@@ -378,19 +378,20 @@ struct mpzch_table {
     Timing tm;
 };
 
-// A device copy of the table descriptors of a group, re-uploaded only when a pointer changes.
-struct DescCache {
-    TableDesc *dev = nullptr;
-    std::vector<TableDesc> host;         // what dev holds
+// A device copy of per-table descriptors of a group, re-uploaded only when one of them changes.
+template <typename D>
+struct DevCache {
+    D *dev = nullptr;
+    std::vector<D> host;                 // what dev holds
     bool uploaded = false;
 
-    mpzch_status_t put(const std::vector<TableDesc> &descs, hipStream_t s)
+    mpzch_status_t put(const std::vector<D> &descs, hipStream_t s)
     {
-        if (!dev && hipMalloc((void **)&dev, sizeof(TableDesc) * MPZCH_MAX_GROUP_TABLES) != hipSuccess) {
+        if (!dev && hipMalloc((void **)&dev, sizeof(D) * MPZCH_MAX_GROUP_TABLES) != hipSuccess) {
             dev = nullptr;
             return MPZCH_ERR_ALLOC;
         }
-        const size_t bytes = sizeof(TableDesc) * descs.size();
+        const size_t bytes = sizeof(D) * descs.size();
         if (!uploaded || host.size() != descs.size() || std::memcmp(host.data(), descs.data(), bytes) != 0) {
             // earlier calls on this stream may still read the old descriptors
             if (hipStreamSynchronize(s) != hipSuccess) return MPZCH_ERR_HIP;
@@ -412,8 +413,9 @@ struct mpzch_group {
     std::vector<TableCfg> cfgs;
     Scratch sc;
     Timing tm;
-    DescCache train;                     // descriptors of mpzch_remap_jagged (identities + metadata)
-    DescCache infer;                     // descriptors of mpzch_lookup_jagged (identities only)
+    DevCache<TableDesc> train;           // descriptors of mpzch_remap_jagged (identities + metadata)
+    DevCache<TableDesc> infer;           // descriptors of mpzch_lookup_jagged (identities only)
+    DevCache<JagRows> rows;              // descriptors of mpzch_reset_rows_jagged
 };
 
 extern "C" {
@@ -714,6 +716,7 @@ mpzch_status_t mpzch_group_destroy(mpzch_group_t *g)
     g->tm.destroy();
     g->train.release();
     g->infer.release();
+    g->rows.release();
     delete g;
     return MPZCH_OK;
 }
@@ -824,6 +827,44 @@ mpzch_status_t mpzch_lookup_jagged(mpzch_group_t *g, const int64_t *const *ident
     p.num_segs = grid * kWavesPerBlock;
     p.seg_chunks = (int32_t)(((total_values + kWave - 1) / kWave + p.num_segs - 1) / p.num_segs);
     TIMED(g->tm, KLookup, s, (launch_discover<false>(p, grid, s)));
+    return MPZCH_OK;
+}
+
+mpzch_status_t mpzch_reset_rows_jagged(mpzch_group_t *g, const int64_t *evicted_slots, const int64_t *evicted_offsets,
+                                       const int64_t *num_evicted, const mpzch_rows_t *tensors, void *stream)
+{
+    if (!g || !evicted_offsets || !num_evicted || !tensors) return MPZCH_ERR_INVALID_ARG;
+    const int T = (int)g->cfgs.size();
+    std::vector<JagRows> descs((size_t)T);
+    std::memset(descs.data(), 0, sizeof(JagRows) * (size_t)T);
+    bool any = false;
+    for (int f = 0; f < T; ++f) {
+        const int64_t cap = evicted_offsets[f + 1] - evicted_offsets[f];
+        if (cap < 0 || evicted_offsets[f] < 0) return MPZCH_ERR_INVALID_ARG;
+        const mpzch_rows_t &t = tensors[f];
+        if (!t.rows || cap == 0) continue;                   // this table has no rows to reset
+        if (t.num_rows < 1) return MPZCH_ERR_INVALID_ARG;
+        const RowGeom geo = row_geom(t.rows, t.row_bytes, t.row_stride_bytes, t.init_row);
+        if (!geo.ok) return MPZCH_ERR_INVALID_ARG;
+        JagRows &d = descs[f];
+        d.rows = (char *)t.rows;
+        d.init_row = t.init_row;
+        d.num_rows = t.num_rows;
+        d.row_stride_bytes = t.row_stride_bytes;
+        d.ev_begin = evicted_offsets[f];
+        d.ev_cap = cap;
+        d.chunks = (int32_t)geo.chunks;
+        d.wide = geo.wide ? 1 : 0;
+        any = true;
+    }
+    if (!any) return MPZCH_OK;
+    if (!evicted_slots) return MPZCH_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    TRY(g->sc.query_device());
+    TRY(g->rows.put(descs, s));
+    hipLaunchKernelGGL(k_reset_rows_jagged, dim3(g->sc.num_cus * 8), dim3(kBlock), 0, s, evicted_slots, num_evicted,
+                       g->rows.dev, T);
+    LAUNCH_CHECK();
     return MPZCH_OK;
 }
 

@@ -1475,6 +1475,49 @@ __global__ __launch_bounds__(kBlock) void k_reset_rows_multi(const int64_t *slot
     }
 }
 
+// Row reset for a group of tables in one launch: table f's evicted slots are
+// slots[ev_begin .. ev_begin + min(counts[f], ev_cap)), its rows are reset as in k_reset_rows.
+struct JagRows {
+    char *rows;               // null: nothing to reset for this table
+    const void *init_row;
+    int64_t num_rows;
+    int64_t row_stride_bytes;
+    int64_t ev_begin;
+    int64_t ev_cap;
+    int32_t chunks;           // 16-byte (wide) or 4-byte chunks per row
+    int32_t wide;
+};
+
+__global__ __launch_bounds__(kBlock) void k_reset_rows_jagged(const int64_t *slots, const int64_t *counts,
+                                                               const JagRows *tables, int num_tables)
+{
+    for (int f = 0; f < num_tables; ++f) {
+        const JagRows t = tables[f];
+        if (!t.rows) continue;
+        int64_t count = counts[f];
+        if (count > t.ev_cap) count = t.ev_cap;
+        if (count < 0) count = 0;
+        const int64_t total = count * t.chunks;
+        for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < total; i += (int64_t)gridDim.x * kBlock) {
+            const int64_t k = i / t.chunks;
+            const int32_t c = (int32_t)(i - k * t.chunks);
+            int64_t s = slots[t.ev_begin + k];
+            if (s < 0) continue;
+            if (s >= t.num_rows) s %= t.num_rows;
+            char *row = t.rows + s * t.row_stride_bytes;
+            if (t.wide) {
+                u32x4 v = u32x4(0);
+                if (t.init_row) v = reinterpret_cast<const u32x4 *>(t.init_row)[c];
+                __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(row) + c);
+            } else {
+                uint32_t v = 0u;
+                if (t.init_row) v = reinterpret_cast<const uint32_t *>(t.init_row)[c];
+                __builtin_nontemporal_store(v, reinterpret_cast<uint32_t *>(row) + c);
+            }
+        }
+    }
+}
+
 // out[k, :] <- rows[slots[k] mod num_rows, :]   (dense output rows of chunks * sizeof(VEC) bytes)
 template <typename VEC>
 __global__ __launch_bounds__(kBlock) void k_gather_rows(const int64_t *slots, const int64_t *count_dev, int64_t cap,

@@ -153,7 +153,10 @@ def test_config5_26_tables_full_jagged_batch():
         mp.mpzch_init_tensors(h, i, m)
     os_ = [oracle.Table(t.num_slots, t.max_probe, oracle.EVICT_TTL, t.ttl, t.hash_seed) for t in spec.tables]
     T = len(spec.tables)
-    for step in (1, 2):
+    # reset target: bf16 rows of 16 values, one per slot (32 GB in all); ones, so that a reset row shows
+    emb = [torch.ones((t.num_slots, 16), dtype=torch.bfloat16, device="cuda") for t in spec.tables]
+    reset_total = 0
+    for step in (1, 8):                              # at step 8 what step 1 brought in has expired (TTL 5)
         values, lengths, offsets = wl.c5_batch(spec, step)
         say(f"c5 step {step}: {len(values)} values")
         v = torch.from_numpy(values).cuda()
@@ -174,11 +177,24 @@ def test_config5_26_tables_full_jagged_batch():
             assert nev_h[f] == len(evs[f])
             assert np.array_equal(np.sort(ev_h[offsets[f]: offsets[f] + nev_h[f]]), np.sort(evs[f]))
             assert dict(zip(mp.STAT_NAMES, st_h[f].tolist())) == sts[f], f
+        # rows of the evicted slots of all 26 tables, one launch
+        mp.mpzch_reset_rows_jagged(group, ev, [int(x) for x in offsets], nev, emb)
+        torch.cuda.synchronize()
+        for f in range(T):
+            if len(evs[f]):
+                rows = torch.from_numpy(np.unique(evs[f])).cuda()
+                assert int((emb[f][rows] != 0).sum().item()) == 0, f
+        reset_total += sum(len(e) for e in evs)
+    say("c5 evictions (rows reset):", reset_total)
+    assert reset_total > 1000
+    zero_rows = sum(int((e.view(torch.int16)[:, 0] == 0).sum().item()) for e in emb)
+    assert zero_rows == reset_total                   # a slot is evicted at most once per step; no other row touched
+    del emb
     for f in range(T):
         assert np.array_equal(I[f].cpu().numpy(), os_[f].identities), f
         assert np.array_equal(M[f].cpu().numpy(), os_[f].metadata), f
     # inference over the same 26 tables: one read-only launch for a whole jagged batch
-    values, lengths, offsets = wl.c5_batch(spec, 3)
+    values, lengths, offsets = wl.c5_batch(spec, 9)
     v = torch.from_numpy(values).cuda()
     out = torch.empty(len(values), dtype=torch.int64, device="cuda")
     found = torch.empty(len(values), dtype=torch.uint8, device="cuda")

@@ -24,6 +24,12 @@ class JaggedPair:
         for h, i, m in zip(self.handles, self.I, self.M):
             mp.mpzch_init_tensors(h, i, m)
         self.o = [oracle.Table(t.num_slots, t.max_probe, ko(t.evict), t.ttl, t.hash_seed) for t in specs]
+        self.emb_o = self.emb_g = None
+
+    def attach_rows(self, shapes):
+        """shapes: per table (rows, dim) of an fp32 tensor whose rows are reset, or None."""
+        self.emb_o = [None if sh is None else wl.embedding_pattern(sh[0], sh[1], np.float32) for sh in shapes]
+        self.emb_g = [None if e is None else torch.from_numpy(e).cuda() for e in self.emb_o]
 
     def step(self, values, offsets, step, ttls=None):
         T = len(self.specs)
@@ -50,6 +56,14 @@ class JaggedPair:
             got = ev_h[ev_off[f]: ev_off[f] + nev_h[f]]
             assert np.array_equal(np.sort(got), np.sort(evs[f])), f
             assert dict(zip(mp.STAT_NAMES, st_h[f].tolist())) == sts[f], f
+        if self.emb_g is not None:
+            # rows of the slots that changed owner, all tables in one launch
+            mp.mpzch_reset_rows_jagged(self.group, ev, ev_off, nev, self.emb_g)
+            torch.cuda.synchronize()
+            for f in range(T):
+                if self.emb_o[f] is not None:
+                    oracle.reset_rows(evs[f], self.emb_o[f])
+                    assert np.array_equal(self.emb_g[f].cpu().numpy(), self.emb_o[f]), f
         return sts
 
     def lookup(self, values, offsets):
@@ -205,4 +219,28 @@ def test_per_value_retention_needs_a_table_that_uses_it():
     values = np.arange(10, dtype=np.int64)
     with pytest.raises(mp.MpzchError):
         jp.step(values, np.array([0, 10], np.int64), 1, np.ones(10, np.int32))
+    jp.close()
+
+
+def test_jagged_row_reset_in_one_launch():
+    """Every table of the group has its own row tensor (one has none, one has fewer rows than
+    slots, one has 12-byte rows): after each jagged remap the rows of evicted slots are reset by
+    ONE launch and compared with the oracle's per-table reset."""
+    specs = [wl.TableSpec(200, 8, 1, True, 31), wl.TableSpec(500, 16, 1, "lru", 32), wl.TableSpec(64, 4, 0, True, 33),
+             wl.TableSpec(1000, 16, 2, True, 34), wl.TableSpec(300, 8, 1, False, 35)]
+    jp = JaggedPair(specs)
+    jp.attach_rows([(200, 16), (500, 8), None, (256, 3), (300, 4)])
+    rng = np.random.Generator(np.random.Philox(key=909))
+    tot = 0
+    for step in range(12):
+        counts = [int(rng.integers(0, 3 * s.num_slots)) for s in specs]
+        vals = [wl.rank_to_id(rng.integers(0, 6 * s.num_slots, size=c)) for s, c in zip(specs, counts)]
+        values = np.concatenate(vals).astype(np.int64)
+        offsets = np.concatenate([[0], np.cumsum(counts)]).astype(np.int64)
+        say("jagged reset step", step, counts)
+        sts = jp.step(values, offsets, step)
+        tot += sum(s["evictions"] for s in sts)
+    assert tot > 100
+    assert sts[4]["evictions"] == 0                                   # eviction off: its rows stay as they were
+    assert np.array_equal(jp.emb_o[4], wl.embedding_pattern(300, 4, np.float32))
     jp.close()
