@@ -56,7 +56,8 @@ typedef enum {
     MPZCH_ERR_ALLOC = 2,       /* device or host allocation failed */
     MPZCH_ERR_HIP = 3,         /* a HIP runtime call failed; when a remap returns it, the tensors may be
                                   left mid-update (their state is undefined), the handle stays usable */
-    MPZCH_ERR_UNSUPPORTED = 4  /* e.g. MPZCH_EVICT_LRU with max_probe > MPZCH_MAX_PROBE_LRU */
+    MPZCH_ERR_UNSUPPORTED = 4, /* e.g. MPZCH_EVICT_LRU with max_probe > MPZCH_MAX_PROBE_LRU */
+    MPZCH_ERR_TOO_LARGE = 5    /* a size beyond the fixed maximum of an entry point that allocates nothing */
 } mpzch_status_t;
 
 typedef enum {
@@ -161,6 +162,27 @@ mpzch_status_t mpzch_remap(mpzch_table_t *t, int64_t *identities, int32_t *metad
                            int64_t *out_slots,
                            int64_t *out_evicted_slots, int64_t evicted_cap, int64_t *out_num_evicted,
                            int64_t *out_stats, void *stream);
+
+/*
+ * mpzch_remap for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same result and same kernels as
+ * mpzch_remap, but the scratch is a fixed area of MPZCH_NOALLOC_SCRATCH_BYTES bytes that the library
+ * holds in every GPU's memory from load until the process ends, instead of the handle's own; the handle
+ * supplies the configuration only and is not modified.  The call allocates and frees nothing and never
+ * synchronises.  The first call on a GPU also looks up that GPU's copy of the area and clears it
+ * with two fill kernels on `stream`: make that call outside graph capture.
+ * n > MPZCH_NOALLOC_MAX_BATCH is rejected with MPZCH_ERR_TOO_LARGE before anything is launched.
+ * All calls on one GPU -- whatever the handle, whatever the stream -- share that GPU's area: calls that
+ * overlap in time on one GPU race; order them on one stream or with events.  Every call leaves the
+ * area ready for the next one (set emptied, counters zeroed).
+ */
+#define MPZCH_NOALLOC_MAX_BATCH ((int64_t)262144)
+#define MPZCH_NOALLOC_SCRATCH_BYTES (9u << 20) /* 9 MiB per GPU */
+mpzch_status_t mpzch_remap_noalloc(const mpzch_table_t *t, int64_t *identities, int32_t *metadata,
+                                   const int64_t *ids, int64_t n, int32_t step,
+                                   int64_t *out_slots,
+                                   int64_t *out_evicted_slots, int64_t evicted_cap, int64_t *out_num_evicted,
+                                   int64_t *out_stats, void *stream);
 
 /*
  * mpzch_remap for a table of kind MPZCH_EVICT_TTL_EXPIRY whose ids come from features with different

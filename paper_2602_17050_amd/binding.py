@@ -26,7 +26,9 @@ EXPORTED = (
     "mpzch_group_set_kernel_timing", "mpzch_group_kernel_times", "mpzch_status_string",
     "mpzch_remap_feature_ttl", "mpzch_reset_rows_multi", "mpzch_lookup_gather", "mpzch_collect_delta", "mpzch_gather_rows", "mpzch_apply_delta",
     "mpzch_remap_jagged_feature_ttl", "mpzch_lookup_jagged", "mpzch_reset_rows_jagged",
+    "mpzch_remap_noalloc",
 )
+NOALLOC_MAX_BATCH = 262144
 
 
 class MpzchError(RuntimeError):
@@ -64,6 +66,7 @@ def load_library(path: str | None = None):
     lib.mpzch_reserve.argtypes = [vp, i64]
     lib.mpzch_init_tensors.argtypes = [vp, vp, vp, vp]
     lib.mpzch_remap.argtypes = [vp, vp, vp, vp, i64, i32, vp, vp, i64, vp, vp, vp]
+    lib.mpzch_remap_noalloc.argtypes = [vp, vp, vp, vp, i64, i32, vp, vp, i64, vp, vp, vp]
     lib.mpzch_remap_feature_ttl.argtypes = [vp, vp, vp, vp, vp, i64, i32, vp, vp, i64, vp, vp, vp]
     lib.mpzch_lookup.argtypes = [vp, vp, vp, i64, vp, vp, vp]
     lib.mpzch_reset_rows.argtypes = [vp, vp, i64, vp, i64, i64, i64, vp, vp]
@@ -149,6 +152,17 @@ def mpzch_remap(handle, identities, metadata, ids, step: int, out_slots, out_evi
                                       _ptr(ids, torch.int64), n, step, _ptr(out_slots, torch.int64),
                                       _ptr(out_evicted_slots, torch.int64), cap, _ptr(out_num_evicted, torch.int64),
                                       _ptr(out_stats, torch.int64), _stream()), "mpzch_remap")
+
+
+def mpzch_remap_noalloc(handle, identities, metadata, ids, step: int, out_slots, out_evicted_slots, out_num_evicted,
+                        out_stats=None):
+    n = ids.numel()
+    cap = 0 if out_evicted_slots is None else out_evicted_slots.numel()
+    _check(load_library().mpzch_remap_noalloc(handle, _ptr(identities, torch.int64), _ptr(metadata, torch.int32),
+                                              _ptr(ids, torch.int64), n, step, _ptr(out_slots, torch.int64),
+                                              _ptr(out_evicted_slots, torch.int64), cap,
+                                              _ptr(out_num_evicted, torch.int64), _ptr(out_stats, torch.int64),
+                                              _stream()), "mpzch_remap_noalloc")
 
 
 def mpzch_remap_feature_ttl(handle, identities, metadata, ids, ttls, step: int, out_slots, out_evicted_slots,

@@ -6,6 +6,7 @@
 
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -121,6 +122,7 @@ struct Scratch {
     StatRow *rows_b = nullptr;
     Control *ctl = nullptr;
     bool dirty = false;            // a launch sequence was cut short: set and counters must be cleared before use
+    bool owned = true;             // base came from hipMalloc (false: it points into the file-scope scratch array)
     int num_cus = 0;
 
     static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -135,7 +137,45 @@ struct Scratch {
         return MPZCH_OK;
     }
 
-    // 29 bytes per position and a few small fixed areas
+    // Where each array sits inside an area that serves batches of up to n positions: 29 bytes per
+    // position and a few small fixed areas.
+    struct Layout {
+        size_t o_list, o_ent, o_first, o_homes, o_hint, o_seg, o_set, o_rows, o_rows_b, o_ctl, total;
+    };
+    static Layout layout_for(int64_t n, int num_cus)
+    {
+        Layout L;
+        const size_t max_blocks = (size_t)num_cus * kDiscoverBlocksPerCuMax;
+        const size_t per_pos = 4 * ((size_t)n + 2 * kWave);   // list-shaped arrays: n + 128 entries
+        L.o_list = 0;
+        L.o_ent = L.o_list + align_up(per_pos);
+        L.o_first = L.o_ent + align_up(per_pos);
+        L.o_homes = L.o_first + align_up(per_pos);
+        L.o_hint = L.o_homes + align_up(2 * per_pos);
+        L.o_seg = L.o_hint + align_up((size_t)n + kWave);
+        L.o_set = L.o_seg + align_up(4 * max_blocks * kWavesPerBlock);
+        L.o_rows = L.o_set + align_up(8 * (size_t)n);
+        L.o_rows_b = L.o_rows + align_up(max_blocks * sizeof(StatRow));
+        L.o_ctl = L.o_rows_b + align_up(max_blocks * sizeof(StatRow));
+        L.total = L.o_ctl + align_up(sizeof(Control));
+        return L;
+    }
+    void bind(char *area, const Layout &L, int64_t n)
+    {
+        base = area;
+        list = (uint32_t *)(base + L.o_list);
+        ent = (uint32_t *)(base + L.o_ent);
+        first_of = (uint32_t *)(base + L.o_first);
+        homes = (int64_t *)(base + L.o_homes);
+        hint = (uint8_t *)(base + L.o_hint);
+        seg_cnt = (uint32_t *)(base + L.o_seg);
+        set_slot = (uint32_t *)(base + L.o_set);
+        rows_a = (StatRow *)(base + L.o_rows);
+        rows_b = (StatRow *)(base + L.o_rows_b);
+        ctl = (Control *)(base + L.o_ctl);
+        cap_n = n;
+    }
+
     mpzch_status_t ensure(int64_t n)
     {
         mpzch_status_t st = query_device();
@@ -148,40 +188,22 @@ struct Scratch {
             base = nullptr;
             cap_n = 0;
         }
-        const size_t max_blocks = (size_t)num_cus * kDiscoverBlocksPerCuMax;
-        const size_t per_pos = 4 * ((size_t)n + 2 * kWave);   // list-shaped arrays: n + 128 entries
-        const size_t o_list = 0;
-        const size_t o_ent = o_list + align_up(per_pos);
-        const size_t o_first = o_ent + align_up(per_pos);
-        const size_t o_homes = o_first + align_up(per_pos);
-        const size_t o_hint = o_homes + align_up(2 * per_pos);
-        const size_t o_seg = o_hint + align_up((size_t)n + kWave);
-        const size_t o_set = o_seg + align_up(4 * max_blocks * kWavesPerBlock);
-        const size_t o_rows = o_set + align_up(8 * (size_t)n);
-        const size_t o_ctl = o_rows + 2 * align_up(max_blocks * sizeof(StatRow));
-        const size_t total = o_ctl + align_up(sizeof(Control));
-        if (hipMalloc((void **)&base, total) != hipSuccess) { base = nullptr; return MPZCH_ERR_ALLOC; }
-        list = (uint32_t *)(base + o_list);
-        ent = (uint32_t *)(base + o_ent);
-        first_of = (uint32_t *)(base + o_first);
-        homes = (int64_t *)(base + o_homes);
-        hint = (uint8_t *)(base + o_hint);
-        seg_cnt = (uint32_t *)(base + o_seg);
-        set_slot = (uint32_t *)(base + o_set);
-        rows_a = (StatRow *)(base + o_rows);
-        rows_b = (StatRow *)(base + o_rows + align_up(max_blocks * sizeof(StatRow)));
-        ctl = (Control *)(base + o_ctl);
+        const Layout L = layout_for(n, num_cus);
+        char *area = nullptr;
+        if (hipMalloc((void **)&area, L.total) != hipSuccess) return MPZCH_ERR_ALLOC;
+        bind(area, L, 0);
         // empty set (0xFFFFFFFF) and zero counters; set entries are re-emptied by every call, so
         // this is the only full clear
-        if (hipMemset(base + o_set, 0xFF, (o_rows - o_set)) != hipSuccess) return MPZCH_ERR_HIP;
-        if (hipMemset(base + o_rows, 0, total - o_rows) != hipSuccess) return MPZCH_ERR_HIP;
+        if (hipMemset(base + L.o_set, 0xFF, (L.o_rows - L.o_set)) != hipSuccess) return MPZCH_ERR_HIP;
+        if (hipMemset(base + L.o_rows, 0, L.total - L.o_rows) != hipSuccess) return MPZCH_ERR_HIP;
         if (hipDeviceSynchronize() != hipSuccess) return MPZCH_ERR_HIP;
         cap_n = n;
         return MPZCH_OK;
     }
     void release()
     {
-        if (base) { (void)hipDeviceSynchronize(); (void)hipFree(base); base = nullptr; }
+        if (base && owned) { (void)hipDeviceSynchronize(); (void)hipFree(base); }
+        base = nullptr;
         cap_n = 0;
     }
 };
@@ -372,6 +394,50 @@ bool valid_cfg(int64_t num_slots, int32_t max_probe, mpzch_eviction_policy_t pol
 
 }  // namespace
 
+// ---- the entry point that allocates nothing ------------------------------------------------------
+// Its scratch is this file-scope array in device memory (every GPU the library runs on holds its own
+// copy until the process ends).  In host code the array's name is only a handle for
+// hipGetSymbolAddress: the address that kernels and fills receive is the one that call returns,
+// queried once per device and kept in g_static.
+constexpr size_t kStaticScratchBytes = (size_t)MPZCH_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+struct StaticState {
+    bool ready = false;
+    Scratch sc;
+};
+StaticState g_static[kMaxDevices];
+std::mutex g_static_mutex;
+
+// Set-up on the current device (first call on it): the array's address on this device, the layout of
+// the scratch arrays inside it, and the one full clear (empty set, zero counters).
+mpzch_status_t static_scratch(hipStream_t s, Scratch **out)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return MPZCH_ERR_HIP;
+    if (dev < 0 || dev >= kMaxDevices) return MPZCH_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    StaticState &st = g_static[dev];
+    if (!st.ready) {
+        TRY(st.sc.query_device());
+        const Scratch::Layout L = Scratch::layout_for(MPZCH_NOALLOC_MAX_BATCH, st.sc.num_cus);
+        if (L.total > kStaticScratchBytes) return MPZCH_ERR_UNSUPPORTED;     // a GPU with far more compute units
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return MPZCH_ERR_HIP;
+        st.sc.owned = false;
+        st.sc.bind((char *)ptr, L, MPZCH_NOALLOC_MAX_BATCH);
+        // fill kernels, not memsets: the first call may sit in a stream whose work a caller replays
+        TRY(fill32((int32_t *)st.sc.set_slot, (int64_t)((L.o_rows - L.o_set) / 4), -1, s));
+        TRY(fill64((int64_t *)(st.sc.base + L.o_rows), (int64_t)((L.total - L.o_rows) / 8), 0, s));
+        st.ready = true;
+    }
+    *out = &st.sc;
+    return MPZCH_OK;
+}
+}  // namespace
+
 struct mpzch_table {
     TableCfg cfg;
     Scratch sc;
@@ -499,6 +565,40 @@ mpzch_status_t mpzch_remap(mpzch_table_t *t, int64_t *identities, int32_t *metad
 {
     return mpzch_remap_feature_ttl(t, identities, metadata, ids, nullptr, n, step, out_slots, out_evicted_slots,
                                    evicted_cap, out_num_evicted, out_stats, stream);
+}
+
+mpzch_status_t mpzch_remap_noalloc(const mpzch_table_t *t, int64_t *identities, int32_t *metadata,
+                                   const int64_t *ids, int64_t n, int32_t step,
+                                   int64_t *out_slots,
+                                   int64_t *out_evicted_slots, int64_t evicted_cap, int64_t *out_num_evicted,
+                                   int64_t *out_stats, void *stream)
+{
+    if (!t || !identities || !metadata || !out_num_evicted) return MPZCH_ERR_INVALID_ARG;
+    if (n < 0 || step < 0 || evicted_cap < 0) return MPZCH_ERR_INVALID_ARG;
+    if (n > MPZCH_NOALLOC_MAX_BATCH) return MPZCH_ERR_TOO_LARGE;
+    if (n > 0 && (!ids || !out_slots)) return MPZCH_ERR_INVALID_ARG;
+    if (evicted_cap > 0 && !out_evicted_slots) return MPZCH_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    if (n == 0) {
+        TRY(fill64(out_num_evicted, 1, 0, s));
+        if (out_stats) TRY(fill64(out_stats, MPZCH_STAT_COUNT, 0, s));
+        return MPZCH_OK;
+    }
+    Scratch *sc = nullptr;
+    TRY(static_scratch(s, &sc));
+    Params p;
+    std::memset(&p, 0, sizeof p);
+    p.ids = ids;
+    p.n = n;
+    p.step = step;
+    p.num_tables = 1;
+    p.out_slots = out_slots;
+    p.t0 = make_desc(t->cfg, identities, metadata, 0, evicted_cap);
+    p.out_evicted = out_evicted_slots;
+    p.out_num_evicted = out_num_evicted;
+    p.out_stats = out_stats;
+    Timing off;                                  // never enabled: records nothing, creates no event
+    return run_remap(*sc, off, p, p.t0.P, p.t0.evict == 2 ? p.t0.P : 0, s);
 }
 
 mpzch_status_t mpzch_lookup(const mpzch_table_t *t, const int64_t *identities,
@@ -906,6 +1006,7 @@ const char *mpzch_status_string(int32_t status)
         case MPZCH_ERR_ALLOC: return "allocation failed";
         case MPZCH_ERR_HIP: return "HIP runtime error";
         case MPZCH_ERR_UNSUPPORTED: return "unsupported";
+        case MPZCH_ERR_TOO_LARGE: return "size beyond the fixed maximum of this entry point";
         default: return "unknown status";
     }
 }
