@@ -187,9 +187,15 @@ mpzch_status_t mpzch_remap_noalloc(const mpzch_table_t *t, int64_t *identities, 
 /*
  * mpzch_remap for a table of kind MPZCH_EVICT_TTL_EXPIRY whose ids come from features with different
  * retention (Sec. 3.4, second paragraph).  ttls [dev] int32[n]: retention in steps (>= 0) of the feature
- * each position belongs to; all copies of an id must carry the same value (else the stored value is
- * that of one of the copies, unspecified which); NULL = policy.ttl for all
- * (then any table kind is accepted and the call is mpzch_remap).  step + ttl must fit int32.
+ * each position belongs to; NULL = policy.ttl for all (then any table kind is accepted and the call is
+ * mpzch_remap).  step + ttl must fit int32.
+ * Metadata rule of this kind: a slot that is claimed gets metadata = step + ttl of the claiming id's
+ * first occurrence; every other write is a refresh on behalf of one position -- a copy of the id that
+ * lives in the slot (copies may carry different ttls), or an id that falls back to the slot as its home
+ * (Case 3) -- and a refresh stores max(metadata, step + ttl of that position): the expiry step of a slot
+ * never moves backward, so a short-lived feature cannot cut short the retention a long-lived one gave,
+ * and the result does not depend on the order of the positions.  (Algorithm 1 as printed stores the
+ * value of whichever position is processed last.)
  */
 mpzch_status_t mpzch_remap_feature_ttl(mpzch_table_t *t, int64_t *identities, int32_t *metadata,
                                        const int64_t *ids, const int32_t *ttls, int64_t n, int32_t step,
@@ -317,8 +323,8 @@ mpzch_status_t mpzch_remap_jagged(mpzch_group_t *g, int64_t *const *identities, 
  * mpzch_remap_jagged for groups with tables of kind MPZCH_EVICT_TTL_EXPIRY whose region of the
  * batch mixes features of different retention (Sec. 3.4, second paragraph: several features share
  * one table).  ttls [dev] int32[total_values]: retention in steps (>= 0) of the feature each value
- * belongs to, read for the values of MPZCH_EVICT_TTL_EXPIRY tables only; all copies of an id inside
- * one table's region must carry the same value; NULL = every table's own policy.ttl.
+ * belongs to, read for the values of MPZCH_EVICT_TTL_EXPIRY tables only (copies of an id may carry
+ * different values: metadata rule of mpzch_remap_feature_ttl); NULL = every table's own policy.ttl.
  * INVALID_ARG when ttls is given and no table of the group has that kind.
  */
 mpzch_status_t mpzch_remap_jagged_feature_ttl(mpzch_group_t *g, int64_t *const *identities, int32_t *const *metadata,

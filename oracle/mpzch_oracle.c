@@ -139,9 +139,20 @@ static int32_t meta_value(const oracle_cfg *c, const int32_t *ttls, int64_t j, i
     return step + (ttls ? ttls[j] : c->ttl);                        /* per-feature TTL: expiry time */
 }
 
+/* "Refresh TTL" (Algorithm 1) of slot s, which keeps its occupant, on behalf of one batch position.
+ * Last-seen metadata: M[s] = step, as printed.  Expiry-step metadata (Sec. 3.4, second paragraph:
+ * features of different retention share a table): the slot keeps the LATEST expiry step any
+ * processing of its occupant has asked for -- a refresh never moves it backward -- so a position of
+ * a short-lived feature cannot cut short the retention a long-lived feature gave the slot, and the
+ * outcome does not depend on the order in which the positions of a batch are taken. */
+static void refresh(const oracle_cfg *c, int32_t *M, int64_t s, int32_t value)
+{
+    if (c->policy != ORACLE_EVICT_TTL_EXPIRY || value > M[s]) M[s] = value;
+}
+
 /* ttls: with ORACLE_EVICT_TTL_EXPIRY, the retention (in steps) of the feature each position
- * belongs to (Sec. 3.4, per-feature TTL); NULL = the table's ttl for every position.  All copies
- * of an id carry the same value; the first occurrence's is used. */
+ * belongs to (Sec. 3.4, per-feature TTL); NULL = the table's ttl for every position.  Copies of
+ * an id may carry different values: every copy refreshes the id's slot (see refresh). */
 int oracle_remap_ttls(const oracle_cfg *c, int64_t *I, int32_t *M,
                       const int64_t *ids, const int32_t *ttls, int64_t n, int32_t step,
                       int64_t *out_slots,
@@ -185,20 +196,20 @@ int oracle_remap_ttls(const oracle_cfg *c, int64_t *I, int32_t *M,
             if (id < 0) { result[j] = h; continue; }           /* invalid: no state change */
             int64_t r = discover(c, I, id, h);
             if (r >= 0) {
-                int64_t s = probe_slot(h, r, N);
-                M[s] = meta_value(c, ttls, j, step);
-                result[j] = s;
+                result[j] = probe_slot(h, r, N);
             } else {
                 result[j] = -1;
                 miss[n_miss++] = j;                             /* ascending position */
             }
         }
-        /* per-position hit statistics (duplicates included) */
+        /* "Update": every position of a resident id refreshes its slot; per-position hit
+         * statistics (duplicates included) */
         for (int64_t j = 0; j < n; ++j) {
             int64_t f = first[j];
             if (ids[j] < 0) { st[ST_INVALID_POS]++; continue; }
             if (result[f] >= 0) {
                 int64_t h = oracle_home(ids[j], c->hash_seed, N);
+                refresh(c, M, result[f], meta_value(c, ttls, j, step));
                 st[ST_HIT_POS]++;
                 st[ST_HIT_PROBE_SUM] += ((result[f] - h + N) % N) + 1;
             } else {
@@ -281,20 +292,29 @@ int oracle_remap_ttls(const oracle_cfg *c, int64_t *I, int32_t *M,
             }
         }
 
-        /* Stage 3 (Case 3, collision fallback): home slot, its metadata refreshed. */
+        /* Stage 3 (Case 3, collision fallback): home slot, its metadata refreshed ("M[h] <- meta";
+         * the home slot keeps its occupant, so this is a refresh in the sense above). */
+        char *missed = (char *)calloc((size_t)n, 1);              /* first positions of missed ids */
+        if (!missed) { free(first); free(result); free(miss); return -1; }
         for (int64_t k = 0; k < n_miss; ++k) {
             int64_t j = miss[k];
+            missed[j] = 1;
             if (result[j] >= 0) continue;
             int64_t h = oracle_home(ids[j], c->hash_seed, N);
             result[j] = h;
-            /* never lowers the stored value: with last-seen steps this is M[h] = step; with
-             * per-feature expiry times a short-lived id must not shorten the resident's retention */
-            if (meta_value(c, ttls, j, step) > M[h]) M[h] = meta_value(c, ttls, j, step);
+            refresh(c, M, h, meta_value(c, ttls, j, step));
             st[ST_COLLISIONS]++;
         }
 
-        /* Stage 4: every copy of an id receives the slot of its first occurrence. */
-        for (int64_t j = 0; j < n; ++j) out_slots[j] = result[first[j]];
+        /* Stage 4: every copy of an id receives the slot of its first occurrence; the later
+         * copies of an id that was placed or fell back in this batch refresh that slot too
+         * (with one value per id, or last-seen metadata, this changes nothing). */
+        for (int64_t j = 0; j < n; ++j) {
+            out_slots[j] = result[first[j]];
+            if (first[j] != j && ids[j] >= 0 && missed[first[j]])
+                refresh(c, M, out_slots[j], meta_value(c, ttls, j, step));
+        }
+        free(missed);
 
         free(first); free(result); free(miss);
     }

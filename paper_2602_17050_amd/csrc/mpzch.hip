@@ -781,15 +781,19 @@ mpzch_status_t mpzch_apply_delta(int64_t *identities, int64_t num_slots,
     if (cap == 0) return MPZCH_OK;
     if (!slots || !ids) return MPZCH_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)stream;
-    const int grid = row_grid(cap * g.chunks);
-    if (g.wide)
-        hipLaunchKernelGGL((k_apply_delta<u32x4>), dim3(grid), dim3(kBlock), 0, s, identities, num_slots, slots, ids,
-                           count_dev, cap, (char *)rows, num_rows, (int32_t)g.chunks, row_stride_bytes,
-                           (const u32x4 *)delta_rows);
-    else
-        hipLaunchKernelGGL((k_apply_delta<uint32_t>), dim3(grid), dim3(kBlock), 0, s, identities, num_slots, slots, ids,
-                           count_dev, cap, (char *)rows, num_rows, (int32_t)g.chunks, row_stride_bytes,
-                           (const uint32_t *)delta_rows);
+    if (rows) {
+        const int grid = row_grid(cap * g.chunks);
+        if (g.wide)
+            hipLaunchKernelGGL((k_apply_delta_rows<u32x4>), dim3(grid), dim3(kBlock), 0, s, num_slots, slots, count_dev, cap,
+                               (char *)rows, num_rows, (int32_t)g.chunks, row_stride_bytes, (const u32x4 *)delta_rows);
+        else
+            hipLaunchKernelGGL((k_apply_delta_rows<uint32_t>), dim3(grid), dim3(kBlock), 0, s, num_slots, slots, count_dev,
+                               cap, (char *)rows, num_rows, (int32_t)g.chunks, row_stride_bytes,
+                               (const uint32_t *)delta_rows);
+        LAUNCH_CHECK();
+    }
+    hipLaunchKernelGGL(k_apply_delta_ids, dim3(row_grid(cap)), dim3(kBlock), 0, s, identities, num_slots, slots, ids,
+                       count_dev, cap);
     LAUNCH_CHECK();
     return MPZCH_OK;
 }

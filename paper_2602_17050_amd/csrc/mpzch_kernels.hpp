@@ -216,10 +216,14 @@ __device__ __forceinline__ int32_t meta_value(const Params &p, const Tab &d, int
     return p.step + (p.ttls ? p.ttls[pos] : d.ttl);
 }
 
-// Metadata write of k_finalize.  With last-seen metadata every writer of a call stores the same step.
-// With per-feature expiry times the writers of one slot -- the id placed there and the ids that fall
-// back to it as their home -- carry different values; the slot keeps the maximum (a refresh never
-// lowers the stored value), which also makes the result independent of their order.
+// Metadata write on behalf of one batch position.  With last-seen metadata every writer of a call
+// stores the same step.  With per-feature expiry times (Sec. 3.4, second paragraph) the writers of one
+// slot -- the copies of the id that lives there, which may come from features of different retention,
+// and the ids that fall back to it as their home -- carry different values; the slot keeps the latest
+// expiry step any of them asks for: a refresh never moves it backward, so a short-lived feature
+// cannot cut short the retention a long-lived one gave the slot, and the result does not depend on
+// the order of the writers.  (A slot that is claimed held -1 or an expired value, which is below
+// every value written at this step.)
 __device__ __forceinline__ void store_meta(const Tab &d, int64_t s, int32_t value)
 {
     if (d.evict == 3) __hip_atomic_fetch_max(&d.M[s], value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -433,7 +437,7 @@ __device__ __forceinline__ void discover_body(const Params &p)
     auto finish_hit = [&](const Tab &d, int64_t pos, int64_t home, int dist, bool emit) {
         const int64_t slot = wrap(home + dist, d.N);
         if (TRAIN) {
-            d.M[slot] = meta_value(p, d, pos);        // "Update": refresh the resident's metadata
+            store_meta(d, slot, meta_value(p, d, pos));   // "Update": refresh the resident's metadata
             st_hit++;
             st_probe += (unsigned long long)(dist + 1);
         }
@@ -1340,7 +1344,15 @@ __global__ __launch_bounds__(kBlock) void k_emit_dups(Params p)
         for (uint32_t j = lane; j < cnt; j += kWave) {
             const uint32_t pos = p.list[seg_base + j];
             const uint32_t first = p.first_of[seg_base + j];
-            if (first != pos) p.out_slots[pos] = p.out_slots[first];
+            if (first != pos) {
+                const int64_t s = p.out_slots[first];
+                p.out_slots[pos] = s;
+                if (p.ttls) {
+                    // per-feature retention: a later copy may ask for a later expiry step than the first
+                    const Tab d = view(p.num_tables > 1 ? p.descs[find_table(p.offsets, p.num_tables, (int64_t)pos)] : p.t0);
+                    if (d.evict == 3) store_meta(d, s, meta_value(p, d, pos));
+                }
+            }
         }
     }
 
@@ -1541,13 +1553,15 @@ __global__ __launch_bounds__(kBlock) void k_gather_rows(const int64_t *slots, co
     }
 }
 
-// Streaming delta, receiving side (Sec. 3.8): rows[slots[k] mod num_rows, :] <- delta_rows[k, :] and then
-// identities[slots[k]] <- ids[k], so that an identity never points at a row that is older than it.
+// Streaming delta, receiving side (Sec. 3.8): rows[slots[k] mod num_rows, :] <- delta_rows[k, :] in one launch
+// and identities[slots[k]] <- ids[k] in the next one on the same stream, so that every row of the delta
+// has landed before any identity points at it (a reader on another stream never finds a new id in
+// front of a row that is still partly old).
 template <typename VEC>
-__global__ __launch_bounds__(kBlock) void k_apply_delta(int64_t *identities, int64_t num_slots, const int64_t *slots,
-                                                         const int64_t *ids, const int64_t *count_dev, int64_t cap,
-                                                         char *rows, int64_t num_rows, int32_t chunks,
-                                                         int64_t row_stride_bytes, const VEC *delta_rows)
+__global__ __launch_bounds__(kBlock) void k_apply_delta_rows(int64_t num_slots, const int64_t *slots,
+                                                              const int64_t *count_dev, int64_t cap,
+                                                              char *rows, int64_t num_rows, int32_t chunks,
+                                                              int64_t row_stride_bytes, const VEC *delta_rows)
 {
     int64_t count = count_dev ? *count_dev : cap;
     if (count > cap) count = cap;
@@ -1558,14 +1572,21 @@ __global__ __launch_bounds__(kBlock) void k_apply_delta(int64_t *identities, int
         const int32_t c = (int32_t)(i - k * chunks);
         const int64_t s = slots[k];
         if (s < 0 || s >= num_slots) continue;
-        if (rows) {
-            const int64_t r = s >= num_rows ? s % num_rows : s;
-            reinterpret_cast<VEC *>(rows + r * row_stride_bytes)[c] = delta_rows[i];
-        }
-        if (c == chunks - 1) {
-            __threadfence();
-            __hip_atomic_store(&identities[s], ids[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
+        const int64_t r = s >= num_rows ? s % num_rows : s;
+        reinterpret_cast<VEC *>(rows + r * row_stride_bytes)[c] = delta_rows[i];
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void k_apply_delta_ids(int64_t *identities, int64_t num_slots, const int64_t *slots,
+                                                             const int64_t *ids, const int64_t *count_dev, int64_t cap)
+{
+    int64_t count = count_dev ? *count_dev : cap;
+    if (count > cap) count = cap;
+    if (count < 0) count = 0;
+    for (int64_t k = (int64_t)blockIdx.x * kBlock + threadIdx.x; k < count; k += (int64_t)gridDim.x * kBlock) {
+        const int64_t s = slots[k];
+        if (s < 0 || s >= num_slots) continue;
+        __hip_atomic_store(&identities[s], ids[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
@@ -1573,12 +1594,13 @@ __global__ __launch_bounds__(kBlock) void k_apply_delta(int64_t *identities, int
 // list (slot, id), order unspecified.  A workgroup scans a contiguous range of slots, stages its finds in
 // LDS and appends them with one reservation per kDeltaStage finds.
 constexpr int kDeltaStage = 1024;
+constexpr int kDeltaPerThread = 4;     // slots a thread looks at between two workgroup barriers
 
 __global__ __launch_bounds__(kBlock) void k_collect_delta(const int64_t *identities, const int32_t *metadata,
                                                           int64_t num_slots, int32_t since, int64_t *out_slots,
                                                           int64_t *out_ids, int64_t cap, unsigned long long *out_count)
 {
-    __shared__ int64_t s_slot[kDeltaStage + kBlock];
+    __shared__ int64_t s_slot[kDeltaStage + kDeltaPerThread * kBlock];
     __shared__ int s_n;
     __shared__ unsigned long long s_base;
     const int64_t per_block = (num_slots + gridDim.x - 1) / gridDim.x;
@@ -1586,24 +1608,29 @@ __global__ __launch_bounds__(kBlock) void k_collect_delta(const int64_t *identit
     const int64_t hi = lo + per_block < num_slots ? lo + per_block : num_slots;
     if (threadIdx.x == 0) s_n = 0;
     __syncthreads();
-    auto flush = [&]() {       // reached by all threads
-        __syncthreads();
+    auto flush = [&]() {       // reached by all threads, with the staging complete and s_n at rest
         const int n = s_n;
         if (threadIdx.x == 0 && n) s_base = atomicAdd(out_count, (unsigned long long)n);
-        __syncthreads();
+        __syncthreads();       // everyone has read s_n and sees s_base
         for (int i = threadIdx.x; i < n; i += kBlock) {
             const int64_t at = (int64_t)s_base + i;
             if (at < cap) { out_slots[at] = s_slot[i]; out_ids[at] = identities[s_slot[i]]; }
         }
-        __syncthreads();
         if (threadIdx.x == 0) s_n = 0;
-        __syncthreads();
+        __syncthreads();       // the staging area is free again before anyone adds to it
     };
-    for (int64_t base = lo; base < hi; base += kBlock) {
-        const int64_t s = base + threadIdx.x;
-        if (s < hi && identities[s] >= 0 && metadata[s] >= since) s_slot[atomicAdd(&s_n, 1)] = s;
+    for (int64_t base = lo; base < hi; base += kDeltaPerThread * kBlock) {
+#pragma unroll
+        for (int k = 0; k < kDeltaPerThread; ++k) {
+            const int64_t s = base + k * kBlock + threadIdx.x;
+            if (s < hi && identities[s] >= 0 && metadata[s] >= since) s_slot[atomicAdd(&s_n, 1)] = s;
+        }
         __syncthreads();
-        if (s_n > kDeltaStage) flush();
+        // The decision to flush is taken by all threads from the same value: s_n does not change
+        // between the barrier above and the one inside flush (or the one below).
+        const bool full = s_n > kDeltaStage;
+        if (full) flush();
+        else __syncthreads();  // nobody adds to s_n before everyone has looked at it
     }
     flush();
 }

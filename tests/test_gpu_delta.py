@@ -112,3 +112,31 @@ def test_streaming_delta_brings_an_inference_copy_up_to_date():
     torch.cuda.synchronize()
     assert torch.equal(inf2[d_slots[:n]], d_ids[:n]) and int((inf2 >= 0).sum().item()) == n
     p.close()
+
+
+def test_collect_delta_on_a_dense_multi_million_slot_table():
+    """Most workgroups fill their staging area many times over: every occupied slot touched since
+    `since` must come out exactly once (count, slots and ids against the numpy statement)."""
+    n_slots = 6_000_011
+    rng = np.random.Generator(np.random.Philox(key=606))
+    I = np.where(rng.random(n_slots) < 0.7, rng.integers(0, 1 << 62, size=n_slots), -1).astype(np.int64)
+    M = rng.integers(0, 10, size=n_slots).astype(np.int32)
+    I[1000:9000] = np.arange(8000)                                # a fully occupied, fully qualifying stretch
+    M[1000:9000] = 9
+    I[20000:40000] = -1                                           # and an empty one
+    o = oracle.Table(n_slots, 8, oracle.EVICT_TTL, 1, 5, I, M)
+    h = mp.mpzch_create(n_slots, 8, (mp.EVICT_TTL, 1), 5)
+    gI, gM = torch.from_numpy(I).cuda(), torch.from_numpy(M).cuda()
+    d_slots = torch.empty(n_slots, dtype=torch.int64, device="cuda")
+    d_ids = torch.empty(n_slots, dtype=torch.int64, device="cuda")
+    d_cnt = torch.zeros(1, dtype=torch.int64, device="cuda")
+    for since in (0, 5, 9, 10):
+        say("collect_delta since", since)
+        mp.mpzch_collect_delta(h, gI, gM, since, d_slots, d_ids, d_cnt)
+        n = int(d_cnt.item())
+        so, io = oracle.collect_delta(o, since)
+        assert n == len(so), (since, n, len(so))
+        got = d_slots[:n].cpu().numpy()
+        order = np.argsort(got, kind="stable")
+        assert np.array_equal(got[order], so) and np.array_equal(d_ids[:n].cpu().numpy()[order], io)
+    mp.mpzch_destroy(h)

@@ -16,6 +16,11 @@ def _ttl_of(ids):
     return (np.abs(ids) % 4).astype(np.int32) * 2
 
 
+def _ttl_per_position(rng, ids):
+    """one table serving several features: the same id arrives with different retention in one batch"""
+    return rng.integers(0, 7, size=len(ids)).astype(np.int32)
+
+
 @pytest.mark.parametrize("case", CASES, ids=[f"N{c[0]}_P{c[1]}" for c in CASES])
 def test_feature_ttl_contended_small_tables(case):
     n_slots, max_probe, universe, batch, steps = case
@@ -31,7 +36,9 @@ def test_feature_ttl_contended_small_tables(case):
         else:
             ids = wl.rank_to_id(rng.integers(universe, 3 * universe, size=batch))
         say("feature-ttl case", case, "step", step)
-        r = p.step(ids, step, ttls=None if k == 4 else _ttl_of(ids))     # one call with the table's own ttl
+        # one call with the table's own ttl; every other call lets copies of an id disagree
+        ttls = None if k == 4 else (_ttl_per_position(rng, ids) if k % 2 else _ttl_of(ids))
+        r = p.step(ids, step, ttls=ttls)
         ev += r.stats["evictions"]
         assert p.o.check_state()[0] == 0
     assert ev > 0 or n_slots == 1
@@ -44,9 +51,11 @@ def test_feature_ttl_one_million_slots():
     step0, pre = wl.c2_prefill()
     p.step(pre, step0, check_state=False, ttls=_ttl_of(pre))
     tot = 0
+    rng = np.random.Generator(np.random.Philox(key=31337))
     for step in range(1, 31):
         ids = wl.c2_batch(step)
-        tot += p.step(ids, step, check_state=(step % 10 == 0), ttls=_ttl_of(ids)).stats["evictions"]
+        ttls = _ttl_per_position(rng, ids) if step % 2 else _ttl_of(ids)
+        tot += p.step(ids, step, check_state=(step % 10 == 0), ttls=ttls).stats["evictions"]
     say("feature-ttl evictions", tot)
     assert tot > 1000
     p.check_state()

@@ -201,7 +201,10 @@ def test_jagged_regions_that_mix_features_of_different_retention():
         vals = [rng.integers(0, 4 * s.num_slots, size=c) for s, c in zip(specs, counts)]
         values = np.concatenate(vals).astype(np.int64)
         offsets = np.concatenate([[0], np.cumsum(counts)]).astype(np.int64)
-        ttls = ((values >> 2) % 6).astype(np.int32)          # the id's feature decides: equal ids, equal value
+        if it % 2:
+            ttls = ((values >> 2) % 6).astype(np.int32)      # the id's feature decides: equal ids, equal value
+        else:
+            ttls = rng.integers(0, 6, size=values.size).astype(np.int32)     # copies of an id disagree
         say("feature-ttl group step", step, counts)
         sts = jp.step(values, offsets, step, ttls)
         tot += sum(s["evictions"] for s in sts)

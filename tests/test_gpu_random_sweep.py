@@ -47,8 +47,11 @@ def test_random_tables_every_policy(block):
             ids = draw_ids(rng, n, universe) if n else np.empty(0, np.int64)
             ttls = None
             if policy == "expiry" and rng.random() < 0.7:
-                # the retention belongs to the id's feature: all copies of an id carry the same value
-                ttls = ((np.asarray(ids, dtype=np.int64) >> 3) % 5).astype(np.int32)
+                if rng.random() < 0.5:
+                    # the retention belongs to the id's feature: all copies of an id carry the same value
+                    ttls = ((np.asarray(ids, dtype=np.int64) >> 3) % 5).astype(np.int32)
+                else:
+                    ttls = rng.integers(0, 5, size=len(ids)).astype(np.int32)    # copies of an id disagree
             say("sweep block", block, "case", case, "policy", policy, "N", n_slots, "P", max_probe, "ttl", ttl,
                 "step", step, "n", len(ids))
             p.step(ids, step, ttls=ttls)

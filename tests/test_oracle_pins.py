@@ -42,10 +42,14 @@ def ids_with_home(target_home, seed, n_slots, count, start=0, avoid=()):
 
 
 class Alg1Table:
-    """Algorithm 1 for ONE id at a time, as printed: Pass 1 sets `exists`, Pass 2 walks
-    the range again doing update / insert / evict, Case 3 falls back to the home slot.
-    `meta` is split into the value written (the step) and the expiry test
-    step - M > ttl (Sec. 3.4: a slot whose stored time lies before now is expired)."""
+    """What processing ONE id does to a table, stated as a definition rather than as the paper's
+    two loops (Sec. 3.2, the three outcomes of Pass 2; Sec. 3.4 for "expired"):
+      window  = the min(P, N) slots from the id's home slot on, wrapping;
+      hit     : the window holds the id             -> that slot, time stamp refreshed;
+      claim   : else the first slot of the window that is empty, or (eviction on) whose time
+                stamp is more than ttl steps old     -> the id moves in, time stamp = step,
+                evicted exactly when the slot held another id;
+      collide : else the home slot, whose time stamp is refreshed (Case 3)."""
 
     def __init__(self, n_slots, max_probe, ttl, evict, seed):
         self.I = [-1] * n_slots
@@ -54,22 +58,18 @@ class Alg1Table:
 
     def lookup_one(self, id_, step):
         h = py_home(id_, self.seed, self.N)
-        exists = False
-        for i in range(self.P):
-            if self.I[(h + i) % self.N] == id_:
-                exists = True
-                break
-        for i in range(self.P):
-            slot = (h + i) % self.N
-            id_curr, meta_curr = self.I[slot], self.M[slot]
-            if id_curr == id_ or id_curr == -1:
-                self.I[slot] = id_
-                self.M[slot] = step
-                return slot, False
-            if self.evict and not exists and step - meta_curr > self.ttl:
-                self.I[slot] = id_
-                self.M[slot] = step
-                return slot, True
+        window = [(h + i) % self.N for i in range(self.P)]
+        holding = [s for s in window if self.I[s] == id_]
+        if holding:
+            self.M[holding[0]] = step
+            return holding[0], False
+        free = [s for s in window
+                if self.I[s] == -1 or (self.evict and step - self.M[s] > self.ttl)]
+        if free:
+            s = free[0]
+            evicted = self.I[s] != -1
+            self.I[s], self.M[s] = id_, step
+            return s, evicted
         self.M[h] = step
         return h, False
 
