@@ -213,14 +213,7 @@ def test_config5_26_tables_full_jagged_batch():
         mp.mpzch_destroy(h)
 
 
-@pytest.mark.parametrize("size_m,max_probe", [(150, 16), (200, 8), (200, 64), (300, 64)])
-def test_table1_cells_at_full_scale(size_m, max_probe):
-    """Sec. 3.3, Table 1 at the paper's own scale: 150 M distinct ids, eviction off.  The fraction
-    of ids left without a slot must match the printed cell (5 % relative or four standard
-    deviations of the count: the measured cells lie 0.01-0.1 % below the printed ones where the rate is
-    large and 3 % below in the far tail, e.g. 0.0289 % against 0.0299 % -- other ids, another hash);
-    2.0x capacity with P = 64 must print as 0.0000 %."""
-    import math
+def _table1_golden():
     import os
     golden = {}
     with open(os.path.join(os.path.dirname(__file__), "golden", "table1_collision_rate.txt")) as f:
@@ -228,7 +221,23 @@ def test_table1_cells_at_full_scale(size_m, max_probe):
             if line.strip() and not line.startswith("#"):
                 v = line.split()
                 golden[int(v[0])] = dict(zip((8, 16, 32, 64, 128, 256, 512), map(float, v[3:])))
-    n_ids, batch = 150_000_000, 262144
+    return golden
+
+
+T1_IDS, T1_BATCH = 150_000_000, 262144
+
+
+@pytest.mark.parametrize("size_m,max_probe", [(150, 16), (200, 8), (200, 32), (300, 64)])
+def test_table1_cells_at_full_scale(size_m, max_probe):
+    """Sec. 3.3, Table 1 at the paper's own scale: 150 M distinct ids, eviction off.  The fraction
+    of ids left without a slot must match the printed cell within 3 % relative or four standard
+    deviations of the count; 2.0x capacity with P = 64 must print as the paper's 0.0000 %.  (The far-tail
+    cell 200 M / P = 64 is replayed by the oracle below instead: textbook probing under a uniform hash
+    gives 0.0292 % there, 2.4 % below the printed 0.0299 %, so a 3 % band around the printed value
+    is not what a correct implementation lands in.)"""
+    import math
+    golden = _table1_golden()
+    n_ids, batch = T1_IDS, T1_BATCH
     n_slots = size_m * 1_000_000
     h = mp.mpzch_create(n_slots, max_probe, (mp.EVICT_NONE, 0), wl.HASH_SEED_BASE)
     I = torch.empty(n_slots, dtype=torch.int64, device="cuda")
@@ -251,10 +260,78 @@ def test_table1_cells_at_full_scale(size_m, max_probe):
     want = golden[size_m][max_probe]
     sigma = 100.0 * math.sqrt(max(want / 100.0 * n_ids, 1.0)) / n_ids
     say(f"table1 {size_m}M P={max_probe}: {got:.4f}% (paper {want:.4f}%)")
-    assert abs(got - want) <= max(0.05 * want, 4 * sigma)
+    assert abs(got - want) <= max(0.03 * want, 4 * sigma)
     if size_m == 300 and max_probe == 64:
-        assert got < 0.00005                              # prints as the paper's 0.0000 %
+        # the printed 0.0000 % means fewer than 75 of the 150 M ids; a uniform hash leaves a handful
+        # (expected count about 1 at this load), the oracle included
+        assert got < 0.00005 and tot["collisions"] < 10
     mp.mpzch_destroy(h)
+
+
+class _Table1Replay:
+    """State of the cell that the oracle replays call by call, kept between the parts of the test."""
+    size_m, max_probe, parts = 200, 64, 6
+
+    def __init__(self):
+        self.n_slots = self.size_m * 1_000_000
+        self.h = mp.mpzch_create(self.n_slots, self.max_probe, (mp.EVICT_NONE, 0), wl.HASH_SEED_BASE)
+        self.I = torch.empty(self.n_slots, dtype=torch.int64, device="cuda")
+        self.M = torch.empty(self.n_slots, dtype=torch.int32, device="cuda")
+        mp.mpzch_init_tensors(self.h, self.I, self.M)
+        mp.mpzch_reserve(self.h, T1_BATCH)
+        self.o = oracle.Table(self.n_slots, self.max_probe, oracle.EVICT_NONE, 0, wl.HASH_SEED_BASE)
+        self.calls = (T1_IDS + T1_BATCH - 1) // T1_BATCH
+        self.next_call = 0
+        self.collisions = 0
+        self.failed = False
+
+    def close(self):
+        mp.mpzch_destroy(self.h)
+        self.I = self.M = self.o = None
+
+
+@pytest.fixture(scope="module")
+def table1_replay():
+    st = _Table1Replay()
+    yield st
+    st.close()
+
+
+@pytest.mark.parametrize("part", range(_Table1Replay.parts))
+def test_table1_cell_replayed_by_the_oracle(table1_replay, part):
+    """Sec. 3.3, Table 1, the cell 200 M slots / P = 64 at full scale (150 M distinct ids, 262 144 per
+    call, eviction off), with the oracle fed the same calls: collisions and out_slots of EVERY call are
+    compared, and after the last call the whole identities and metadata tensors, bit for bit.  The 573
+    calls are spread over the parts of this test (the oracle needs some 25 s per part), which share
+    their state and must run in order."""
+    st = table1_replay
+    assert not st.failed and st.next_call == part * ((st.calls + st.parts - 1) // st.parts), "parts run in order"
+    st.failed = True
+    per_part = (st.calls + st.parts - 1) // st.parts
+    out = torch.empty(T1_BATCH, dtype=torch.int64, device="cuda")
+    nev = torch.zeros(1, dtype=torch.int64, device="cuda")
+    stats = torch.zeros(mp.STAT_COUNT, dtype=torch.int64, device="cuda")
+    t0 = time.time()
+    for k in range(part * per_part, min((part + 1) * per_part, st.calls)):
+        lo = k * T1_BATCH
+        ids = wl.distinct_ids_device(lo, min(lo + T1_BATCH, T1_IDS), "cuda")
+        n = ids.numel()
+        mp.mpzch_remap(st.h, st.I, st.M, ids, k, out[:n], None, nev, stats)
+        r = st.o.remap(ids.cpu().numpy(), k)
+        got = dict(zip(mp.STAT_NAMES, stats.tolist()))
+        assert got == r.stats, (k, got, r.stats)
+        assert np.array_equal(out[:n].cpu().numpy(), r.slots), f"out_slots differ in call {k}"
+        st.collisions += r.stats["collisions"]
+        st.next_call = k + 1
+    say(f"table1 replay part {part}: calls up to {st.next_call} of {st.calls}, {st.collisions} collisions so far, "
+        f"{time.time() - t0:.1f}s")
+    if st.next_call == st.calls:
+        assert np.array_equal(st.I.cpu().numpy(), st.o.identities)
+        assert np.array_equal(st.M.cpu().numpy(), st.o.metadata)
+        pct = 100.0 * st.collisions / T1_IDS
+        say(f"table1 200M P=64 replayed: {pct:.4f}% (paper 0.0299%)")
+        assert 0.027 < pct < 0.031                                  # the printed 0.0299 % is context, the oracle is the bar
+    st.failed = False
 
 
 def test_maximum_batch_in_one_call():
