@@ -89,7 +89,9 @@ enum {
     MPZCH_STAT_COLLISIONS = 5,    /* distinct missed ids left without a slot (Table 1)     */
     MPZCH_STAT_INVALID_POS = 6,   /* positions holding a negative id                       */
     MPZCH_STAT_HIT_PROBE_SUM = 7, /* sum over hit positions of (probe distance + 1)        */
-    MPZCH_STAT_COUNT = 8
+    MPZCH_STAT_MISS_PROBE_SUM = 8, /* sum over miss positions of the slots Pass 1 has to read: up to and
+                                     including the first empty slot of the range, else the whole range */
+    MPZCH_STAT_COUNT = 9
 };
 
 #define MPZCH_MAX_BATCH ((int64_t)1 << 30) /* positions per remap / lookup call          */
@@ -246,15 +248,17 @@ mpzch_status_t mpzch_reset_rows_multi(const int64_t *slots, const int64_t *num_s
                                       const mpzch_rows_t *tensors, int32_t num_tensors, void *stream);
 
 /*
- * Inference lookup fused with the embedding gather (Sec. 3.7): out_rows[j, :] = rows[slot_j mod num_rows, :]
- * where slot_j is what mpzch_lookup returns for ids[j] (the home slot's row when the id is not resident).
- * out_rows [dev] n x row_bytes bytes, dense.  scratch_slots [dev] int64[n]: the looked-up slots (also an
- * output).  out_found [dev] uint8[n] or NULL.
+ * Inference lookup fused with the embedding gather (Sec. 3.7), one kernel: the lanes that resolve the
+ * slots of 64 ids copy their rows, out_rows[j, :] = rows[slot_j mod num_rows, :], where slot_j is what
+ * mpzch_lookup returns for ids[j] (the home slot's row when the id is not resident).
+ * rows as in mpzch_reset_rows; out_rows [dev] n x row_bytes bytes, dense; row_bytes <= 16 MiB.
+ * out_slots [dev] int64[n] or NULL: the looked-up slots, written only when given.
+ * out_found [dev] uint8[n] or NULL.
  */
 mpzch_status_t mpzch_lookup_gather(const mpzch_table_t *t, const int64_t *identities,
                                    const int64_t *ids, int64_t n,
                                    const void *rows, int64_t num_rows, int64_t row_bytes, int64_t row_stride_bytes,
-                                   void *out_rows, int64_t *scratch_slots, uint8_t *out_found, void *stream);
+                                   void *out_rows, int64_t *out_slots, uint8_t *out_found, void *stream);
 
 /*
  * Streaming delta (Sec. 3.8: sparse delta publishing; "the corresponding entries in the identities tensor

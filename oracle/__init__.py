@@ -25,7 +25,7 @@ EVICT_TTL_EXPIRY = 3
 
 STAT_NAMES = (
     "hit_pos", "miss_pos", "distinct_miss", "inserts",
-    "evictions", "collisions", "invalid_pos", "hit_probe_sum",
+    "evictions", "collisions", "invalid_pos", "hit_probe_sum", "miss_probe_sum",
 )
 
 

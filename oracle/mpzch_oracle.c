@@ -65,6 +65,8 @@ enum {
     ST_COLLISIONS,       /* distinct missed ids that fell back to home       */
     ST_INVALID_POS,      /* positions holding a negative id                  */
     ST_HIT_PROBE_SUM,    /* sum over hit positions of (probe distance + 1)   */
+    ST_MISS_PROBE_SUM,   /* sum over miss positions of the slots Pass 1 has to read: up to and
+                            including the first empty slot of the range, else the whole range */
     ST_COUNT
 };
 
@@ -213,7 +215,13 @@ int oracle_remap_ttls(const oracle_cfg *c, int64_t *I, int32_t *M,
                 st[ST_HIT_POS]++;
                 st[ST_HIT_PROBE_SUM] += ((result[f] - h + N) % N) + 1;
             } else {
+                /* no id lies beyond an empty slot of its range (a slot never becomes empty again),
+                 * so that is as far as a search for an absent id has to read */
+                int64_t h = oracle_home(ids[j], c->hash_seed, N), len = P;
+                for (int64_t r = 0; r < P; ++r)
+                    if (I[probe_slot(h, r, N)] == -1) { len = r + 1; break; }
                 st[ST_MISS_POS]++;
+                st[ST_MISS_PROBE_SUM] += len;
             }
         }
         st[ST_DISTINCT_MISS] = n_miss;

@@ -16,7 +16,7 @@ _LIB_PATH = os.path.join(_HERE, "libmpzch.so")
 
 EVICT_NONE, EVICT_TTL, EVICT_LRU, EVICT_TTL_EXPIRY = 0, 1, 2, 3
 STAT_NAMES = ("hit_pos", "miss_pos", "distinct_miss", "inserts",
-              "evictions", "collisions", "invalid_pos", "hit_probe_sum")
+              "evictions", "collisions", "invalid_pos", "hit_probe_sum", "miss_probe_sum")
 STAT_COUNT = len(STAT_NAMES)
 
 EXPORTED = (
@@ -213,12 +213,12 @@ def mpzch_reset_rows_multi(slots, num_slots_dev, tensors, init_rows=None):
                                                  slots.numel(), arr, len(tensors), _stream()), "mpzch_reset_rows_multi")
 
 
-def mpzch_lookup_gather(handle, identities, ids, rows, out_rows, scratch_slots, out_found=None):
+def mpzch_lookup_gather(handle, identities, ids, rows, out_rows, out_slots=None, out_found=None):
     n, rb, st = _row_geometry(rows)
     assert out_rows.is_contiguous() and out_rows.numel() * out_rows.element_size() == ids.numel() * rb
     _check(load_library().mpzch_lookup_gather(handle, _ptr(identities, torch.int64), _ptr(ids, torch.int64), ids.numel(),
                                               ctypes.c_void_p(rows.data_ptr()), n, rb, st,
-                                              ctypes.c_void_p(out_rows.data_ptr()), _ptr(scratch_slots, torch.int64),
+                                              ctypes.c_void_p(out_rows.data_ptr()), _ptr(out_slots, torch.int64),
                                               _ptr(out_found, torch.uint8), _stream()), "mpzch_lookup_gather")
 
 

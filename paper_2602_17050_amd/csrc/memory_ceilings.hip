@@ -62,6 +62,84 @@ __global__ void k_line(const long long *t, uint64_t n, uint64_t ops, long long *
     if (a == 0x1234567) sink[0] = a;
 }
 
+// As k_line<true>, but the accesses are issued in address order at the granularity of `buckets` equal
+// parts of the array: access j falls into part j * buckets / ops, at a random line inside it (what a
+// batch looks like after its positions were bucketed by the top bits of their home slot).
+__global__ void k_line_bucketed(const long long *t, uint64_t n, uint64_t ops, uint64_t buckets, long long *sink)
+{
+    long long a = 0;
+    const uint64_t tid = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x;
+    const uint64_t groups = ((uint64_t)gridDim.x * blockDim.x) >> 4;
+    const int r = tid & 15;
+    const uint64_t part = (n - 32) / buckets;
+    const double scale = (double)buckets / (double)ops;
+    // a workgroup walks a contiguous range of accesses, so that neighbouring workgroups stay in neighbouring parts
+    const uint64_t per_group = (ops + groups - 1) / groups;
+    const uint64_t j0 = (tid >> 4) * per_group;
+    for (uint64_t k = 0; k < per_group; k += 4) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint64_t j = j0 + k + u;
+            if (k + u < per_group && j < ops) {
+                uint64_t b = (uint64_t)((double)j * scale);     // the part, up to rounding at its borders
+                if (b >= buckets) b = buckets - 1;
+                uint64_t s = b * part + __umul64hi(mix64(j), part);
+                s &= ~15ull;
+                a += t[s + r];
+            }
+        }
+    }
+    if (a == 0x1234567) sink[0] = a;
+}
+
+// 4-byte stores in the same bucketed order
+__global__ void k_store4_bucketed(int *t, uint64_t n, uint64_t ops, uint64_t buckets)
+{
+    const uint64_t tid = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x;
+    const uint64_t threads = (uint64_t)gridDim.x * blockDim.x;
+    const uint64_t part = n / buckets;
+    const double scale = (double)buckets / (double)ops;
+    const uint64_t per_wave = (ops + threads - 1) / threads * 64;
+    const uint64_t j0 = (tid >> 6) * per_wave + (tid & 63);
+    for (uint64_t k = 0; k < per_wave; k += 64) {
+        const uint64_t j = j0 + k;
+        if (j < ops) {
+            uint64_t b = (uint64_t)((double)j * scale);
+            if (b >= buckets) b = buckets - 1;
+            t[b * part + __umul64hi(mix64(j), part)] = 7;
+        }
+    }
+}
+
+// The metadata refresh as part of the line that was fetched for the identities: 16 lanes read one random
+// aligned 128-byte line, then one of them stores 4 bytes -- into the SAME line (an interleaved
+// identities + metadata layout) or into a second array at the matching place (the two-tensor layout).
+template <bool SAME>
+__global__ void k_line_then_store4(long long *t, int *m, uint64_t n, uint64_t ops, long long *sink)
+{
+    long long a = 0;
+    const uint64_t tid = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x;
+    const uint64_t groups = ((uint64_t)gridDim.x * blockDim.x) >> 4;
+    const int r = tid & 15;
+    for (uint64_t i = tid >> 4; i < ops; i += groups * 4) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint64_t j = i + u * groups;
+            if (j < ops) {
+                const uint64_t s = __umul64hi(mix64(j), n - 32) & ~15ull;
+                const long long v = t[s + r];
+                a += v;
+                if (r == 15) {
+                    // the store depends on the value read, as a refresh depends on the match
+                    if (SAME) reinterpret_cast<int *>(&t[s + 15])[1] = (int)v | 7;
+                    else m[s + 15] = (int)v | 7;
+                }
+            }
+        }
+    }
+    if (a == 0x1234567) sink[0] = a;
+}
+
 __global__ void k_store4(int *t, uint64_t n, uint64_t ops)
 {
     for (uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; i < ops; i += (uint64_t)gridDim.x * blockDim.x)
@@ -172,8 +250,24 @@ int main(int argc, char **argv)
     report("random aligned 128-byte lines (16 lanes each)", (double)ops, 128.0);
     TIME((k_line<false><<<8192, 256>>>(t, n, ops, (long long *)c + 8)));
     report("random unaligned 128-byte windows (16 lanes each)", (double)ops, 128.0);
+    for (uint64_t buckets : {2048ull, 65536ull, 2097152ull}) {
+        char name[96];
+        TIME((k_line_bucketed<<<8192, 256>>>(t, n, ops, buckets, (long long *)c + 8)));
+        std::snprintf(name, sizeof name, "aligned 128-byte lines in address order, %llu parts", (unsigned long long)buckets);
+        report(name, (double)ops, 128.0);
+    }
+    TIME((k_line_then_store4<false><<<8192, 256>>>(t, m, n, ops, (long long *)c + 8)));
+    report("random line read + 4-byte store into a second array", (double)ops, 132.0);
+    TIME((k_line_then_store4<true><<<8192, 256>>>(t, m, n, ops, (long long *)c + 8)));
+    report("random line read + 4-byte store into the same line", (double)ops, 132.0);
     TIME((k_store4<<<8192, 256>>>(m, n, ops)));
     report("random 4-byte stores (one per lane)", (double)ops, 4.0);
+    for (uint64_t buckets : {2048ull, 65536ull, 2097152ull}) {
+        char name[96];
+        TIME((k_store4_bucketed<<<8192, 256>>>(m, n, ops, buckets)));
+        std::snprintf(name, sizeof name, "4-byte stores in address order, %llu parts", (unsigned long long)buckets);
+        report(name, (double)ops, 4.0);
+    }
     TIME((k_store4_nt<<<8192, 256>>>(m, n, ops)));
     report("random 4-byte non-temporal stores (one per lane)", (double)ops, 4.0);
     TIME((k_load_store4<<<8192, 256>>>(m, n, ops)));

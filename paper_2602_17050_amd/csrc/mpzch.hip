@@ -741,12 +741,43 @@ mpzch_status_t mpzch_gather_rows(const int64_t *slots, const int64_t *count_dev,
 mpzch_status_t mpzch_lookup_gather(const mpzch_table_t *t, const int64_t *identities,
                                    const int64_t *ids, int64_t n,
                                    const void *rows, int64_t num_rows, int64_t row_bytes, int64_t row_stride_bytes,
-                                   void *out_rows, int64_t *scratch_slots, uint8_t *out_found, void *stream)
+                                   void *out_rows, int64_t *out_slots, uint8_t *out_found, void *stream)
 {
-    if (n > 0 && !scratch_slots) return MPZCH_ERR_INVALID_ARG;
-    mpzch_status_t st = mpzch_lookup(t, identities, ids, n, scratch_slots, out_found, stream);
-    if (st != MPZCH_OK) return st;
-    return mpzch_gather_rows(scratch_slots, nullptr, n, rows, num_rows, row_bytes, row_stride_bytes, out_rows, stream);
+    if (!t || !identities) return MPZCH_ERR_INVALID_ARG;
+    if (n < 0 || n > MPZCH_MAX_BATCH) return MPZCH_ERR_INVALID_ARG;
+    if (!rows || num_rows < 1 || !out_rows) return MPZCH_ERR_INVALID_ARG;
+    const RowGeom g = row_geom(rows, row_bytes, row_stride_bytes, out_rows);
+    if (!g.ok || g.chunks > (1 << 20)) return MPZCH_ERR_INVALID_ARG;
+    if (n == 0) return MPZCH_OK;
+    if (!ids) return MPZCH_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    mpzch_table *mt = const_cast<mpzch_table *>(t);
+    TRY(mt->sc.query_device());
+    Params p;
+    std::memset(&p, 0, sizeof p);
+    p.ids = ids;
+    p.n = n;
+    p.num_tables = 1;
+    p.out_slots = out_slots;
+    p.out_found = out_found;
+    p.t0 = make_desc(t->cfg, const_cast<int64_t *>(identities), nullptr, 0, 0);
+    p.g_rows = (const char *)rows;
+    p.g_out = (char *)out_rows;
+    p.g_num_rows = num_rows;
+    p.g_stride = row_stride_bytes;
+    p.g_chunks = (int32_t)g.chunks;
+    p.g_wide = g.wide ? 1 : 0;
+    p.g_shift = -1;
+    for (int b = 0; b <= 20; ++b)
+        if (g.chunks == ((int64_t)1 << b)) p.g_shift = b;
+    const int grid = grid_for(n, kBlock, mt->sc.num_cus, discover_blocks_per_cu());
+    p.num_segs = grid * kWavesPerBlock;
+    p.seg_chunks = (int32_t)(((n + kWave - 1) / kWave + p.num_segs - 1) / p.num_segs);
+    if (!mt->tm.begin(KLookup, s)) return MPZCH_ERR_HIP;
+    hipLaunchKernelGGL(k_lookup_gather, dim3(grid), dim3(kBlock), 0, s, p);
+    LAUNCH_CHECK();
+    if (!mt->tm.end(s)) return MPZCH_ERR_HIP;
+    return MPZCH_OK;
 }
 
 mpzch_status_t mpzch_collect_delta(const mpzch_table_t *t, const int64_t *identities, const int32_t *metadata,

@@ -37,16 +37,18 @@
 
 namespace mpzch {
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
 constexpr int kWave = 64;
 constexpr int kBlock = 256;
 constexpr int kWavesPerBlock = kBlock / kWave;
 constexpr int kMaxTables = 64;
-constexpr int kStatCount = 8;
+constexpr int kStatCount = 9;
 constexpr int kLine = 16;              // identities per 128-byte line
 constexpr int kStage = 512;            // missed positions staged per wavefront before they are entered
 constexpr int kEvBuf = 256;            // evicted slots staged per wavefront before a flush
 
-enum Stat { kHitPos = 0, kMissPos, kDistinctMiss, kInserts, kEvictions, kCollisions, kInvalidPos, kHitProbeSum };
+enum Stat { kHitPos = 0, kMissPos, kDistinctMiss, kInserts, kEvictions, kCollisions, kInvalidPos, kHitProbeSum, kMissProbeSum };
 
 struct TableDesc {
     int64_t *I;            // identities
@@ -103,6 +105,14 @@ struct Params {
     const TableDesc *descs;        // device array [num_tables]
     const int64_t *offsets;        // device array [num_tables + 1]
     TableDesc t0;
+    // lookup fused with the embedding gather: out[pos, :] <- rows[slot mod num_rows, :]
+    const char *g_rows;
+    char *g_out;
+    int64_t g_num_rows;
+    int64_t g_stride;              // bytes between rows
+    int32_t g_chunks;              // 16-byte (g_wide) or 4-byte pieces per row
+    int32_t g_wide;
+    int32_t g_shift;               // log2(g_chunks) when that is a power of two, else -1
     // outputs
     int64_t *out_evicted;
     int64_t *out_num_evicted;
@@ -341,20 +351,24 @@ __device__ __forceinline__ void block_stat_row(const Params &p, StatRow *rows, i
 }
 
 // ------------------------------------------------------------------ Pass 1 (discovery)
-// One probe pass over the 64 ids held one per lane: the id of lane L is compared with the 16
-// slots of rounds [q, q + 16) of its window (q may be negative: rounds below 0 do not exist;
-// q >= d.P switches the lane off).  A 16-lane group serves one id per access, so with q chosen
-// such that home + q is a multiple of 16 slots every access reads exactly one 128-byte line.
-// All 16 accesses are issued before the first result is looked at; a lane without a slot to
-// look at re-reads the home slot (a valid address, same or neighbouring line; slot 0 if the
-// lane belongs to another table), so the loads carry no branch and stay in flight together.
-// d is wave-uniform.  Returns the round of the match, kProbeGoOn when the id is not among these
-// slots, or kProbeAbsent when in addition one of them is empty: a slot never becomes empty again
-// once it was occupied, so no resident id lies beyond an empty slot of its window and the search
-// can end there.
+// One probe pass over the 64 ids held one per lane: the id of lane L is compared with the G
+// slots of rounds [q, q + G) of its window (q may be negative: rounds below 0 do not exist;
+// q >= d.P switches the lane off).  A G-lane group serves one id per access, so with q chosen
+// such that home + q is a multiple of G slots every access reads one aligned block of 8 G bytes.
+// All G accesses are issued before the first result is looked at; a lane without a slot to
+// look at re-reads the home slot (a valid address, same or neighbouring line; slot 0 if the id
+// is switched off or belongs to another table), so the loads carry no branch and stay in flight
+// together.  d is wave-uniform.  Returns the round of the match; kProbeGoOn when the id is not among
+// these slots; or, when in addition one of them is empty, a value <= kProbeAbsent that names the round
+// of the first empty slot (probe_absent / absent_len): a slot never becomes empty again once it was
+// occupied, so no resident id lies beyond an empty slot of its window and the search can end there.
 constexpr int kFirstG = 8;             // slots looked at by the first pass: the aligned 64 bytes that hold the home slot
 constexpr int kProbeGoOn = -1;
 constexpr int kProbeAbsent = -2;
+
+__device__ __forceinline__ int probe_absent(int empty_round) { return kProbeAbsent - empty_round; }
+// slots of the window read until the search ended: up to and including the first empty one
+__device__ __forceinline__ int absent_len(int code) { return -code - 1; }
 
 template <int G>
 __device__ __forceinline__ int probe_pass(const Tab &d, int64_t id, int64_t home, int q)
@@ -368,10 +382,13 @@ __device__ __forceinline__ int probe_pass(const Tab &d, int64_t id, int64_t home
     for (int t = 0; t < G; ++t) {
         const int src = t * IPI + g;
         const int64_t ghome = shfl64(home, src);
-        const int round = __shfl(q, src) + r;
+        const int gq = __shfl(q, src);
+        const int round = gq + r;
         const bool act = round >= 0 && round < d.P;
-        // inactive lanes may carry the home slot of another (larger) table: keep the address inside d
-        v[t] = d.I[act ? wrap(ghome + round, d.N) : (ghome < d.N ? ghome : 0)];
+        // lanes without a slot: the home slot when their id is being probed (the line is fetched anyway),
+        // else slot 0 (ids that are switched off share one line; the home slot of another, larger table
+        // would not be a valid address here)
+        v[t] = d.I[act ? wrap(ghome + round, d.N) : ((gq < d.P && ghome < d.N) ? ghome : 0)];
         act_bits |= (uint32_t)act << t;
     }
     int found = kProbeGoOn;
@@ -382,24 +399,78 @@ __device__ __forceinline__ int probe_pass(const Tab &d, int64_t id, int64_t home
         const int gq = __shfl(q, src);         // shuffles stay outside conditionals: every lane must take part
         const bool act = (act_bits >> t) & 1u;
         const int first = group_first<G>(__ballot(act && v[t] == gid), g);
-        const bool empty = group_first<G>(__ballot(act && v[t] == -1), g) >= 0;
-        const int got = __shfl(first >= 0 ? gq + first : (empty ? kProbeAbsent : kProbeGoOn), (lane % IPI) * G);
+        const int efirst = group_first<G>(__ballot(act && v[t] == -1), g);
+        const int got = __shfl(first >= 0 ? gq + first : (efirst >= 0 ? probe_absent(gq + efirst) : kProbeGoOn), (lane % IPI) * G);
         if (lane / IPI == t) found = got;
     }
     return found;
 }
 
+// out[pos, :] <- rows[slot mod num_rows, :] for the positions of the active lanes (Sec. 3.7: the lookup
+// fused with the embedding gather).  The 64 rows are copied by the whole wavefront, consecutive lanes
+// moving consecutive 16-byte (or 4-byte) pieces of a row, several loads in flight per lane.
+template <typename VEC>
+__device__ __forceinline__ void gather_rows_wave(const Params &p, uint64_t am, int64_t pos, int64_t row)
+{
+    constexpr int U = 4;
+    const int lane = lane_id();
+    const int C = p.g_chunks;
+    const int total = kWave * C;
+    for (int i0 = 0; i0 < total; i0 += kWave * U) {
+        VEC v[U];
+        int64_t dst[U];
+        bool ok[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int idx = i0 + u * kWave + lane;
+            const bool in = idx < total;
+            const int src = in ? (p.g_shift >= 0 ? idx >> p.g_shift : idx / C) : 0;
+            const int c = idx - src * C;
+            const int64_t srow = shfl64(row, src);
+            const int64_t spos = shfl64(pos, src);
+            ok[u] = in && ((am >> src) & 1ull);
+            dst[u] = spos * C + c;
+            v[u] = VEC(0);
+            if (ok[u]) v[u] = reinterpret_cast<const VEC *>(p.g_rows + srow * p.g_stride)[c];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (ok[u]) __builtin_nontemporal_store(v[u], reinterpret_cast<VEC *>(p.g_out) + dst[u]);
+    }
+}
+
+__device__ __forceinline__ void gather_wave(const Params &p, bool active, int64_t pos, int64_t slot)
+{
+    const uint64_t am = __ballot(active);
+    if (!am) return;
+    int64_t row = active ? slot : 0;
+    if (row >= p.g_num_rows) row %= p.g_num_rows;
+    if (p.g_wide) gather_rows_wave<u32x4>(p, am, pos, row);
+    else gather_rows_wave<uint32_t>(p, am, pos, row);
+}
+
 // Every wavefront owns one segment of positions.  Per 64-position chunk it probes the line that
 // holds each id's home slot.  Ids that were not found there but whose window goes on are parked
-// in LDS (position, home, next round) and resolved later, 64 at a time, so that the second
+// in LDS (position, next round) and resolved later, 64 at a time, so that the second
 // memory round trip is paid once per 64 parked ids instead of once per chunk.  What remains
 // unfound is the segment's miss list.
-template <bool TRAIN, bool MULTI>
+//
+// Input de-duplication in LDS (Sec. 3.6): every wavefront keeps a small direct-mapped cache of the
+// ids it has resolved (id -> probe result).  A position whose id is in the cache takes the cached
+// result: no access to the table and no second metadata store.  Copies of an id inside one chunk
+// elect one lane through the same cache entry; the others take that lane's result.  Skew is what
+// this serves: the hot ids of a Zipf stream occur in every chunk, and without it every copy is a
+// request to the same line, queued behind the others at one channel of the cache.
+constexpr int kCache = 256;                     // entries per wavefront
+constexpr int32_t kCachePending = 0x40000000;   // values from here on: not resolved (pending + electing lane)
+
+template <bool TRAIN, bool MULTI, bool GATHER>
 __device__ __forceinline__ void discover_body(const Params &p)
 {
     __shared__ uint32_t s_pos[kWavesPerBlock][kStage];
-    __shared__ int64_t s_home[kWavesPerBlock][kStage];
-    __shared__ int32_t s_q[kWavesPerBlock][kStage];
+    __shared__ int32_t s_q[kWavesPerBlock][kStage];      // > 0: next round to look at; < 0: absent, -(slots read)
+    __shared__ int64_t c_id[kWavesPerBlock][kCache];
+    __shared__ int32_t c_val[kWavesPerBlock][kCache];
     __shared__ unsigned long long s_red[kWavesPerBlock][kStatCount];
     __shared__ int s_tab[kWavesPerBlock];
 
@@ -414,35 +485,46 @@ __device__ __forceinline__ void discover_body(const Params &p)
     const bool want_stats = TRAIN && p.out_stats != nullptr;
 
     // per-lane counters of the table currently being processed
-    unsigned long long st_hit = 0, st_miss = 0, st_inv = 0, st_probe = 0;
+    unsigned long long st_hit = 0, st_miss = 0, st_inv = 0, st_probe = 0, st_mlen = 0;
     int st_table = 0;
     int staged = 0, flushed = 0;                 // wave-uniform: parked ids in LDS / misses already listed
+    int cache_table = 0;                         // wave-uniform: the table the cached ids belong to
+
+    auto cache_clear = [&]() {
+        for (int i = lane; i < kCache; i += kWave) c_id[w][i] = -1;          // no valid id is negative
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    };
+    cache_clear();
 
     // counters are kept for one table at a time
     auto stats_table = [&](int f) {
         if (!want_stats || f == st_table) return;
         // table changed inside this wavefront's range (rare): hand the counters over
-        const unsigned long long a = wave_sum(st_hit), b = wave_sum(st_miss), x = wave_sum(st_inv), y = wave_sum(st_probe);
+        const unsigned long long a = wave_sum(st_hit), b = wave_sum(st_miss), x = wave_sum(st_inv), y = wave_sum(st_probe),
+                                 z = wave_sum(st_mlen);
         if (lane == 0) {
             if (a) atomicAdd(&p.ctl->stats[st_table][kHitPos], a);
             if (b) atomicAdd(&p.ctl->stats[st_table][kMissPos], b);
             if (x) atomicAdd(&p.ctl->stats[st_table][kInvalidPos], x);
             if (y) atomicAdd(&p.ctl->stats[st_table][kHitProbeSum], y);
+            if (z) atomicAdd(&p.ctl->stats[st_table][kMissProbeSum], z);
         }
-        st_hit = st_miss = st_inv = st_probe = 0;
+        st_hit = st_miss = st_inv = st_probe = st_mlen = 0;
         st_table = f;
     };
-    // a position whose id is resident at `dist` probes from home
+    // a position whose id is resident at `dist` probes from home.  refresh: this position writes the
+    // metadata ("Update"); copies served from the cache need not, another position of this wavefront has
+    // stored the same value -- unless copies may carry different expiry steps.
     // (the first pass stores the outputs of its whole chunk itself: emit = false)
-    auto finish_hit = [&](const Tab &d, int64_t pos, int64_t home, int dist, bool emit) {
+    auto finish_hit = [&](const Tab &d, int64_t pos, int64_t home, int dist, bool emit, bool refresh) {
         const int64_t slot = wrap(home + dist, d.N);
         if (TRAIN) {
-            store_meta(d, slot, meta_value(p, d, pos));   // "Update": refresh the resident's metadata
+            if (refresh || (d.evict == 3 && p.ttls)) store_meta(d, slot, meta_value(p, d, pos));
             st_hit++;
             st_probe += (unsigned long long)(dist + 1);
         }
         if (emit) {
-            p.out_slots[pos] = slot;
+            if (!GATHER || p.out_slots) p.out_slots[pos] = slot;
             if (!TRAIN && p.out_found) p.out_found[pos] = 1;
         }
     };
@@ -455,8 +537,7 @@ __device__ __forceinline__ void discover_body(const Params &p)
         for (int e0 = 0; e0 < staged; e0 += kWave) {
             const bool have = e0 + lane < staged;
             const uint32_t pos = have ? s_pos[w][e0 + lane] : 0;
-            const int64_t home = have ? s_home[w][e0 + lane] : 0;
-            int q = have ? s_q[w][e0 + lane] : 0;
+            const int q0 = have ? s_q[w][e0 + lane] : 0;
             const int64_t id = have ? p.ids[pos] : -1;
             const int f = (have && multi) ? find_table(p.offsets, p.num_tables, (int64_t)pos) : 0;
             bool todo = have;
@@ -465,29 +546,31 @@ __device__ __forceinline__ void discover_body(const Params &p)
                 const bool mine = todo && f == f0;
                 const Tab d = view(multi ? p.descs[f0] : p.t0);
                 stats_table(f0);
+                const int64_t home = mine ? home_slot(id, d.seed, d.N) : 0;
                 int dist = -1;
+                int mlen = q0 < 0 ? -q0 : 0;                // > 0: the search has ended at an empty slot
+                int q = q0 > 0 ? q0 : d.P;
                 for (;;) {
-                    const bool need = mine && dist < 0 && q < d.P;
+                    const bool need = mine && dist < 0 && mlen == 0 && q < d.P;
                     if (!__any(need)) break;
-                    const int got = probe_pass<kLine>(d, id, mine ? home : 0, need ? q : d.P);
+                    const int got = probe_pass<kLine>(d, id, home, need ? q : d.P);
                     if (need) {
                         if (got >= 0) dist = got;
-                        else if (got == kProbeAbsent) q = d.P;      // an empty slot ends the search
+                        else if (got <= kProbeAbsent) mlen = absent_len(got);   // an empty slot ends the search
                         else q += kLine;
                     }
                 }
-                if (mine && dist >= 0) finish_hit(d, (int64_t)pos, home, dist, true);
+                if (mine && dist >= 0) finish_hit(d, (int64_t)pos, home, dist, true, true);
                 const bool miss = mine && dist < 0;
                 const uint64_t mb = __ballot(miss);
-                if (miss) {
-                    if (TRAIN) {
-                        const int at = nmiss + __popcll(mb & ((1ull << lane) - 1ull));      // slots already consumed
-                        s_pos[w][at] = pos;
-                        s_home[w][at] = home;
-                        st_miss++;
-                    }
-                    // lookup: the first pass has already stored home and "not found"
+                if (miss && TRAIN) {
+                    const int at = nmiss + __popcll(mb & ((1ull << lane) - 1ull));      // slots already consumed
+                    s_pos[w][at] = pos;
+                    st_miss++;
+                    st_mlen += (unsigned long long)(mlen ? mlen : d.P);
                 }
+                // lookup: the first pass has already stored home and "not found"
+                if (GATHER) gather_wave(p, mine, (int64_t)pos, dist >= 0 ? wrap(home + dist, d.N) : home);
                 nmiss += __popcll(mb);
                 todo = todo && !mine;
             }
@@ -496,12 +579,20 @@ __device__ __forceinline__ void discover_body(const Params &p)
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             for (int j = lane; j < nmiss; j += kWave) {
                 const uint32_t pos = s_pos[w][j];
+                const int64_t id = p.ids[pos];
                 uint64_t sb, ss;
                 set_region(p, (int64_t)pos, sb, ss);
-                const uint32_t e = set_insert(p, p.ids[pos], pos, sb, ss);
+                const uint32_t e = set_insert(p, id, pos, sb, ss);
+                int64_t home;
+                if (multi) {
+                    const TableDesc &td = p.descs[find_table(p.offsets, p.num_tables, (int64_t)pos)];
+                    home = home_slot(id, td.seed, td.N);
+                } else {
+                    home = home_slot(id, p.t0.seed, p.t0.N);
+                }
                 p.list[seg_base + flushed + j] = pos;
                 p.ent[seg_base + flushed + j] = e;
-                p.homes[seg_base + flushed + j] = s_home[w][j];
+                p.homes[seg_base + flushed + j] = home;
             }
             flushed += nmiss;
         }
@@ -535,37 +626,64 @@ __device__ __forceinline__ void discover_body(const Params &p)
                 if (seg_hi <= first_pos) seg_hi = first_pos + 1;
                 d = view(p.descs[f]);
                 mine = todo && pos < seg_hi;
+                if (f != cache_table) {                   // the cached ids belong to the previous table
+                    cache_clear();
+                    cache_table = f;
+                }
             } else {
                 d = view(p.t0);
             }
             stats_table(f);
 
             const bool valid = mine && id >= 0;
-            const int64_t home = mine ? home_slot(id, d.seed, d.N) : 0;
+            const uint64_t hsh = mix64((uint64_t)id ^ d.seed);
+            const int64_t home = mine ? (int64_t)__umul64hi(hsh, (uint64_t)d.N) : 0;
+            // the cache: a resolved copy of this id, or an election among the copies in this chunk
+            const int ci = (int)(hsh & (uint64_t)(kCache - 1));
+            bool cached = false;
+            int res = kProbeGoOn;
+            if (valid) {
+                const int32_t ev = c_val[w][ci];
+                if (c_id[w][ci] == id && ev < kCachePending) { cached = true; res = ev; }
+            }
+            const bool cand = valid && !cached;
+            if (cand) c_id[w][ci] = id;                   // one id per entry survives
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            const bool grp = cand && c_id[w][ci] == id;   // the copies of the surviving id
+            if (grp) c_val[w][ci] = kCachePending + lane; // one of them survives: the elected lane
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            const int owner = grp ? c_val[w][ci] - kCachePending : lane;
+            const bool leader = cand && owner == lane;    // elected, or an id that lost its entry to another
             // first pass: the line that holds the home slot
             const int o = (int)((home + (int64_t)(((uintptr_t)d.I >> 3) & (kFirstG - 1))) & (kFirstG - 1));
-            const int dist = probe_pass<kFirstG>(d, id, home, valid ? -o : d.P);
-            const bool hit = valid && dist >= 0;
-            if (hit) finish_hit(d, pos, home, dist, false);
+            int got = probe_pass<kFirstG>(d, id, home, leader ? -o : d.P);
+            if (got == kProbeGoOn && kFirstG - o >= d.P) got = probe_absent(d.P - 1);    // the whole window was read
+            const int lgot = __shfl(got, owner);
+            if (cand) res = leader ? got : lgot;
+            if (grp && leader && res != kProbeGoOn) c_val[w][ci] = res;                  // resolved: later chunks reuse it
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            const bool hit = valid && res >= 0;
+            if (hit) finish_hit(d, pos, home, res, false, leader);
             else if (TRAIN && mine && !valid) st_inv++;
             // One store for the whole chunk keeps the 64-byte sectors of the outputs complete (a
             // sector written with holes leaves the cache as narrow writes).  A position that is
             // not decided yet gets its home slot: final for a negative id (home of its bit
             // pattern) and for a lookup miss, rewritten later otherwise.
+            const int64_t slot = hit ? wrap(home + res, d.N) : home;
             if (mine) {
-                p.out_slots[pos] = hit ? wrap(home + dist, d.N) : home;
+                if (!GATHER || p.out_slots) p.out_slots[pos] = slot;
                 if (!TRAIN && p.out_found) p.out_found[pos] = hit ? 1 : 0;
             }
-            // not found so far: parked (its window may go on, or it is a miss)
-            const bool park = valid && dist < 0;
+            // not found so far: parked when its window goes on, or (training) to be listed as a miss
+            const bool park = valid && (res == kProbeGoOn || (TRAIN && res <= kProbeAbsent));
             const uint64_t pb = __ballot(park);
             if (park) {
                 const int at = staged + __popcll(pb & ((1ull << lane) - 1ull));
                 s_pos[w][at] = (uint32_t)pos;
-                s_home[w][at] = home;
-                s_q[w][at] = dist == kProbeAbsent ? d.P : kFirstG - o;  // d.P: nothing left to look at
+                s_q[w][at] = res <= kProbeAbsent ? -absent_len(res) : kFirstG - o;
             }
             staged += __popcll(pb);
+            if (GATHER) gather_wave(p, mine && !park, pos, slot);
             todo = todo && !mine;
         }
         if (staged > kStage - kWave) resolve_stage();
@@ -573,35 +691,40 @@ __device__ __forceinline__ void discover_body(const Params &p)
     resolve_stage();
     if (TRAIN && lane == 0 && seg < p.num_segs) p.seg_cnt[seg] = (uint32_t)flushed;
     if (want_stats) {
-        const int idx[4] = {kHitPos, kMissPos, kInvalidPos, kHitProbeSum};
-        const unsigned long long vals[4] = {st_hit, st_miss, st_inv, st_probe};
-        block_stat_row(p, p.rows_a, p.blocks_a, idx, vals, 4, st_table, s_red, s_tab);
+        const int idx[5] = {kHitPos, kMissPos, kInvalidPos, kHitProbeSum, kMissProbeSum};
+        const unsigned long long vals[5] = {st_hit, st_miss, st_inv, st_probe, st_mlen};
+        block_stat_row(p, p.rows_a, p.blocks_a, idx, vals, 5, st_table, s_red, s_tab);
     }
 }
 
-// Four kernels around the one body, each compiled for the number of wavefronts per SIMD that
+// The kernels around the one body, each compiled for the number of wavefronts per SIMD that
 // measured best: the training pass over one table is bound by its metadata stores and does not
 // gain from more wavefronts than two; the read-only lookup hides its load latency with four; with
 // several tables the chunk's table is looked up before its ids can be hashed (a chain of
 // dependent loads), which three wavefronts (training) or four (lookup) hide better.
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_discover(Params p)
 {
-    discover_body<true, false>(p);
+    discover_body<true, false, false>(p);
 }
 
 __global__ __launch_bounds__(kBlock, 4) void k_lookup(Params p)
 {
-    discover_body<false, false>(p);
+    discover_body<false, false, false>(p);
+}
+
+__global__ __launch_bounds__(kBlock, 2) void k_lookup_gather(Params p)
+{
+    discover_body<false, false, true>(p);
 }
 
 __global__ __launch_bounds__(kBlock, 3) void k_discover_tables(Params p)
 {
-    discover_body<true, true>(p);
+    discover_body<true, true, false>(p);
 }
 
 __global__ __launch_bounds__(kBlock, 4) void k_lookup_tables(Params p)
 {
-    discover_body<false, true>(p);
+    discover_body<false, true, false>(p);
 }
 
 // ------------------------------------------------------------------ allocation
@@ -1423,7 +1546,6 @@ __global__ __launch_bounds__(kBlock) void k_fill32(int32_t *dst, int64_t count, 
 
 // rows[(slots[k] mod num_rows)] <- init (or zero bits).  One thread per VEC-byte chunk of a row,
 // so a row is written by consecutive lanes with full-width stores.
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 template <typename VEC>
 __global__ __launch_bounds__(kBlock) void k_reset_rows(const int64_t *slots, const int64_t *count_dev, int64_t cap,

@@ -35,25 +35,76 @@ def test_reset_rows_multi_resets_weights_and_optimizer_state_in_one_launch():
 
 
 def test_lookup_gather_returns_the_rows_of_the_looked_up_slots():
+    """One kernel resolves the slots and copies the rows (Sec. 3.7); the slots themselves are an optional output."""
     p = Pair(50_000, 16, 3, True, 77)
     rng = np.random.Generator(np.random.Philox(key=11))
     for step in range(4):
         p.step(wl.zipf_ids(rng, 20_000, 1.05, 60_000), step, check_state=False)
-    for dim, dtype in ((32, torch.float32), (128, torch.bfloat16), (3, torch.float32)):
-        rows_np = wl.embedding_pattern(20_000, dim, np.float32)           # fewer rows than slots
+    cases = ((32, torch.float32, 20_000), (128, torch.bfloat16, 20_000), (3, torch.float32, 20_000),
+             (1, torch.float32, 50_000), (40, torch.float32, 7), (256, torch.float32, 50_000))
+    for k, (dim, dtype, nrows) in enumerate(cases):
+        rows_np = wl.embedding_pattern(nrows, dim, np.float32)            # mostly fewer rows than slots
         rows = torch.from_numpy(rows_np).cuda().to(dtype)
-        q = np.concatenate([wl.zipf_ids(rng, 5000, 1.05, 60_000), rng.integers(-3, 1 << 40, size=500)])
+        q = np.concatenate([wl.zipf_ids(rng, 5000 + 37 * k, 1.05, 60_000), rng.integers(-3, 1 << 40, size=500)])
+        q = q[rng.permutation(len(q))]
         ids = torch.from_numpy(q).cuda()
-        out = torch.empty((len(q), dim), dtype=dtype, device="cuda")
-        slots = torch.empty(len(q), dtype=torch.int64, device="cuda")
-        found = torch.empty(len(q), dtype=torch.uint8, device="cuda")
+        out = torch.full((len(q), dim), -1, dtype=dtype, device="cuda")
+        slots = torch.empty(len(q), dtype=torch.int64, device="cuda") if k % 2 == 0 else None
+        found = torch.empty(len(q), dtype=torch.uint8, device="cuda") if k % 3 != 2 else None
+        say("lookup_gather", dim, dtype, nrows)
         mp.mpzch_lookup_gather(p.g.handle, p.g.identities, ids, rows, out, slots, found)
         torch.cuda.synchronize()
         so, fo = p.o.lookup(q)
-        assert np.array_equal(slots.cpu().numpy(), so) and np.array_equal(found.cpu().numpy(), fo)
+        if slots is not None:
+            assert np.array_equal(slots.cpu().numpy(), so)
+        if found is not None:
+            assert np.array_equal(found.cpu().numpy(), fo)
         want = oracle.gather_rows(so, rows.float().cpu().numpy())
         assert np.array_equal(out.float().cpu().numpy(), want)
+    # rows with a stride: a view of every second column block
+    wide = torch.from_numpy(wl.embedding_pattern(20_000, 64, np.float32)).cuda()
+    view = wide[:, :32]
+    q = wl.zipf_ids(rng, 3000, 1.05, 60_000)
+    out = torch.empty((len(q), 32), dtype=torch.float32, device="cuda")
+    mp.mpzch_lookup_gather(p.g.handle, p.g.identities, torch.from_numpy(q).cuda(), view, out)
+    torch.cuda.synchronize()
+    so, _ = p.o.lookup(q)
+    assert np.array_equal(out.cpu().numpy(), oracle.gather_rows(so, wide.cpu().numpy()[:, :32]))
     p.close()
+
+
+def test_lookup_gather_at_the_size_of_the_inference_configuration():
+    """1 M ids against a 100 M-slot table 80 % full (max_probe 32), rows of 128 bf16 values: a sample of the
+    output rows is compared with the oracle's lookup + gather; the whole output with mpzch_lookup + torch indexing."""
+    n_slots, batch = 100_000_000, 1_000_000
+    spec = wl.c3_spec(n_slots)
+    n_res = int(0.8 * n_slots)
+    g = mp.MpzchTable(n_slots, spec.max_probe, mp.EVICT_NONE, 0, spec.hash_seed, max_batch=1 << 22)
+    chunk = 1 << 22
+    tmp = torch.empty(chunk, dtype=torch.int64, device="cuda")
+    for lo in range(0, n_res, chunk):
+        hi = min(lo + chunk, n_res)
+        g.remap(torch.from_numpy(wl.c3_prefill_ids(lo, hi)).cuda(), 0, tmp[: hi - lo])
+    num_rows = 10_000_000
+    rows = (torch.arange(num_rows * 128, dtype=torch.int32, device="cuda") % 30011).to(torch.bfloat16).view(num_rows, 128)
+    q = wl.c3_batch(3, batch, n_res)
+    ids = torch.from_numpy(q).cuda()
+    out = torch.empty((batch, 128), dtype=torch.bfloat16, device="cuda")
+    found = torch.empty(batch, dtype=torch.uint8, device="cuda")
+    mp.mpzch_lookup_gather(g.handle, g.identities, ids, rows, out, None, found)
+    sl, fd = g.lookup(ids)
+    torch.cuda.synchronize()
+    assert torch.equal(fd, found)
+    assert torch.equal(out, rows[sl % num_rows])
+    # the oracle on a sample of the positions, from a host copy of the identities
+    o = oracle.Table(n_slots, spec.max_probe, oracle.EVICT_NONE, 0, spec.hash_seed, g.identities.cpu().numpy(),
+                     np.zeros(n_slots, np.int32))
+    pos = np.sort(np.random.default_rng(5).integers(0, batch, size=50_000))
+    so, fo = o.lookup(q[pos])
+    pos_t = torch.from_numpy(pos).cuda()
+    assert np.array_equal(found[pos_t].cpu().numpy(), fo)
+    assert torch.equal(out[pos_t], rows[torch.from_numpy(so % num_rows).cuda()])
+    g.close()
 
 
 def test_streaming_delta_brings_an_inference_copy_up_to_date():

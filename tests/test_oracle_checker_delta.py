@@ -179,3 +179,25 @@ def test_remap_jagged_by_hand():
     out, evs, sts = oracle.remap_jagged([t0, t1, t2], [x, x], [0, 1, 1, 2], 2)
     assert out.tolist() == [2, 2] and sts[0]["hit_pos"] == 1 and sts[2]["hit_pos"] == 1
     assert t0.metadata[2] == 2 and t2.metadata[2] == 2 and t2.metadata[4] == 1
+
+
+# ---------------------------------------------------------------- the probe-length counters
+def test_probe_length_counters_by_hand():
+    """hit_probe_sum: slots from home up to the resident, per hit position; miss_probe_sum: slots a
+    search for an absent id has to read -- up to and including the first empty slot of its range,
+    or the whole range -- per miss position (the algorithmic bytes of Pass 1 are 8 x these)."""
+    seed, n = 41, 16
+    a, b, c, e = ids_with_home(5, seed, n, 4)
+    d = ids_with_home(9, seed, n, 1)[0]
+    t = oracle.Table(n, 4, oracle.EVICT_NONE, 0, seed)
+    r = t.remap([a, b], 1)                                       # a -> 5, b -> 6; both searched an empty table
+    assert r.slots.tolist() == [5, 6] and r.stats["miss_probe_sum"] == 1 + 1 and r.stats["hit_probe_sum"] == 0
+    r = t.remap([c, d, c, b, a], 2)                              # c: 5, 6 taken, 7 empty -> 3 (twice); d: 1
+    assert r.slots.tolist() == [7, 9, 7, 6, 5]
+    assert r.stats["miss_probe_sum"] == 3 + 1 + 3 and r.stats["miss_pos"] == 3
+    assert r.stats["hit_probe_sum"] == 2 + 1 and r.stats["hit_pos"] == 2
+    f = ids_with_home(5, seed, n, 5)[4]
+    r = t.remap([e], 3)                                          # 5, 6, 7 taken, 8 empty -> 4, placed at 8
+    assert r.slots[0] == 8 and r.stats["miss_probe_sum"] == 4
+    r = t.remap([f], 4)                                          # range 5..8 full: the whole range, then Case 3
+    assert r.slots[0] == 5 and r.stats["miss_probe_sum"] == 4 and r.stats["collisions"] == 1
