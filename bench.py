@@ -70,6 +70,8 @@ def main():
     ap.add_argument("--all-kernel-timing", action="store_true",
                     help="bracket every kernel with events (a breakdown; costs a step some 30 us), not only Pass 1")
     ap.add_argument("--policy", default="ttl", choices=["ttl", "lru"], help="eviction policy (headline / c4 workloads)")
+    ap.add_argument("--graph", action="store_true",
+                    help="c1 / c2: capture the timed steps into one HIP graph and time its replay (no launch overhead on the host)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build runs on ONE GPU (a table shard and every operation on it are local to its GPU). "
@@ -371,16 +373,38 @@ def bench_small_table(args, np, torch, mp, wl, dev):
     for (s, b), o in list(zip(batches, outs))[:W]:
         g.remap(b, s, o)
     torch.cuda.synchronize()
-    if not args.no_kernel_timing:
-        # two event records per launch: every kernel costs these small steps some 30 us, Pass 1 alone a few
-        mp.mpzch_set_kernel_timing(g.handle, 1 if args.all_kernel_timing else 2)
-    t0 = time.perf_counter()
-    for (s, b), o in list(zip(batches, outs))[W:]:
-        g.remap(b, s, o)
-        g.reset_rows(emb)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ktimes = {} if args.no_kernel_timing else mp.mpzch_kernel_times(g.handle)
+    if args.graph:
+        # the timed steps as one captured graph: the table state before the capture is restored before the
+        # timed replay (a capture only records, but the warm-up replay below runs the steps once)
+        I0, M0 = g.identities.clone(), g.metadata.clone()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for (s, b), o in list(zip(batches, outs))[W:]:
+                g.remap(b, s, o)
+                g.reset_rows(emb)
+        graph.replay()
+        torch.cuda.synchronize()
+        g.identities.copy_(I0)
+        g.metadata.copy_(M0)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        graph.replay()
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        ktimes = {}
+    else:
+        if not args.no_kernel_timing:
+            # two event records per launch: every kernel costs these small steps some 30 us, Pass 1 alone a few
+            mp.mpzch_set_kernel_timing(g.handle, 1 if args.all_kernel_timing else 2)
+        t0 = time.perf_counter()
+        for (s, b), o in list(zip(batches, outs))[W:]:
+            g.remap(b, s, o)
+            g.reset_rows(emb)
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        ktimes = {} if args.no_kernel_timing else mp.mpzch_kernel_times(g.handle)
     K = len(batches) - W
     total = sum(b.numel() for _, b in batches[W:])
     cpu = None

@@ -344,9 +344,9 @@ mpzch_status_t launch_remap(Scratch &sc, Timing &tm, Params p, int32_t max_p, in
     p.rows_b = sc.rows_b;
     p.ctl = sc.ctl;
 
+    const int64_t num_chunks = (p.n + kWave - 1) / kWave;
     // k_discover: every wavefront owns one segment of seg_chunks 64-position chunks
     const int g_disc = grid_for(p.n, kBlock, sc.num_cus, discover_blocks_per_cu());
-    const int64_t num_chunks = (p.n + kWave - 1) / kWave;
     p.num_segs = g_disc * kWavesPerBlock;
     p.seg_chunks = (int32_t)((num_chunks + p.num_segs - 1) / p.num_segs);
     // the other kernels walk the segments' miss lists, one segment per wavefront pass

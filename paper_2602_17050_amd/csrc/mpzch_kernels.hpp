@@ -812,22 +812,21 @@ struct TabWords {
     int32_t P, ttl, evict, pad_;
 };
 
+// One wavefront serves the segments vblock, vblock + vgrid, ...; s_I and s_d are that wavefront's own
+// areas of LDS (s_d only with several tables).
 template <int PMAX, bool MULTI>
-__global__ __launch_bounds__(kWave) void k_allocate(Params p)
+__device__ __forceinline__ void allocate_body(const Params &p, int64_t vblock, int64_t vgrid,
+                                              int64_t (*s_I)[PMAX + 1], TabWords *s_d)
 {
     constexpr int G = PMAX < kLine ? PMAX : kLine;   // lanes that read one claimant's window together
     constexpr int APL = kWave / G;                   // claimants served by one load instruction
     constexpr int CH = PMAX / G;                     // load instructions per claimant
     constexpr int NT = kWave / APL;
-    // what a lane needs to know of a slot: -1 empty, a claim tag (<= -2), 1 = holds an expired id,
-    // 0 = holds a live id
-    __shared__ int64_t s_I[kWave][PMAX + 1];         // +1: rows fall into different banks
-    __shared__ TabWords s_d[MULTI ? kWave : 1];      // every lane's table, for the lanes that load for it
 
-    const int lane = threadIdx.x;
+    const int lane = lane_id();
     const int g = lane / G, r = lane % G;
     const Tab d0 = view(p.t0);
-    for (int64_t seg = blockIdx.x; seg < p.num_segs; seg += gridDim.x) {
+    for (int64_t seg = vblock; seg < p.num_segs; seg += vgrid) {
         const uint32_t cnt = p.seg_cnt[seg];
         const int64_t seg_base = seg * p.seg_chunks * kWave;
         if (seg_base >= p.n) break;                           // segments past the batch hold nothing
@@ -950,6 +949,16 @@ __global__ __launch_bounds__(kWave) void k_allocate(Params p)
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         }
     }
+}
+
+// What a lane needs to know of a slot in s_I: -1 empty, a claim tag (<= -2), 1 = holds an expired id,
+// 0 = holds a live id.  (+1 column: rows fall into different banks.)
+template <int PMAX, bool MULTI>
+__global__ __launch_bounds__(kWave) void k_allocate(Params p)
+{
+    __shared__ int64_t s_I[kWave][PMAX + 1];
+    __shared__ TabWords s_d[MULTI ? kWave : 1];      // every lane's table, for the lanes that load for it
+    allocate_body<PMAX, MULTI>(p, blockIdx.x, gridDim.x, s_I, s_d);
 }
 
 // ------------------------------------------------------------------ allocation, LRU policy
@@ -1358,7 +1367,7 @@ __device__ __forceinline__ void finalize_epilogue(const Params &p, FinalizeState
     }
 }
 
-__global__ __launch_bounds__(kBlock) void k_finalize(Params p)
+__device__ __forceinline__ void finalize_body(const Params &p)
 {
     __shared__ int64_t s_ev[kWavesPerBlock][kEvBuf];
     __shared__ unsigned long long s_red[kWavesPerBlock][kStatCount];
@@ -1452,8 +1461,13 @@ __global__ __launch_bounds__(kBlock) void k_finalize(Params p)
     finalize_epilogue(p, fs, s_ev, s_cnt, s_tab, &s_base, s_red, want_stats);
 }
 
+__global__ __launch_bounds__(kBlock) void k_finalize(Params p)
+{
+    finalize_body(p);
+}
+
 // ------------------------------------------------------------------ duplicates, cleanup, counters
-__global__ __launch_bounds__(kBlock) void k_emit_dups(Params p)
+__device__ __forceinline__ void emit_dups_body(const Params &p)
 {
     __shared__ unsigned long long s_bins[kMaxTables][kStatCount];
     __shared__ bool s_last;
@@ -1529,6 +1543,11 @@ __global__ __launch_bounds__(kBlock) void k_emit_dups(Params p)
     __syncthreads();
     unsigned long long *z = reinterpret_cast<unsigned long long *>(p.ctl);
     for (int i = threadIdx.x; i < (int)(sizeof(Control) / sizeof(unsigned long long)); i += kBlock) z[i] = 0ull;
+}
+
+__global__ __launch_bounds__(kBlock) void k_emit_dups(Params p)
+{
+    emit_dups_body(p);
 }
 
 // ------------------------------------------------------------------ fills and row reset
