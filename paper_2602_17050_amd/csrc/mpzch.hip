@@ -23,8 +23,8 @@ struct TableCfg {
 };
 
 // ---- per-kernel timing --------------------------------------------------------------------
-enum KernelId { KDiscover = 0, KAllocate, KFinalize, KEmitDups, KLookup, KernelCount };
-const char *const kKernelNames[KernelCount] = {"k_discover", "k_allocate", "k_finalize", "k_emit_dups", "k_lookup"};
+enum KernelId { KDiscover = 0, KAllocate, KFinalize, KLookup, KernelCount };
+const char *const kKernelNames[KernelCount] = {"k_discover", "k_allocate", "k_finalize", "k_lookup"};
 
 struct Timing {
     bool enabled = false;
@@ -118,8 +118,6 @@ struct Scratch {
     uint8_t *hint = nullptr;
     uint32_t *seg_cnt = nullptr;
     uint32_t *set_slot = nullptr;
-    StatRow *rows_a = nullptr;
-    StatRow *rows_b = nullptr;
     Control *ctl = nullptr;
     bool dirty = false;            // a launch sequence was cut short: set and counters must be cleared before use
     bool owned = true;             // base came from hipMalloc (false: it points into the file-scope scratch array)
@@ -140,7 +138,7 @@ struct Scratch {
     // Where each array sits inside an area that serves batches of up to n positions: 29 bytes per
     // position and a few small fixed areas.
     struct Layout {
-        size_t o_list, o_ent, o_first, o_homes, o_hint, o_seg, o_set, o_rows, o_rows_b, o_ctl, total;
+        size_t o_list, o_ent, o_first, o_homes, o_hint, o_seg, o_set, o_ctl, total;
     };
     static Layout layout_for(int64_t n, int num_cus)
     {
@@ -154,9 +152,7 @@ struct Scratch {
         L.o_hint = L.o_homes + align_up(2 * per_pos);
         L.o_seg = L.o_hint + align_up((size_t)n + kWave);
         L.o_set = L.o_seg + align_up(4 * max_blocks * kWavesPerBlock);
-        L.o_rows = L.o_set + align_up(8 * (size_t)n);
-        L.o_rows_b = L.o_rows + align_up(max_blocks * sizeof(StatRow));
-        L.o_ctl = L.o_rows_b + align_up(max_blocks * sizeof(StatRow));
+        L.o_ctl = L.o_set + align_up(8 * (size_t)n);
         L.total = L.o_ctl + align_up(sizeof(Control));
         return L;
     }
@@ -170,8 +166,6 @@ struct Scratch {
         hint = (uint8_t *)(base + L.o_hint);
         seg_cnt = (uint32_t *)(base + L.o_seg);
         set_slot = (uint32_t *)(base + L.o_set);
-        rows_a = (StatRow *)(base + L.o_rows);
-        rows_b = (StatRow *)(base + L.o_rows_b);
         ctl = (Control *)(base + L.o_ctl);
         cap_n = n;
     }
@@ -194,8 +188,8 @@ struct Scratch {
         bind(area, L, 0);
         // empty set (0xFFFFFFFF) and zero counters; set entries are re-emptied by every call, so
         // this is the only full clear
-        if (hipMemset(base + L.o_set, 0xFF, (L.o_rows - L.o_set)) != hipSuccess) return MPZCH_ERR_HIP;
-        if (hipMemset(base + L.o_rows, 0, L.total - L.o_rows) != hipSuccess) return MPZCH_ERR_HIP;
+        if (hipMemset(base + L.o_set, 0xFF, (L.o_ctl - L.o_set)) != hipSuccess) return MPZCH_ERR_HIP;
+        if (hipMemset(base + L.o_ctl, 0, L.total - L.o_ctl) != hipSuccess) return MPZCH_ERR_HIP;
         if (hipDeviceSynchronize() != hipSuccess) return MPZCH_ERR_HIP;
         cap_n = n;
         return MPZCH_OK;
@@ -340,8 +334,6 @@ mpzch_status_t launch_remap(Scratch &sc, Timing &tm, Params p, int32_t max_p, in
     p.homes = sc.homes;
     p.seg_cnt = sc.seg_cnt;
     p.set_slot = sc.set_slot;
-    p.rows_a = sc.rows_a;
-    p.rows_b = sc.rows_b;
     p.ctl = sc.ctl;
 
     const int64_t num_chunks = (p.n + kWave - 1) / kWave;
@@ -351,16 +343,10 @@ mpzch_status_t launch_remap(Scratch &sc, Timing &tm, Params p, int32_t max_p, in
     p.seg_chunks = (int32_t)((num_chunks + p.num_segs - 1) / p.num_segs);
     // the other kernels walk the segments' miss lists, one segment per wavefront pass
     const int g_grp = grid_for((int64_t)p.num_segs, kWavesPerBlock, sc.num_cus, group_blocks_per_cu());
-    p.blocks_a = g_disc;
-    p.blocks_b = g_grp;
 
     TIMED(tm, KDiscover, s, (launch_discover<true>(p, g_disc, s)));
     TIMED(tm, KAllocate, s, launch_allocate(max_p, max_p_lru, p, sc.num_cus, s));
     TIMED(tm, KFinalize, s, launch_finalize(p, g_grp, s));
-    if (!tm.begin(KEmitDups, s)) return MPZCH_ERR_HIP;
-    hipLaunchKernelGGL(k_emit_dups, dim3(g_grp), dim3(kBlock), 0, s, p);
-    LAUNCH_CHECK();
-    if (!tm.end(s)) return MPZCH_ERR_HIP;
     return MPZCH_OK;
 }
 
@@ -429,8 +415,8 @@ mpzch_status_t static_scratch(hipStream_t s, Scratch **out)
         st.sc.owned = false;
         st.sc.bind((char *)ptr, L, MPZCH_NOALLOC_MAX_BATCH);
         // fill kernels, not memsets: the first call may sit in a stream whose work a caller replays
-        TRY(fill32((int32_t *)st.sc.set_slot, (int64_t)((L.o_rows - L.o_set) / 4), -1, s));
-        TRY(fill64((int64_t *)(st.sc.base + L.o_rows), (int64_t)((L.total - L.o_rows) / 8), 0, s));
+        TRY(fill32((int32_t *)st.sc.set_slot, (int64_t)((L.o_ctl - L.o_set) / 4), -1, s));
+        TRY(fill64((int64_t *)(st.sc.base + L.o_ctl), (int64_t)((L.total - L.o_ctl) / 8), 0, s));
         st.ready = true;
     }
     *out = &st.sc;

@@ -17,11 +17,10 @@
 //                displaced is carried on by the displacing lane from its next round.  The
 //                fixed point is the unique stable assignment, the same one a sequential
 //                round-major / position-minor sweep produces.
-//   k_finalize   every elected id finds its tag in its window, replaces it by the id, sets
-//                metadata = step and reports evicted slots; ids without a tag fall back to home.
-//                The scratch set entries that were used are emptied again.
-//   k_emit_dups  the other copies of a missed id copy the slot of the elected position; counters
-//                are published.
+//   k_finalize   every listed position finds the slot that carries its id's claim; the elected one
+//                replaces the tag by the id, sets the metadata and reports evicted slots; ids
+//                without a claim fall back to home.  The scratch set entries that were used are
+//                emptied again; the workgroup that finishes last publishes the call's counters.
 // k_allocate / k_finalize work with one lane per claimant on the first slots of the window and
 // hand the few claimants that need more to the whole wavefront (64 slots per access).  Tables
 // under the LRU policy allocate in k_allocate_lru (a group of lanes per claimant) or
@@ -29,8 +28,8 @@
 //
 // No kernel funnels work through one hot address: an atomic on a single address costs about
 // 12 ns on this GPU however many lanes it serves, so miss lists are per wavefront (no shared
-// cursor), counters are accumulated per workgroup and reduced once, and evicted slots are staged
-// in LDS and appended with one reservation per workgroup.
+// cursor), counters are accumulated per workgroup and added to one of several copies, and evicted
+// slots are staged in LDS and appended with one reservation per workgroup.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -63,18 +62,16 @@ struct TableDesc {
     int64_t ev_cap;
 };
 
-// Counters of one call that do go through atomics (few per call).  The block is all zero between
-// calls: the workgroup of k_emit_dups that publishes the counters clears it again.
+// Counters of one call.  Every workgroup adds its partial counts once, into one of kBins copies of the
+// counters chosen by its index: an atomic on ONE address costs about 12 ns whatever it adds, so a
+// few thousand workgroups on one address would take longer than the kernel, spread over kBins addresses
+// they vanish in it.  The workgroup of k_finalize that finishes last sums the copies, publishes the
+// totals and clears the block: it is all zero between calls (so a captured launch sequence can be replayed).
+constexpr int kBins = 16;
 struct Control {
     unsigned long long num_evicted[kMaxTables];
-    unsigned long long stats[kMaxTables][kStatCount];
-    unsigned long long done;       // workgroups of k_emit_dups that have added their share of the rows
-};
-
-// Per-workgroup partial counters, written once with plain stores and summed by k_emit_dups.
-struct StatRow {
-    unsigned long long v[kStatCount];
-    long long table;
+    unsigned long long stats[kBins][kMaxTables][kStatCount];
+    unsigned long long done;       // workgroups of k_finalize that have finished
 };
 
 struct Params {
@@ -92,14 +89,12 @@ struct Params {
     uint32_t *ent;                 // entry of the position's id in the scratch set
     int64_t *homes;                // home slot of the position's id
     uint32_t *first_of;            // position of the first occurrence of the position's id
-    uint8_t *hint;                 // round at which k_allocate placed the position's claim (lane form)
+    uint8_t *hint;                 // by batch position: round at which k_allocate placed the claim of the id
+                                   // elected there (written for elected positions only)
     uint32_t *seg_cnt;
     int32_t seg_chunks;
     int32_t num_segs;
     uint32_t *set_slot;            // scratch hash set of batch positions, empty = 0xFFFFFFFF
-    StatRow *rows_a;               // per workgroup of k_discover
-    StatRow *rows_b;               // per workgroup of k_finalize
-    int32_t blocks_a, blocks_b;
     Control *ctl;
     // several tables
     const TableDesc *descs;        // device array [num_tables]
@@ -320,12 +315,17 @@ __device__ __forceinline__ void set_region(const Params &p, int64_t pos, uint64_
     size = 2ull * (uint64_t)(hi - lo);
 }
 
-// Sums per-lane counters over the workgroup and stores one StatRow (or, when the wavefronts of
-// the workgroup ended on different tables, hands them over through atomics).  Must be reached
-// by all threads of the workgroup.
-__device__ __forceinline__ void block_stat_row(const Params &p, StatRow *rows, int num_rows, const int *idx,
-                                               const unsigned long long *vals, int count, int table,
-                                               unsigned long long (*s_red)[kStatCount], int *s_tab)
+__device__ __forceinline__ unsigned long long *stat_word(const Params &p, int table, int k)
+{
+    return &p.ctl->stats[blockIdx.x % kBins][table][k];
+}
+
+// Sums per-lane counters over the workgroup and adds them to this workgroup's copy of the call's
+// counters: one atomic per counter when all its wavefronts ended on the same table (the rule), one
+// per wavefront and counter otherwise.  Must be reached by all threads of the workgroup.
+__device__ __forceinline__ void block_stat_add(const Params &p, const int *idx, const unsigned long long *vals,
+                                               int count, int table, unsigned long long (*s_red)[kStatCount],
+                                               int *s_tab)
 {
     const int lane = lane_id(), w = threadIdx.x / kWave;
     for (int k = 0; k < count; ++k) {
@@ -334,19 +334,18 @@ __device__ __forceinline__ void block_stat_row(const Params &p, StatRow *rows, i
     }
     if (lane == 0) s_tab[w] = table;
     __syncthreads();
-    if (threadIdx.x == 0) {
+    if ((int)threadIdx.x < count) {
+        const int k = idx[threadIdx.x];
         bool same = true;
         for (int i = 1; i < kWavesPerBlock; ++i) same = same && s_tab[i] == s_tab[0];
-        StatRow row;
-        for (int k = 0; k < kStatCount; ++k) row.v[k] = 0;
-        row.table = s_tab[0];
-        for (int i = 0; i < kWavesPerBlock; ++i)
-            for (int k = 0; k < count; ++k) {
-                const unsigned long long v = s_red[i][idx[k]];
-                if (same || i == 0) row.v[idx[k]] += v;
-                else if (v) atomicAdd(&p.ctl->stats[s_tab[i]][idx[k]], v);
-            }
-        if ((int)blockIdx.x < num_rows) rows[blockIdx.x] = row;
+        if (same) {
+            unsigned long long v = 0;
+            for (int i = 0; i < kWavesPerBlock; ++i) v += s_red[i][k];
+            if (v) atomicAdd(stat_word(p, s_tab[0], k), v);
+        } else {
+            for (int i = 0; i < kWavesPerBlock; ++i)
+                if (s_red[i][k]) atomicAdd(stat_word(p, s_tab[i], k), s_red[i][k]);
+        }
     }
 }
 
@@ -454,23 +453,11 @@ __device__ __forceinline__ void gather_wave(const Params &p, bool active, int64_
 // in LDS (position, next round) and resolved later, 64 at a time, so that the second
 // memory round trip is paid once per 64 parked ids instead of once per chunk.  What remains
 // unfound is the segment's miss list.
-//
-// Input de-duplication in LDS (Sec. 3.6): every wavefront keeps a small direct-mapped cache of the
-// ids it has resolved (id -> probe result).  A position whose id is in the cache takes the cached
-// result: no access to the table and no second metadata store.  Copies of an id inside one chunk
-// elect one lane through the same cache entry; the others take that lane's result.  Skew is what
-// this serves: the hot ids of a Zipf stream occur in every chunk, and without it every copy is a
-// request to the same line, queued behind the others at one channel of the cache.
-constexpr int kCache = 256;                     // entries per wavefront
-constexpr int32_t kCachePending = 0x40000000;   // values from here on: not resolved (pending + electing lane)
-
 template <bool TRAIN, bool MULTI, bool GATHER>
 __device__ __forceinline__ void discover_body(const Params &p)
 {
     __shared__ uint32_t s_pos[kWavesPerBlock][kStage];
     __shared__ int32_t s_q[kWavesPerBlock][kStage];      // > 0: next round to look at; < 0: absent, -(slots read)
-    __shared__ int64_t c_id[kWavesPerBlock][kCache];
-    __shared__ int32_t c_val[kWavesPerBlock][kCache];
     __shared__ unsigned long long s_red[kWavesPerBlock][kStatCount];
     __shared__ int s_tab[kWavesPerBlock];
 
@@ -488,13 +475,6 @@ __device__ __forceinline__ void discover_body(const Params &p)
     unsigned long long st_hit = 0, st_miss = 0, st_inv = 0, st_probe = 0, st_mlen = 0;
     int st_table = 0;
     int staged = 0, flushed = 0;                 // wave-uniform: parked ids in LDS / misses already listed
-    int cache_table = 0;                         // wave-uniform: the table the cached ids belong to
-
-    auto cache_clear = [&]() {
-        for (int i = lane; i < kCache; i += kWave) c_id[w][i] = -1;          // no valid id is negative
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    };
-    cache_clear();
 
     // counters are kept for one table at a time
     auto stats_table = [&](int f) {
@@ -503,23 +483,21 @@ __device__ __forceinline__ void discover_body(const Params &p)
         const unsigned long long a = wave_sum(st_hit), b = wave_sum(st_miss), x = wave_sum(st_inv), y = wave_sum(st_probe),
                                  z = wave_sum(st_mlen);
         if (lane == 0) {
-            if (a) atomicAdd(&p.ctl->stats[st_table][kHitPos], a);
-            if (b) atomicAdd(&p.ctl->stats[st_table][kMissPos], b);
-            if (x) atomicAdd(&p.ctl->stats[st_table][kInvalidPos], x);
-            if (y) atomicAdd(&p.ctl->stats[st_table][kHitProbeSum], y);
-            if (z) atomicAdd(&p.ctl->stats[st_table][kMissProbeSum], z);
+            if (a) atomicAdd(stat_word(p, st_table, kHitPos), a);
+            if (b) atomicAdd(stat_word(p, st_table, kMissPos), b);
+            if (x) atomicAdd(stat_word(p, st_table, kInvalidPos), x);
+            if (y) atomicAdd(stat_word(p, st_table, kHitProbeSum), y);
+            if (z) atomicAdd(stat_word(p, st_table, kMissProbeSum), z);
         }
         st_hit = st_miss = st_inv = st_probe = st_mlen = 0;
         st_table = f;
     };
-    // a position whose id is resident at `dist` probes from home.  refresh: this position writes the
-    // metadata ("Update"); copies served from the cache need not, another position of this wavefront has
-    // stored the same value -- unless copies may carry different expiry steps.
+    // a position whose id is resident at `dist` probes from home
     // (the first pass stores the outputs of its whole chunk itself: emit = false)
-    auto finish_hit = [&](const Tab &d, int64_t pos, int64_t home, int dist, bool emit, bool refresh) {
+    auto finish_hit = [&](const Tab &d, int64_t pos, int64_t home, int dist, bool emit) {
         const int64_t slot = wrap(home + dist, d.N);
         if (TRAIN) {
-            if (refresh || (d.evict == 3 && p.ttls)) store_meta(d, slot, meta_value(p, d, pos));
+            store_meta(d, slot, meta_value(p, d, pos));   // "Update": refresh the resident's metadata
             st_hit++;
             st_probe += (unsigned long long)(dist + 1);
         }
@@ -560,7 +538,7 @@ __device__ __forceinline__ void discover_body(const Params &p)
                         else q += kLine;
                     }
                 }
-                if (mine && dist >= 0) finish_hit(d, (int64_t)pos, home, dist, true, true);
+                if (mine && dist >= 0) finish_hit(d, (int64_t)pos, home, dist, true);
                 const bool miss = mine && dist < 0;
                 const uint64_t mb = __ballot(miss);
                 if (miss && TRAIN) {
@@ -626,44 +604,19 @@ __device__ __forceinline__ void discover_body(const Params &p)
                 if (seg_hi <= first_pos) seg_hi = first_pos + 1;
                 d = view(p.descs[f]);
                 mine = todo && pos < seg_hi;
-                if (f != cache_table) {                   // the cached ids belong to the previous table
-                    cache_clear();
-                    cache_table = f;
-                }
             } else {
                 d = view(p.t0);
             }
             stats_table(f);
 
             const bool valid = mine && id >= 0;
-            const uint64_t hsh = mix64((uint64_t)id ^ d.seed);
-            const int64_t home = mine ? (int64_t)__umul64hi(hsh, (uint64_t)d.N) : 0;
-            // the cache: a resolved copy of this id, or an election among the copies in this chunk
-            const int ci = (int)(hsh & (uint64_t)(kCache - 1));
-            bool cached = false;
-            int res = kProbeGoOn;
-            if (valid) {
-                const int32_t ev = c_val[w][ci];
-                if (c_id[w][ci] == id && ev < kCachePending) { cached = true; res = ev; }
-            }
-            const bool cand = valid && !cached;
-            if (cand) c_id[w][ci] = id;                   // one id per entry survives
-            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-            const bool grp = cand && c_id[w][ci] == id;   // the copies of the surviving id
-            if (grp) c_val[w][ci] = kCachePending + lane; // one of them survives: the elected lane
-            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-            const int owner = grp ? c_val[w][ci] - kCachePending : lane;
-            const bool leader = cand && owner == lane;    // elected, or an id that lost its entry to another
-            // first pass: the line that holds the home slot
+            const int64_t home = mine ? home_slot(id, d.seed, d.N) : 0;
+            // first pass: the aligned 64 bytes that hold the home slot
             const int o = (int)((home + (int64_t)(((uintptr_t)d.I >> 3) & (kFirstG - 1))) & (kFirstG - 1));
-            int got = probe_pass<kFirstG>(d, id, home, leader ? -o : d.P);
-            if (got == kProbeGoOn && kFirstG - o >= d.P) got = probe_absent(d.P - 1);    // the whole window was read
-            const int lgot = __shfl(got, owner);
-            if (cand) res = leader ? got : lgot;
-            if (grp && leader && res != kProbeGoOn) c_val[w][ci] = res;                  // resolved: later chunks reuse it
-            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            int res = probe_pass<kFirstG>(d, id, home, valid ? -o : d.P);
+            if (res == kProbeGoOn && kFirstG - o >= d.P) res = probe_absent(d.P - 1);    // the whole window was read
             const bool hit = valid && res >= 0;
-            if (hit) finish_hit(d, pos, home, res, false, leader);
+            if (hit) finish_hit(d, pos, home, res, false);
             else if (TRAIN && mine && !valid) st_inv++;
             // One store for the whole chunk keeps the 64-byte sectors of the outputs complete (a
             // sector written with holes leaves the cache as narrow writes).  A position that is
@@ -693,7 +646,7 @@ __device__ __forceinline__ void discover_body(const Params &p)
     if (want_stats) {
         const int idx[5] = {kHitPos, kMissPos, kInvalidPos, kHitProbeSum, kMissProbeSum};
         const unsigned long long vals[5] = {st_hit, st_miss, st_inv, st_probe, st_mlen};
-        block_stat_row(p, p.rows_a, p.blocks_a, idx, vals, 5, st_table, s_red, s_tab);
+        block_stat_add(p, idx, vals, 5, st_table, s_red, s_tab);
     }
 }
 
@@ -945,7 +898,7 @@ __device__ __forceinline__ void allocate_body(const Params &p, int64_t vblock, i
                 if (lane == src && cpos == own)
                     hint = fr < 0 ? kHintUnplaced : (fr < (int32_t)kHintUnknown ? (uint32_t)fr : kHintUnknown);
             }
-            if (have) p.hint[idx] = (uint8_t)hint;
+            if (agent) p.hint[pos] = (uint8_t)hint;
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         }
     }
@@ -1065,12 +1018,13 @@ __global__ __launch_bounds__(kWave) void k_allocate_lru(Params p)
         for (uint32_t j0 = 0; j0 < cnt; j0 += kWave) {
             const int64_t idx = seg_base + j0 + lane;
             const bool have = j0 + lane < cnt;
-            uint32_t pos = 0;
+            uint32_t pos = 0, e = 0;
             bool agent = false;
             int f = 0;
             if (have) {
                 pos = p.list[idx];
-                const uint32_t first = p.set_slot[p.ent[idx]];
+                e = p.ent[idx];
+                const uint32_t first = p.set_slot[e];
                 p.first_of[idx] = first;
                 agent = first == pos;
                 if (MULTI && agent) {
@@ -1101,7 +1055,7 @@ __global__ __launch_bounds__(kWave) void k_allocate_lru(Params p)
                     if (lane == sk) hint = frk < 0 ? kHintUnplaced : (uint32_t)frk;
                 }
             }
-            if (MULTI ? agent : have) p.hint[idx] = (uint8_t)hint;
+            if (agent) p.hint[pos] = (uint8_t)hint;
         }
     }
 }
@@ -1222,12 +1176,13 @@ __global__ __launch_bounds__(kWave) void k_allocate_lru_long(Params p)
         for (uint32_t j0 = 0; j0 < cnt; j0 += kWave) {
             const int64_t idx = seg_base + j0 + lane;
             const bool have = j0 + lane < cnt;
-            uint32_t pos = 0;
+            uint32_t pos = 0, e = 0;
             bool agent = false;
             int f = 0;
             if (have) {
                 pos = p.list[idx];
-                const uint32_t first = p.set_slot[p.ent[idx]];
+                e = p.ent[idx];
+                const uint32_t first = p.set_slot[e];
                 p.first_of[idx] = first;
                 agent = first == pos;
                 if (MULTI && agent) {
@@ -1247,7 +1202,7 @@ __global__ __launch_bounds__(kWave) void k_allocate_lru_long(Params p)
                 if (lane == src)
                     hint = fr < 0 ? kHintUnplaced : (fr < (int32_t)kHintUnknown ? (uint32_t)fr : kHintUnknown);
             }
-            if (MULTI ? agent : have) p.hint[idx] = (uint8_t)hint;
+            if (agent) p.hint[pos] = (uint8_t)hint;
         }
     }
 }
@@ -1293,9 +1248,9 @@ __device__ __forceinline__ void finalize_account(const Params &p, FinalizeState 
                 const int f0 = __shfl(f, __ffsll((unsigned long long)dm) - 1);
                 if (f0 != fs.st_table) {
                     // rare (feature boundary): hand the counters over through atomics
-                    if (fs.st_ins) atomicAdd(&p.ctl->stats[fs.st_table][kInserts], fs.st_ins);
-                    if (fs.st_evi) atomicAdd(&p.ctl->stats[fs.st_table][kEvictions], fs.st_evi);
-                    if (fs.st_col) atomicAdd(&p.ctl->stats[fs.st_table][kCollisions], fs.st_col);
+                    if (fs.st_ins) atomicAdd(stat_word(p, fs.st_table, kInserts), fs.st_ins);
+                    if (fs.st_evi) atomicAdd(stat_word(p, fs.st_table, kEvictions), fs.st_evi);
+                    if (fs.st_col) atomicAdd(stat_word(p, fs.st_table, kCollisions), fs.st_col);
                     fs.st_ins = fs.st_evi = fs.st_col = 0;
                     fs.st_table = f0;
                 }
@@ -1303,7 +1258,7 @@ __device__ __forceinline__ void finalize_account(const Params &p, FinalizeState 
         }
         if (done) {
             if (f != fs.st_table) {
-                atomicAdd(&p.ctl->stats[f][outcome == 0 ? kInserts : outcome == 1 ? kEvictions : kCollisions], 1ull);
+                atomicAdd(stat_word(p, f, outcome == 0 ? kInserts : outcome == 1 ? kEvictions : kCollisions), 1ull);
             } else {
                 fs.st_ins += outcome == 0;
                 fs.st_evi += outcome == 1;
@@ -1363,17 +1318,54 @@ __device__ __forceinline__ void finalize_epilogue(const Params &p, FinalizeState
     if (want_stats) {
         const int idx[3] = {kInserts, kEvictions, kCollisions};
         const unsigned long long vals[3] = {fs.st_ins, fs.st_evi, fs.st_col};
-        block_stat_row(p, p.rows_b, p.blocks_b, idx, vals, 3, fs.st_table, s_red, s_tab);
+        block_stat_add(p, idx, vals, 3, fs.st_table, s_red, s_tab);
     }
 }
 
+// Sums the kBins copies of the call's counters, writes out_num_evicted / out_stats and clears the block.
+// Run by the workgroup of k_finalize that finishes last.
+__device__ __forceinline__ void publish_counters(const Params &p, unsigned long long (*s_bins)[kStatCount])
+{
+    for (int i = threadIdx.x; i < p.num_tables; i += kBlock)
+        p.out_num_evicted[i] =
+            (int64_t)__hip_atomic_load(&p.ctl->num_evicted[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (p.out_stats) {
+        const int nbins = p.num_tables * kStatCount;
+        for (int i = threadIdx.x; i < nbins; i += kBlock) {
+            unsigned long long v = 0;
+            for (int b = 0; b < kBins; ++b)
+                v += __hip_atomic_load(&p.ctl->stats[b][i / kStatCount][i % kStatCount], __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+            s_bins[i / kStatCount][i % kStatCount] = v;
+        }
+        __syncthreads();
+        for (int t = threadIdx.x; t < p.num_tables; t += kBlock)
+            s_bins[t][kDistinctMiss] = s_bins[t][kInserts] + s_bins[t][kEvictions] + s_bins[t][kCollisions];
+        __syncthreads();
+        for (int i = threadIdx.x; i < nbins; i += kBlock)
+            p.out_stats[i] = (int64_t)s_bins[i / kStatCount][i % kStatCount];
+    }
+    __syncthreads();
+    unsigned long long *z = reinterpret_cast<unsigned long long *>(p.ctl);
+    for (int i = threadIdx.x; i < (int)(sizeof(Control) / sizeof(unsigned long long)); i += kBlock) z[i] = 0ull;
+}
+
+// Every entry of the miss lists -- the elected position of an id (its agent) and the other copies of
+// the id alike -- finds the slot that carries the agent's claim: where k_allocate left it (the hint,
+// kept under the agent's batch position, which every copy knows), else by a search of the window by
+// the whole wavefront (a claimant displaced after its hint was written).  A copy may find the claim
+// tag or, when the agent has been quicker, already the id.  The agent turns the tag into the id,
+// writes the metadata and accounts for the outcome; every entry stores its output slot.  Entries
+// without a claim fall back to the home slot (Case 3).
 __device__ __forceinline__ void finalize_body(const Params &p)
 {
     __shared__ int64_t s_ev[kWavesPerBlock][kEvBuf];
     __shared__ unsigned long long s_red[kWavesPerBlock][kStatCount];
+    __shared__ unsigned long long s_bins[kMaxTables][kStatCount];
     __shared__ int s_cnt[kWavesPerBlock];
     __shared__ int s_tab[kWavesPerBlock];
     __shared__ unsigned long long s_base;
+    __shared__ bool s_last;
 
     const int lane = lane_id();
     const int w = threadIdx.x / kWave;
@@ -1387,38 +1379,43 @@ __device__ __forceinline__ void finalize_body(const Params &p)
         const uint32_t cnt = p.seg_cnt[seg];
         const int64_t seg_base = seg * p.seg_chunks * kWave;
         for (uint32_t j0 = 0; j0 < cnt; j0 += kWave) {
+            const bool have = j0 + lane < cnt;
+            const int64_t idx = seg_base + j0 + lane;
             bool agent = false;
-            uint32_t pos = 0;
-            if (j0 + lane < cnt) {
-                pos = p.list[seg_base + j0 + lane];
-                agent = p.first_of[seg_base + j0 + lane] == pos;
-                p.set_slot[p.ent[seg_base + j0 + lane]] = kSetEmpty;   // the scratch set is left empty again
-            }
+            uint32_t pos = 0, first = 0, h = kHintUnplaced;
             int outcome = 2, f = 0;
             int64_t s_final = 0, home = 0, id = 0;
             Tab d = view(p.t0);
-            bool search = false;         // the hint did not lead to the tag: the window is searched
             int at = -1;
             uint32_t occ = 0;
-            if (agent) {
+            // does slot value v carry the claim of the id whose first occurrence is `fst`?
+            auto is_claim_of = [](int64_t v, uint32_t fst, int64_t cid) {
+                return is_tag(v) ? tag_pos(v) == fst : v == cid;
+            };
+            bool search = false;
+            if (have) {
+                pos = p.list[idx];
+                first = p.first_of[idx];
+                agent = first == pos;
+                p.set_slot[p.ent[idx]] = kSetEmpty;            // the scratch set is left empty again
                 if (multi) { f = find_table(p.offsets, p.num_tables, (int64_t)pos); d = view(p.descs[f]); }
                 id = p.ids[pos];
-                home = p.homes[seg_base + j0 + lane];
-                // the slot that carries this claimant's tag: where k_allocate left it, unless the
-                // claimant was displaced afterwards
-                const uint32_t h = p.hint[seg_base + j0 + lane];
+                home = p.homes[idx];
+                h = p.hint[first];
                 if (h < kHintUnknown) {
                     const int64_t v = d.I[wrap(home + (int)h, d.N)];
-                    if (is_tag(v) && tag_pos(v) == pos) { at = (int)h; occ = tag_occ(v); }
+                    if (is_claim_of(v, first, id)) { at = (int)h; occ = tag_occ(v); }
                 }
                 search = at < 0 && h != kHintUnplaced;
             }
-            // searches are served one after the other by the whole wavefront, 64 slots per access
+            // the hint did not lead to the claim (the claimant was displaced afterwards): the window is
+            // searched; searches are served one after the other by the whole wavefront, 64 slots per access
             uint64_t sm = __ballot(search);
             while (sm) {
                 const int src = __ffsll((unsigned long long)sm) - 1;
                 sm &= sm - 1;
-                const uint32_t cpos = __shfl(pos, src);
+                const uint32_t cfirst = __shfl(first, src);
+                const int64_t cid = shfl64(id, src);
                 const int64_t chome = shfl64(home, src);
                 const Tab dw = view(multi ? p.descs[__shfl(f, src)] : p.t0);
                 int found_round = -1;
@@ -1429,7 +1426,7 @@ __device__ __forceinline__ void finalize_body(const Params &p)
                     uint32_t o = 0;
                     if (round < dw.P) {
                         const int64_t v = dw.I[wrap(chome + round, dw.N)];
-                        mine = is_tag(v) && tag_pos(v) == cpos;
+                        mine = is_claim_of(v, cfirst, cid);
                         o = tag_occ(v);
                     }
                     const uint64_t mb = __ballot(mine);
@@ -1441,17 +1438,20 @@ __device__ __forceinline__ void finalize_body(const Params &p)
                 }
                 if (lane == src) { at = found_round; occ = found_occ; }
             }
-            if (agent) {
-                if (at >= 0) {
-                    // the claim becomes the id; metadata gets the step (Algorithm 1, Pass 2)
-                    s_final = wrap(home + at, d.N);
-                    d.I[s_final] = id;
+            if (have) {
+                s_final = at >= 0 ? wrap(home + at, d.N) : home;
+                if (agent) {
+                    // the claim becomes the id, metadata gets its value (Algorithm 1, Pass 2); without a
+                    // claim: Case 3, the home slot's metadata is refreshed.  (The agent always meets its
+                    // own tag: nobody else replaces it.)
+                    if (at >= 0) {
+                        d.I[s_final] = id;
+                        outcome = (int)occ;
+                    }
                     store_meta(d, s_final, meta_value(p, d, pos));
-                    outcome = (int)occ;
-                } else {
-                    // Case 3: no empty or evictable slot -> home slot, its metadata refreshed
-                    s_final = home;
-                    store_meta(d, home, meta_value(p, d, pos));
+                } else if (p.ttls && d.evict == 3) {
+                    // per-feature retention: a later copy may ask for a later expiry step than the first
+                    store_meta(d, s_final, meta_value(p, d, pos));
                 }
                 p.out_slots[pos] = s_final;
             }
@@ -1459,95 +1459,21 @@ __device__ __forceinline__ void finalize_body(const Params &p)
         }
     }
     finalize_epilogue(p, fs, s_ev, s_cnt, s_tab, &s_base, s_red, want_stats);
+    // The workgroup that finishes last publishes the call's counters.  Everything it reads -- evicted
+    // counts and counter copies -- was added with device-scope atomics, which are performed where all
+    // dies see them; a workgroup waits until its own have been acknowledged and then reports in.  (A
+    // device-scope release fence here would also write back the die's whole L2, once per workgroup.)
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __syncthreads();
+    if (threadIdx.x == 0)
+        s_last = atomicAdd(&p.ctl->done, 1ull) == (unsigned long long)(gridDim.x - 1);
+    __syncthreads();
+    if (s_last) publish_counters(p, s_bins);
 }
 
 __global__ __launch_bounds__(kBlock) void k_finalize(Params p)
 {
     finalize_body(p);
-}
-
-// ------------------------------------------------------------------ duplicates, cleanup, counters
-__device__ __forceinline__ void emit_dups_body(const Params &p)
-{
-    __shared__ unsigned long long s_bins[kMaxTables][kStatCount];
-    __shared__ bool s_last;
-    const int lane = lane_id();
-    const int64_t wave_global = ((int64_t)blockIdx.x * kBlock + threadIdx.x) / kWave;
-    const int64_t num_waves = (int64_t)gridDim.x * kWavesPerBlock;
-
-    for (int64_t seg = wave_global; seg < p.num_segs; seg += num_waves) {
-        const uint32_t cnt = p.seg_cnt[seg];
-        const int64_t seg_base = seg * p.seg_chunks * kWave;
-        for (uint32_t j = lane; j < cnt; j += kWave) {
-            const uint32_t pos = p.list[seg_base + j];
-            const uint32_t first = p.first_of[seg_base + j];
-            if (first != pos) {
-                const int64_t s = p.out_slots[first];
-                p.out_slots[pos] = s;
-                if (p.ttls) {
-                    // per-feature retention: a later copy may ask for a later expiry step than the first
-                    const Tab d = view(p.num_tables > 1 ? p.descs[find_table(p.offsets, p.num_tables, (int64_t)pos)] : p.t0);
-                    if (d.evict == 3) store_meta(d, s, meta_value(p, d, pos));
-                }
-            }
-        }
-    }
-
-    // Counters: the per-workgroup rows of k_discover and k_finalize are summed by the first
-    // workgroups of this grid, kBlock rows each, into the call's counter block; the workgroup
-    // that finishes last reads the totals back, publishes them and leaves the block zeroed for
-    // the next call (so a captured launch sequence can be replayed).
-    const int rows = p.out_stats ? p.blocks_a + p.blocks_b : 0;
-    int helpers = (rows + kBlock - 1) / kBlock;
-    if (helpers > (int)gridDim.x) helpers = (int)gridDim.x;
-    if (helpers < 1) helpers = 1;
-    if ((int)blockIdx.x >= helpers) return;
-    const int nbins = p.num_tables * kStatCount;
-    if (p.out_stats) {
-        for (int i = threadIdx.x; i < nbins; i += kBlock) s_bins[i / kStatCount][i % kStatCount] = 0ull;
-        __syncthreads();
-        for (int i = blockIdx.x * kBlock + threadIdx.x; i < rows; i += helpers * kBlock) {
-            const StatRow *row = i < p.blocks_a ? &p.rows_a[i] : &p.rows_b[i - p.blocks_a];
-            const int t = (int)row->table;
-            for (int k = 0; k < kStatCount; ++k) {
-                const unsigned long long v = row->v[k];
-                if (v) atomicAdd(&s_bins[t][k], v);
-            }
-        }
-        __syncthreads();
-        for (int i = threadIdx.x; i < nbins; i += kBlock) {
-            const unsigned long long v = s_bins[i / kStatCount][i % kStatCount];
-            if (v) atomicAdd(&p.ctl->stats[i / kStatCount][i % kStatCount], v);
-        }
-    }
-    __threadfence();                     // this workgroup's additions are visible before it counts as done
-    __syncthreads();
-    if (threadIdx.x == 0) s_last = atomicAdd(&p.ctl->done, 1ull) == (unsigned long long)(helpers - 1);
-    __syncthreads();
-    if (!s_last) return;
-    __threadfence();
-    for (int i = threadIdx.x; i < p.num_tables; i += kBlock)
-        p.out_num_evicted[i] =
-            (int64_t)__hip_atomic_load(&p.ctl->num_evicted[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (p.out_stats) {
-        for (int i = threadIdx.x; i < nbins; i += kBlock)
-            s_bins[i / kStatCount][i % kStatCount] =
-                __hip_atomic_load(&p.ctl->stats[i / kStatCount][i % kStatCount], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __syncthreads();
-        for (int t = threadIdx.x; t < p.num_tables; t += kBlock)
-            s_bins[t][kDistinctMiss] = s_bins[t][kInserts] + s_bins[t][kEvictions] + s_bins[t][kCollisions];
-        __syncthreads();
-        for (int i = threadIdx.x; i < nbins; i += kBlock)
-            p.out_stats[i] = (int64_t)s_bins[i / kStatCount][i % kStatCount];
-    }
-    __syncthreads();
-    unsigned long long *z = reinterpret_cast<unsigned long long *>(p.ctl);
-    for (int i = threadIdx.x; i < (int)(sizeof(Control) / sizeof(unsigned long long)); i += kBlock) z[i] = 0ull;
-}
-
-__global__ __launch_bounds__(kBlock) void k_emit_dups(Params p)
-{
-    emit_dups_body(p);
 }
 
 // ------------------------------------------------------------------ fills and row reset
