@@ -23,16 +23,66 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# Random-access ceilings of MI355X measured with paper_2602_17050_amd/memory_ceilings.bin
-# (profiles/memory_ceilings_mi355x.txt): aligned 128-byte line reads and 4-byte stores per second.
-CEIL_LINES_PER_S = 38.1e9
-CEIL_STORES_PER_S = 22.9e9
-# HBM bytes per k_discover launch on the full-size headline workload, from rocprofv3 --pmc
-# FETCH_SIZE and WRITE_SIZE (KiB per dispatch x 1024).  Calibrated against a copy kernel of known
-# size, FETCH_SIZE reads half the bytes on this GPU (every read request is 128 bytes and is priced
-# as 64) and WRITE_SIZE reads them all: factors 2.000 and 1.000, profiles/counter_calibration_mi355x.txt;
-# figures from profiles/remap_headline_1Bslots_4Mids.txt.  Only valid for that workload at scale 1.
-HEADLINE_DISCOVER_TRAFFIC_BYTES = int((2.0 * 347449.5 + 1.0 * 182988.6) * 1024)
+PROFILES = os.path.join(ROOT, "profiles")
+# which tracked rocprofv3 summary holds the HBM traffic of a workload's dominant kernel
+TRAFFIC_PROFILE = {"headline": "remap_headline_1Bslots_4Mids.txt", "c4": "remap_c4_500Mslots_2Mids.txt",
+                   "c5": "remap_jagged_c5_26tables.txt", "c3": "lookup_c3_100Mslots_1Mids.txt"}
+
+
+def measured_ceilings():
+    """(aligned 128-byte line reads per second, 4-byte stores per second) at random addresses of an 8 GB
+    array, as measured on MI355X by paper_2602_17050_amd/memory_ceilings.bin and kept in
+    profiles/memory_ceilings_mi355x.txt -- the figures are read from that file so that they cannot drift."""
+    lines = stores = None
+    try:
+        with open(os.path.join(PROFILES, "memory_ceilings_mi355x.txt")) as fh:
+            for ln in fh:
+                if ln.startswith("random aligned 128-byte lines"):
+                    lines = float(ln.split("ms")[1].split("G ops/s")[0]) * 1e9
+                elif ln.startswith("random 4-byte stores (one per lane)"):
+                    stores = float(ln.split("ms")[1].split("G ops/s")[0]) * 1e9
+    except OSError:
+        pass
+    return lines, stores
+
+
+def profiled_traffic(workload, kernel, scale):
+    """HBM bytes per launch of `kernel` from the tracked rocprofv3 --pmc summary of this workload at full
+    scale: FETCH_SIZE and WRITE_SIZE (KiB per dispatch), each scaled by what the counter reads for a copy
+    kernel of known size (profiles/counter_calibration_mi355x.txt: FETCH_SIZE x 2.000, WRITE_SIZE x 1.000)."""
+    name = TRAFFIC_PROFILE.get(workload)
+    if name is None or scale != 1.0:
+        return None
+    try:
+        with open(os.path.join(PROFILES, name)) as fh:
+            for ln in fh:
+                if ln.startswith("traffic:") and f"kernel={kernel} " in ln:
+                    kv = dict(x.split("=") for x in ln.split()[1:])
+                    return int((2.0 * float(kv["FETCH_SIZE_KiB"]) + 1.0 * float(kv["WRITE_SIZE_KiB"])) * 1024)
+    except (OSError, KeyError, ValueError):
+        pass
+    return None
+
+
+def roofline_entry(workload, scale, kernel, avg_ms, alg_bytes, lines_per_launch=None, stores_per_launch=None, note=None):
+    """`achieved` = algorithmic bytes per launch of the dominant kernel / its average duration (HIP events
+    recorded by the library on the launch stream), against the 8 TB/s HBM peak."""
+    ach = alg_bytes / (avg_ms * 1e-3) / 1e9
+    traffic = profiled_traffic(workload, kernel, scale)
+    r = {"bound": "hbm", "kernel": kernel, "achieved": round(ach, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+         "frac": round(ach / HBM_PEAK_GBS, 5), "traffic": traffic, "avg_kernel_ms": round(avg_ms, 4),
+         "alg_bytes_per_launch": round(alg_bytes),
+         # all HBM bytes the kernel moves (useful or not) against the same peak
+         "traffic_frac_of_peak": None if traffic is None else round(traffic / (avg_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+    c_lines, c_stores = measured_ceilings()
+    if lines_per_launch is not None and c_lines and c_stores:
+        # what the measured random-access ceilings allow for this launch
+        floor_ms = (lines_per_launch / c_lines + (stores_per_launch or 0.0) / c_stores) * 1e3
+        r["random_access_floor_ms"] = round(floor_ms, 4)
+        r["frac_of_random_access_ceiling"] = round(floor_ms / avg_ms, 3)
+    if note:
+        r["note"] = note
+    return r
 
 
 def log(*a):
@@ -187,31 +237,20 @@ def main():
 
     # ---- roofline of the dominant kernel
     roofline = None
+    mlen_sum = st[:, sname["miss_probe_sum"]].sum()
+    mean_miss_len = mlen_sum / max(miss_pos, 1.0)
     if ktimes:
         dom = max(ktimes, key=lambda k: ktimes[k][0])     # k_discover (the only kernel timed unless --all-kernel-timing)
         ms_total, launches = ktimes[dom]
         avg_ms = ms_total / launches
-        # algorithmic bytes of Pass 1 per launch: id in (8/position), slot out (8/hit position),
-        # per distinct resident id its probe prefix 8(d+1) + a 4-byte metadata store,
-        # per distinct missed id its whole window 8P.
-        alg = {
-            "k_discover": (8.0 * total_ids + 8.0 * hit_pos + u_hit * (8.0 * mean_probe + 4.0) + d_miss * 8.0 * P) / K,
-        }.get(dom)
-        if alg is not None:
-            ach = alg / (avg_ms * 1e-3) / 1e9
-            # what the random-access ceilings allow for this launch: one line read per position
-            # (plus the further lines of parked ids) and one metadata store per hit position
+        if dom == "k_discover":
+            # algorithmic bytes of Pass 1 per launch: id in (8/position), slot out (8/hit position), per
+            # distinct resident id its probe prefix 8(d+1) + a 4-byte metadata store, per distinct missed id
+            # the slots up to the first empty one of its range (else the whole range), 8 bytes each
+            alg = (8.0 * total_ids + 8.0 * hit_pos + u_hit * (8.0 * mean_probe + 4.0) + d_miss * 8.0 * mean_miss_len) / K
+            # requests: one line read per position (plus the further lines of parked ids), one metadata store per hit position
             lines = total_ids / K + (miss_pos + max(probe_sum - hit_pos, 0) / 8.0) / K
-            floor_ms = (lines / CEIL_LINES_PER_S + (hit_pos / K) / CEIL_STORES_PER_S) * 1e3
-            traffic = HEADLINE_DISCOVER_TRAFFIC_BYTES if (args.workload == "headline" and args.scale == 1.0) else None
-            roofline = {"bound": "hbm", "kernel": dom, "achieved": round(ach, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                        "frac": round(ach / HBM_PEAK_GBS, 5), "traffic": traffic,
-                        "avg_kernel_ms": round(avg_ms, 4), "alg_bytes_per_launch": round(alg),
-                        "random_access_floor_ms": round(floor_ms, 4),
-                        "frac_of_random_access_ceiling": round(floor_ms / avg_ms, 3),
-                        # all HBM bytes the kernel moves (useful or not) against the same peak
-                        "traffic_frac_of_peak": None if traffic is None else
-                        round(traffic / (avg_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+            roofline = roofline_entry(args.workload, args.scale, dom, avg_ms, alg, lines, hit_pos / K)
         else:
             roofline = {"bound": "hbm", "kernel": dom, "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                         "frac": None, "traffic": None, "avg_kernel_ms": round(avg_ms, 4)}
@@ -264,6 +303,7 @@ def main():
             "miss_positions": round(miss_pos / K, 1), "distinct_misses": round(d_miss / K, 1),
             "inserts": round(inserts / K, 1), "evictions": round(evictions / K, 1),
             "collisions": round(collisions / K, 1), "mean_hit_probe_len": round(mean_probe, 3),
+            "mean_miss_probe_len": round(mean_miss_len, 3),
         },
         "kernel_ms_per_step": {k: round(v[0] / K, 4) for k, v in ktimes.items()},
         "roofline": roofline,
@@ -317,30 +357,72 @@ def bench_lookup(args, np, torch, mp, wl, dev):
                "sample": f"first {n_cpu} timed batches of {batch} ids", "matches_gpu_out_slots": same}
     ms_total, launches = ktimes["k_lookup"]
     hit_frac = float(found[W:].float().mean().item())
+    # byte accounting (outside the timed region): the counting lookup gives the probe lengths of the
+    # timed batches, the host the number of distinct resident / absent ids
+    mp.mpzch_set_kernel_timing(g.handle, 0)
+    st = torch.zeros((K, mp.STAT_COUNT), dtype=torch.int64, device=dev)
+    tmp_s = torch.empty(batch, dtype=torch.int64, device=dev)
+    tmp_f = torch.empty(batch, dtype=torch.uint8, device=dev)
+    for i in range(W, W + K):
+        mp.mpzch_lookup_stats(g.handle, g.identities, batches[i], tmp_s, tmp_f, st[i - W])
+    torch.cuda.synchronize()
+    stn = st.cpu().numpy().astype(np.float64).sum(axis=0)
+    sname = {n: i for i, n in enumerate(mp.STAT_NAMES)}
+    hit_pos, miss_pos = stn[sname["hit_pos"]], stn[sname["miss_pos"]]
+    mean_probe = stn[sname["hit_probe_sum"]] / max(hit_pos, 1.0)
+    mean_miss_len = stn[sname["miss_probe_sum"]] / max(miss_pos, 1.0)
+    u_hit = u_miss = 0.0
+    for i in range(W, W + K):
+        f_np = found[i].cpu().numpy().astype(bool)
+        valid = batches_np[i] >= 0
+        u_hit += np.unique(batches_np[i][f_np]).size
+        u_miss += np.unique(batches_np[i][~f_np & valid]).size
+    # per position: id in (8), slot out (8), found flag (1); per distinct resident id its probe prefix,
+    # per distinct absent id the slots up to the first empty one of its range
+    alg = (17.0 * batch * K + u_hit * 8.0 * mean_probe + u_miss * 8.0 * mean_miss_len) / K
+    lines = batch + (miss_pos + max(stn[sname["hit_probe_sum"]] - hit_pos, 0) / 8.0) / K
+    roofline = roofline_entry("c3", args.scale, "k_lookup", ms_total / launches, alg, lines, 0.0)
+    roofline["hit_fraction"] = round(hit_frac, 4)
     result = {
         "metric": "remapped IDs/sec (infer lookup) at 1 GPU", "value": round(batch * K / elapsed, 1), "unit": "ids/s",
         "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(elapsed / K * 1e3, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "int64", "data": "synthetic",
         "config": {"workload": f"c3: lookup-only, {n_slots}-slot table 80% full, P=32, {batch} ids/batch, "
                                f"95% resident Zipf(1.2), 5% unseen", "scale": args.scale},
+        "per_step": {"distinct_resident_ids": round(u_hit / K, 1), "distinct_absent_ids": round(u_miss / K, 1),
+                     "mean_hit_probe_len": round(mean_probe, 3), "mean_miss_probe_len": round(mean_miss_len, 3)},
         "kernel_ms_per_step": {k: round(v[0] / K, 4) for k, v in ktimes.items()},
-        "roofline": {"bound": "hbm", "kernel": "k_lookup", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": None, "traffic": None, "avg_kernel_ms": round(ms_total / launches, 4),
-                     "hit_fraction": round(hit_frac, 4)},
+        "roofline": roofline,
         "cpu_baseline": cpu,
     }
     print(json.dumps(result), flush=True)
 
 
-def _emit(metric, value, K, W, elapsed, workload, ktimes, cpu, extra=None):
+def training_alg_bytes(np, positions, st_rows, distinct, names):
+    """Algorithmic bytes of Pass 1 over some calls on ONE table: st_rows = their counter rows (float array
+    [calls, STAT_COUNT]), positions = input positions in all, distinct = distinct valid ids in all.  Also
+    returns the random requests (line reads, metadata stores) these calls need at least."""
+    n = {k: i for i, k in enumerate(names)}
+    tot = st_rows.sum(axis=0)
+    hit_pos, miss_pos, d_miss = tot[n["hit_pos"]], tot[n["miss_pos"]], tot[n["distinct_miss"]]
+    mean_probe = tot[n["hit_probe_sum"]] / max(hit_pos, 1.0)
+    mean_miss_len = tot[n["miss_probe_sum"]] / max(miss_pos, 1.0)
+    u_hit = max(distinct - d_miss, 0.0)
+    alg = 8.0 * positions + 8.0 * hit_pos + u_hit * (8.0 * mean_probe + 4.0) + d_miss * 8.0 * mean_miss_len
+    lines = positions + miss_pos + max(tot[n["hit_probe_sum"]] - hit_pos, 0) / 8.0
+    return alg, lines, hit_pos
+
+
+def _emit(metric, value, K, W, elapsed, workload, ktimes, cpu, extra=None, roofline=None):
     dom = max(ktimes, key=lambda k: ktimes[k][0]) if ktimes else None
     result = {
         "metric": metric, "value": round(value, 1), "unit": "ids/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": round(elapsed / K * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int64", "data": "synthetic", "config": {"workload": workload},
         "kernel_ms_per_step": {k: round(v[0] / K, 4) for k, v in ktimes.items()},
-        "roofline": {"bound": "hbm", "kernel": dom, "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None,
-                     "traffic": None, "avg_kernel_ms": round(ktimes[dom][0] / ktimes[dom][1], 4) if dom else None},
+        "roofline": roofline or {"bound": "hbm", "kernel": dom, "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                 "frac": None, "traffic": None,
+                                 "avg_kernel_ms": round(ktimes[dom][0] / ktimes[dom][1], 4) if dom else None},
         "cpu_baseline": cpu,
     }
     if extra:
@@ -373,6 +455,16 @@ def bench_small_table(args, np, torch, mp, wl, dev):
     for (s, b), o in list(zip(batches, outs))[:W]:
         g.remap(b, s, o)
     torch.cuda.synchronize()
+    nb = len(batches)
+    stats = torch.zeros((nb, mp.STAT_COUNT), dtype=torch.int64, device=dev)
+    ev = torch.empty(max(b.numel() for _, b in batches), dtype=torch.int64, device=dev)
+    nev = torch.zeros(1, dtype=torch.int64, device=dev)
+
+    def one(i):
+        s_, b_ = batches[i]
+        mp.mpzch_remap(g.handle, g.identities, g.metadata, b_, s_, outs[i], ev, nev, stats[i])
+        mp.mpzch_reset_rows(ev, nev, emb)
+
     if args.graph:
         # the timed steps as one captured graph: the table state before the capture is restored before the
         # timed replay (a capture only records, but the warm-up replay below runs the steps once)
@@ -381,9 +473,8 @@ def bench_small_table(args, np, torch, mp, wl, dev):
         side.wait_stream(torch.cuda.current_stream())
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=side):
-            for (s, b), o in list(zip(batches, outs))[W:]:
-                g.remap(b, s, o)
-                g.reset_rows(emb)
+            for i in range(W, nb):
+                one(i)
         graph.replay()
         torch.cuda.synchronize()
         g.identities.copy_(I0)
@@ -399,9 +490,8 @@ def bench_small_table(args, np, torch, mp, wl, dev):
             # two event records per launch: every kernel costs these small steps some 30 us, Pass 1 alone a few
             mp.mpzch_set_kernel_timing(g.handle, 1 if args.all_kernel_timing else 2)
         t0 = time.perf_counter()
-        for (s, b), o in list(zip(batches, outs))[W:]:
-            g.remap(b, s, o)
-            g.reset_rows(emb)
+        for i in range(W, nb):
+            one(i)
         torch.cuda.synchronize()
         elapsed = time.perf_counter() - t0
         ktimes = {} if args.no_kernel_timing else mp.mpzch_kernel_times(g.handle)
@@ -421,8 +511,17 @@ def bench_small_table(args, np, torch, mp, wl, dev):
         cpu = {"value": round(total / (time.perf_counter() - c0), 1), "unit": "ids/s", "cores": 1, "kind": "oracle",
                "sample": "all timed steps", "matches_gpu_out_slots": same}
     occ = int((g.identities >= 0).sum().item())
+    roofline = None
+    if "k_discover" in ktimes:
+        distinct = float(sum(np.unique(b[b >= 0]).size for _, b in batches_np[W:]))
+        alg, lines, hit_pos = training_alg_bytes(np, float(total), stats[W:].cpu().numpy().astype(np.float64), distinct,
+                                                 mp.STAT_NAMES)
+        ms_total, launches = ktimes["k_discover"]
+        roofline = roofline_entry(args.workload, 1.0, "k_discover", ms_total / launches, alg / K, lines / K, hit_pos / K,
+                                  note="the table lives in L2 / Infinity Cache and the step is bound by launches: the "
+                                       "HBM fraction says little here")
     _emit("remapped IDs/sec (train insert+evict) at 1 GPU", total / elapsed, K, W, elapsed, name, ktimes, cpu,
-          {"final_load": round(occ / spec.num_slots, 4)})
+          {"final_load": round(occ / spec.num_slots, 4)}, roofline)
 
 
 def bench_jagged(args, np, torch, mp, wl, dev):
@@ -464,12 +563,28 @@ def bench_jagged(args, np, torch, mp, wl, dev):
     elapsed = time.perf_counter() - t0
     ktimes = mp.mpzch_group_kernel_times(group)
     total = sum(dev_b[i][0].numel() for i in range(W, W + K))
-    st = stats[W:].cpu().numpy().reshape(K, T, mp.STAT_COUNT).sum(axis=(0, 1))
+    st_all = stats[W:].cpu().numpy().reshape(K, T, mp.STAT_COUNT).astype(np.float64)
+    st = st_all.sum(axis=(0, 1))
+    roofline = None
+    if "k_discover" in ktimes:
+        alg = lines = stores = 0.0
+        for f in range(T):                       # the byte accounting is per table: every table has its own probe lengths
+            distinct = positions = 0.0
+            for i in range(W, W + K):
+                v, _, o = data[i]
+                sl = v[int(o[f]):int(o[f + 1])]
+                distinct += np.unique(sl[sl >= 0]).size
+                positions += sl.size
+            a, l, h = training_alg_bytes(np, positions, st_all[:, f, :], distinct, mp.STAT_NAMES)
+            alg, lines, stores = alg + a, lines + l, stores + h
+        ms_total, launches = ktimes["k_discover"]
+        roofline = roofline_entry("c5", args.scale, "k_discover", ms_total / launches, alg / K, lines / K, stores / K,
+                                  note="k_discover_tables; most of the 26 tables live in L2 / Infinity Cache")
     _emit("remapped IDs/sec (train insert+evict) at 1 GPU", total / elapsed, K, W, elapsed,
           f"c5: 26 tables ({sum(t.num_slots for t in spec.tables)} slots in all), P=16, TTL=5, {spec.samples} samples, "
           f"pooling 1..50, about {total // K} values per step, one mpzch_remap_jagged + one mpzch_reset_rows_jagged call "
           f"per step (bf16 x16 rows per slot)", ktimes, None,
-          {"totals_over_timed_steps": dict(zip(mp.STAT_NAMES, [int(x) for x in st]))})
+          {"totals_over_timed_steps": dict(zip(mp.STAT_NAMES, [int(x) for x in st]))}, roofline)
 
 
 def bench_table1(args, np, torch, mp, wl, dev):

@@ -216,6 +216,17 @@ mpzch_status_t mpzch_lookup(const mpzch_table_t *t, const int64_t *identities,
                             int64_t *out_slots, uint8_t *out_found, void *stream);
 
 /*
+ * mpzch_lookup that also counts (Sec. 3.7; the numbers a serving system watches, and what the benchmark's
+ * byte accounting needs): out_stats [dev] int64[MPZCH_STAT_COUNT] receives HIT_POS, MISS_POS, INVALID_POS,
+ * HIT_PROBE_SUM and MISS_PROBE_SUM of this call (the other entries are written as zero).  Uses a small
+ * counter block owned by the handle (allocated by the first such call, which synchronises the device
+ * once), hence the non-const handle; one counting lookup or remap per handle at a time.
+ */
+mpzch_status_t mpzch_lookup_stats(mpzch_table_t *t, const int64_t *identities,
+                                  const int64_t *ids, int64_t n,
+                                  int64_t *out_slots, uint8_t *out_found, int64_t *out_stats, void *stream);
+
+/*
  * Reset of reassigned rows (Sec. 3.4: "upon eviction, both the embedding weights and the
  * optimizer state are reset"): for k < min(*num_slots_dev, slots_cap):
  *     rows[(slots[k] mod num_rows) * row_stride_bytes .. + row_bytes) <- init_row

@@ -71,7 +71,7 @@ def _load():
         lib.oracle_remap_ttls.argtypes = [ctypes.POINTER(_Cfg), p, p, p, p, ctypes.c_int64, ctypes.c_int32,
                                           p, p, ctypes.c_int64, p, p]
         lib.oracle_lookup.restype = ctypes.c_int
-        lib.oracle_lookup.argtypes = [ctypes.POINTER(_Cfg), p, p, ctypes.c_int64, p, p]
+        lib.oracle_lookup.argtypes = [ctypes.POINTER(_Cfg), p, p, ctypes.c_int64, p, p, p]
         lib.oracle_reset_rows.restype = ctypes.c_int
         lib.oracle_reset_rows.argtypes = [p, ctypes.c_int64, p, ctypes.c_int64, ctypes.c_int64,
                                           ctypes.c_int64, p]
@@ -144,15 +144,19 @@ class Table:
             raise RuntimeError("oracle_remap failed")
         return RemapResult(out, ev[: int(nev[0])].copy(), dict(zip(STAT_NAMES, st.tolist())))
 
-    def lookup(self, ids):
+    def lookup(self, ids, want_stats: bool = False):
+        """Returns (slots, found), or (slots, found, stats dict) with want_stats."""
         ids = _i64(ids)
         n = ids.shape[0]
         out = np.empty(n, dtype=np.int64)
         found = np.empty(n, dtype=np.uint8)
+        st = np.zeros(len(STAT_NAMES), dtype=np.int64)
         rc = _load().oracle_lookup(ctypes.byref(self.cfg), _ptr(self.identities), _ptr(ids), n,
-                                   _ptr(out), _ptr(found))
+                                   _ptr(out), _ptr(found), _ptr(st))
         if rc != 0:
             raise RuntimeError("oracle_lookup failed")
+        if want_stats:
+            return out, found, dict(zip(STAT_NAMES, st.tolist()))
         return out, found
 
     def check_state(self, lo: int = 0, hi: int | None = None):

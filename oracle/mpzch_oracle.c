@@ -341,19 +341,36 @@ int oracle_remap(const oracle_cfg *c, int64_t *I, int32_t *M,
                              out_num_evicted, stats);
 }
 
-/* Sec. 3.7: read-only lookup.  Miss -> home slot, found flag 0. */
+/* Sec. 3.7: read-only lookup.  Miss -> home slot, found flag 0.  stats (may be NULL) receives the
+ * per-position counters of the call: hit / miss / invalid positions and the two probe-length sums. */
 int oracle_lookup(const oracle_cfg *c, const int64_t *I,
                   const int64_t *ids, int64_t n,
-                  int64_t *out_slots, uint8_t *out_found)
+                  int64_t *out_slots, uint8_t *out_found, int64_t *stats)
 {
     if (!c || c->num_slots < 1 || c->max_probe < 1 || n < 0) return -1;
+    int64_t st[ST_COUNT];
+    memset(st, 0, sizeof st);
+    const int64_t N = c->num_slots, P = p_eff(c);
     for (int64_t j = 0; j < n; ++j) {
         int64_t id = ids[j];
-        int64_t h = oracle_home(id, c->hash_seed, c->num_slots);
+        int64_t h = oracle_home(id, c->hash_seed, N);
         int64_t r = id >= 0 ? discover(c, I, id, h) : -1;
-        out_slots[j] = r >= 0 ? probe_slot(h, r, c->num_slots) : h;
+        out_slots[j] = r >= 0 ? probe_slot(h, r, N) : h;
         if (out_found) out_found[j] = (uint8_t)(r >= 0);
+        if (id < 0) {
+            st[ST_INVALID_POS]++;
+        } else if (r >= 0) {
+            st[ST_HIT_POS]++;
+            st[ST_HIT_PROBE_SUM] += r + 1;
+        } else {
+            int64_t len = P;                   /* as far as a search for an absent id has to read */
+            for (int64_t k = 0; k < P; ++k)
+                if (I[probe_slot(h, k, N)] == -1) { len = k + 1; break; }
+            st[ST_MISS_POS]++;
+            st[ST_MISS_PROBE_SUM] += len;
+        }
     }
+    if (stats) memcpy(stats, st, sizeof st);
     return 0;
 }
 

@@ -26,7 +26,7 @@ EXPORTED = (
     "mpzch_group_set_kernel_timing", "mpzch_group_kernel_times", "mpzch_status_string",
     "mpzch_remap_feature_ttl", "mpzch_reset_rows_multi", "mpzch_lookup_gather", "mpzch_collect_delta", "mpzch_gather_rows", "mpzch_apply_delta",
     "mpzch_remap_jagged_feature_ttl", "mpzch_lookup_jagged", "mpzch_reset_rows_jagged",
-    "mpzch_remap_noalloc",
+    "mpzch_remap_noalloc", "mpzch_lookup_stats",
 )
 NOALLOC_MAX_BATCH = 262144
 
@@ -69,6 +69,7 @@ def load_library(path: str | None = None):
     lib.mpzch_remap_noalloc.argtypes = [vp, vp, vp, vp, i64, i32, vp, vp, i64, vp, vp, vp]
     lib.mpzch_remap_feature_ttl.argtypes = [vp, vp, vp, vp, vp, i64, i32, vp, vp, i64, vp, vp, vp]
     lib.mpzch_lookup.argtypes = [vp, vp, vp, i64, vp, vp, vp]
+    lib.mpzch_lookup_stats.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp]
     lib.mpzch_reset_rows.argtypes = [vp, vp, i64, vp, i64, i64, i64, vp, vp]
     lib.mpzch_reset_rows_multi.argtypes = [vp, vp, i64, ctypes.POINTER(_Rows), i32, vp]
     lib.mpzch_lookup_gather.argtypes = [vp, vp, vp, i64, vp, i64, i64, i64, vp, vp, vp, vp]
@@ -181,6 +182,12 @@ def mpzch_lookup(handle, identities, ids, out_slots, out_found=None):
     _check(load_library().mpzch_lookup(handle, _ptr(identities, torch.int64), _ptr(ids, torch.int64), ids.numel(),
                                        _ptr(out_slots, torch.int64), _ptr(out_found, torch.uint8), _stream()),
            "mpzch_lookup")
+
+
+def mpzch_lookup_stats(handle, identities, ids, out_slots, out_found, out_stats):
+    _check(load_library().mpzch_lookup_stats(handle, _ptr(identities, torch.int64), _ptr(ids, torch.int64), ids.numel(),
+                                             _ptr(out_slots, torch.int64), _ptr(out_found, torch.uint8),
+                                             _ptr(out_stats, torch.int64), _stream()), "mpzch_lookup_stats")
 
 
 def mpzch_reset_rows(slots, num_slots_dev, rows, init_row=None, num_rows: int | None = None):

@@ -119,6 +119,7 @@ struct Scratch {
     uint32_t *seg_cnt = nullptr;
     uint32_t *set_slot = nullptr;
     Control *ctl = nullptr;
+    Control *lookup_ctl = nullptr; // counter block of counting lookups while there is no scratch area
     bool dirty = false;            // a launch sequence was cut short: set and counters must be cleared before use
     bool owned = true;             // base came from hipMalloc (false: it points into the file-scope scratch array)
     int num_cus = 0;
@@ -194,9 +195,22 @@ struct Scratch {
         cap_n = n;
         return MPZCH_OK;
     }
+    // the counter block alone (a counting lookup needs nothing else): the scratch area's when there is one
+    mpzch_status_t ensure_ctl(Control **out)
+    {
+        if (base) { *out = ctl; return MPZCH_OK; }
+        if (!lookup_ctl) {
+            if (hipMalloc((void **)&lookup_ctl, sizeof(Control)) != hipSuccess) { lookup_ctl = nullptr; return MPZCH_ERR_ALLOC; }
+            if (hipMemset(lookup_ctl, 0, sizeof(Control)) != hipSuccess) return MPZCH_ERR_HIP;
+            if (hipDeviceSynchronize() != hipSuccess) return MPZCH_ERR_HIP;
+        }
+        *out = lookup_ctl;
+        return MPZCH_OK;
+    }
     void release()
     {
         if (base && owned) { (void)hipDeviceSynchronize(); (void)hipFree(base); }
+        if (lookup_ctl) { (void)hipDeviceSynchronize(); (void)hipFree(lookup_ctl); lookup_ctl = nullptr; }
         base = nullptr;
         cap_n = 0;
     }
@@ -610,6 +624,36 @@ mpzch_status_t mpzch_lookup(const mpzch_table_t *t, const int64_t *identities,
     p.num_segs = grid * kWavesPerBlock;
     p.seg_chunks = (int32_t)(((n + kWave - 1) / kWave + p.num_segs - 1) / p.num_segs);
     TIMED(mt->tm, KLookup, s, (launch_discover<false>(p, grid, s)));
+    return MPZCH_OK;
+}
+
+mpzch_status_t mpzch_lookup_stats(mpzch_table_t *t, const int64_t *identities,
+                                  const int64_t *ids, int64_t n,
+                                  int64_t *out_slots, uint8_t *out_found, int64_t *out_stats, void *stream)
+{
+    if (!t || !identities || !out_stats) return MPZCH_ERR_INVALID_ARG;
+    if (n < 0 || n > MPZCH_MAX_BATCH) return MPZCH_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    if (n == 0) return fill64(out_stats, MPZCH_STAT_COUNT, 0, s);
+    if (!ids || !out_slots) return MPZCH_ERR_INVALID_ARG;
+    TRY(t->sc.query_device());
+    Params p;
+    std::memset(&p, 0, sizeof p);
+    TRY(t->sc.ensure_ctl(&p.ctl));
+    p.ids = ids;
+    p.n = n;
+    p.num_tables = 1;
+    p.out_slots = out_slots;
+    p.out_found = out_found;
+    p.out_stats = out_stats;
+    p.t0 = make_desc(t->cfg, const_cast<int64_t *>(identities), nullptr, 0, 0);
+    const int grid = grid_for(n, kBlock, t->sc.num_cus, discover_blocks_per_cu());
+    p.num_segs = grid * kWavesPerBlock;
+    p.seg_chunks = (int32_t)(((n + kWave - 1) / kWave + p.num_segs - 1) / p.num_segs);
+    if (!t->tm.begin(KLookup, s)) return MPZCH_ERR_HIP;
+    hipLaunchKernelGGL(k_lookup_counting, dim3(grid), dim3(kBlock), 0, s, p);
+    LAUNCH_CHECK();
+    if (!t->tm.end(s)) return MPZCH_ERR_HIP;
     return MPZCH_OK;
 }
 

@@ -349,6 +349,35 @@ __device__ __forceinline__ void block_stat_add(const Params &p, const int *idx, 
     }
 }
 
+// Sums the kBins copies of the call's counters, writes out_num_evicted / out_stats and clears the block.
+// Run by the workgroup that finishes last (of k_finalize; of a counting lookup).
+__device__ __forceinline__ void publish_counters(const Params &p, unsigned long long (*s_bins)[kStatCount])
+{
+    if (p.out_num_evicted)
+        for (int i = threadIdx.x; i < p.num_tables; i += kBlock)
+            p.out_num_evicted[i] =
+                (int64_t)__hip_atomic_load(&p.ctl->num_evicted[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (p.out_stats) {
+        const int nbins = p.num_tables * kStatCount;
+        for (int i = threadIdx.x; i < nbins; i += kBlock) {
+            unsigned long long v = 0;
+            for (int b = 0; b < kBins; ++b)
+                v += __hip_atomic_load(&p.ctl->stats[b][i / kStatCount][i % kStatCount], __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+            s_bins[i / kStatCount][i % kStatCount] = v;
+        }
+        __syncthreads();
+        for (int t = threadIdx.x; t < p.num_tables; t += kBlock)
+            s_bins[t][kDistinctMiss] = s_bins[t][kInserts] + s_bins[t][kEvictions] + s_bins[t][kCollisions];
+        __syncthreads();
+        for (int i = threadIdx.x; i < nbins; i += kBlock)
+            p.out_stats[i] = (int64_t)s_bins[i / kStatCount][i % kStatCount];
+    }
+    __syncthreads();
+    unsigned long long *z = reinterpret_cast<unsigned long long *>(p.ctl);
+    for (int i = threadIdx.x; i < (int)(sizeof(Control) / sizeof(unsigned long long)); i += kBlock) z[i] = 0ull;
+}
+
 // ------------------------------------------------------------------ Pass 1 (discovery)
 // One probe pass over the 64 ids held one per lane: the id of lane L is compared with the G
 // slots of rounds [q, q + G) of its window (q may be negative: rounds below 0 do not exist;
@@ -453,7 +482,7 @@ __device__ __forceinline__ void gather_wave(const Params &p, bool active, int64_
 // in LDS (position, next round) and resolved later, 64 at a time, so that the second
 // memory round trip is paid once per 64 parked ids instead of once per chunk.  What remains
 // unfound is the segment's miss list.
-template <bool TRAIN, bool MULTI, bool GATHER>
+template <bool TRAIN, bool MULTI, bool GATHER, bool COUNT = TRAIN>
 __device__ __forceinline__ void discover_body(const Params &p)
 {
     __shared__ uint32_t s_pos[kWavesPerBlock][kStage];
@@ -469,7 +498,7 @@ __device__ __forceinline__ void discover_body(const Params &p)
     const int64_t c_end = c_begin + p.seg_chunks < num_chunks ? c_begin + p.seg_chunks : num_chunks;
     const int64_t seg_base = c_begin * kWave;
     constexpr bool multi = MULTI;
-    const bool want_stats = TRAIN && p.out_stats != nullptr;
+    const bool want_stats = COUNT && p.out_stats != nullptr;
 
     // per-lane counters of the table currently being processed
     unsigned long long st_hit = 0, st_miss = 0, st_inv = 0, st_probe = 0, st_mlen = 0;
@@ -498,6 +527,8 @@ __device__ __forceinline__ void discover_body(const Params &p)
         const int64_t slot = wrap(home + dist, d.N);
         if (TRAIN) {
             store_meta(d, slot, meta_value(p, d, pos));   // "Update": refresh the resident's metadata
+        }
+        if (COUNT) {
             st_hit++;
             st_probe += (unsigned long long)(dist + 1);
         }
@@ -544,6 +575,8 @@ __device__ __forceinline__ void discover_body(const Params &p)
                 if (miss && TRAIN) {
                     const int at = nmiss + __popcll(mb & ((1ull << lane) - 1ull));      // slots already consumed
                     s_pos[w][at] = pos;
+                }
+                if (miss && COUNT) {
                     st_miss++;
                     st_mlen += (unsigned long long)(mlen ? mlen : d.P);
                 }
@@ -617,7 +650,11 @@ __device__ __forceinline__ void discover_body(const Params &p)
             if (res == kProbeGoOn && kFirstG - o >= d.P) res = probe_absent(d.P - 1);    // the whole window was read
             const bool hit = valid && res >= 0;
             if (hit) finish_hit(d, pos, home, res, false);
-            else if (TRAIN && mine && !valid) st_inv++;
+            else if (COUNT && mine && !valid) st_inv++;
+            if (COUNT && !TRAIN && valid && res <= kProbeAbsent) {           // a lookup miss decided here is final
+                st_miss++;
+                st_mlen += (unsigned long long)absent_len(res);
+            }
             // One store for the whole chunk keeps the 64-byte sectors of the outputs complete (a
             // sector written with holes leaves the cache as narrow writes).  A position that is
             // not decided yet gets its home slot: final for a negative id (home of its bit
@@ -648,6 +685,16 @@ __device__ __forceinline__ void discover_body(const Params &p)
         const unsigned long long vals[5] = {st_hit, st_miss, st_inv, st_probe, st_mlen};
         block_stat_add(p, idx, vals, 5, st_table, s_red, s_tab);
     }
+    if constexpr (COUNT && !TRAIN) {
+        // a counting lookup publishes its own counters (see finalize_body for the training remap)
+        __shared__ unsigned long long s_bins[kMaxTables][kStatCount];
+        __shared__ bool s_last;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __syncthreads();
+        if (threadIdx.x == 0) s_last = atomicAdd(&p.ctl->done, 1ull) == (unsigned long long)(gridDim.x - 1);
+        __syncthreads();
+        if (s_last) publish_counters(p, s_bins);
+    }
 }
 
 // The kernels around the one body, each compiled for the number of wavefronts per SIMD that
@@ -668,6 +715,11 @@ __global__ __launch_bounds__(kBlock, 4) void k_lookup(Params p)
 __global__ __launch_bounds__(kBlock, 2) void k_lookup_gather(Params p)
 {
     discover_body<false, false, true>(p);
+}
+
+__global__ __launch_bounds__(kBlock, 3) void k_lookup_counting(Params p)
+{
+    discover_body<false, false, false, true>(p);
 }
 
 __global__ __launch_bounds__(kBlock, 3) void k_discover_tables(Params p)
@@ -1320,34 +1372,6 @@ __device__ __forceinline__ void finalize_epilogue(const Params &p, FinalizeState
         const unsigned long long vals[3] = {fs.st_ins, fs.st_evi, fs.st_col};
         block_stat_add(p, idx, vals, 3, fs.st_table, s_red, s_tab);
     }
-}
-
-// Sums the kBins copies of the call's counters, writes out_num_evicted / out_stats and clears the block.
-// Run by the workgroup of k_finalize that finishes last.
-__device__ __forceinline__ void publish_counters(const Params &p, unsigned long long (*s_bins)[kStatCount])
-{
-    for (int i = threadIdx.x; i < p.num_tables; i += kBlock)
-        p.out_num_evicted[i] =
-            (int64_t)__hip_atomic_load(&p.ctl->num_evicted[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (p.out_stats) {
-        const int nbins = p.num_tables * kStatCount;
-        for (int i = threadIdx.x; i < nbins; i += kBlock) {
-            unsigned long long v = 0;
-            for (int b = 0; b < kBins; ++b)
-                v += __hip_atomic_load(&p.ctl->stats[b][i / kStatCount][i % kStatCount], __ATOMIC_RELAXED,
-                                       __HIP_MEMORY_SCOPE_AGENT);
-            s_bins[i / kStatCount][i % kStatCount] = v;
-        }
-        __syncthreads();
-        for (int t = threadIdx.x; t < p.num_tables; t += kBlock)
-            s_bins[t][kDistinctMiss] = s_bins[t][kInserts] + s_bins[t][kEvictions] + s_bins[t][kCollisions];
-        __syncthreads();
-        for (int i = threadIdx.x; i < nbins; i += kBlock)
-            p.out_stats[i] = (int64_t)s_bins[i / kStatCount][i % kStatCount];
-    }
-    __syncthreads();
-    unsigned long long *z = reinterpret_cast<unsigned long long *>(p.ctl);
-    for (int i = threadIdx.x; i < (int)(sizeof(Control) / sizeof(unsigned long long)); i += kBlock) z[i] = 0ull;
 }
 
 // Every entry of the miss lists -- the elected position of an id (its agent) and the other copies of

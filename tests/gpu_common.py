@@ -68,12 +68,21 @@ class Pair:
             assert np.array_equal(self.emb_g.cpu().numpy(), self.emb_o), "embedding rows differ"
 
     def lookup(self, ids_np):
+        """mpzch_lookup and the counting mpzch_lookup_stats against the oracle's lookup."""
         ids_np = np.ascontiguousarray(ids_np, dtype=np.int64)
-        out, found = self.g.lookup(torch.from_numpy(ids_np).cuda())
+        ids_g = torch.from_numpy(ids_np).cuda()
+        out, found = self.g.lookup(ids_g)
+        out2 = torch.full_like(out, -9)
+        found2 = torch.full_like(found, 9)
+        stats = torch.full((mp.STAT_COUNT,), -9, dtype=torch.int64, device="cuda")
+        mp.mpzch_lookup_stats(self.g.handle, self.g.identities, ids_g, out2, found2, stats)
         torch.cuda.synchronize()
-        so, fo = self.o.lookup(ids_np)
+        so, fo, st = self.o.lookup(ids_np, want_stats=True)
         assert np.array_equal(out.cpu().numpy(), so)
         assert np.array_equal(found.cpu().numpy(), fo)
+        assert torch.equal(out, out2) and torch.equal(found, found2)
+        got = dict(zip(mp.STAT_NAMES, stats.cpu().numpy().tolist()))
+        assert got == st, (got, st)
         return so, fo
 
     def close(self):

@@ -201,3 +201,13 @@ def test_probe_length_counters_by_hand():
     assert r.slots[0] == 8 and r.stats["miss_probe_sum"] == 4
     r = t.remap([f], 4)                                          # range 5..8 full: the whole range, then Case 3
     assert r.slots[0] == 5 and r.stats["miss_probe_sum"] == 4 and r.stats["collisions"] == 1
+    # a read-only lookup counts the same way, per position, and changes nothing
+    before = t.identities.copy()
+    so, fo, st = t.lookup([a, f, -4, c, d + 1000003, a], want_stats=True)
+    g = d + 1000003                                              # some id that is not resident
+    hg = py_home(g, seed, n)
+    want_len = next((k + 1 for k in range(4) if t.identities[(hg + k) % n] == -1), 4)
+    assert fo.tolist() == [1, 0, 0, 1, 0, 1] and so[0] == 5 and so[1] == 5 and so[3] == 7
+    assert st["hit_pos"] == 3 and st["hit_probe_sum"] == 1 + 3 + 1
+    assert st["miss_pos"] == 2 and st["miss_probe_sum"] == 4 + want_len and st["invalid_pos"] == 1
+    assert np.array_equal(before, t.identities)
