@@ -88,24 +88,29 @@ struct Timing {
 };
 
 // ---- device scratch -----------------------------------------------------------------------
-// grid caps in workgroups per compute unit
-int env_int(const char *name, int dflt)
-{
-    const char *v = getenv(name);
-    if (!v || !*v) return dflt;
-    const int x = atoi(v);
-    return x > 0 ? x : dflt;
-}
+// Grid caps in workgroups per compute unit.  8 is the measured best for Pass 1 (4 and 16 are within a few
+// per cent) and for the kernels that walk the miss lists; scratch is sized for up to kDiscoverBlocksPerCuMax.
 const int kDiscoverBlocksPerCuMax = 16;
-int discover_blocks_per_cu()
+constexpr int discover_blocks_per_cu() { return 8; }
+constexpr int group_blocks_per_cu() { return 8; }
+
+// Compute units of the current device, asked once per device and process (no handle state: read-only
+// entry points take const handles).
+mpzch_status_t device_cus(int *out)
 {
-    static const int v = [] { int x = env_int("MPZCH_DISCOVER_BPC", 8); return x > kDiscoverBlocksPerCuMax ? kDiscoverBlocksPerCuMax : x; }();
-    return v;
-}
-int group_blocks_per_cu()
-{
-    static const int v = [] { int x = env_int("MPZCH_GROUP_BPC", 8); return x > kDiscoverBlocksPerCuMax ? kDiscoverBlocksPerCuMax : x; }();
-    return v;
+    static std::mutex mu;
+    static int cus[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return MPZCH_ERR_HIP;
+    if (dev < 0 || dev >= 64) return MPZCH_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!cus[dev]) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) return MPZCH_ERR_HIP;
+        cus[dev] = n;
+    }
+    *out = cus[dev];
+    return MPZCH_OK;
 }
 
 struct Scratch {
@@ -129,11 +134,7 @@ struct Scratch {
     mpzch_status_t query_device()
     {
         if (num_cus) return MPZCH_OK;
-        int dev = 0;
-        if (hipGetDevice(&dev) != hipSuccess) return MPZCH_ERR_HIP;
-        if (hipDeviceGetAttribute(&num_cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || num_cus < 1)
-            return MPZCH_ERR_HIP;
-        return MPZCH_OK;
+        return device_cus(&num_cus);
     }
 
     // Where each array sits inside an area that serves batches of up to n positions: 29 bytes per
@@ -441,7 +442,7 @@ mpzch_status_t static_scratch(hipStream_t s, Scratch **out)
 struct mpzch_table {
     TableCfg cfg;
     Scratch sc;
-    Timing tm;
+    mutable Timing tm;             // benchmark instrumentation: also records the launches of read-only calls
 };
 
 // A device copy of per-table descriptors of a group, re-uploaded only when one of them changes.
@@ -610,8 +611,8 @@ mpzch_status_t mpzch_lookup(const mpzch_table_t *t, const int64_t *identities,
     if (n == 0) return MPZCH_OK;
     if (!ids || !out_slots) return MPZCH_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)stream;
-    mpzch_table *mt = const_cast<mpzch_table *>(t);
-    TRY(mt->sc.query_device());
+    int num_cus = 0;
+    TRY(device_cus(&num_cus));
     Params p;
     std::memset(&p, 0, sizeof p);
     p.ids = ids;
@@ -620,10 +621,10 @@ mpzch_status_t mpzch_lookup(const mpzch_table_t *t, const int64_t *identities,
     p.out_slots = out_slots;
     p.out_found = out_found;
     p.t0 = make_desc(t->cfg, const_cast<int64_t *>(identities), nullptr, 0, 0);
-    const int grid = grid_for(n, kBlock, mt->sc.num_cus, discover_blocks_per_cu());
+    const int grid = grid_for(n, kBlock, num_cus, discover_blocks_per_cu());
     p.num_segs = grid * kWavesPerBlock;
     p.seg_chunks = (int32_t)(((n + kWave - 1) / kWave + p.num_segs - 1) / p.num_segs);
-    TIMED(mt->tm, KLookup, s, (launch_discover<false>(p, grid, s)));
+    TIMED(t->tm, KLookup, s, (launch_discover<false>(p, grid, s)));
     return MPZCH_OK;
 }
 
@@ -781,8 +782,8 @@ mpzch_status_t mpzch_lookup_gather(const mpzch_table_t *t, const int64_t *identi
     if (n == 0) return MPZCH_OK;
     if (!ids) return MPZCH_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)stream;
-    mpzch_table *mt = const_cast<mpzch_table *>(t);
-    TRY(mt->sc.query_device());
+    int num_cus = 0;
+    TRY(device_cus(&num_cus));
     Params p;
     std::memset(&p, 0, sizeof p);
     p.ids = ids;
@@ -800,13 +801,13 @@ mpzch_status_t mpzch_lookup_gather(const mpzch_table_t *t, const int64_t *identi
     p.g_shift = -1;
     for (int b = 0; b <= 20; ++b)
         if (g.chunks == ((int64_t)1 << b)) p.g_shift = b;
-    const int grid = grid_for(n, kBlock, mt->sc.num_cus, discover_blocks_per_cu());
+    const int grid = grid_for(n, kBlock, num_cus, discover_blocks_per_cu());
     p.num_segs = grid * kWavesPerBlock;
     p.seg_chunks = (int32_t)(((n + kWave - 1) / kWave + p.num_segs - 1) / p.num_segs);
-    if (!mt->tm.begin(KLookup, s)) return MPZCH_ERR_HIP;
+    if (!t->tm.begin(KLookup, s)) return MPZCH_ERR_HIP;
     hipLaunchKernelGGL(k_lookup_gather, dim3(grid), dim3(kBlock), 0, s, p);
     LAUNCH_CHECK();
-    if (!mt->tm.end(s)) return MPZCH_ERR_HIP;
+    if (!t->tm.end(s)) return MPZCH_ERR_HIP;
     return MPZCH_OK;
 }
 
@@ -817,10 +818,10 @@ mpzch_status_t mpzch_collect_delta(const mpzch_table_t *t, const int64_t *identi
     if (!t || !identities || !metadata || !out_count || cap < 0) return MPZCH_ERR_INVALID_ARG;
     if (cap > 0 && (!out_slots || !out_ids)) return MPZCH_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)stream;
-    mpzch_table *mt = const_cast<mpzch_table *>(t);
-    TRY(mt->sc.query_device());
+    int num_cus = 0;
+    TRY(device_cus(&num_cus));
     TRY(fill64(out_count, 1, 0, s));
-    const int grid = grid_for(t->cfg.num_slots, 4 * kBlock, mt->sc.num_cus, 8);
+    const int grid = grid_for(t->cfg.num_slots, 4 * kBlock, num_cus, 8);
     hipLaunchKernelGGL(k_collect_delta, dim3(grid), dim3(kBlock), 0, s, identities, metadata, t->cfg.num_slots,
                        since_step, out_slots, out_ids, cap, (unsigned long long *)out_count);
     LAUNCH_CHECK();

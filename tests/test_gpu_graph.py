@@ -82,3 +82,76 @@ def test_captured_step_replays_match_the_oracle(policy):
     one_step()
     check(b, "eager call after the replays")
     g.close()
+
+
+def test_captured_jagged_step_replays_match_the_oracle():
+    """A step over a group of tables (mpzch_remap_jagged + mpzch_reset_rows_jagged) captured into a HIP
+    graph after mpzch_group_reserve and one eager call (which uploads the descriptors): the replays only
+    launch kernels.  Values and feature offsets live in device buffers that change between the replays;
+    total_values, step and the evicted-list layout are those of the capture."""
+    from test_gpu_jagged import JaggedPair
+
+    specs = [wl.TableSpec(3000, 16, 1, True, 41), wl.TableSpec(500, 8, 1, True, 42), wl.TableSpec(2000, 40, 0, False, 43),
+             wl.TableSpec(800, 16, 0, "lru", 44)]
+    jp = JaggedPair(specs)
+    jp.attach_rows([(3000, 8), (250, 4), None, (800, 16)])
+    T, total, step = len(specs), 6000, 4
+    rng = np.random.Generator(np.random.Philox(key=5150))
+    mp.mpzch_group_reserve(jp.group, total)
+    v = torch.zeros(total, dtype=torch.int64, device="cuda")
+    off = torch.zeros(T + 1, dtype=torch.int64, device="cuda")
+    out = torch.empty(total, dtype=torch.int64, device="cuda")
+    ev = torch.empty(total, dtype=torch.int64, device="cuda")
+    nev = torch.zeros(T, dtype=torch.int64, device="cuda")
+    stats = torch.zeros(T * mp.STAT_COUNT, dtype=torch.int64, device="cuda")
+    ev_off = [0, 1500, 3000, 4500, 6000]                     # fixed regions of the evicted list
+
+    def draw(k):
+        cuts = np.sort(rng.integers(0, total + 1, size=T - 1))
+        offsets = np.concatenate([[0], cuts, [total]]).astype(np.int64)
+        counts = np.diff(offsets)
+        vals = [wl.rank_to_id(rng.integers(0, 3 * s.num_slots, size=c) + (k % 3) * s.num_slots) for s, c in zip(specs, counts)]
+        return np.concatenate(vals).astype(np.int64), offsets
+
+    def one_step(at_step=step):
+        mp.mpzch_remap_jagged(jp.group, jp.I, jp.M, v, off, at_step, out, ev, ev_off, nev, stats)
+        mp.mpzch_reset_rows_jagged(jp.group, ev, ev_off, nev, jp.emb_g)
+
+    def check(values, offsets, what, at_step=step):
+        torch.cuda.synchronize()
+        so, evs, sts = oracle.remap_jagged(jp.o, values, offsets, at_step)
+        assert np.array_equal(out.cpu().numpy(), so), what
+        nev_h, ev_h = nev.cpu().numpy(), ev.cpu().numpy()
+        st_h = stats.cpu().numpy().reshape(T, mp.STAT_COUNT)
+        for f in range(T):
+            assert nev_h[f] == len(evs[f]) <= ev_off[f + 1] - ev_off[f], (what, f)
+            assert np.array_equal(np.sort(ev_h[ev_off[f]: ev_off[f] + nev_h[f]]), np.sort(evs[f])), (what, f)
+            assert dict(zip(mp.STAT_NAMES, st_h[f].tolist())) == sts[f], (what, f)
+            if jp.emb_o[f] is not None:
+                oracle.reset_rows(evs[f], jp.emb_o[f])
+                assert np.array_equal(jp.emb_g[f].cpu().numpy(), jp.emb_o[f]), (what, f)
+        jp.check_state()
+        return sum(s["evictions"] for s in sts)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    for early in range(3):                                   # eager calls at steps 0..2 fill the tables with ids
+        values, offsets = draw(early)                        # that have expired at the captured step; the first
+        with torch.cuda.stream(side):                        # one uploads the descriptors of both calls
+            v.copy_(torch.from_numpy(values).cuda())
+            off.copy_(torch.from_numpy(offsets).cuda())
+            one_step(early)
+        check(values, offsets, f"eager call {early}", early)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        one_step()
+    evictions = 0
+    for k in range(1, 6):
+        values, offsets = draw(k)
+        v.copy_(torch.from_numpy(values).cuda())
+        off.copy_(torch.from_numpy(offsets).cuda())
+        say("jagged graph replay", k)
+        graph.replay()
+        evictions += check(values, offsets, f"replay {k}")
+    assert evictions > 0
+    jp.close()
