@@ -25,7 +25,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 PROFILES = os.path.join(ROOT, "profiles")
 # which tracked rocprofv3 summary holds the HBM traffic of a workload's dominant kernel
-TRAFFIC_PROFILE = {"headline": "remap_headline_1Bslots_4Mids.txt", "c4": "remap_c4_500Mslots_2Mids.txt",
+TRAFFIC_PROFILE = {"headline": "remap_headline_1Bslots_4Mids.txt", "headline-separate": "remap_headline_1Bslots_4Mids_two_tensors.txt",
+                   "c4": "remap_c4_500Mslots_2Mids.txt", "c4-separate": "remap_c4_500Mslots_2Mids_two_tensors.txt",
                    "c5": "remap_jagged_c5_26tables.txt", "c3": "lookup_c3_100Mslots_1Mids.txt"}
 
 
@@ -120,6 +121,10 @@ def main():
     ap.add_argument("--all-kernel-timing", action="store_true",
                     help="bracket every kernel with events (a breakdown; costs a step some 30 us), not only Pass 1")
     ap.add_argument("--policy", default="ttl", choices=["ttl", "lru"], help="eviction policy (headline / c4 workloads)")
+    ap.add_argument("--layout", default="records", choices=["separate", "records"],
+                    help="headline / c4: identities and metadata as one tensor of 16-byte records {int64 id, int32 "
+                         "metadata, 4 unused bytes} (default: a hit then refreshes the line it has just read), or as "
+                         "two dense tensors")
     ap.add_argument("--graph", action="store_true",
                     help="c1 / c2: capture the timed steps into one HIP graph and time its replay (no launch overhead on the host)")
     args = ap.parse_args()
@@ -154,7 +159,8 @@ def main():
         f"prefill={spec.prefill_ids} emb={t.emb_rows}x{t.emb_dim} {t.emb_dtype}")
 
     kind = mp.EVICT_LRU if args.policy == "lru" else mp.EVICT_TTL
-    g = mp.MpzchTable(t.num_slots, t.max_probe, kind, t.ttl, t.hash_seed, max_batch=max(spec.batch, 1 << 24))
+    g = mp.MpzchTable(t.num_slots, t.max_probe, kind, t.ttl, t.hash_seed, max_batch=max(spec.batch, 1 << 24),
+                      layout=mp.LAYOUT_RECORDS if args.layout == "records" else mp.LAYOUT_SEPARATE)
     emb = torch.ones((t.emb_rows, t.emb_dim), dtype=torch.bfloat16, device=dev)
 
     # ---- prefill at step 0 (ids PREFILL_ID_BASE + k, generated on the device in chunks)
@@ -200,8 +206,8 @@ def main():
     host_I = host_M = None
     if args.cpu_steps > 0:
         t0 = time.perf_counter()
-        host_I = g.identities.cpu().numpy()
-        host_M = g.metadata.cpu().numpy()
+        host_I = np.ascontiguousarray(g.identities.cpu().numpy())
+        host_M = np.ascontiguousarray(g.metadata.cpu().numpy())
         log(f"[bench] copied table state to host in {time.perf_counter() - t0:.2f}s")
 
     # HIP events around the dominant kernel (Pass 1) of every timed step, recorded by the library on
@@ -250,7 +256,9 @@ def main():
             alg = (8.0 * total_ids + 8.0 * hit_pos + u_hit * (8.0 * mean_probe + 4.0) + d_miss * 8.0 * mean_miss_len) / K
             # requests: one line read per position (plus the further lines of parked ids), one metadata store per hit position
             lines = total_ids / K + (miss_pos + max(probe_sum - hit_pos, 0) / 8.0) / K
-            roofline = roofline_entry(args.workload, args.scale, dom, avg_ms, alg, lines, hit_pos / K)
+            key = args.workload if args.layout == "records" else args.workload + "-separate"
+            # with records the refresh goes into the line just read: no separate random store
+            roofline = roofline_entry(key, args.scale, dom, avg_ms, alg, lines, hit_pos / K if args.layout == "separate" else 0.0)
         else:
             roofline = {"bound": "hbm", "kernel": dom, "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                         "frac": None, "traffic": None, "avg_kernel_ms": round(avg_ms, 4)}
@@ -295,8 +303,10 @@ def main():
             "workload": f"{args.workload}: {t.num_slots}-slot table, P={t.max_probe}, "
                         f"{'LRU' if args.policy == 'lru' else 'TTL=' + str(t.ttl)}, load "
                         f"{spec.prefill_ids / t.num_slots:.2f}, {spec.batch} ids/step, "
-                        f"{int(spec.new_fraction * 100)}% new ids/step, reset rows of {t.emb_rows}x{t.emb_dim} bf16",
+                        f"{int(spec.new_fraction * 100)}% new ids/step, reset rows of {t.emb_rows}x{t.emb_dim} bf16, "
+                        f"identities+metadata as {'16-byte records' if args.layout == 'records' else 'two tensors'}",
             "num_slots": t.num_slots, "max_probe": t.max_probe, "ttl": t.ttl, "batch": spec.batch, "scale": args.scale,
+            "layout": args.layout,
         },
         "per_step": {
             "distinct_ids": round(u_total / K, 1), "hit_positions": round(hit_pos / K, 1),

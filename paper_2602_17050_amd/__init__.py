@@ -11,7 +11,7 @@ _BINDING_NAMES = (
     "mpzch_create", "mpzch_destroy", "mpzch_init_tensors", "mpzch_remap", "mpzch_lookup",
     "mpzch_reset_rows", "mpzch_remap_jagged", "mpzch_status_string",
     "mpzch_reset_rows_multi", "mpzch_lookup_gather", "mpzch_collect_delta", "mpzch_gather_rows", "mpzch_apply_delta",
-    "EVICT_NONE", "EVICT_TTL", "EVICT_LRU", "EVICT_TTL_EXPIRY", "mpzch_remap_feature_ttl", "mpzch_remap_jagged_feature_ttl", "mpzch_lookup_jagged", "mpzch_reset_rows_jagged", "STAT_NAMES",
+    "EVICT_NONE", "EVICT_TTL", "EVICT_LRU", "EVICT_TTL_EXPIRY", "mpzch_remap_feature_ttl", "mpzch_remap_jagged_feature_ttl", "mpzch_lookup_jagged", "mpzch_reset_rows_jagged", "STAT_NAMES", "mpzch_create_with_layout", "mpzch_lookup_stats", "mpzch_remap_noalloc", "LAYOUT_SEPARATE", "LAYOUT_RECORDS",
 )
 
 

@@ -26,8 +26,9 @@ EXPORTED = (
     "mpzch_group_set_kernel_timing", "mpzch_group_kernel_times", "mpzch_status_string",
     "mpzch_remap_feature_ttl", "mpzch_reset_rows_multi", "mpzch_lookup_gather", "mpzch_collect_delta", "mpzch_gather_rows", "mpzch_apply_delta",
     "mpzch_remap_jagged_feature_ttl", "mpzch_lookup_jagged", "mpzch_reset_rows_jagged",
-    "mpzch_remap_noalloc", "mpzch_lookup_stats",
+    "mpzch_remap_noalloc", "mpzch_lookup_stats", "mpzch_create_with_layout",
 )
+LAYOUT_SEPARATE, LAYOUT_RECORDS = 0, 1
 NOALLOC_MAX_BATCH = 262144
 
 
@@ -62,6 +63,7 @@ def load_library(path: str | None = None):
     lib = ctypes.CDLL(path)
     vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
     lib.mpzch_create.argtypes = [i64, i32, _Policy, ctypes.c_uint64, ctypes.POINTER(vp)]
+    lib.mpzch_create_with_layout.argtypes = [i64, i32, _Policy, ctypes.c_uint64, i32, ctypes.POINTER(vp)]
     lib.mpzch_destroy.argtypes = [vp]
     lib.mpzch_reserve.argtypes = [vp, i64]
     lib.mpzch_init_tensors.argtypes = [vp, vp, vp, vp]
@@ -112,7 +114,9 @@ def _check(status: int, what: str):
 def _ptr(t, dtype=None):
     if t is None:
         return None
-    assert t.is_cuda and t.is_contiguous(), "device, contiguous tensors only"
+    # dense tensors, or the strided views of a table kept as 16-byte records (identities: every second
+    # int64, metadata: every fourth int32)
+    assert t.is_cuda and (t.is_contiguous() or (t.dim() == 1 and t.stride(0) in (2, 4))), "device, dense tensors only"
     if dtype is not None:
         assert t.dtype == dtype, (t.dtype, dtype)
     return ctypes.c_void_p(t.data_ptr())
@@ -130,6 +134,20 @@ def mpzch_create(num_slots: int, max_probe: int, eviction_policy=(EVICT_TTL, 0),
     _check(load_library().mpzch_create(num_slots, max_probe, pol, ctypes.c_uint64(hash_seed & (2 ** 64 - 1)),
                                        ctypes.byref(h)), "mpzch_create")
     return h
+
+
+def mpzch_create_with_layout(num_slots: int, max_probe: int, eviction_policy=(EVICT_TTL, 0), hash_seed: int = 0,
+                             layout: int = LAYOUT_SEPARATE):
+    h = ctypes.c_void_p()
+    pol = _Policy(int(eviction_policy[0]), int(eviction_policy[1]))
+    _check(load_library().mpzch_create_with_layout(num_slots, max_probe, pol, ctypes.c_uint64(hash_seed & (2 ** 64 - 1)),
+                                                   int(layout), ctypes.byref(h)), "mpzch_create_with_layout")
+    return h
+
+
+def records_views(records, num_slots: int):
+    """(identities, metadata) views of a table kept as num_slots 16-byte records in an int64[2 * num_slots] tensor."""
+    return records.view(num_slots, 2)[:, 0], records.view(torch.int32).view(num_slots, 4)[:, 2]
 
 
 def mpzch_destroy(handle):
@@ -356,11 +374,17 @@ def mpzch_group_kernel_times(group):
 class MpzchTable:
     """Owns the tensors of one table (torch device memory) and its handle."""
 
-    def __init__(self, num_slots, max_probe, kind=EVICT_TTL, ttl=0, hash_seed=0, device="cuda", max_batch=0):
+    def __init__(self, num_slots, max_probe, kind=EVICT_TTL, ttl=0, hash_seed=0, device="cuda", max_batch=0,
+                 layout=LAYOUT_SEPARATE):
         self.num_slots, self.max_probe, self.kind, self.ttl, self.hash_seed = num_slots, max_probe, kind, ttl, hash_seed
-        self.handle = mpzch_create(num_slots, max_probe, (kind, ttl), hash_seed)
-        self.identities = torch.empty(num_slots, dtype=torch.int64, device=device)
-        self.metadata = torch.empty(num_slots, dtype=torch.int32, device=device)
+        self.layout = layout
+        self.handle = mpzch_create_with_layout(num_slots, max_probe, (kind, ttl), hash_seed, layout)
+        if layout == LAYOUT_RECORDS:
+            self.records = torch.empty(2 * num_slots, dtype=torch.int64, device=device)
+            self.identities, self.metadata = records_views(self.records, num_slots)
+        else:
+            self.identities = torch.empty(num_slots, dtype=torch.int64, device=device)
+            self.metadata = torch.empty(num_slots, dtype=torch.int32, device=device)
         mpzch_init_tensors(self.handle, self.identities, self.metadata)
         self.num_evicted = torch.zeros(1, dtype=torch.int64, device=device)
         self.stats = torch.zeros(STAT_COUNT, dtype=torch.int64, device=device)

@@ -20,6 +20,7 @@ struct TableCfg {
     int32_t kind;
     int32_t ttl;
     uint64_t seed;
+    int32_t layout;                // MPZCH_LAYOUT_*
 };
 
 // ---- per-kernel timing --------------------------------------------------------------------
@@ -240,7 +241,7 @@ TableDesc make_desc(const TableCfg &c, int64_t *I, int32_t *M, int64_t ev_begin,
     d.P = p_eff(c);
     d.ttl = c.ttl;
     d.evict = c.kind == MPZCH_EVICT_TTL ? 1 : c.kind == MPZCH_EVICT_LRU ? 2 : c.kind == MPZCH_EVICT_TTL_EXPIRY ? 3 : 0;
-    d.pad_ = 0;
+    d.sh = c.layout == MPZCH_LAYOUT_RECORDS ? 1 : 0;
     d.ev_begin = ev_begin;
     d.ev_cap = ev_cap;
     return d;
@@ -256,6 +257,7 @@ mpzch_status_t launch_discover(const Params &p, int grid, hipStream_t s)
 {
     if (TRAIN) {
         if (p.num_tables > 1) hipLaunchKernelGGL(k_discover_tables, dim3(grid), dim3(kBlock), 0, s, p);
+        else if (p.t0.sh) hipLaunchKernelGGL(k_discover_records, dim3(grid), dim3(kBlock), 0, s, p);
         else hipLaunchKernelGGL(k_discover, dim3(grid), dim3(kBlock), 0, s, p);
     } else {
         if (p.num_tables > 1) hipLaunchKernelGGL(k_lookup_tables, dim3(grid), dim3(kBlock), 0, s, p);
@@ -383,6 +385,16 @@ mpzch_status_t fill32(int32_t *dst, int64_t count, int32_t value, hipStream_t s)
     return MPZCH_OK;
 }
 
+// one tensor of 16-byte records: identities points at record 0 (16-byte aligned), metadata at its third word
+bool records_ok(const int64_t *identities, const int32_t *metadata)
+{
+    return !((uintptr_t)identities & 15) && (const void *)metadata == (const void *)((const int32_t *)identities + 2);
+}
+bool layout_ok(const TableCfg &c, const int64_t *identities, const int32_t *metadata)
+{
+    return c.layout != MPZCH_LAYOUT_RECORDS || records_ok(identities, metadata);
+}
+
 bool valid_cfg(int64_t num_slots, int32_t max_probe, mpzch_eviction_policy_t policy)
 {
     if (num_slots < 1 || max_probe < 1 || max_probe > MPZCH_MAX_PROBE) return false;
@@ -490,13 +502,20 @@ extern "C" {
 mpzch_status_t mpzch_create(int64_t num_slots, int32_t max_probe, mpzch_eviction_policy_t policy,
                             uint64_t hash_seed, mpzch_table_t **out)
 {
+    return mpzch_create_with_layout(num_slots, max_probe, policy, hash_seed, MPZCH_LAYOUT_SEPARATE, out);
+}
+
+mpzch_status_t mpzch_create_with_layout(int64_t num_slots, int32_t max_probe, mpzch_eviction_policy_t policy,
+                                        uint64_t hash_seed, int32_t layout, mpzch_table_t **out)
+{
     if (!out) return MPZCH_ERR_INVALID_ARG;
     *out = nullptr;
+    if (layout != MPZCH_LAYOUT_SEPARATE && layout != MPZCH_LAYOUT_RECORDS) return MPZCH_ERR_INVALID_ARG;
     if (!valid_cfg(num_slots, max_probe, policy)) return MPZCH_ERR_INVALID_ARG;
     if (policy.kind == MPZCH_EVICT_LRU && max_probe > MPZCH_MAX_PROBE_LRU) return MPZCH_ERR_UNSUPPORTED;
     mpzch_table *t = new (std::nothrow) mpzch_table();
     if (!t) return MPZCH_ERR_ALLOC;
-    t->cfg = {num_slots, max_probe, policy.kind, policy.ttl, hash_seed};
+    t->cfg = {num_slots, max_probe, policy.kind, policy.ttl, hash_seed, layout};
     *out = t;
     return MPZCH_OK;
 }
@@ -520,6 +539,14 @@ mpzch_status_t mpzch_init_tensors(const mpzch_table_t *t, int64_t *identities, i
 {
     if (!t || !identities) return MPZCH_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)stream;
+    if (t->cfg.layout == MPZCH_LAYOUT_RECORDS) {
+        if (!records_ok(identities, metadata)) return MPZCH_ERR_INVALID_ARG;
+        const int64_t count = t->cfg.num_slots;
+        const int grid = (int)((count + kBlock - 1) / kBlock < 4096 ? (count + kBlock - 1) / kBlock : 4096);
+        hipLaunchKernelGGL(k_init_records, dim3(grid), dim3(kBlock), 0, s, (u32x4 *)identities, count);
+        LAUNCH_CHECK();
+        return MPZCH_OK;
+    }
     TRY(fill64(identities, t->cfg.num_slots, -1, s));
     if (metadata) TRY(fill32(metadata, t->cfg.num_slots, -1, s));
     return MPZCH_OK;
@@ -534,6 +561,7 @@ mpzch_status_t mpzch_remap_feature_ttl(mpzch_table_t *t, int64_t *identities, in
     if (!t || !identities || !metadata || !out_num_evicted) return MPZCH_ERR_INVALID_ARG;
     if (n < 0 || n > MPZCH_MAX_BATCH || step < 0 || evicted_cap < 0) return MPZCH_ERR_INVALID_ARG;
     if (ttls && t->cfg.kind != MPZCH_EVICT_TTL_EXPIRY) return MPZCH_ERR_INVALID_ARG;
+    if (!layout_ok(t->cfg, identities, metadata)) return MPZCH_ERR_INVALID_ARG;
     if (n > 0 && (!ids || !out_slots)) return MPZCH_ERR_INVALID_ARG;
     if (evicted_cap > 0 && !out_evicted_slots) return MPZCH_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)stream;
@@ -577,6 +605,7 @@ mpzch_status_t mpzch_remap_noalloc(const mpzch_table_t *t, int64_t *identities, 
     if (!t || !identities || !metadata || !out_num_evicted) return MPZCH_ERR_INVALID_ARG;
     if (n < 0 || step < 0 || evicted_cap < 0) return MPZCH_ERR_INVALID_ARG;
     if (n > MPZCH_NOALLOC_MAX_BATCH) return MPZCH_ERR_TOO_LARGE;
+    if (!layout_ok(t->cfg, identities, metadata)) return MPZCH_ERR_INVALID_ARG;
     if (n > 0 && (!ids || !out_slots)) return MPZCH_ERR_INVALID_ARG;
     if (evicted_cap > 0 && !out_evicted_slots) return MPZCH_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)stream;
@@ -608,6 +637,7 @@ mpzch_status_t mpzch_lookup(const mpzch_table_t *t, const int64_t *identities,
 {
     if (!t || !identities) return MPZCH_ERR_INVALID_ARG;
     if (n < 0 || n > MPZCH_MAX_BATCH) return MPZCH_ERR_INVALID_ARG;
+    if (t->cfg.layout == MPZCH_LAYOUT_RECORDS && ((uintptr_t)identities & 15)) return MPZCH_ERR_INVALID_ARG;
     if (n == 0) return MPZCH_OK;
     if (!ids || !out_slots) return MPZCH_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)stream;
@@ -817,12 +847,14 @@ mpzch_status_t mpzch_collect_delta(const mpzch_table_t *t, const int64_t *identi
 {
     if (!t || !identities || !metadata || !out_count || cap < 0) return MPZCH_ERR_INVALID_ARG;
     if (cap > 0 && (!out_slots || !out_ids)) return MPZCH_ERR_INVALID_ARG;
+    if (!layout_ok(t->cfg, identities, metadata)) return MPZCH_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)stream;
     int num_cus = 0;
     TRY(device_cus(&num_cus));
     TRY(fill64(out_count, 1, 0, s));
     const int grid = grid_for(t->cfg.num_slots, 4 * kBlock, num_cus, 8);
-    hipLaunchKernelGGL(k_collect_delta, dim3(grid), dim3(kBlock), 0, s, identities, metadata, t->cfg.num_slots,
+    hipLaunchKernelGGL(k_collect_delta, dim3(grid), dim3(kBlock), 0, s, identities, metadata,
+                       t->cfg.layout == MPZCH_LAYOUT_RECORDS ? 1 : 0, t->cfg.num_slots,
                        since_step, out_slots, out_ids, cap, (unsigned long long *)out_count);
     LAUNCH_CHECK();
     return MPZCH_OK;
@@ -915,6 +947,7 @@ mpzch_status_t mpzch_remap_jagged_feature_ttl(mpzch_group_t *g, int64_t *const *
     std::vector<TableDesc> descs((size_t)T);
     for (int f = 0; f < T; ++f) {
         if (!identities[f] || !metadata[f]) return MPZCH_ERR_INVALID_ARG;
+        if (!layout_ok(g->cfgs[f], identities[f], metadata[f])) return MPZCH_ERR_INVALID_ARG;
         const int64_t cap = evicted_offsets[f + 1] - evicted_offsets[f];
         if (cap < 0 || evicted_offsets[f] < 0) return MPZCH_ERR_INVALID_ARG;
         if (cap > 0 && !out_evicted_slots) return MPZCH_ERR_INVALID_ARG;

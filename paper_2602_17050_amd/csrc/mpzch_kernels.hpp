@@ -57,7 +57,8 @@ struct TableDesc {
     int32_t P;             // min(max_probe, N)
     int32_t ttl;
     int32_t evict;         // 0 = off, 1 = TTL (metadata = last-seen step), 2 = LRU, 3 = TTL with metadata = expiry step
-    int32_t pad_;
+    int32_t sh;            // 0: identities and metadata are two dense tensors; 1: one tensor of 16-byte records
+                           // {int64 id; int32 metadata; int32 unused}, I = &record[0].id, M = &record[0].metadata
     int64_t ev_begin;      // where this table's evicted list starts in out_evicted
     int64_t ev_cap;
 };
@@ -198,7 +199,19 @@ struct Tab {
     int32_t P;
     int32_t ttl;
     int32_t evict;
+    int32_t sh;
 };
+
+// Where slot s lives.  Two dense tensors (sh = 0): I[s], M[s].  One tensor of 16-byte records (sh = 1): the id of
+// slot s is the int64 at I + 2 s, its metadata the int32 at M + 4 s -- the line that a probe fetches then also
+// holds the metadata word that a hit refreshes.
+__device__ __forceinline__ global_ptr<int64_t> id_at(const Tab &d, int64_t s) { return d.I + (s << d.sh); }
+__device__ __forceinline__ global_ptr<int32_t> meta_at(const Tab &d, int64_t s) { return d.M + (s << (2 * d.sh)); }
+// identities of slot s's aligned block of 8 (64 bytes, or 128 bytes of records): how far s lies into it
+__device__ __forceinline__ int block_offset(const Tab &d, int64_t s, int slots)
+{
+    return (int)((s + (int64_t)(((uintptr_t)d.I >> (3 + d.sh)) & (uintptr_t)(slots - 1))) & (slots - 1));
+}
 
 __device__ __forceinline__ Tab view(const TableDesc &d)
 {
@@ -210,6 +223,7 @@ __device__ __forceinline__ Tab view(const TableDesc &d)
     t.P = d.P;
     t.ttl = d.ttl;
     t.evict = d.evict;
+    t.sh = d.sh;
     return t;
 }
 
@@ -231,8 +245,8 @@ __device__ __forceinline__ int32_t meta_value(const Params &p, const Tab &d, int
 // every value written at this step.)
 __device__ __forceinline__ void store_meta(const Tab &d, int64_t s, int32_t value)
 {
-    if (d.evict == 3) __hip_atomic_fetch_max(&d.M[s], value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    else d.M[s] = value;
+    if (d.evict == 3) __hip_atomic_fetch_max(meta_at(d, s), value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else *meta_at(d, s) = value;
 }
 
 // TTL test of Sec. 3.4 on metadata m of a slot that holds an id
@@ -416,7 +430,7 @@ __device__ __forceinline__ int probe_pass(const Tab &d, int64_t id, int64_t home
         // lanes without a slot: the home slot when their id is being probed (the line is fetched anyway),
         // else slot 0 (ids that are switched off share one line; the home slot of another, larger table
         // would not be a valid address here)
-        v[t] = d.I[act ? wrap(ghome + round, d.N) : ((gq < d.P && ghome < d.N) ? ghome : 0)];
+        v[t] = *id_at(d, act ? wrap(ghome + round, d.N) : ((gq < d.P && ghome < d.N) ? ghome : 0));
         act_bits |= (uint32_t)act << t;
     }
     int found = kProbeGoOn;
@@ -645,7 +659,7 @@ __device__ __forceinline__ void discover_body(const Params &p)
             const bool valid = mine && id >= 0;
             const int64_t home = mine ? home_slot(id, d.seed, d.N) : 0;
             // first pass: the aligned 64 bytes that hold the home slot
-            const int o = (int)((home + (int64_t)(((uintptr_t)d.I >> 3) & (kFirstG - 1))) & (kFirstG - 1));
+            const int o = block_offset(d, home, kFirstG);
             int res = probe_pass<kFirstG>(d, id, home, valid ? -o : d.P);
             if (res == kProbeGoOn && kFirstG - o >= d.P) res = probe_absent(d.P - 1);    // the whole window was read
             const bool hit = valid && res >= 0;
@@ -707,6 +721,13 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     discover_body<true, false, false>(p);
 }
 
+// the same pass over a table kept as 16-byte records: the metadata store lands in the line just read, the
+// pass is bound by its reads and gains a little from more wavefronts (measured: 2 and 3 alike, 4 best)
+__global__ __launch_bounds__(kBlock, 4) void k_discover_records(Params p)
+{
+    discover_body<true, false, false>(p);
+}
+
 __global__ __launch_bounds__(kBlock, 4) void k_lookup(Params p)
 {
     discover_body<false, false, false>(p);
@@ -736,7 +757,7 @@ __global__ __launch_bounds__(kBlock, 4) void k_lookup_tables(Params p)
 // TTL test of Sec. 3.4 on a slot that holds an id
 __device__ __forceinline__ bool expired(const Tab &d, int32_t step, int64_t s)
 {
-    return is_expired(d.evict, d.ttl, step, d.M[s]);
+    return is_expired(d.evict, d.ttl, step, *meta_at(d, s));
 }
 
 // One workgroup = one wavefront.  Lane phase: the first PMAX slots of the windows (identities and
@@ -767,7 +788,7 @@ __device__ __forceinline__ int32_t claim_wave(const Params &p, const Tab &d, uin
         int64_t s = 0;
         if (round < d.P) {
             s = wrap(home + round, d.N);
-            const int64_t v = __hip_atomic_load(&d.I[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const int64_t v = __hip_atomic_load(id_at(d, s), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (v == -1) cand = true;
             else if (v >= 0) { cand = expired(d, p.step, s); occ = 1; }
             else { occ = tag_occ(v); cand = v > make_tag((uint32_t)round, cpos, occ); }
@@ -782,7 +803,7 @@ __device__ __forceinline__ int32_t claim_wave(const Params &p, const Tab &d, uin
             int64_t old = 0, mine = 0;
             if (lane == first) {
                 mine = make_tag((uint32_t)round, cpos, occ);
-                old = __hip_atomic_fetch_min(&d.I[s], mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                old = __hip_atomic_fetch_min(id_at(d, s), mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
             old = shfl64(old, first);
             mine = shfl64(mine, first);
@@ -814,7 +835,7 @@ __device__ __forceinline__ int32_t claim_wave(const Params &p, const Tab &d, uin
 // What the lanes that load a claimant's window need of the claimant's table (several tables only)
 struct TabWords {
     int64_t I, M, N;
-    int32_t P, ttl, evict, pad_;
+    int32_t P, ttl, evict, sh;
 };
 
 // One wavefront serves the segments vblock, vblock + vgrid, ...; s_I and s_d are that wavefront's own
@@ -860,7 +881,7 @@ __device__ __forceinline__ void allocate_body(const Params &p, int64_t vblock, i
             }
             if (!agent) home = 0;
             if constexpr (MULTI) {
-                s_d[lane] = TabWords{(int64_t)d.I, (int64_t)d.M, d.N, d.P, d.ttl, d.evict, 0};
+                s_d[lane] = TabWords{(int64_t)d.I, (int64_t)d.M, d.N, d.P, d.ttl, d.evict, d.sh};
                 __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             }
             // cooperative loads; lanes without a slot to read use slot 0 / the home slot (valid addresses)
@@ -873,20 +894,21 @@ __device__ __forceinline__ void allocate_body(const Params &p, int64_t vblock, i
                 global_ptr<int64_t> gI = d0.I;
                 global_ptr<int32_t> gM = d0.M;
                 int64_t gN = d0.N;
-                int gP = d0.P;
+                int gP = d0.P, gsh = d0.sh;
                 if constexpr (MULTI) {
                     const TabWords &gd = s_d[a];
                     gI = (global_ptr<int64_t>)gd.I;
                     gM = (global_ptr<int32_t>)gd.M;
                     gN = gd.N;
                     gP = gd.P;
+                    gsh = gd.sh;
                 }
 #pragma unroll
                 for (int c = 0; c < CH; ++c) {
                     const int k = c * G + r;
                     const int64_t sl = k < gP ? wrap(ghome + k, gN) : ghome;
-                    vi[t * CH + c] = __hip_atomic_load(&gI[sl], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    vm[t * CH + c] = gM[sl];
+                    vi[t * CH + c] = __hip_atomic_load(gI + (sl << gsh), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    vm[t * CH + c] = gM[sl << (2 * gsh)];
                 }
             }
 #pragma unroll
@@ -922,7 +944,7 @@ __device__ __forceinline__ void allocate_body(const Params &p, int64_t vblock, i
                     else { occ = tag_occ(v); cand = v > make_tag((uint32_t)k, pos, occ); }
                     if (!cand) continue;
                     const int64_t mine = make_tag((uint32_t)k, pos, occ);
-                    const int64_t old = __hip_atomic_fetch_min(&d.I[wrap(home + k, d.N)], mine, __ATOMIC_RELAXED,
+                    const int64_t old = __hip_atomic_fetch_min(id_at(d, wrap(home + k, d.N)), mine, __ATOMIC_RELAXED,
                                                                __HIP_MEMORY_SCOPE_AGENT);
                     if (is_tag(old) && old < mine) continue;      // a better claim got there first
                     hint = (uint32_t)k;
@@ -995,8 +1017,8 @@ __device__ __forceinline__ int32_t claim_group_lru(const Params &p, const Tab &d
         int32_t m = 0;
         if (in) {
             s = wrap(home_slot(p.ids[cpos], d.seed, d.N) + r, d.N);
-            v = __hip_atomic_load(&d.I[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            m = d.M[s];
+            v = __hip_atomic_load(id_at(d, s), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            m = *meta_at(d, s);
         }
         const bool base_empty = in && (v == -1 || (is_tag(v) && !tag_occ(v)));
         const bool evictable = in && (v >= 0 || (is_tag(v) && tag_occ(v))) && m != p.step;
@@ -1023,7 +1045,7 @@ __device__ __forceinline__ int32_t claim_group_lru(const Params &p, const Tab &d
             int64_t old = 0, mine = 0;
             if (lane == who) {
                 mine = make_tag((uint32_t)choice, cpos, base_empty ? 0u : 1u);
-                old = __hip_atomic_fetch_min(&d.I[s], mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                old = __hip_atomic_fetch_min(id_at(d, s), mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
             const int from = who >= 0 ? who : lane;
             old = shfl64(old, from);
@@ -1145,8 +1167,8 @@ __device__ __forceinline__ int32_t claim_wave_lru_long(const Params &p, const Ta
             const int round = c * kWave + lane;
             const bool in = c < C && round < d.P;
             const int64_t s = in ? wrap(home + round, d.N) : home;      // a valid address either way
-            const int64_t v = __hip_atomic_load(&d.I[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            m[c] = d.M[s];
+            const int64_t v = __hip_atomic_load(id_at(d, s), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            m[c] = *meta_at(d, s);
             const bool be = v == -1 || (is_tag(v) && !tag_occ(v));
             const bool oc = v >= 0 || (is_tag(v) && tag_occ(v));
             if (in && be) emp |= 1u << c;
@@ -1198,7 +1220,7 @@ __device__ __forceinline__ int32_t claim_wave_lru_long(const Params &p, const Ta
             int64_t old = 0, mine = 0;
             if (lane == who) {
                 mine = make_tag((uint32_t)choice, cpos, occ);
-                old = __hip_atomic_fetch_min(&d.I[wrap(home + round, d.N)], mine, __ATOMIC_RELAXED,
+                old = __hip_atomic_fetch_min(id_at(d, wrap(home + round, d.N)), mine, __ATOMIC_RELAXED,
                                              __HIP_MEMORY_SCOPE_AGENT);
             }
             old = shfl64(old, who);
@@ -1427,7 +1449,7 @@ __device__ __forceinline__ void finalize_body(const Params &p)
                 home = p.homes[idx];
                 h = p.hint[first];
                 if (h < kHintUnknown) {
-                    const int64_t v = d.I[wrap(home + (int)h, d.N)];
+                    const int64_t v = *id_at(d, wrap(home + (int)h, d.N));
                     if (is_claim_of(v, first, id)) { at = (int)h; occ = tag_occ(v); }
                 }
                 search = at < 0 && h != kHintUnplaced;
@@ -1449,7 +1471,7 @@ __device__ __forceinline__ void finalize_body(const Params &p)
                     bool mine = false;
                     uint32_t o = 0;
                     if (round < dw.P) {
-                        const int64_t v = dw.I[wrap(chome + round, dw.N)];
+                        const int64_t v = *id_at(dw, wrap(chome + round, dw.N));
                         mine = is_claim_of(v, cfirst, cid);
                         o = tag_occ(v);
                     }
@@ -1469,7 +1491,7 @@ __device__ __forceinline__ void finalize_body(const Params &p)
                     // claim: Case 3, the home slot's metadata is refreshed.  (The agent always meets its
                     // own tag: nobody else replaces it.)
                     if (at >= 0) {
-                        d.I[s_final] = id;
+                        *id_at(d, s_final) = id;
                         outcome = (int)occ;
                     }
                     store_meta(d, s_final, meta_value(p, d, pos));
@@ -1505,6 +1527,14 @@ __global__ __launch_bounds__(kBlock) void k_fill64(long long *dst, int64_t count
 {
     for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < count; i += (int64_t)gridDim.x * kBlock)
         dst[i] = value;
+}
+
+// initial state of a table kept as 16-byte records: id = -1, metadata = -1, the unused word 0
+__global__ __launch_bounds__(kBlock) void k_init_records(u32x4 *dst, int64_t count)
+{
+    const u32x4 v = {0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0u};
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < count; i += (int64_t)gridDim.x * kBlock)
+        dst[i] = v;
 }
 
 __global__ __launch_bounds__(kBlock) void k_fill32(int32_t *dst, int64_t count, int32_t value)
@@ -1687,7 +1717,7 @@ __global__ __launch_bounds__(kBlock) void k_apply_delta_ids(int64_t *identities,
 constexpr int kDeltaStage = 1024;
 constexpr int kDeltaPerThread = 4;     // slots a thread looks at between two workgroup barriers
 
-__global__ __launch_bounds__(kBlock) void k_collect_delta(const int64_t *identities, const int32_t *metadata,
+__global__ __launch_bounds__(kBlock) void k_collect_delta(const int64_t *identities, const int32_t *metadata, int sh,
                                                           int64_t num_slots, int32_t since, int64_t *out_slots,
                                                           int64_t *out_ids, int64_t cap, unsigned long long *out_count)
 {
@@ -1705,7 +1735,7 @@ __global__ __launch_bounds__(kBlock) void k_collect_delta(const int64_t *identit
         __syncthreads();       // everyone has read s_n and sees s_base
         for (int i = threadIdx.x; i < n; i += kBlock) {
             const int64_t at = (int64_t)s_base + i;
-            if (at < cap) { out_slots[at] = s_slot[i]; out_ids[at] = identities[s_slot[i]]; }
+            if (at < cap) { out_slots[at] = s_slot[i]; out_ids[at] = identities[s_slot[i] << sh]; }
         }
         if (threadIdx.x == 0) s_n = 0;
         __syncthreads();       // the staging area is free again before anyone adds to it
@@ -1714,7 +1744,7 @@ __global__ __launch_bounds__(kBlock) void k_collect_delta(const int64_t *identit
 #pragma unroll
         for (int k = 0; k < kDeltaPerThread; ++k) {
             const int64_t s = base + k * kBlock + threadIdx.x;
-            if (s < hi && identities[s] >= 0 && metadata[s] >= since) s_slot[atomicAdd(&s_n, 1)] = s;
+            if (s < hi && identities[s << sh] >= 0 && metadata[s << (2 * sh)] >= since) s_slot[atomicAdd(&s_n, 1)] = s;
         }
         __syncthreads();
         // The decision to flush is taken by all threads from the same value: s_n does not change

@@ -15,12 +15,14 @@ def say(*a):
 class Pair:
     """One table on both sides."""
 
-    def __init__(self, num_slots, max_probe, ttl, evict=True, hash_seed=0, emb=None):
+    def __init__(self, num_slots, max_probe, ttl, evict=True, hash_seed=0, emb=None, layout="separate"):
         # evict: True = TTL, False = off, "lru" = LRU, "expiry" = per-feature TTL (metadata = expiry step)
         kind_g = {"lru": mp.EVICT_LRU, "expiry": mp.EVICT_TTL_EXPIRY}.get(evict, mp.EVICT_TTL if evict else mp.EVICT_NONE)
         kind_o = {"lru": oracle.EVICT_LRU, "expiry": oracle.EVICT_TTL_EXPIRY}.get(
             evict, oracle.EVICT_TTL if evict else oracle.EVICT_NONE)
-        self.g = mp.MpzchTable(num_slots, max_probe, kind_g, ttl, hash_seed)
+        # layout: "separate" = two dense tensors, "records" = one tensor of 16-byte records
+        self.g = mp.MpzchTable(num_slots, max_probe, kind_g, ttl, hash_seed,
+                               layout=mp.LAYOUT_RECORDS if layout == "records" else mp.LAYOUT_SEPARATE)
         self.o = oracle.Table(num_slots, max_probe, kind_o, ttl, hash_seed)
         self.emb_o = None
         self.emb_g = None
@@ -29,11 +31,11 @@ class Pair:
             self.emb_g = torch.from_numpy(emb).cuda()
 
     @classmethod
-    def from_spec(cls, spec: wl.TableSpec, with_emb=True):
+    def from_spec(cls, spec: wl.TableSpec, with_emb=True, layout="separate"):
         emb = None
         if with_emb and spec.emb_rows:
             emb = wl.embedding_pattern(spec.emb_rows, spec.emb_dim, np.float32)
-        return cls(spec.num_slots, spec.max_probe, spec.ttl, spec.evict, spec.hash_seed, emb)
+        return cls(spec.num_slots, spec.max_probe, spec.ttl, spec.evict, spec.hash_seed, emb, layout)
 
     def step(self, ids_np, step, check_state=True, init_row=None, ttls=None):
         ids_np = np.ascontiguousarray(ids_np, dtype=np.int64)

@@ -38,15 +38,16 @@ def _sampled_state_check(o, rng, ranges=4, width=1_000_000):
     assert bad == 0, first_bad
 
 
-def _stream_parity(spec, steps, emb_check_rows=0, lru=False):
+def _stream_parity(spec, steps, emb_check_rows=0, lru=False, records=False):
     t = spec.table
     kind_g, kind_o = (mp.EVICT_LRU, oracle.EVICT_LRU) if lru else (mp.EVICT_TTL, oracle.EVICT_TTL)
-    g = mp.MpzchTable(t.num_slots, t.max_probe, kind_g, t.ttl, t.hash_seed, max_batch=1 << 24)
+    g = mp.MpzchTable(t.num_slots, t.max_probe, kind_g, t.ttl, t.hash_seed, max_batch=1 << 24,
+                      layout=mp.LAYOUT_RECORDS if records else mp.LAYOUT_SEPARATE)
     t0 = time.time()
     _prefill_stream(g, spec)
     say(f"prefilled {spec.prefill_ids} ids in {time.time() - t0:.1f}s")
-    I = g.identities.cpu().numpy()
-    M = g.metadata.cpu().numpy()
+    I = np.ascontiguousarray(g.identities.cpu().numpy())
+    M = np.ascontiguousarray(g.metadata.cpu().numpy())
     occ = int(np.count_nonzero(I >= 0))
     say(f"occupied {occ} of {t.num_slots} ({occ / t.num_slots:.3f})")
     # bounded probing: at load 0.9 with P = 16 some 5 % of the ids end without a slot (cf. Table 1)
@@ -91,15 +92,18 @@ def _stream_parity(spec, steps, emb_check_rows=0, lru=False):
     g.close()
 
 
-def test_headline_one_billion_slots_two_steps():
-    """1 B slots, P = 16, TTL 20, load 0.7, 4 M ids per step (the workload bench.py times)."""
-    _stream_parity(wl.headline_spec(), steps=2)
+@pytest.mark.parametrize("layout", ["records", "separate"])
+def test_headline_one_billion_slots_two_steps(layout):
+    """1 B slots, P = 16, TTL 20, load 0.7, 4 M ids per step (the workload bench.py times), with the
+    table as one tensor of 16-byte records (what bench.py times by default) and as two dense tensors."""
+    _stream_parity(wl.headline_spec(), steps=2, records=layout == "records")
 
 
-def test_config4_500m_slots_with_row_reset():
+@pytest.mark.parametrize("layout", ["records", "separate"])
+def test_config4_500m_slots_with_row_reset(layout):
     """500 M slots at load 0.9, 2 M ids per step, rows of a 100 M x 128 bf16 embedding
     addressed as slot mod rows."""
-    _stream_parity(wl.c4_spec(), steps=3, emb_check_rows=1)
+    _stream_parity(wl.c4_spec(), steps=3, emb_check_rows=1, records=layout == "records")
 
 
 def test_config4_500m_slots_lru():

@@ -12,10 +12,14 @@ from gpu_common import Pair, say
 pytestmark = pytest.mark.gpu
 
 
-def test_config1_tiny_table_every_step():
+LAYOUTS = ["separate", "records"]     # two dense tensors / one tensor of 16-byte records
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_config1_tiny_table_every_step(layout):
     """4 096 slots, P = 8, TTL 3, fp32 4096x16 rows, 8 Zipf(1.1) batches of 1 024 ids (then
     32 more steps so that eviction and fallback are well exercised)."""
-    p = Pair.from_spec(wl.c1_spec())
+    p = Pair.from_spec(wl.c1_spec(), layout=layout)
     tot = dict(evictions=0, collisions=0, inserts=0)
     batches = wl.c1_batches() + [(s, wl.zipf_ids(wl.rng_for(1, s), 1024, 1.1, 16384)) for s in range(9, 41)]
     for step, ids in batches:
@@ -47,13 +51,14 @@ CASES = [
 ]
 
 
+@pytest.mark.parametrize("layout", LAYOUTS)
 @pytest.mark.parametrize("case", CASES, ids=[f"N{c[0]}_P{c[1]}" for c in CASES])
-def test_contended_small_tables(case):
+def test_contended_small_tables(case, layout):
     """Small tables under heavy contention: many ids compete for few slots, windows wrap
     around the table end, P crosses every group width (8/16/32/64 and multi-chunk)."""
     n_slots, max_probe, ttl, evict, universe, batch, steps = case
     rng = np.random.Generator(np.random.Philox(key=hash(case) & 0xFFFFFFFF))
-    p = Pair(n_slots, max_probe, ttl, evict, hash_seed=0xABC0 + n_slots)
+    p = Pair(n_slots, max_probe, ttl, evict, hash_seed=0xABC0 + n_slots, layout=layout)
     step = 0
     for k in range(steps):
         step += int(rng.integers(0, 3))
@@ -83,11 +88,12 @@ def test_empty_and_single_element_batches():
     p.close()
 
 
-def test_config2_one_million_slots():
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_config2_one_million_slots(layout):
     """1 M slots, P = 16, TTL 10, fp32 1Mx64 rows: prefill to load 0.3, then 50 batches of
     65 536 Zipf(1.05) ids (+5 % never-seen ids) -- insert, evict and row reset."""
     spec = wl.c2_spec()
-    p = Pair.from_spec(spec)
+    p = Pair.from_spec(spec, layout=layout)
     step0, pre = wl.c2_prefill()
     p.step(pre, step0, check_state=False)
     tot_ev = 0
@@ -107,7 +113,7 @@ def test_config3_lookup_scaled():
     """Read-only lookups, P = 32, table prefilled to 80 %: 95 % Zipf(1.2) over residents,
     5 % unseen ids -> home slot + found = 0.  (1/100 of the 100 M-slot table.)"""
     spec = wl.c3_spec(1_000_000)
-    p = Pair(spec.num_slots, spec.max_probe, 0, False, spec.hash_seed)
+    p = Pair(spec.num_slots, spec.max_probe, 0, False, spec.hash_seed, layout="records")
     n_res = 800_000
     for k, lo in enumerate(range(0, n_res, 100_000)):
         p.step(wl.c3_prefill_ids(lo, lo + 100_000), k, check_state=False)

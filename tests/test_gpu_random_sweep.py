@@ -40,7 +40,9 @@ def test_random_tables_every_policy(block):
         max_probe = int(rng.choice([1, 2, 7, 8, 9, 15, 16, 17, 31, 32, 33, 63, 64, p_hi]))
         ttl = int(rng.integers(0, 4))
         universe = max(2, int(n_slots * float(rng.choice([0.5, 1.5, 4.0]))))
-        p = Pair(n_slots, max_probe, ttl, policy, hash_seed=int(rng.integers(0, 1 << 62)))
+        # every other table is kept as one tensor of 16-byte records
+        p = Pair(n_slots, max_probe, ttl, policy, hash_seed=int(rng.integers(0, 1 << 62)),
+                 layout="records" if case % 2 else "separate")
         step = int(rng.integers(0, 5))
         for k in range(int(rng.integers(3, 7))):
             n = int(rng.choice([0, 1, 63, 64, 65, 500, 4097])) if rng.random() < 0.5 else int(rng.integers(0, 6 * n_slots + 2))
