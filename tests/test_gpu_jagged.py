@@ -12,15 +12,26 @@ pytestmark = pytest.mark.gpu
 
 
 class JaggedPair:
-    def __init__(self, specs):
+    def __init__(self, specs, records=()):
+        """records: indices of the tables kept as one tensor of 16-byte records (the others: two dense tensors)."""
         self.specs = specs
         kg = lambda e: {"lru": mp.EVICT_LRU, "expiry": mp.EVICT_TTL_EXPIRY}.get(e, mp.EVICT_TTL if e else mp.EVICT_NONE)
         ko = lambda e: {"lru": oracle.EVICT_LRU, "expiry": oracle.EVICT_TTL_EXPIRY}.get(
             e, oracle.EVICT_TTL if e else oracle.EVICT_NONE)
-        self.handles = [mp.mpzch_create(t.num_slots, t.max_probe, (kg(t.evict), t.ttl), t.hash_seed) for t in specs]
+        self.handles = [mp.mpzch_create_with_layout(t.num_slots, t.max_probe, (kg(t.evict), t.ttl), t.hash_seed,
+                                                    mp.LAYOUT_RECORDS if f in records else mp.LAYOUT_SEPARATE)
+                        for f, t in enumerate(specs)]
         self.group = mp.mpzch_group_create(self.handles)
-        self.I = [torch.empty(t.num_slots, dtype=torch.int64, device="cuda") for t in specs]
-        self.M = [torch.empty(t.num_slots, dtype=torch.int32, device="cuda") for t in specs]
+        self.I, self.M, self.rec = [], [], []
+        for f, t in enumerate(specs):
+            if f in records:
+                self.rec.append(torch.empty(2 * t.num_slots, dtype=torch.int64, device="cuda"))
+                i, m = mp.records_views(self.rec[-1], t.num_slots)
+            else:
+                i = torch.empty(t.num_slots, dtype=torch.int64, device="cuda")
+                m = torch.empty(t.num_slots, dtype=torch.int32, device="cuda")
+            self.I.append(i)
+            self.M.append(m)
         for h, i, m in zip(self.handles, self.I, self.M):
             mp.mpzch_init_tensors(h, i, m)
         self.o = [oracle.Table(t.num_slots, t.max_probe, ko(t.evict), t.ttl, t.hash_seed) for t in specs]
@@ -98,6 +109,35 @@ class JaggedPair:
         mp.mpzch_group_destroy(self.group)
         for h in self.handles:
             mp.mpzch_destroy(h)
+
+
+def test_group_with_tables_of_both_layouts():
+    """A group whose tables are kept as 16-byte records (tables 0, 2, 3) or as two dense tensors (1, 4), every
+    policy among them: jagged remap, row reset, jagged lookup."""
+    specs = [wl.TableSpec(700, 16, 1, True, 51), wl.TableSpec(300, 8, 1, True, 52), wl.TableSpec(900, 33, 0, "lru", 53),
+             wl.TableSpec(128, 16, 1, "expiry", 54), wl.TableSpec(50, 4, 0, False, 55)]
+    jp = JaggedPair(specs, records=(0, 2, 3))
+    jp.attach_rows([(700, 4), (300, 8), (450, 4), None, (50, 4)])
+    rng = np.random.Generator(np.random.Philox(key=6060))
+    step, tot = 0, 0
+    for it in range(12):
+        step += int(rng.integers(0, 3))
+        counts = [int(rng.integers(0, 4 * s.num_slots)) for s in specs]
+        vals = [wl.rank_to_id(rng.integers(0, 5 * s.num_slots, size=c)) for s, c in zip(specs, counts)]
+        values = np.concatenate(vals).astype(np.int64)
+        offsets = np.concatenate([[0], np.cumsum(counts)]).astype(np.int64)
+        say("mixed-layout group step", step, counts)
+        sts = jp.step(values, offsets, step, rng.integers(0, 4, size=values.size).astype(np.int32) if it % 2 else None)
+        tot += sum(s["evictions"] for s in sts)
+        jp.check_state()
+        jp.lookup(values[::3].copy(), _offsets_of_every_third(offsets))
+    assert tot > 0
+    jp.close()
+
+
+def _offsets_of_every_third(offsets):
+    """feature offsets of values[::3] given those of values"""
+    return np.array([(int(o) + 2) // 3 for o in offsets], dtype=np.int64)
 
 
 def test_config5_jagged_scaled():
