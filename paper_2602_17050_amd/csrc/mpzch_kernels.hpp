@@ -839,15 +839,21 @@ struct TabWords {
 };
 
 // One wavefront serves the segments vblock, vblock + vgrid, ...; s_I and s_d are that wavefront's own
-// areas of LDS (s_d only with several tables).
+// areas of LDS (s_d only with several tables).  The lane phase looks at the window in stages of 8
+// slots (64 bytes of identities; one 128-byte line of records): nearly every claimant of a table with
+// room, or with expired ids, is placed among the first 8, and the second stage is loaded only when a
+// lane of the wavefront still needs it.
+constexpr int kAllocG = 8;                           // lanes that read one stage of one claimant's window together
+
 template <int PMAX, bool MULTI>
 __device__ __forceinline__ void allocate_body(const Params &p, int64_t vblock, int64_t vgrid,
-                                              int64_t (*s_I)[PMAX + 1], TabWords *s_d)
+                                              int64_t (*s_I)[kAllocG + 1], TabWords *s_d)
 {
-    constexpr int G = PMAX < kLine ? PMAX : kLine;   // lanes that read one claimant's window together
+    constexpr int G = kAllocG;
     constexpr int APL = kWave / G;                   // claimants served by one load instruction
-    constexpr int CH = PMAX / G;                     // load instructions per claimant
-    constexpr int NT = kWave / APL;
+    constexpr int NT = kWave / APL;                  // load instructions per stage
+    constexpr int STAGES = PMAX / G;
+    static_assert(PMAX % G == 0, "the lane phase works in stages of 8 slots");
 
     const int lane = lane_id();
     const int g = lane / G, r = lane % G;
@@ -884,81 +890,85 @@ __device__ __forceinline__ void allocate_body(const Params &p, int64_t vblock, i
                 s_d[lane] = TabWords{(int64_t)d.I, (int64_t)d.M, d.N, d.P, d.ttl, d.evict, d.sh};
                 __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             }
-            // cooperative loads; lanes without a slot to read use slot 0 / the home slot (valid addresses)
-            int64_t vi[NT * CH];
-            int32_t vm[NT * CH];
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                const int a = t * APL + g;
-                const int64_t ghome = shfl64(home, a);
-                global_ptr<int64_t> gI = d0.I;
-                global_ptr<int32_t> gM = d0.M;
-                int64_t gN = d0.N;
-                int gP = d0.P, gsh = d0.sh;
-                if constexpr (MULTI) {
-                    const TabWords &gd = s_d[a];
-                    gI = (global_ptr<int64_t>)gd.I;
-                    gM = (global_ptr<int32_t>)gd.M;
-                    gN = gd.N;
-                    gP = gd.P;
-                    gsh = gd.sh;
-                }
-#pragma unroll
-                for (int c = 0; c < CH; ++c) {
-                    const int k = c * G + r;
-                    const int64_t sl = k < gP ? wrap(ghome + k, gN) : ghome;
-                    vi[t * CH + c] = __hip_atomic_load(gI + (sl << gsh), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    vm[t * CH + c] = gM[sl << (2 * gsh)];
-                }
-            }
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                int32_t gttl = d0.ttl, gev = d0.evict;        // the claimant's table: ttl and eviction mode
-                if constexpr (MULTI) {
-                    gttl = s_d[t * APL + g].ttl;
-                    gev = s_d[t * APL + g].evict;
-                }
-#pragma unroll
-                for (int c = 0; c < CH; ++c) {
-                    int64_t w = vi[t * CH + c];
-                    if (w >= 0) w = is_expired(gev, gttl, p.step, vm[t * CH + c]) ? 1 : 0;
-                    s_I[t * APL + g][c * G + r] = w;
-                }
-            }
-            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-            // lane phase
-            uint32_t hint = kHintNone;
+            uint32_t hint = agent ? kHintUnplaced : kHintNone;
+            bool placed = false;
             bool more = false;           // a claimant of this lane goes on in the wave phase
             uint32_t mpos = 0;
             int32_t mr = 0;
-            if (agent) {
-                hint = kHintUnplaced;
-                const int lim = d.P < PMAX ? d.P : PMAX;
-                bool placed = false;
-                for (int k = 0; k < lim; ++k) {
-                    const int64_t v = s_I[lane][k];
-                    uint32_t occ = 0;
-                    bool cand;
-                    if (v == -1) cand = true;
-                    else if (v >= 0) { cand = v == 1; occ = 1; }
-                    else { occ = tag_occ(v); cand = v > make_tag((uint32_t)k, pos, occ); }
-                    if (!cand) continue;
-                    const int64_t mine = make_tag((uint32_t)k, pos, occ);
-                    const int64_t old = __hip_atomic_fetch_min(id_at(d, wrap(home + k, d.N)), mine, __ATOMIC_RELAXED,
-                                                               __HIP_MEMORY_SCOPE_AGENT);
-                    if (is_tag(old) && old < mine) continue;      // a better claim got there first
-                    hint = (uint32_t)k;
-                    placed = true;
-                    if (is_tag(old) && (int32_t)tag_round(old) + 1 < d.P) {
-                        // the displaced claimant goes on from its next round (same table: same slot)
-                        more = true;
-                        mpos = tag_pos(old);
-                        mr = (int32_t)tag_round(old) + 1;
+#pragma unroll
+            for (int st = 0; st < STAGES; ++st) {
+                const int kb = st * G;
+                const bool need = agent && !placed && kb < d.P;
+                if (st > 0 && !__any(need)) break;
+                // cooperative loads of slots kb .. kb + 7 of every claimant that goes on; lanes without
+                // a slot to read use the home slot / slot 0 (valid addresses)
+                int64_t vi[NT];
+                int32_t vm[NT];
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                    const int a = t * APL + g;
+                    const int64_t ghome = shfl64(home, a);
+                    const bool gneed = __shfl((int)need, a) != 0;
+                    global_ptr<int64_t> gI = d0.I;
+                    global_ptr<int32_t> gM = d0.M;
+                    int64_t gN = d0.N;
+                    int gP = d0.P, gsh = d0.sh;
+                    if constexpr (MULTI) {
+                        const TabWords &gd = s_d[a];
+                        gI = (global_ptr<int64_t>)gd.I;
+                        gM = (global_ptr<int32_t>)gd.M;
+                        gN = gd.N;
+                        gP = gd.P;
+                        gsh = gd.sh;
                     }
-                    break;
+                    const int k = kb + r;
+                    const int64_t sl = (gneed && k < gP) ? wrap(ghome + k, gN) : ghome;
+                    vi[t] = __hip_atomic_load(gI + (sl << gsh), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    vm[t] = gM[sl << (2 * gsh)];
                 }
-                if (!placed && d.P > PMAX) { more = true; mpos = pos; mr = PMAX; }
+                // what a lane needs to know of a slot: -1 empty, a claim tag (<= -2), 1 = holds an expired
+                // id, 0 = holds a live id
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                    int32_t gttl = d0.ttl, gev = d0.evict;        // the claimant's table: ttl and eviction mode
+                    if constexpr (MULTI) {
+                        gttl = s_d[t * APL + g].ttl;
+                        gev = s_d[t * APL + g].evict;
+                    }
+                    int64_t w = vi[t];
+                    if (w >= 0) w = is_expired(gev, gttl, p.step, vm[t]) ? 1 : 0;
+                    s_I[t * APL + g][r] = w;
+                }
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                // lane phase: every lane walks this stage of its own claimant's window
+                if (need) {
+                    const int lim = d.P < kb + G ? d.P : kb + G;
+                    for (int k = kb; k < lim; ++k) {
+                        const int64_t v = s_I[lane][k - kb];
+                        uint32_t occ = 0;
+                        bool cand;
+                        if (v == -1) cand = true;
+                        else if (v >= 0) { cand = v == 1; occ = 1; }
+                        else { occ = tag_occ(v); cand = v > make_tag((uint32_t)k, pos, occ); }
+                        if (!cand) continue;
+                        const int64_t mine = make_tag((uint32_t)k, pos, occ);
+                        const int64_t old = __hip_atomic_fetch_min(id_at(d, wrap(home + k, d.N)), mine, __ATOMIC_RELAXED,
+                                                                   __HIP_MEMORY_SCOPE_AGENT);
+                        if (is_tag(old) && old < mine) continue;      // a better claim got there first
+                        hint = (uint32_t)k;
+                        placed = true;
+                        if (is_tag(old) && (int32_t)tag_round(old) + 1 < d.P) {
+                            // the displaced claimant goes on from its next round (same table: same slot)
+                            more = true;
+                            mpos = tag_pos(old);
+                            mr = (int32_t)tag_round(old) + 1;
+                        }
+                        break;
+                    }
+                }
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // s_I is rewritten by the next stage
             }
+            if (agent && !placed && d.P > PMAX) { more = true; mpos = pos; mr = PMAX; }
             // wave phase
             uint64_t lm = __ballot(more);
             while (lm) {
@@ -978,12 +988,11 @@ __device__ __forceinline__ void allocate_body(const Params &p, int64_t vblock, i
     }
 }
 
-// What a lane needs to know of a slot in s_I: -1 empty, a claim tag (<= -2), 1 = holds an expired id,
-// 0 = holds a live id.  (+1 column: rows fall into different banks.)
+// (+1 column in s_I: rows fall into different banks.)
 template <int PMAX, bool MULTI>
 __global__ __launch_bounds__(kWave) void k_allocate(Params p)
 {
-    __shared__ int64_t s_I[kWave][PMAX + 1];
+    __shared__ int64_t s_I[kWave][kAllocG + 1];
     __shared__ TabWords s_d[MULTI ? kWave : 1];      // every lane's table, for the lanes that load for it
     allocate_body<PMAX, MULTI>(p, blockIdx.x, gridDim.x, s_I, s_d);
 }
