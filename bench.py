@@ -31,20 +31,22 @@ TRAFFIC_PROFILE = {"headline": "remap_headline_1Bslots_4Mids.txt", "headline-sep
 
 
 def measured_ceilings():
-    """(aligned 128-byte line reads per second, 4-byte stores per second) at random addresses of an 8 GB
-    array, as measured on MI355X by paper_2602_17050_amd/memory_ceilings.bin and kept in
-    profiles/memory_ceilings_mi355x.txt -- the figures are read from that file so that they cannot drift."""
-    lines = stores = None
+    """Random-access rates (operations per second on an 8 GB array) measured on MI355X by
+    paper_2602_17050_amd/memory_ceilings.bin and kept in profiles/memory_ceilings_mi355x.txt: aligned
+    128-byte line reads, 4-byte stores, and "line read + 4-byte store into the same line".  The figures
+    are read from that file so that they cannot drift; None when the file is missing."""
+    keys = {"lines": "random aligned 128-byte lines", "stores": "random 4-byte stores (one per lane)",
+            "line_store": "random line read + 4-byte store into the same line"}
+    out = {k: None for k in keys}
     try:
         with open(os.path.join(PROFILES, "memory_ceilings_mi355x.txt")) as fh:
             for ln in fh:
-                if ln.startswith("random aligned 128-byte lines"):
-                    lines = float(ln.split("ms")[1].split("G ops/s")[0]) * 1e9
-                elif ln.startswith("random 4-byte stores (one per lane)"):
-                    stores = float(ln.split("ms")[1].split("G ops/s")[0]) * 1e9
+                for k, prefix in keys.items():
+                    if ln.startswith(prefix):
+                        out[k] = float(ln.split("ms")[1].split("G ops/s")[0]) * 1e9
     except OSError:
         pass
-    return lines, stores
+    return out
 
 
 def profiled_traffic(workload, kernel, scale):
@@ -65,7 +67,8 @@ def profiled_traffic(workload, kernel, scale):
     return None
 
 
-def roofline_entry(workload, scale, kernel, avg_ms, alg_bytes, lines_per_launch=None, stores_per_launch=None, note=None):
+def roofline_entry(workload, scale, kernel, avg_ms, alg_bytes, lines_per_launch=None, stores_per_launch=None, note=None,
+                   same_line=False):
     """`achieved` = algorithmic bytes per launch of the dominant kernel / its average duration (HIP events
     recorded by the library on the launch stream), against the 8 TB/s HBM peak."""
     ach = alg_bytes / (avg_ms * 1e-3) / 1e9
@@ -75,10 +78,16 @@ def roofline_entry(workload, scale, kernel, avg_ms, alg_bytes, lines_per_launch=
          "alg_bytes_per_launch": round(alg_bytes),
          # all HBM bytes the kernel moves (useful or not) against the same peak
          "traffic_frac_of_peak": None if traffic is None else round(traffic / (avg_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
-    c_lines, c_stores = measured_ceilings()
-    if lines_per_launch is not None and c_lines and c_stores:
-        # what the measured random-access ceilings allow for this launch
-        floor_ms = (lines_per_launch / c_lines + (stores_per_launch or 0.0) / c_stores) * 1e3
+    c = measured_ceilings()
+    if lines_per_launch is not None and all(c.values()):
+        # what the measured random-access ceilings allow for this launch: its line reads and its metadata
+        # refreshes -- narrow stores into a tensor of their own, or (a table of records) stores into lines just
+        # read, priced as "line read + store into the same line" instead of as a line read
+        refresh = stores_per_launch or 0.0
+        if same_line:
+            floor_ms = (max(lines_per_launch - refresh, 0.0) / c["lines"] + refresh / c["line_store"]) * 1e3
+        else:
+            floor_ms = (lines_per_launch / c["lines"] + refresh / c["stores"]) * 1e3
         r["random_access_floor_ms"] = round(floor_ms, 4)
         r["frac_of_random_access_ceiling"] = round(floor_ms / avg_ms, 3)
     if note:
@@ -125,6 +134,8 @@ def main():
                     help="headline / c4: identities and metadata as one tensor of 16-byte records {int64 id, int32 "
                          "metadata, 4 unused bytes} (default: a hit then refreshes the line it has just read), or as "
                          "two dense tensors")
+    ap.add_argument("--gather", action="store_true",
+                    help="c3: time mpzch_lookup_gather (the lookup fused with the gather of 128 x bf16 rows) instead of mpzch_lookup")
     ap.add_argument("--graph", action="store_true",
                     help="c1 / c2: capture the timed steps into one HIP graph and time its replay (no launch overhead on the host)")
     args = ap.parse_args()
@@ -257,8 +268,7 @@ def main():
             # requests: one line read per position (plus the further lines of parked ids), one metadata store per hit position
             lines = total_ids / K + (miss_pos + max(probe_sum - hit_pos, 0) / 8.0) / K
             key = args.workload if args.layout == "records" else args.workload + "-separate"
-            # with records the refresh goes into the line just read: no separate random store
-            roofline = roofline_entry(key, args.scale, dom, avg_ms, alg, lines, hit_pos / K if args.layout == "separate" else 0.0)
+            roofline = roofline_entry(key, args.scale, dom, avg_ms, alg, lines, hit_pos / K, same_line=args.layout == "records")
         else:
             roofline = {"bound": "hbm", "kernel": dom, "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                         "frac": None, "traffic": None, "avg_kernel_ms": round(avg_ms, 4)}
@@ -341,13 +351,25 @@ def bench_lookup(args, np, torch, mp, wl, dev):
     batches = [torch.from_numpy(b).to(dev) for b in batches_np]
     outs = torch.empty((W + K, batch), dtype=torch.int64, device=dev)
     found = torch.empty((W + K, batch), dtype=torch.uint8, device=dev)
+    rows = out_rows = None
+    if args.gather:
+        # rows of 128 bf16 values, one per slot (25.6 GB at full scale); the output of a batch is 256 MB
+        rows = torch.ones((n_slots, 128), dtype=torch.bfloat16, device=dev)
+        out_rows = torch.empty((batch, 128), dtype=torch.bfloat16, device=dev)
+
+    def one(i):
+        if args.gather:
+            mp.mpzch_lookup_gather(g.handle, g.identities, batches[i], rows, out_rows, outs[i], found[i])
+        else:
+            mp.mpzch_lookup(g.handle, g.identities, batches[i], outs[i], found[i])
+
     for i in range(W):
-        mp.mpzch_lookup(g.handle, g.identities, batches[i], outs[i], found[i])
+        one(i)
     torch.cuda.synchronize()
     mp.mpzch_set_kernel_timing(g.handle, 1)
     t0 = time.perf_counter()
     for i in range(W, W + K):
-        mp.mpzch_lookup(g.handle, g.identities, batches[i], outs[i], found[i])
+        one(i)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ktimes = mp.mpzch_kernel_times(g.handle)
@@ -391,14 +413,19 @@ def bench_lookup(args, np, torch, mp, wl, dev):
     # per distinct absent id the slots up to the first empty one of its range
     alg = (17.0 * batch * K + u_hit * 8.0 * mean_probe + u_miss * 8.0 * mean_miss_len) / K
     lines = batch + (miss_pos + max(stn[sname["hit_probe_sum"]] - hit_pos, 0) / 8.0) / K
-    roofline = roofline_entry("c3", args.scale, "k_lookup", ms_total / launches, alg, lines, 0.0)
+    if args.gather:
+        alg += 2.0 * 256.0 * batch          # every position's row read and written (256 bytes)
+        lines += 2.0 * batch                # a row is two 128-byte lines
+    roofline = roofline_entry("c3-gather" if args.gather else "c3", args.scale, "k_lookup", ms_total / launches, alg, lines, 0.0)
     roofline["hit_fraction"] = round(hit_frac, 4)
     result = {
         "metric": "remapped IDs/sec (infer lookup) at 1 GPU", "value": round(batch * K / elapsed, 1), "unit": "ids/s",
         "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(elapsed / K * 1e3, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "int64", "data": "synthetic",
         "config": {"workload": f"c3: lookup-only, {n_slots}-slot table 80% full, P=32, {batch} ids/batch, "
-                               f"95% resident Zipf(1.2), 5% unseen", "scale": args.scale},
+                               f"95% resident Zipf(1.2), 5% unseen" +
+                               (", fused with the gather of 128 x bf16 rows (mpzch_lookup_gather)" if args.gather else ""),
+                   "scale": args.scale},
         "per_step": {"distinct_resident_ids": round(u_hit / K, 1), "distinct_absent_ids": round(u_miss / K, 1),
                      "mean_hit_probe_len": round(mean_probe, 3), "mean_miss_probe_len": round(mean_miss_len, 3)},
         "kernel_ms_per_step": {k: round(v[0] / K, 4) for k, v in ktimes.items()},
