@@ -565,10 +565,16 @@ def bench_jagged(args, np, torch, mp, wl, dev):
     """Config 5: 26 tables, one mpzch_remap_jagged call per step."""
     spec = wl.c5_spec(total_slots_cap=int(1_000_000_000 * args.scale), samples=max(int(65536 * args.scale), 64))
     K, W = min(args.steps, 5), min(args.warmup, 2)
-    handles = [mp.mpzch_create(t.num_slots, t.max_probe, (mp.EVICT_TTL, t.ttl), t.hash_seed) for t in spec.tables]
+    records = args.layout == "records"
+    handles = [mp.mpzch_create_with_layout(t.num_slots, t.max_probe, (mp.EVICT_TTL, t.ttl), t.hash_seed,
+                                           mp.LAYOUT_RECORDS if records else mp.LAYOUT_SEPARATE) for t in spec.tables]
     group = mp.mpzch_group_create(handles)
-    I = [torch.empty(t.num_slots, dtype=torch.int64, device=dev) for t in spec.tables]
-    M = [torch.empty(t.num_slots, dtype=torch.int32, device=dev) for t in spec.tables]
+    if records:
+        rec = [torch.empty(2 * t.num_slots, dtype=torch.int64, device=dev) for t in spec.tables]
+        I, M = map(list, zip(*[mp.records_views(r, t.num_slots) for r, t in zip(rec, spec.tables)]))
+    else:
+        I = [torch.empty(t.num_slots, dtype=torch.int64, device=dev) for t in spec.tables]
+        M = [torch.empty(t.num_slots, dtype=torch.int32, device=dev) for t in spec.tables]
     for h, i, m in zip(handles, I, M):
         mp.mpzch_init_tensors(h, i, m)
     T = len(spec.tables)
@@ -615,12 +621,14 @@ def bench_jagged(args, np, torch, mp, wl, dev):
             a, l, h = training_alg_bytes(np, positions, st_all[:, f, :], distinct, mp.STAT_NAMES)
             alg, lines, stores = alg + a, lines + l, stores + h
         ms_total, launches = ktimes["k_discover"]
-        roofline = roofline_entry("c5", args.scale, "k_discover", ms_total / launches, alg / K, lines / K, stores / K,
-                                  note="k_discover_tables; most of the 26 tables live in L2 / Infinity Cache")
+        roofline = roofline_entry("c5" if records else "c5-separate", args.scale, "k_discover", ms_total / launches,
+                                  alg / K, lines / K, stores / K, same_line=records,
+                                  note="k_discover_tables; the small ones of the 26 tables live in L2 / Infinity Cache")
     _emit("remapped IDs/sec (train insert+evict) at 1 GPU", total / elapsed, K, W, elapsed,
           f"c5: 26 tables ({sum(t.num_slots for t in spec.tables)} slots in all), P=16, TTL=5, {spec.samples} samples, "
           f"pooling 1..50, about {total // K} values per step, one mpzch_remap_jagged + one mpzch_reset_rows_jagged call "
-          f"per step (bf16 x16 rows per slot)", ktimes, None,
+          f"per step (bf16 x16 rows per slot), identities+metadata as {'16-byte records' if records else 'two tensors'}",
+          ktimes, None,
           {"totals_over_timed_steps": dict(zip(mp.STAT_NAMES, [int(x) for x in st]))}, roofline)
 
 

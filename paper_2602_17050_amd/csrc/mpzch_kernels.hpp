@@ -72,8 +72,14 @@ constexpr int kBins = 16;
 struct Control {
     unsigned long long num_evicted[kMaxTables];
     unsigned long long stats[kBins][kMaxTables][kStatCount];
-    unsigned long long done;       // workgroups of k_finalize that have finished
+    unsigned long long done;       // workgroups that have finished (k_finalize: counted in the bits from kArriveShift up)
 };
+// k_finalize reports in by adding kArriveOne to `done`.  With one table the same atomic also reserves the
+// workgroup's part of the evicted list, whose length is kept in the low bits of `done` (num_evicted[0]
+// stays unused): one round trip to one address at the end of a workgroup instead of two to two.
+constexpr int kArriveShift = 40;
+constexpr unsigned long long kArriveOne = 1ull << kArriveShift;
+constexpr unsigned long long kEvictedMask = kArriveOne - 1ull;
 
 struct Params {
     const int64_t *ids;
@@ -367,10 +373,16 @@ __device__ __forceinline__ void block_stat_add(const Params &p, const int *idx, 
 // Run by the workgroup that finishes last (of k_finalize; of a counting lookup).
 __device__ __forceinline__ void publish_counters(const Params &p, unsigned long long (*s_bins)[kStatCount])
 {
-    if (p.out_num_evicted)
-        for (int i = threadIdx.x; i < p.num_tables; i += kBlock)
-            p.out_num_evicted[i] =
-                (int64_t)__hip_atomic_load(&p.ctl->num_evicted[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (p.out_num_evicted) {
+        if (p.num_tables > 1) {
+            for (int i = threadIdx.x; i < p.num_tables; i += kBlock)
+                p.out_num_evicted[i] =
+                    (int64_t)__hip_atomic_load(&p.ctl->num_evicted[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        } else if (threadIdx.x == 0) {
+            p.out_num_evicted[0] =
+                (int64_t)(__hip_atomic_load(&p.ctl->done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & kEvictedMask);
+        }
+    }
     if (p.out_stats) {
         const int nbins = p.num_tables * kStatCount;
         for (int i = threadIdx.x; i < nbins; i += kBlock) {
@@ -519,6 +531,28 @@ __device__ __forceinline__ void discover_body(const Params &p)
     int st_table = 0;
     int staged = 0, flushed = 0;                 // wave-uniform: parked ids in LDS / misses already listed
 
+    // Several tables: the table that owns the positions this wavefront is working through, with the
+    // range of positions it owns (all wave-uniform).  Positions arrive in ascending order, so the
+    // search through the offsets and the load of the descriptor -- a chain of dependent loads in
+    // front of every hash -- are paid when the range is left, not once per chunk.
+    int t_f = 0;
+    int64_t t_lo = 0, t_hi = 0;
+    Tab t_d = view(p.t0);
+    auto table_at = [&](int64_t upos) {
+        if (upos >= t_lo && upos < t_hi) return;
+        t_f = __builtin_amdgcn_readfirstlane(find_table(p.offsets, p.num_tables, upos));
+        // find_table skips empty features that share this offset; the clamps keep every loop
+        // finite and every range inside the batch even if the offsets break their contract
+        int64_t lo = p.offsets[t_f], hi = p.offsets[t_f + 1];
+        if (t_f == p.num_tables - 1 || hi > p.n) hi = p.n;
+        if (hi <= upos) hi = upos + 1;
+        if (lo > upos) lo = upos;
+        if (lo < 0) lo = 0;
+        t_lo = lo;
+        t_hi = hi;
+        t_d = view(p.descs[t_f]);
+    };
+
     // counters are kept for one table at a time
     auto stats_table = [&](int f) {
         if (!want_stats || f == st_table) return;
@@ -557,17 +591,21 @@ __device__ __forceinline__ void discover_body(const Params &p)
         // the outputs stored by the first pass are performed before any lane rewrites them below
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
         int nmiss = 0;
+        bool all_cached = true;                 // wave-uniform: every parked position is of the cached table
         for (int e0 = 0; e0 < staged; e0 += kWave) {
             const bool have = e0 + lane < staged;
             const uint32_t pos = have ? s_pos[w][e0 + lane] : 0;
             const int q0 = have ? s_q[w][e0 + lane] : 0;
             const int64_t id = have ? p.ids[pos] : -1;
-            const int f = (have && multi) ? find_table(p.offsets, p.num_tables, (int64_t)pos) : 0;
+            // parked positions nearly always belong to the table of the chunks just read
+            const bool cached = !multi || __all(!have || ((int64_t)pos >= t_lo && (int64_t)pos < t_hi));
+            if (!cached) all_cached = false;
+            const int f = (have && !cached) ? find_table(p.offsets, p.num_tables, (int64_t)pos) : t_f;
             bool todo = have;
             while (__any(todo)) {
-                const int f0 = __shfl(f, __ffsll((unsigned long long)__ballot(todo)) - 1);
+                const int f0 = cached ? t_f : __shfl(f, __ffsll((unsigned long long)__ballot(todo)) - 1);
                 const bool mine = todo && f == f0;
-                const Tab d = view(multi ? p.descs[f0] : p.t0);
+                const Tab d = !multi ? view(p.t0) : cached ? t_d : view(p.descs[f0]);
                 stats_table(f0);
                 const int64_t home = mine ? home_slot(id, d.seed, d.N) : 0;
                 int dist = -1;
@@ -606,15 +644,21 @@ __device__ __forceinline__ void discover_body(const Params &p)
                 const uint32_t pos = s_pos[w][j];
                 const int64_t id = p.ids[pos];
                 uint64_t sb, ss;
-                set_region(p, (int64_t)pos, sb, ss);
-                const uint32_t e = set_insert(p, id, pos, sb, ss);
                 int64_t home;
-                if (multi) {
+                if (!multi) {
+                    sb = 0;
+                    ss = 2ull * (uint64_t)p.n;
+                    home = home_slot(id, p.t0.seed, p.t0.N);
+                } else if (all_cached) {
+                    sb = 2ull * (uint64_t)t_lo;
+                    ss = 2ull * (uint64_t)(t_hi - t_lo);
+                    home = home_slot(id, t_d.seed, t_d.N);
+                } else {
+                    set_region(p, (int64_t)pos, sb, ss);
                     const TableDesc &td = p.descs[find_table(p.offsets, p.num_tables, (int64_t)pos)];
                     home = home_slot(id, td.seed, td.N);
-                } else {
-                    home = home_slot(id, p.t0.seed, p.t0.N);
                 }
+                const uint32_t e = set_insert(p, id, pos, sb, ss);
                 p.list[seg_base + flushed + j] = pos;
                 p.ent[seg_base + flushed + j] = e;
                 p.homes[seg_base + flushed + j] = home;
@@ -642,15 +686,10 @@ __device__ __forceinline__ void discover_body(const Params &p)
             bool mine = todo;
             if (multi) {
                 const uint64_t tb = __ballot(todo);
-                const int64_t first_pos = base + __ffsll((unsigned long long)tb) - 1;
-                f = __builtin_amdgcn_readfirstlane(find_table(p.offsets, p.num_tables, first_pos));
-                // find_table skips empty features that share this offset; the clamp keeps the
-                // loop finite even if the offsets break their contract
-                int64_t seg_hi = p.offsets[f + 1];
-                if (f == p.num_tables - 1 || seg_hi > p.n) seg_hi = p.n;
-                if (seg_hi <= first_pos) seg_hi = first_pos + 1;
-                d = view(p.descs[f]);
-                mine = todo && pos < seg_hi;
+                table_at(base + __ffsll((unsigned long long)tb) - 1);
+                f = t_f;
+                d = t_d;
+                mine = todo && pos < t_hi;
             } else {
                 d = view(p.t0);
             }
@@ -751,6 +790,17 @@ __global__ __launch_bounds__(kBlock, 3) void k_discover_tables(Params p)
 __global__ __launch_bounds__(kBlock, 4) void k_lookup_tables(Params p)
 {
     discover_body<false, true, false>(p);
+}
+
+// Several tables: the table of a whole segment of positions [seg_base, seg_base + seg_len), when one
+// table owns them all (the rule: a segment is a few thousand positions, a feature's share of the
+// batch many times that).  Its number and descriptor are then wave-uniform and read once per segment
+// instead of once per lane and list entry.  Returns false when the segment straddles a boundary.
+__device__ __forceinline__ bool segment_table(const Params &p, int64_t seg_base, int64_t seg_len, int &f, Tab &d)
+{
+    f = __builtin_amdgcn_readfirstlane(find_table(p.offsets, p.num_tables, seg_base));
+    d = view(p.descs[f]);
+    return f == p.num_tables - 1 || seg_base + seg_len <= p.offsets[f + 1];
 }
 
 // ------------------------------------------------------------------ allocation
@@ -862,6 +912,10 @@ __device__ __forceinline__ void allocate_body(const Params &p, int64_t vblock, i
         const uint32_t cnt = p.seg_cnt[seg];
         const int64_t seg_base = seg * p.seg_chunks * kWave;
         if (seg_base >= p.n) break;                           // segments past the batch hold nothing
+        int seg_f = 0;
+        Tab seg_d = d0;
+        bool seg_one = true;
+        if constexpr (MULTI) seg_one = segment_table(p, seg_base, p.seg_chunks * kWave, seg_f, seg_d);
         for (uint32_t j0 = 0;; j0 += kWave) {
             // the list entries are requested before the count is known: the count is at most the
             // number of positions of the segment and the arrays have room for n + 128 entries, so
@@ -880,8 +934,13 @@ __device__ __forceinline__ void allocate_body(const Params &p, int64_t vblock, i
                 p.first_of[idx] = first;
                 agent = first == pos;                         // else: a later copy of the id
                 if (MULTI && agent) {
-                    f = find_table(p.offsets, p.num_tables, (int64_t)pos);
-                    d = view(p.descs[f]);
+                    if (seg_one) {
+                        f = seg_f;
+                        d = seg_d;
+                    } else {
+                        f = find_table(p.offsets, p.num_tables, (int64_t)pos);
+                        d = view(p.descs[f]);
+                    }
                     if (d.evict == 2) agent = false;          // claimants of LRU tables are served by k_allocate_lru
                 }
             }
@@ -1298,7 +1357,9 @@ __device__ __forceinline__ void flush_evicted(const Params &p, const int64_t *bu
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     const int lane = lane_id();
     unsigned long long base = 0;
-    if (lane == 0) base = atomicAdd(&p.ctl->num_evicted[table], (unsigned long long)count);
+    if (lane == 0)
+        base = p.num_tables > 1 ? atomicAdd(&p.ctl->num_evicted[table], (unsigned long long)count)
+                                : atomicAdd(&p.ctl->done, (unsigned long long)count) & kEvictedMask;
     base = (unsigned long long)shfl64((int64_t)base, 0);
     const int64_t ev_begin = p.num_tables > 1 ? p.descs[table].ev_begin : p.t0.ev_begin;
     const int64_t ev_cap = p.num_tables > 1 ? p.descs[table].ev_cap : p.t0.ev_cap;
@@ -1364,10 +1425,15 @@ __device__ __forceinline__ void finalize_account(const Params &p, FinalizeState 
     }
 }
 
-// End of k_finalize: one reservation per workgroup when all its wavefronts staged for the same
-// table, then the per-workgroup counter row.  Must be reached by all threads.
-__device__ __forceinline__ void finalize_epilogue(const Params &p, FinalizeState &fs, int64_t (*s_ev)[kEvBuf],
-                                                  int *s_cnt, int *s_tab, unsigned long long *s_base,
+// End of k_finalize, reached by all threads: the workgroup adds its counters to its copy of the call's
+// counters, reserves its part of the evicted list (one reservation when all its wavefronts staged for
+// the same table) and reports in; returns true in the workgroup that reported in last.  Everything that
+// workgroup will read -- evicted counts and counter copies -- was added with device-scope atomics,
+// which are performed where all dies see them; a workgroup waits until its own have been acknowledged
+// before it reports in.  (A device-scope release fence here would also write back the die's whole L2,
+// once per workgroup.)
+__device__ __forceinline__ bool finalize_epilogue(const Params &p, FinalizeState &fs, int64_t (*s_ev)[kEvBuf],
+                                                  int *s_cnt, int *s_tab, unsigned long long *s_base, bool *s_last,
                                                   unsigned long long (*s_red)[kStatCount], bool want_stats)
 {
     const int lane = lane_id(), w = threadIdx.x / kWave;
@@ -1384,25 +1450,37 @@ __device__ __forceinline__ void finalize_epilogue(const Params &p, FinalizeState
         if (i < w) before += s_cnt[i];
         total += s_cnt[i];
     }
-    if (total > 0) {
-        if (same) {
-            if (threadIdx.x == 0) *s_base = atomicAdd(&p.ctl->num_evicted[tab], (unsigned long long)total);
-            __syncthreads();
-            const int64_t base = (int64_t)*s_base + before;
-            const int64_t ev_begin = multi ? p.descs[tab].ev_begin : p.t0.ev_begin;
-            const int64_t ev_cap = multi ? p.descs[tab].ev_cap : p.t0.ev_cap;
-            for (int i = lane; i < fs.ev_cnt; i += kWave)
-                if (base + i < ev_cap) p.out_evicted[ev_begin + base + i] = s_ev[w][i];
-        } else {
-            flush_evicted(p, s_ev[w], fs.ev_cnt, fs.ev_table);
-        }
-    }
-    __syncthreads();
+    __syncthreads();                                              // s_tab is used again by block_stat_add
     if (want_stats) {
         const int idx[3] = {kInserts, kEvictions, kCollisions};
         const unsigned long long vals[3] = {fs.st_ins, fs.st_evi, fs.st_col};
         block_stat_add(p, idx, vals, 3, fs.st_table, s_red, s_tab);
     }
+    if (multi && total > 0 && !same) flush_evicted(p, s_ev[w], fs.ev_cnt, fs.ev_table);
+    const bool reserve = total > 0 && (same || !multi);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned long long arrived;
+        if (multi) {
+            // the reservation is acknowledged (its result is used) before the workgroup reports in
+            if (reserve) *s_base = atomicAdd(&p.ctl->num_evicted[tab], (unsigned long long)total);
+            arrived = atomicAdd(&p.ctl->done, kArriveOne);
+        } else {
+            arrived = atomicAdd(&p.ctl->done, kArriveOne + (unsigned long long)total);
+            *s_base = arrived & kEvictedMask;
+        }
+        *s_last = (arrived >> kArriveShift) == (unsigned long long)(gridDim.x - 1);
+    }
+    __syncthreads();
+    if (reserve) {
+        const int64_t base = (int64_t)*s_base + before;
+        const int64_t ev_begin = multi ? p.descs[tab].ev_begin : p.t0.ev_begin;
+        const int64_t ev_cap = multi ? p.descs[tab].ev_cap : p.t0.ev_cap;
+        for (int i = lane; i < fs.ev_cnt; i += kWave)
+            if (base + i < ev_cap) p.out_evicted[ev_begin + base + i] = s_ev[w][i];
+    }
+    return *s_last;
 }
 
 // Every entry of the miss lists -- the elected position of an id (its agent) and the other copies of
@@ -1433,6 +1511,10 @@ __device__ __forceinline__ void finalize_body(const Params &p)
     for (int64_t seg = wave_global; seg < p.num_segs; seg += num_waves) {
         const uint32_t cnt = p.seg_cnt[seg];
         const int64_t seg_base = seg * p.seg_chunks * kWave;
+        int seg_f = 0;
+        Tab seg_d = view(p.t0);
+        bool seg_one = true;
+        if (multi && cnt > 0) seg_one = segment_table(p, seg_base, p.seg_chunks * kWave, seg_f, seg_d);
         for (uint32_t j0 = 0; j0 < cnt; j0 += kWave) {
             const bool have = j0 + lane < cnt;
             const int64_t idx = seg_base + j0 + lane;
@@ -1453,7 +1535,15 @@ __device__ __forceinline__ void finalize_body(const Params &p)
                 first = p.first_of[idx];
                 agent = first == pos;
                 p.set_slot[p.ent[idx]] = kSetEmpty;            // the scratch set is left empty again
-                if (multi) { f = find_table(p.offsets, p.num_tables, (int64_t)pos); d = view(p.descs[f]); }
+                if (multi) {
+                    if (seg_one) {
+                        f = seg_f;
+                        d = seg_d;
+                    } else {
+                        f = find_table(p.offsets, p.num_tables, (int64_t)pos);
+                        d = view(p.descs[f]);
+                    }
+                }
                 id = p.ids[pos];
                 home = p.homes[idx];
                 h = p.hint[first];
@@ -1513,17 +1603,9 @@ __device__ __forceinline__ void finalize_body(const Params &p)
             finalize_account(p, fs, s_ev[w], agent, outcome, s_final, f, want_stats);
         }
     }
-    finalize_epilogue(p, fs, s_ev, s_cnt, s_tab, &s_base, s_red, want_stats);
-    // The workgroup that finishes last publishes the call's counters.  Everything it reads -- evicted
-    // counts and counter copies -- was added with device-scope atomics, which are performed where all
-    // dies see them; a workgroup waits until its own have been acknowledged and then reports in.  (A
-    // device-scope release fence here would also write back the die's whole L2, once per workgroup.)
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __syncthreads();
-    if (threadIdx.x == 0)
-        s_last = atomicAdd(&p.ctl->done, 1ull) == (unsigned long long)(gridDim.x - 1);
-    __syncthreads();
-    if (s_last) publish_counters(p, s_bins);
+    // the workgroup that finishes last publishes the call's counters
+    const bool last = finalize_epilogue(p, fs, s_ev, s_cnt, s_tab, &s_base, &s_last, s_red, want_stats);
+    if (last) publish_counters(p, s_bins);
 }
 
 __global__ __launch_bounds__(kBlock) void k_finalize(Params p)
