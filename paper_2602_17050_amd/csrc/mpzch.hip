@@ -394,6 +394,11 @@ bool layout_ok(const TableCfg &c, const int64_t *identities, const int32_t *meta
 {
     return c.layout != MPZCH_LAYOUT_RECORDS || records_ok(identities, metadata);
 }
+// the read-only entry points see the identities only: records start at a multiple of 16 bytes
+bool identities_ok(const TableCfg &c, const int64_t *identities)
+{
+    return identities && (c.layout != MPZCH_LAYOUT_RECORDS || !((uintptr_t)identities & 15));
+}
 
 bool valid_cfg(int64_t num_slots, int32_t max_probe, mpzch_eviction_policy_t policy)
 {
@@ -635,9 +640,8 @@ mpzch_status_t mpzch_lookup(const mpzch_table_t *t, const int64_t *identities,
                             const int64_t *ids, int64_t n,
                             int64_t *out_slots, uint8_t *out_found, void *stream)
 {
-    if (!t || !identities) return MPZCH_ERR_INVALID_ARG;
+    if (!t || !identities_ok(t->cfg, identities)) return MPZCH_ERR_INVALID_ARG;
     if (n < 0 || n > MPZCH_MAX_BATCH) return MPZCH_ERR_INVALID_ARG;
-    if (t->cfg.layout == MPZCH_LAYOUT_RECORDS && ((uintptr_t)identities & 15)) return MPZCH_ERR_INVALID_ARG;
     if (n == 0) return MPZCH_OK;
     if (!ids || !out_slots) return MPZCH_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)stream;
@@ -662,7 +666,7 @@ mpzch_status_t mpzch_lookup_stats(mpzch_table_t *t, const int64_t *identities,
                                   const int64_t *ids, int64_t n,
                                   int64_t *out_slots, uint8_t *out_found, int64_t *out_stats, void *stream)
 {
-    if (!t || !identities || !out_stats) return MPZCH_ERR_INVALID_ARG;
+    if (!t || !identities_ok(t->cfg, identities) || !out_stats) return MPZCH_ERR_INVALID_ARG;
     if (n < 0 || n > MPZCH_MAX_BATCH) return MPZCH_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)stream;
     if (n == 0) return fill64(out_stats, MPZCH_STAT_COUNT, 0, s);
@@ -804,7 +808,7 @@ mpzch_status_t mpzch_lookup_gather(const mpzch_table_t *t, const int64_t *identi
                                    const void *rows, int64_t num_rows, int64_t row_bytes, int64_t row_stride_bytes,
                                    void *out_rows, int64_t *out_slots, uint8_t *out_found, void *stream)
 {
-    if (!t || !identities) return MPZCH_ERR_INVALID_ARG;
+    if (!t || !identities_ok(t->cfg, identities)) return MPZCH_ERR_INVALID_ARG;
     if (n < 0 || n > MPZCH_MAX_BATCH) return MPZCH_ERR_INVALID_ARG;
     if (!rows || num_rows < 1 || !out_rows) return MPZCH_ERR_INVALID_ARG;
     const RowGeom g = row_geom(rows, row_bytes, row_stride_bytes, out_rows);
@@ -1003,7 +1007,7 @@ mpzch_status_t mpzch_lookup_jagged(mpzch_group_t *g, const int64_t *const *ident
     const int T = (int)g->cfgs.size();
     std::vector<TableDesc> descs((size_t)T);
     for (int f = 0; f < T; ++f) {
-        if (!identities[f]) return MPZCH_ERR_INVALID_ARG;
+        if (!identities_ok(g->cfgs[f], identities[f])) return MPZCH_ERR_INVALID_ARG;
         descs[f] = make_desc(g->cfgs[f], const_cast<int64_t *>(identities[f]), nullptr, 0, 0);
     }
     if (total_values == 0) return MPZCH_OK;

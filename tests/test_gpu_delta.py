@@ -34,9 +34,13 @@ def test_reset_rows_multi_resets_weights_and_optimizer_state_in_one_launch():
     assert np.array_equal(v.float().cpu().numpy(), v_np)
 
 
-def test_lookup_gather_returns_the_rows_of_the_looked_up_slots():
+LAYOUTS = ("separate", "records")
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_lookup_gather_returns_the_rows_of_the_looked_up_slots(layout):
     """One kernel resolves the slots and copies the rows (Sec. 3.7); the slots themselves are an optional output."""
-    p = Pair(50_000, 16, 3, True, 77)
+    p = Pair(50_000, 16, 3, True, 77, layout=layout)
     rng = np.random.Generator(np.random.Philox(key=11))
     for step in range(4):
         p.step(wl.zipf_ids(rng, 20_000, 1.05, 60_000), step, check_state=False)
@@ -107,13 +111,15 @@ def test_lookup_gather_at_the_size_of_the_inference_configuration():
     g.close()
 
 
-def test_streaming_delta_brings_an_inference_copy_up_to_date():
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_streaming_delta_brings_an_inference_copy_up_to_date(layout):
     """Train for a while, publish a full snapshot (identities + rows), train on, publish a delta of
-    what was touched since: the inference copy must equal the training state wherever it matters."""
+    what was touched since: the inference copy must equal the training state wherever it matters.
+    (The inference copy is a dense identities tensor whatever the layout of the training table.)"""
     spec = wl.c4_spec(1 / 2000)                                          # 250 K slots
     t = spec.table
     dim = 16
-    p = Pair(t.num_slots, t.max_probe, t.ttl, True, t.hash_seed)
+    p = Pair(t.num_slots, t.max_probe, t.ttl, True, t.hash_seed, layout=layout)
     rows = torch.from_numpy(wl.embedding_pattern(t.num_slots, dim, np.float32)).cuda()
     for lo in range(0, spec.prefill_ids, 50_000):
         p.step(wl.stream_prefill_ids(lo, min(lo + 50_000, spec.prefill_ids)), 0, check_state=False)
@@ -165,7 +171,8 @@ def test_streaming_delta_brings_an_inference_copy_up_to_date():
     p.close()
 
 
-def test_collect_delta_on_a_dense_multi_million_slot_table():
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_collect_delta_on_a_dense_multi_million_slot_table(layout):
     """Most workgroups fill their staging area many times over: every occupied slot touched since
     `since` must come out exactly once (count, slots and ids against the numpy statement)."""
     n_slots = 6_000_011
@@ -176,8 +183,15 @@ def test_collect_delta_on_a_dense_multi_million_slot_table():
     M[1000:9000] = 9
     I[20000:40000] = -1                                           # and an empty one
     o = oracle.Table(n_slots, 8, oracle.EVICT_TTL, 1, 5, I, M)
-    h = mp.mpzch_create(n_slots, 8, (mp.EVICT_TTL, 1), 5)
-    gI, gM = torch.from_numpy(I).cuda(), torch.from_numpy(M).cuda()
+    if layout == "records":
+        h = mp.mpzch_create_with_layout(n_slots, 8, (mp.EVICT_TTL, 1), 5, mp.LAYOUT_RECORDS)
+        rec = torch.zeros(2 * n_slots, dtype=torch.int64, device="cuda")
+        gI, gM = mp.records_views(rec, n_slots)
+        gI.copy_(torch.from_numpy(I).cuda())
+        gM.copy_(torch.from_numpy(M).cuda())
+    else:
+        h = mp.mpzch_create(n_slots, 8, (mp.EVICT_TTL, 1), 5)
+        gI, gM = torch.from_numpy(I).cuda(), torch.from_numpy(M).cuda()
     d_slots = torch.empty(n_slots, dtype=torch.int64, device="cuda")
     d_ids = torch.empty(n_slots, dtype=torch.int64, device="cuda")
     d_cnt = torch.zeros(1, dtype=torch.int64, device="cuda")

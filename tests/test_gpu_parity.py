@@ -216,3 +216,45 @@ def test_bad_arguments_are_rejected_before_launch():
     with pytest.raises(mp.MpzchError):
         mp.mpzch_reset_rows(out, g.num_evicted, rows)
     g.close()
+
+
+def test_a_record_table_is_rejected_unless_its_tensors_are_one_tensor_of_aligned_records():
+    """Every entry point that reads a table kept as 16-byte records checks, before anything is launched, that
+    the identities start at a multiple of 16 bytes (and, where it writes metadata, that metadata is the third
+    word of the same records)."""
+    n = 64
+    h = mp.mpzch_create_with_layout(n, 8, (mp.EVICT_TTL, 1), 3, mp.LAYOUT_RECORDS)
+    rec = torch.zeros(2 * n + 2, dtype=torch.int64, device="cuda")
+    good_i, good_m = mp.records_views(rec[: 2 * n], n)
+    odd_i, odd_m = mp.records_views(rec[1: 2 * n + 1], n)             # 8 bytes off
+    mp.mpzch_init_tensors(h, good_i, good_m)
+    ids = torch.arange(4, dtype=torch.int64, device="cuda")
+    out = torch.empty(4, dtype=torch.int64, device="cuda")
+    nev = torch.zeros(1, dtype=torch.int64, device="cuda")
+    stats = torch.zeros(mp.STAT_COUNT, dtype=torch.int64, device="cuda")
+    rows = torch.zeros(n, 4, dtype=torch.float32, device="cuda")
+    out_rows = torch.zeros(4, 4, dtype=torch.float32, device="cuda")
+    other_m = torch.zeros(n, dtype=torch.int32, device="cuda")
+    before = rec.clone()
+    calls = [
+        lambda: mp.mpzch_remap(h, odd_i, odd_m, ids, 1, out, out.clone(), nev, None),
+        lambda: mp.mpzch_remap(h, good_i, other_m, ids, 1, out, out.clone(), nev, None),       # metadata elsewhere
+        lambda: mp.mpzch_remap_noalloc(h, odd_i, odd_m, ids, 1, out, out.clone(), nev, None),
+        lambda: mp.mpzch_lookup(h, odd_i, ids, out),
+        lambda: mp.mpzch_lookup_stats(h, odd_i, ids, out, None, stats),
+        lambda: mp.mpzch_lookup_gather(h, odd_i, ids, rows, out_rows),
+        lambda: mp.mpzch_init_tensors(h, odd_i, odd_m),
+    ]
+    for k, call in enumerate(calls):
+        with pytest.raises(mp.MpzchError) as e:
+            call()
+        assert e.value.status == 1, k                                  # MPZCH_ERR_INVALID_ARG
+    grp = mp.mpzch_group_create([h])
+    with pytest.raises(mp.MpzchError):
+        mp.mpzch_lookup_jagged(grp, [odd_i], ids, torch.tensor([0, 4], dtype=torch.int64, device="cuda"), out)
+    mp.mpzch_group_destroy(grp)
+    torch.cuda.synchronize()
+    assert torch.equal(rec, before)
+    mp.mpzch_lookup(h, good_i, ids, out)                               # and the well-formed call goes through
+    torch.cuda.synchronize()
+    mp.mpzch_destroy(h)

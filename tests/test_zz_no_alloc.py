@@ -15,9 +15,9 @@ from gpu_common import say
 pytestmark = pytest.mark.gpu
 
 
-def _twin(n_slots, max_probe, kind, ttl, seed):
+def _twin(n_slots, max_probe, kind, ttl, seed, records=False):
     a = mp.MpzchTable(n_slots, max_probe, kind, ttl, seed)
-    b = mp.MpzchTable(n_slots, max_probe, kind, ttl, seed)
+    b = mp.MpzchTable(n_slots, max_probe, kind, ttl, seed, layout=mp.LAYOUT_RECORDS if records else mp.LAYOUT_SEPARATE)
     return a, b
 
 
@@ -33,11 +33,12 @@ def _call(fn, t, ids, step):
     return out[:n].cpu().numpy(), np.sort(ev[:k].cpu().numpy()), k, stats.cpu().numpy()
 
 
-@pytest.mark.parametrize("policy", ["ttl", "lru"])
+@pytest.mark.parametrize("policy", ["ttl", "lru", "ttl-records"])
 def test_noalloc_equals_remap_on_consecutive_calls(policy):
+    """("ttl-records": the table of the entry point under test is kept as 16-byte records, the other as two tensors.)"""
     kind = mp.EVICT_LRU if policy == "lru" else mp.EVICT_TTL
     n_slots, max_probe, ttl, seed = 60_000, 16, 2, 4711
-    a, b = _twin(n_slots, max_probe, kind, ttl, seed)
+    a, b = _twin(n_slots, max_probe, kind, ttl, seed, records=policy.endswith("records"))
     rng = np.random.Generator(np.random.Philox(key=777))
     # the first batch fills the table to load 0.9, so the later, smaller ones evict
     sizes = [54_000, 200_000, 3_000, 0, 150_000, 64]
