@@ -96,6 +96,7 @@ enum {
 
 #define MPZCH_MAX_BATCH ((int64_t)1 << 30) /* positions per remap / lookup call          */
 #define MPZCH_MAX_PROBE (1 << 20)          /* upper bound accepted for max_probe          */
+#define MPZCH_MAX_SLOTS ((int64_t)1 << 40) /* upper bound accepted for num_slots (8 TB of identities) */
 #define MPZCH_MAX_GROUP_TABLES 64          /* tables per mpzch_group_t                    */
 #define MPZCH_MAX_PROBE_LRU 1024           /* largest max_probe with MPZCH_EVICT_LRU      */
 
@@ -103,7 +104,7 @@ enum {
  * Creates a table handle (Algorithm 1's globals: P = max_probe; Sec. 3.4: policy).
  * Allocates no tensor and touches no GPU: scratch is allocated by the first remap
  * (or by mpzch_reserve) on the device that is current then.
- * Errors: INVALID_ARG for num_slots < 1, max_probe < 1 or > MPZCH_MAX_PROBE, ttl < 0,
+ * Errors: INVALID_ARG for num_slots < 1 or > MPZCH_MAX_SLOTS, max_probe < 1 or > MPZCH_MAX_PROBE, ttl < 0,
  * unknown policy kind, out == NULL; UNSUPPORTED for MPZCH_EVICT_LRU with max_probe > MPZCH_MAX_PROBE_LRU.
  * max_probe > num_slots is accepted and behaves as max_probe == num_slots.
  */

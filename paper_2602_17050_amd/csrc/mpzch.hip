@@ -402,7 +402,7 @@ bool identities_ok(const TableCfg &c, const int64_t *identities)
 
 bool valid_cfg(int64_t num_slots, int32_t max_probe, mpzch_eviction_policy_t policy)
 {
-    if (num_slots < 1 || max_probe < 1 || max_probe > MPZCH_MAX_PROBE) return false;
+    if (num_slots < 1 || num_slots > MPZCH_MAX_SLOTS || max_probe < 1 || max_probe > MPZCH_MAX_PROBE) return false;
     if (policy.kind != MPZCH_EVICT_NONE && policy.kind != MPZCH_EVICT_TTL && policy.kind != MPZCH_EVICT_LRU &&
         policy.kind != MPZCH_EVICT_TTL_EXPIRY)
         return false;

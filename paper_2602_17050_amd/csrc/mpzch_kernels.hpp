@@ -424,39 +424,71 @@ __device__ __forceinline__ int probe_absent(int empty_round) { return kProbeAbse
 // slots of the window read until the search ended: up to and including the first empty one
 __device__ __forceinline__ int absent_len(int code) { return -code - 1; }
 
+// What the lane that holds an id leaves in LDS for the lanes that load for it: the id, and `where`
+// = first slot to read (bits 0..43; tables have at most MPZCH_MAX_SLOTS slots) with, in bits 48 + r,
+// whether round q + r exists (r < G <= 16).
+struct alignas(16) ProbeReq {
+    int64_t id;
+    uint64_t where;
+};
+constexpr int kWhereSlotBits = 44;
+static_assert((int64_t)MPZCH_MAX_SLOTS <= ((int64_t)1 << (kWhereSlotBits - 1)), "slot numbers are packed into ProbeReq::where");
+
+// s_req: 64 requests, s_code: 64 * G bytes, both this wavefront's own areas of LDS.  The G lanes of
+// a group read G consecutive slots of one id per access; what each saw (1 = the id, 2 = an empty
+// slot, 0 = neither) goes back through LDS as one byte per slot, and the id's own lane reads its G
+// bytes at once: no cross-lane operation depends on a load, and nothing branches.
 template <int G>
-__device__ __forceinline__ int probe_pass(const Tab &d, int64_t id, int64_t home, int q)
+__device__ __forceinline__ int probe_pass(const Tab &d, int64_t id, int64_t home, int q, ProbeReq *s_req,
+                                          uint8_t *s_code)
 {
+    static_assert(G == 8 || G == 16, "the codes of one id are read back as one or two 64-bit words");
     constexpr int IPI = kWave / G;
     const int lane = lane_id();
     const int g = lane / G, r = lane % G;
+    // the rounds of [q, q + G) that exist are r_lo <= r < r_hi; none when the lane is switched off
+    const int r_lo = q < 0 ? -q : 0;
+    const int r_hi = d.P - q < G ? d.P - q : G;
+    const bool on = r_hi > r_lo;
+    const uint32_t rounds = on ? ((1u << r_hi) - 1u) & ~((1u << r_lo) - 1u) : 0u;
+    const int64_t first_slot = on ? wrap(home + (q + r_lo), d.N) : 0;
+    s_req[lane] = ProbeReq{id, (uint64_t)first_slot | ((uint64_t)rounds << 48)};
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     int64_t v[G];
     uint32_t act_bits = 0;
+    const uint32_t below = (1u << r) - 1u;
 #pragma unroll
     for (int t = 0; t < G; ++t) {
-        const int src = t * IPI + g;
-        const int64_t ghome = shfl64(home, src);
-        const int gq = __shfl(q, src);
-        const int round = gq + r;
-        const bool act = round >= 0 && round < d.P;
-        // lanes without a slot: the home slot when their id is being probed (the line is fetched anyway),
-        // else slot 0 (ids that are switched off share one line; the home slot of another, larger table
-        // would not be a valid address here)
-        v[t] = *id_at(d, act ? wrap(ghome + round, d.N) : ((gq < d.P && ghome < d.N) ? ghome : 0));
+        const ProbeReq rq = s_req[t * IPI + g];
+        const uint32_t grounds = (uint32_t)(rq.where >> 48);
+        const bool act = (grounds >> r) & 1u;
+        // an active lane reads the slot of its round; the others the first slot (r < r_lo) or the one
+        // after the last (r >= r_hi): valid addresses in or next to the line that is fetched anyway
+        // (slot 0 when the id is switched off)
+        const uint32_t k = (uint32_t)__popc(grounds & below);
+        v[t] = *id_at(d, wrap((int64_t)(rq.where & ((1ull << kWhereSlotBits) - 1ull)) + (int64_t)k, d.N));
         act_bits |= (uint32_t)act << t;
     }
-    int found = kProbeGoOn;
 #pragma unroll
     for (int t = 0; t < G; ++t) {
-        const int src = t * IPI + g;
-        const int64_t gid = shfl64(id, src);
-        const int gq = __shfl(q, src);         // shuffles stay outside conditionals: every lane must take part
-        const bool act = (act_bits >> t) & 1u;
-        const int first = group_first<G>(__ballot(act && v[t] == gid), g);
-        const int efirst = group_first<G>(__ballot(act && v[t] == -1), g);
-        const int got = __shfl(first >= 0 ? gq + first : (efirst >= 0 ? probe_absent(gq + efirst) : kProbeGoOn), (lane % IPI) * G);
-        if (lane / IPI == t) found = got;
+        const int64_t gid = s_req[t * IPI + g].id;
+        uint32_t code = v[t] == gid ? 1u : (v[t] == -1 ? 2u : 0u);
+        if (!((act_bits >> t) & 1u)) code = 0u;
+        s_code[t * kWave + lane] = (uint8_t)code;            // = byte r of id t * IPI + g
     }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    // the lowest set bit of the id's G bytes: bit 8 j = found at round q + j, bit 8 j + 1 = round q + j is empty
+    const uint64_t *mine = reinterpret_cast<const uint64_t *>(s_code + lane * G);
+    uint64_t x = mine[0];
+    int j0 = 0;
+    if constexpr (G == 16) {
+        const uint64_t x1 = mine[1];
+        if (x == 0) { x = x1; j0 = 8; }
+    }
+    const int bit = __ffsll((unsigned long long)x) - 1;
+    const int round = q + j0 + (bit >> 3);
+    const int found = x == 0 ? kProbeGoOn : ((bit & 1) ? probe_absent(round) : round);
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");    // the areas are written again by the next pass
     return found;
 }
 
@@ -515,6 +547,9 @@ __device__ __forceinline__ void discover_body(const Params &p)
     __shared__ int32_t s_q[kWavesPerBlock][kStage];      // > 0: next round to look at; < 0: absent, -(slots read)
     __shared__ unsigned long long s_red[kWavesPerBlock][kStatCount];
     __shared__ int s_tab[kWavesPerBlock];
+    __shared__ ProbeReq s_req[kWavesPerBlock][kWave];
+    __shared__ __attribute__((aligned(16))) uint8_t s_code[kWavesPerBlock][kWave * kLine];
+    constexpr int kNextG = 8;                    // slots per id and access of the passes after the first
 
     const int lane = lane_id();
     const int w = threadIdx.x / kWave;
@@ -614,11 +649,11 @@ __device__ __forceinline__ void discover_body(const Params &p)
                 for (;;) {
                     const bool need = mine && dist < 0 && mlen == 0 && q < d.P;
                     if (!__any(need)) break;
-                    const int got = probe_pass<kLine>(d, id, home, need ? q : d.P);
+                    const int got = probe_pass<kNextG>(d, id, home, need ? q : d.P, s_req[w], s_code[w]);
                     if (need) {
                         if (got >= 0) dist = got;
                         else if (got <= kProbeAbsent) mlen = absent_len(got);   // an empty slot ends the search
-                        else q += kLine;
+                        else q += kNextG;
                     }
                 }
                 if (mine && dist >= 0) finish_hit(d, (int64_t)pos, home, dist, true);
@@ -699,7 +734,7 @@ __device__ __forceinline__ void discover_body(const Params &p)
             const int64_t home = mine ? home_slot(id, d.seed, d.N) : 0;
             // first pass: the aligned 64 bytes that hold the home slot
             const int o = block_offset(d, home, kFirstG);
-            int res = probe_pass<kFirstG>(d, id, home, valid ? -o : d.P);
+            int res = probe_pass<kFirstG>(d, id, home, valid ? -o : d.P, s_req[w], s_code[w]);
             if (res == kProbeGoOn && kFirstG - o >= d.P) res = probe_absent(d.P - 1);    // the whole window was read
             const bool hit = valid && res >= 0;
             if (hit) finish_hit(d, pos, home, res, false);
