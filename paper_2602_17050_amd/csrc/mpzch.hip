@@ -390,14 +390,21 @@ bool records_ok(const int64_t *identities, const int32_t *metadata)
 {
     return !((uintptr_t)identities & 15) && (const void *)metadata == (const void *)((const int32_t *)identities + 2);
 }
+// the kernels keep the address of a slot in 48 bits (device addresses have no more)
+bool addresses_ok(const TableCfg &c, const int64_t *identities)
+{
+    const uint64_t bytes = (uint64_t)c.num_slots << (c.layout == MPZCH_LAYOUT_RECORDS ? 4 : 3);
+    const uint64_t begin = (uint64_t)(uintptr_t)identities;
+    return identities && !(begin >> 48) && !((begin + bytes) >> 48);
+}
 bool layout_ok(const TableCfg &c, const int64_t *identities, const int32_t *metadata)
 {
-    return c.layout != MPZCH_LAYOUT_RECORDS || records_ok(identities, metadata);
+    return addresses_ok(c, identities) && (c.layout != MPZCH_LAYOUT_RECORDS || records_ok(identities, metadata));
 }
 // the read-only entry points see the identities only: records start at a multiple of 16 bytes
 bool identities_ok(const TableCfg &c, const int64_t *identities)
 {
-    return identities && (c.layout != MPZCH_LAYOUT_RECORDS || !((uintptr_t)identities & 15));
+    return addresses_ok(c, identities) && (c.layout != MPZCH_LAYOUT_RECORDS || !((uintptr_t)identities & 15));
 }
 
 bool valid_cfg(int64_t num_slots, int32_t max_probe, mpzch_eviction_policy_t policy)

@@ -425,69 +425,76 @@ __device__ __forceinline__ int probe_absent(int empty_round) { return kProbeAbse
 __device__ __forceinline__ int absent_len(int code) { return -code - 1; }
 
 // What the lane that holds an id leaves in LDS for the lanes that load for it: the id, and `where`
-// = first slot to read (bits 0..43; tables have at most MPZCH_MAX_SLOTS slots) with, in bits 48 + r,
-// whether round q + r exists (r < G <= 16).
+// = address of the identity of the first slot to read (bits 0..47: device addresses have no more)
+// with, in bit 48 + r, whether round q + r exists (r < G).
 struct alignas(16) ProbeReq {
     int64_t id;
     uint64_t where;
 };
-constexpr int kWhereSlotBits = 44;
-static_assert((int64_t)MPZCH_MAX_SLOTS <= ((int64_t)1 << (kWhereSlotBits - 1)), "slot numbers are packed into ProbeReq::where");
+constexpr int kWhereAddrBits = 48;
+
+// the loads of one pass: lane r of a group reads slot number k(r) behind the first one, where k counts the rounds
+// that exist below its own -- its own slot when its round exists, else the first slot (r < r_lo) or the one after
+// the last (r >= r_hi): valid addresses in or next to the line that is fetched anyway.  Slots past the end of the
+// table go on at slot 0.
+template <int G>
+__device__ __forceinline__ void probe_loads(const Tab &d, const ProbeReq *s_req, int64_t (&v)[G])
+{
+    constexpr int IPI = kWave / G;
+    const int lane = lane_id();
+    const int g = lane / G, r = lane % G;
+    const uint32_t below = (1u << r) - 1u;
+    const int sh3 = 3 + d.sh;
+    const uint64_t table_bytes = (uint64_t)d.N << sh3;
+    const uint64_t table_end = (uint64_t)(uintptr_t)(int64_t *)d.I + table_bytes;
+#pragma unroll
+    for (int t = 0; t < G; ++t) {
+        const uint64_t where = s_req[t * IPI + g].where;
+        const uint32_t k = (uint32_t)__popc((uint32_t)(where >> kWhereAddrBits) & below);
+        uint64_t a = (where & ((1ull << kWhereAddrBits) - 1ull)) + (uint64_t)(k << sh3);
+        if (a >= table_end) a -= table_bytes;
+        v[t] = *(global_ptr<int64_t>)(uintptr_t)a;
+    }
+}
 
 // s_req: 64 requests, s_code: 64 * G bytes, both this wavefront's own areas of LDS.  The G lanes of
 // a group read G consecutive slots of one id per access; what each saw (1 = the id, 2 = an empty
 // slot, 0 = neither) goes back through LDS as one byte per slot, and the id's own lane reads its G
-// bytes at once: no cross-lane operation depends on a load, and nothing branches.
+// bytes at once and drops those of rounds that do not exist: no cross-lane operation depends on a
+// load, and nothing branches.
 template <int G>
 __device__ __forceinline__ int probe_pass(const Tab &d, int64_t id, int64_t home, int q, ProbeReq *s_req,
                                           uint8_t *s_code)
 {
-    static_assert(G == 8 || G == 16, "the codes of one id are read back as one or two 64-bit words");
+    static_assert(G == 8, "the codes of one id are read back as one 64-bit word");
     constexpr int IPI = kWave / G;
     const int lane = lane_id();
-    const int g = lane / G, r = lane % G;
+    const int g = lane / G;
     // the rounds of [q, q + G) that exist are r_lo <= r < r_hi; none when the lane is switched off
     const int r_lo = q < 0 ? -q : 0;
     const int r_hi = d.P - q < G ? d.P - q : G;
-    const bool on = r_hi > r_lo;
+    const int count = r_hi - r_lo;
+    const bool on = count > 0;
     const uint32_t rounds = on ? ((1u << r_hi) - 1u) & ~((1u << r_lo) - 1u) : 0u;
+    // the slots read for this id are first_slot .. first_slot + count (the last by lanes without a round)
     const int64_t first_slot = on ? wrap(home + (q + r_lo), d.N) : 0;
-    s_req[lane] = ProbeReq{id, (uint64_t)first_slot | ((uint64_t)rounds << 48)};
+    s_req[lane] = ProbeReq{id, (uint64_t)(uintptr_t)(int64_t *)id_at(d, first_slot) | ((uint64_t)rounds << kWhereAddrBits)};
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     int64_t v[G];
-    uint32_t act_bits = 0;
-    const uint32_t below = (1u << r) - 1u;
-#pragma unroll
-    for (int t = 0; t < G; ++t) {
-        const ProbeReq rq = s_req[t * IPI + g];
-        const uint32_t grounds = (uint32_t)(rq.where >> 48);
-        const bool act = (grounds >> r) & 1u;
-        // an active lane reads the slot of its round; the others the first slot (r < r_lo) or the one
-        // after the last (r >= r_hi): valid addresses in or next to the line that is fetched anyway
-        // (slot 0 when the id is switched off)
-        const uint32_t k = (uint32_t)__popc(grounds & below);
-        v[t] = *id_at(d, wrap((int64_t)(rq.where & ((1ull << kWhereSlotBits) - 1ull)) + (int64_t)k, d.N));
-        act_bits |= (uint32_t)act << t;
-    }
+    probe_loads<G>(d, s_req, v);
 #pragma unroll
     for (int t = 0; t < G; ++t) {
         const int64_t gid = s_req[t * IPI + g].id;
-        uint32_t code = v[t] == gid ? 1u : (v[t] == -1 ? 2u : 0u);
-        if (!((act_bits >> t) & 1u)) code = 0u;
-        s_code[t * kWave + lane] = (uint8_t)code;            // = byte r of id t * IPI + g
+        s_code[t * kWave + lane] = v[t] == gid ? 1 : (v[t] == -1 ? 2 : 0);        // = byte r of id t * IPI + g
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    // the lowest set bit of the id's G bytes: bit 8 j = found at round q + j, bit 8 j + 1 = round q + j is empty
-    const uint64_t *mine = reinterpret_cast<const uint64_t *>(s_code + lane * G);
-    uint64_t x = mine[0];
-    int j0 = 0;
-    if constexpr (G == 16) {
-        const uint64_t x1 = mine[1];
-        if (x == 0) { x = x1; j0 = 8; }
-    }
+    // the lowest set bit of the bytes of the rounds that exist: bit 8 j = found at round q + r_lo + j,
+    // bit 8 j + 1 = that round's slot is empty
+    const uint64_t x = *reinterpret_cast<const uint64_t *>(s_code + lane * G) >> (8 * r_lo);
     const int bit = __ffsll((unsigned long long)x) - 1;
-    const int round = q + j0 + (bit >> 3);
-    const int found = x == 0 ? kProbeGoOn : ((bit & 1) ? probe_absent(round) : round);
+    const int j = bit >> 3;
+    const int round = q + r_lo + j;
+    const int found = (x == 0 || j >= count) ? kProbeGoOn : ((bit & 1) ? probe_absent(round) : round);
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");    // the areas are written again by the next pass
     return found;
 }
@@ -548,7 +555,7 @@ __device__ __forceinline__ void discover_body(const Params &p)
     __shared__ unsigned long long s_red[kWavesPerBlock][kStatCount];
     __shared__ int s_tab[kWavesPerBlock];
     __shared__ ProbeReq s_req[kWavesPerBlock][kWave];
-    __shared__ __attribute__((aligned(16))) uint8_t s_code[kWavesPerBlock][kWave * kLine];
+    __shared__ __attribute__((aligned(16))) uint8_t s_code[kWavesPerBlock][kWave * kFirstG];
     constexpr int kNextG = 8;                    // slots per id and access of the passes after the first
 
     const int lane = lane_id();

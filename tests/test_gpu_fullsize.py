@@ -111,11 +111,14 @@ def test_config4_500m_slots_lru():
     _stream_parity(wl.c4_spec(), steps=2, lru=True)
 
 
-def test_config3_100m_slots_lookup():
-    """100 M slots, 80 M resident ids, P = 32: 1 M lookups per batch, 95 % resident."""
+@pytest.mark.parametrize("layout", ["separate", "records"])
+def test_config3_100m_slots_lookup(layout):
+    """100 M slots, 80 M resident ids, P = 32: 1 M lookups per batch, 95 % resident; every output of every batch
+    is compared with the oracle, and a repeated call must return the same."""
     spec = wl.c3_spec()
     n_res = 80_000_000
-    g = mp.MpzchTable(spec.num_slots, spec.max_probe, mp.EVICT_NONE, 0, spec.hash_seed, max_batch=1 << 23)
+    g = mp.MpzchTable(spec.num_slots, spec.max_probe, mp.EVICT_NONE, 0, spec.hash_seed, max_batch=1 << 23,
+                      layout=mp.LAYOUT_RECORDS if layout == "records" else mp.LAYOUT_SEPARATE)
     chunk = 1 << 23
     out = torch.empty(chunk, dtype=torch.int64, device="cuda")
     collisions = 0
@@ -124,7 +127,7 @@ def test_config3_100m_slots_lookup():
         g.remap(torch.from_numpy(wl.c3_prefill_ids(lo, hi)).cuda(), 0, out[: hi - lo])
         collisions += g.stats_dict()["collisions"]
     torch.cuda.synchronize()
-    I = g.identities.cpu().numpy()
+    I = np.ascontiguousarray(g.identities.cpu().numpy())
     occ = int(np.count_nonzero(I >= 0))
     say(f"c3 prefill: occupied {occ}, collisions {collisions}")
     assert occ + collisions == n_res
@@ -132,12 +135,15 @@ def test_config3_100m_slots_lookup():
                      np.zeros(spec.num_slots, np.int32))
     _sampled_state_check(o, np.random.default_rng(3))
     before = int(g.identities.sum().item())
-    for s in range(3):
+    for s in range(4):
         ids = wl.c3_batch(s, 1_000_000, n_res)
-        sg, fg = g.lookup(torch.from_numpy(ids).cuda())
+        ids_g = torch.from_numpy(ids).cuda()
+        sg, fg = g.lookup(ids_g)
         so, fo = o.lookup(ids)
         assert np.array_equal(sg.cpu().numpy(), so) and np.array_equal(fg.cpu().numpy(), fo)
         assert 0.93 < fo.mean() <= 0.951
+        sg2, fg2 = g.lookup(ids_g)
+        assert torch.equal(sg, sg2) and torch.equal(fg, fg2)
     assert int(g.identities.sum().item()) == before                  # read-only
     g.close()
 
