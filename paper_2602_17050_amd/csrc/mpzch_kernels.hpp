@@ -792,18 +792,16 @@ __device__ __forceinline__ void discover_body(const Params &p)
     }
 }
 
-// The kernels around the one body, each compiled for the number of wavefronts per SIMD that
-// measured best: the training pass over one table is bound by its metadata stores and does not
-// gain from more wavefronts than two; the read-only lookup hides its load latency with four; with
-// several tables the chunk's table is looked up before its ids can be hashed (a chain of
-// dependent loads), which three wavefronts (training) or four (lookup) hide better.
-__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_discover(Params p)
+// The kernels around the one body.  At most four wavefronts per SIMD (the compiler then has 128 registers
+// and needs about 90): the pass is bound by memory, and measured within 2 % of its best from three to six
+// wavefronts for both table layouts; fewer hide the latency of the loads less well, more only add to the
+// queues of the memory system.
+__global__ __launch_bounds__(kBlock, 4) void k_discover(Params p)
 {
     discover_body<true, false, false>(p);
 }
 
-// the same pass over a table kept as 16-byte records: the metadata store lands in the line just read, the
-// pass is bound by its reads and gains a little from more wavefronts (measured: 2 and 3 alike, 4 best)
+// the same pass over a table kept as 16-byte records: the metadata store lands in the line just read
 __global__ __launch_bounds__(kBlock, 4) void k_discover_records(Params p)
 {
     discover_body<true, false, false>(p);
