@@ -27,7 +27,8 @@ PROFILES = os.path.join(ROOT, "profiles")
 # which tracked rocprofv3 summary holds the HBM traffic of a workload's dominant kernel
 TRAFFIC_PROFILE = {"headline": "remap_headline_1Bslots_4Mids.txt", "headline-separate": "remap_headline_1Bslots_4Mids_two_tensors.txt",
                    "c4": "remap_c4_500Mslots_2Mids.txt", "c4-separate": "remap_c4_500Mslots_2Mids_two_tensors.txt",
-                   "c5": "remap_jagged_c5_26tables.txt", "c3": "lookup_c3_100Mslots_1Mids.txt"}
+                   "c5": "remap_jagged_c5_26tables.txt", "c5-separate": "remap_jagged_c5_26tables_two_tensors.txt",
+                   "c3": "lookup_c3_100Mslots_1Mids.txt"}
 
 
 def measured_ceilings():
