@@ -2,8 +2,10 @@
 """Benchmark of the MPZCH remap hot path on one MI355X.
 
 A step is one pass of the whole hot path over one batch that is already resident
-in HBM: mpzch_remap (discover, allocate, finalize, duplicate emit, cleanup) followed
-by mpzch_reset_rows on the embedding.  Prints ONE JSON line.
+in HBM: the remap (discover, allocate, finalize) and the reset of the embedding rows
+of the evicted slots -- one mpzch_remap_reset call, whose finalize kernel also resets
+the rows (--no-fused-reset: mpzch_remap followed by mpzch_reset_rows).  Prints ONE
+JSON line.
 
 Default workload ("headline"): a single 1 B-slot table (P = 16, TTL = 20 steps)
 prefilled to load 0.7, 4 M ids per step from the streaming-freshness generator
@@ -131,6 +133,9 @@ def main():
     ap.add_argument("--all-kernel-timing", action="store_true",
                     help="bracket every kernel with events (a breakdown; costs a step some 30 us), not only Pass 1")
     ap.add_argument("--policy", default="ttl", choices=["ttl", "lru"], help="eviction policy (headline / c4 workloads)")
+    ap.add_argument("--no-fused-reset", action="store_true",
+                    help="headline / c4: a step is mpzch_remap + mpzch_reset_rows (two calls, four launches) instead of "
+                         "mpzch_remap_reset (the rows are reset by the finalize kernel)")
     ap.add_argument("--layout", default="records", choices=["separate", "records"],
                     help="headline / c4: identities and metadata as one tensor of 16-byte records {int64 id, int32 "
                          "metadata, 4 unused bytes} (default: a hit then refreshes the line it has just read), or as "
@@ -202,7 +207,13 @@ def main():
     ev_a = [torch.cuda.Event(enable_timing=True) for _ in range(W + K)]
     ev_b = [torch.cuda.Event(enable_timing=True) for _ in range(W + K)]
 
+    fused = not args.no_fused_reset
+
     def one_step(i):
+        if fused:                 # the rows are reset by the kernel that decides the evictions (k_finalize)
+            mp.mpzch_remap_reset(g.handle, g.identities, g.metadata, batches[i], steps[i], outs[i], evicted, nev[i],
+                                 stats[i], emb)
+            return
         mp.mpzch_remap(g.handle, g.identities, g.metadata, batches[i], steps[i], outs[i], evicted, nev[i], stats[i])
         if args.all_kernel_timing:
             ev_a[i].record()      # the binding launches on torch's current stream, so these events see it
@@ -234,7 +245,7 @@ def main():
     elapsed = time.perf_counter() - t0
     ktimes = {} if args.no_kernel_timing else mp.mpzch_kernel_times(g.handle)
     mp.mpzch_set_kernel_timing(g.handle, False)
-    if ktimes and args.all_kernel_timing:
+    if ktimes and args.all_kernel_timing and not fused:
         ktimes["k_reset_rows"] = (sum(ev_a[i].elapsed_time(ev_b[i]) for i in range(W, W + K)), K)
 
     total_ids = spec.batch * K
@@ -315,7 +326,8 @@ def main():
                         f"{'LRU' if args.policy == 'lru' else 'TTL=' + str(t.ttl)}, load "
                         f"{spec.prefill_ids / t.num_slots:.2f}, {spec.batch} ids/step, "
                         f"{int(spec.new_fraction * 100)}% new ids/step, reset rows of {t.emb_rows}x{t.emb_dim} bf16, "
-                        f"identities+metadata as {'16-byte records' if args.layout == 'records' else 'two tensors'}",
+                        f"identities+metadata as {'16-byte records' if args.layout == 'records' else 'two tensors'}, "
+                        f"{'one mpzch_remap_reset call' if fused else 'mpzch_remap + mpzch_reset_rows'} per step",
             "num_slots": t.num_slots, "max_probe": t.max_probe, "ttl": t.ttl, "batch": spec.batch, "scale": args.scale,
             "layout": args.layout,
         },

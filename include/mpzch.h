@@ -186,6 +186,26 @@ mpzch_status_t mpzch_remap(mpzch_table_t *t, int64_t *identities, int32_t *metad
                            int64_t *out_stats, void *stream);
 
 /*
+ * mpzch_remap that also resets the embedding rows of the slots it evicts (Sec. 3.4: the weights
+ * of an evicted id must not be inherited by the id that takes its slot), in the kernel that
+ * decides the evictions: rows[(slot mod num_rows), 0..row_bytes) <- init_row, or zero bits when
+ * init_row is NULL, for EVERY slot that changed owner in this call -- also for those beyond
+ * evicted_cap, which mpzch_remap + mpzch_reset_rows would leave out.  Otherwise identical to
+ * mpzch_remap followed by mpzch_reset_rows (the evicted list and its count are still written, for
+ * further tensors to reset with mpzch_reset_rows_multi); one launch less, and the list does not
+ * travel through HBM before the rows are written.
+ * rows [dev], num_rows >= 1, row_bytes, row_stride_bytes, init_row [dev]: as for mpzch_reset_rows.
+ * Errors: those of mpzch_remap and of mpzch_reset_rows; INVALID_ARG when rows == NULL.
+ */
+mpzch_status_t mpzch_remap_reset(mpzch_table_t *t, int64_t *identities, int32_t *metadata,
+                                 const int64_t *ids, int64_t n, int32_t step,
+                                 int64_t *out_slots,
+                                 int64_t *out_evicted_slots, int64_t evicted_cap, int64_t *out_num_evicted,
+                                 int64_t *out_stats,
+                                 void *rows, int64_t num_rows, int64_t row_bytes, int64_t row_stride_bytes,
+                                 const void *init_row, void *stream);
+
+/*
  * mpzch_remap for callers that cannot allocate device memory: code under HIP graph capture, tight
  * serving loops, harnesses that forbid hipMalloc.  Same arguments, same result and same kernels as
  * mpzch_remap, but the scratch is a fixed area of MPZCH_NOALLOC_SCRATCH_BYTES bytes that the library

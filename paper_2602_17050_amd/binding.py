@@ -26,7 +26,7 @@ EXPORTED = (
     "mpzch_group_set_kernel_timing", "mpzch_group_kernel_times", "mpzch_status_string",
     "mpzch_remap_feature_ttl", "mpzch_reset_rows_multi", "mpzch_lookup_gather", "mpzch_collect_delta", "mpzch_gather_rows", "mpzch_apply_delta",
     "mpzch_remap_jagged_feature_ttl", "mpzch_lookup_jagged", "mpzch_reset_rows_jagged",
-    "mpzch_remap_noalloc", "mpzch_lookup_stats", "mpzch_create_with_layout",
+    "mpzch_remap_noalloc", "mpzch_lookup_stats", "mpzch_create_with_layout", "mpzch_remap_reset",
 )
 LAYOUT_SEPARATE, LAYOUT_RECORDS = 0, 1
 NOALLOC_MAX_BATCH = 262144
@@ -69,6 +69,7 @@ def load_library(path: str | None = None):
     lib.mpzch_init_tensors.argtypes = [vp, vp, vp, vp]
     lib.mpzch_remap.argtypes = [vp, vp, vp, vp, i64, i32, vp, vp, i64, vp, vp, vp]
     lib.mpzch_remap_noalloc.argtypes = [vp, vp, vp, vp, i64, i32, vp, vp, i64, vp, vp, vp]
+    lib.mpzch_remap_reset.argtypes = [vp, vp, vp, vp, i64, i32, vp, vp, i64, vp, vp, vp, i64, i64, i64, vp, vp]
     lib.mpzch_remap_feature_ttl.argtypes = [vp, vp, vp, vp, vp, i64, i32, vp, vp, i64, vp, vp, vp]
     lib.mpzch_lookup.argtypes = [vp, vp, vp, i64, vp, vp, vp]
     lib.mpzch_lookup_stats.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp]
@@ -171,6 +172,26 @@ def mpzch_remap(handle, identities, metadata, ids, step: int, out_slots, out_evi
                                       _ptr(ids, torch.int64), n, step, _ptr(out_slots, torch.int64),
                                       _ptr(out_evicted_slots, torch.int64), cap, _ptr(out_num_evicted, torch.int64),
                                       _ptr(out_stats, torch.int64), _stream()), "mpzch_remap")
+
+
+def mpzch_remap_reset(handle, identities, metadata, ids, step: int, out_slots, out_evicted_slots, out_num_evicted,
+                      out_stats, rows, init_row=None, num_rows: int | None = None):
+    """mpzch_remap that also resets rows[slot mod num_rows] of every slot it evicts; rows: 2-D tensor (num_rows, dim)."""
+    n = ids.numel()
+    cap = 0 if out_evicted_slots is None else out_evicted_slots.numel()
+    assert rows.dim() == 2 and rows.stride(1) == 1 and rows.is_cuda
+    nrows = rows.shape[0] if num_rows is None else num_rows
+    row_bytes = rows.shape[1] * rows.element_size()
+    stride = rows.stride(0) * rows.element_size()
+    if init_row is not None:
+        assert init_row.is_cuda and init_row.is_contiguous() and init_row.numel() * init_row.element_size() == row_bytes
+    _check(load_library().mpzch_remap_reset(handle, _ptr(identities, torch.int64), _ptr(metadata, torch.int32),
+                                            _ptr(ids, torch.int64), n, step, _ptr(out_slots, torch.int64),
+                                            _ptr(out_evicted_slots, torch.int64), cap, _ptr(out_num_evicted, torch.int64),
+                                            _ptr(out_stats, torch.int64), ctypes.c_void_p(rows.data_ptr()), nrows,
+                                            row_bytes, stride,
+                                            None if init_row is None else ctypes.c_void_p(init_row.data_ptr()),
+                                            _stream()), "mpzch_remap_reset")
 
 
 def mpzch_remap_noalloc(handle, identities, metadata, ids, step: int, out_slots, out_evicted_slots, out_num_evicted,
@@ -401,6 +422,17 @@ class MpzchTable:
             self._evicted = torch.empty(max(n, 1), dtype=torch.int64, device=ids.device)
         mpzch_remap_feature_ttl(self.handle, self.identities, self.metadata, ids, ttls, step, out_slots,
                                 self._evicted, self.num_evicted, self.stats)
+        return out_slots
+
+    def remap_reset(self, ids, step, rows, init_row=None, out_slots=None):
+        """remap + reset of the evicted slots' rows in one call (mpzch_remap_reset)"""
+        n = ids.numel()
+        if out_slots is None:
+            out_slots = torch.empty(n, dtype=torch.int64, device=ids.device)
+        if self._evicted is None or self._evicted.numel() < n:
+            self._evicted = torch.empty(max(n, 1), dtype=torch.int64, device=ids.device)
+        mpzch_remap_reset(self.handle, self.identities, self.metadata, ids, step, out_slots, self._evicted,
+                          self.num_evicted, self.stats, rows, init_row)
         return out_slots
 
     @property

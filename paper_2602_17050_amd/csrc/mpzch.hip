@@ -564,11 +564,40 @@ mpzch_status_t mpzch_init_tensors(const mpzch_table_t *t, int64_t *identities, i
     return MPZCH_OK;
 }
 
-mpzch_status_t mpzch_remap_feature_ttl(mpzch_table_t *t, int64_t *identities, int32_t *metadata,
-                                       const int64_t *ids, const int32_t *ttls, int64_t n, int32_t step,
-                           int64_t *out_slots,
-                           int64_t *out_evicted_slots, int64_t evicted_cap, int64_t *out_num_evicted,
-                           int64_t *out_stats, void *stream)
+namespace {
+// geometry shared by the row movers: 16-byte chunks when everything is 16-byte aligned, else 4-byte
+struct RowGeom { bool ok; bool wide; int64_t chunks; };
+RowGeom row_geom(const void *rows, int64_t row_bytes, int64_t row_stride_bytes, const void *other)
+{
+    RowGeom g{false, false, 0};
+    if (row_bytes < 4 || row_stride_bytes < row_bytes || (row_bytes & 3) || (row_stride_bytes & 3)) return g;
+    if (((uintptr_t)rows & 3) || ((uintptr_t)other & 3)) return g;
+    g.wide = !(row_bytes & 15) && !(row_stride_bytes & 15) && !((uintptr_t)rows & 15) && !((uintptr_t)other & 15);
+    g.chunks = g.wide ? row_bytes / 16 : row_bytes / 4;
+    g.ok = g.chunks <= 0x7FFFFFFF;
+    return g;
+}
+int row_grid(int64_t items)
+{
+    int64_t want = (items + kBlock - 1) / kBlock;
+    if (want > 8192) want = 8192;
+    if (want < 1) want = 1;
+    return (int)want;
+}
+}  // namespace
+
+namespace {
+// rows that a remap resets itself (mpzch_remap_reset), or none
+struct ResetRows {
+    void *rows = nullptr;
+    int64_t num_rows = 0, row_bytes = 0, row_stride_bytes = 0;
+    const void *init_row = nullptr;
+};
+
+mpzch_status_t remap_one(mpzch_table_t *t, int64_t *identities, int32_t *metadata, const int64_t *ids,
+                         const int32_t *ttls, int64_t n, int32_t step, int64_t *out_slots,
+                         int64_t *out_evicted_slots, int64_t evicted_cap, int64_t *out_num_evicted,
+                         int64_t *out_stats, const ResetRows &rr, void *stream)
 {
     if (!t || !identities || !metadata || !out_num_evicted) return MPZCH_ERR_INVALID_ARG;
     if (n < 0 || n > MPZCH_MAX_BATCH || step < 0 || evicted_cap < 0) return MPZCH_ERR_INVALID_ARG;
@@ -576,6 +605,12 @@ mpzch_status_t mpzch_remap_feature_ttl(mpzch_table_t *t, int64_t *identities, in
     if (!layout_ok(t->cfg, identities, metadata)) return MPZCH_ERR_INVALID_ARG;
     if (n > 0 && (!ids || !out_slots)) return MPZCH_ERR_INVALID_ARG;
     if (evicted_cap > 0 && !out_evicted_slots) return MPZCH_ERR_INVALID_ARG;
+    RowGeom g{true, false, 0};
+    if (rr.rows) {
+        if (rr.num_rows < 1) return MPZCH_ERR_INVALID_ARG;
+        g = row_geom(rr.rows, rr.row_bytes, rr.row_stride_bytes, rr.init_row);
+        if (!g.ok) return MPZCH_ERR_INVALID_ARG;
+    }
     hipStream_t s = (hipStream_t)stream;
     if (n == 0) {
         TRY(fill64(out_num_evicted, 1, 0, s));
@@ -595,7 +630,29 @@ mpzch_status_t mpzch_remap_feature_ttl(mpzch_table_t *t, int64_t *identities, in
     p.out_evicted = out_evicted_slots;
     p.out_num_evicted = out_num_evicted;
     p.out_stats = out_stats;
+    if (rr.rows) {
+        p.r_rows = (char *)rr.rows;
+        p.r_init = rr.init_row;
+        p.g_num_rows = rr.num_rows;
+        p.g_stride = rr.row_stride_bytes;
+        p.g_chunks = (int32_t)g.chunks;
+        p.g_wide = g.wide ? 1 : 0;
+        p.g_shift = -1;
+        for (int b = 0; b < 31; ++b)
+            if (g.chunks == ((int64_t)1 << b)) p.g_shift = b;
+    }
     return run_remap(t->sc, t->tm, p, p.t0.P, p.t0.evict == 2 ? p.t0.P : 0, s);
+}
+}  // namespace
+
+mpzch_status_t mpzch_remap_feature_ttl(mpzch_table_t *t, int64_t *identities, int32_t *metadata,
+                                       const int64_t *ids, const int32_t *ttls, int64_t n, int32_t step,
+                                       int64_t *out_slots,
+                                       int64_t *out_evicted_slots, int64_t evicted_cap, int64_t *out_num_evicted,
+                                       int64_t *out_stats, void *stream)
+{
+    return remap_one(t, identities, metadata, ids, ttls, n, step, out_slots, out_evicted_slots, evicted_cap,
+                     out_num_evicted, out_stats, ResetRows{}, stream);
 }
 
 mpzch_status_t mpzch_remap(mpzch_table_t *t, int64_t *identities, int32_t *metadata,
@@ -604,8 +661,27 @@ mpzch_status_t mpzch_remap(mpzch_table_t *t, int64_t *identities, int32_t *metad
                            int64_t *out_evicted_slots, int64_t evicted_cap, int64_t *out_num_evicted,
                            int64_t *out_stats, void *stream)
 {
-    return mpzch_remap_feature_ttl(t, identities, metadata, ids, nullptr, n, step, out_slots, out_evicted_slots,
-                                   evicted_cap, out_num_evicted, out_stats, stream);
+    return remap_one(t, identities, metadata, ids, nullptr, n, step, out_slots, out_evicted_slots, evicted_cap,
+                     out_num_evicted, out_stats, ResetRows{}, stream);
+}
+
+mpzch_status_t mpzch_remap_reset(mpzch_table_t *t, int64_t *identities, int32_t *metadata,
+                                 const int64_t *ids, int64_t n, int32_t step,
+                                 int64_t *out_slots,
+                                 int64_t *out_evicted_slots, int64_t evicted_cap, int64_t *out_num_evicted,
+                                 int64_t *out_stats,
+                                 void *rows, int64_t num_rows, int64_t row_bytes, int64_t row_stride_bytes,
+                                 const void *init_row, void *stream)
+{
+    if (!rows) return MPZCH_ERR_INVALID_ARG;
+    ResetRows rr;
+    rr.rows = rows;
+    rr.num_rows = num_rows;
+    rr.row_bytes = row_bytes;
+    rr.row_stride_bytes = row_stride_bytes;
+    rr.init_row = init_row;
+    return remap_one(t, identities, metadata, ids, nullptr, n, step, out_slots, out_evicted_slots, evicted_cap,
+                     out_num_evicted, out_stats, rr, stream);
 }
 
 mpzch_status_t mpzch_remap_noalloc(const mpzch_table_t *t, int64_t *identities, int32_t *metadata,
@@ -729,27 +805,6 @@ mpzch_status_t mpzch_reset_rows(const int64_t *slots, const int64_t *num_slots_d
     return MPZCH_OK;
 }
 
-namespace {
-// geometry shared by the row movers: 16-byte chunks when everything is 16-byte aligned, else 4-byte
-struct RowGeom { bool ok; bool wide; int64_t chunks; };
-RowGeom row_geom(const void *rows, int64_t row_bytes, int64_t row_stride_bytes, const void *other)
-{
-    RowGeom g{false, false, 0};
-    if (row_bytes < 4 || row_stride_bytes < row_bytes || (row_bytes & 3) || (row_stride_bytes & 3)) return g;
-    if (((uintptr_t)rows & 3) || ((uintptr_t)other & 3)) return g;
-    g.wide = !(row_bytes & 15) && !(row_stride_bytes & 15) && !((uintptr_t)rows & 15) && !((uintptr_t)other & 15);
-    g.chunks = g.wide ? row_bytes / 16 : row_bytes / 4;
-    g.ok = g.chunks <= 0x7FFFFFFF;
-    return g;
-}
-int row_grid(int64_t items)
-{
-    int64_t want = (items + kBlock - 1) / kBlock;
-    if (want > 8192) want = 8192;
-    if (want < 1) want = 1;
-    return (int)want;
-}
-}  // namespace
 
 mpzch_status_t mpzch_reset_rows_multi(const int64_t *slots, const int64_t *num_slots_dev, int64_t slots_cap,
                                       const mpzch_rows_t *tensors, int32_t num_tensors, void *stream)

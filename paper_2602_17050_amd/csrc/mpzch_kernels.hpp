@@ -115,6 +115,10 @@ struct Params {
     int32_t g_chunks;              // 16-byte (g_wide) or 4-byte pieces per row
     int32_t g_wide;
     int32_t g_shift;               // log2(g_chunks) when that is a power of two, else -1
+    // training remap that also resets the rows of the slots it evicts (one table; geometry in g_num_rows,
+    // g_stride, g_chunks, g_wide, g_shift): rows[slot mod num_rows, :] <- init row, or zero bits
+    char *r_rows;
+    const void *r_init;
     // outputs
     int64_t *out_evicted;
     int64_t *out_num_evicted;
@@ -1390,11 +1394,37 @@ __global__ __launch_bounds__(kWave) void k_allocate_lru_long(Params p)
 }
 
 // ------------------------------------------------------------------ finalize
-// Appends the staged evicted slots of one wavefront to table `table`'s list.
-__device__ __forceinline__ void flush_evicted(const Params &p, const int64_t *buf, int &count, int table)
+// Sec. 3.4, fused with the remap: the rows of the evicted slots that this wavefront has staged (row numbers in
+// rows_buf) get their initial value.  A row is written by consecutive lanes, 16 (or 4) bytes each.
+template <typename VEC>
+__device__ __forceinline__ void reset_rows_wave(const Params &p, const int64_t *rows_buf, int count)
+{
+    const int lane = lane_id();
+    const int C = p.g_chunks;
+    const int64_t total = (int64_t)count * C;
+    for (int64_t i = lane; i < total; i += kWave) {
+        const int k = p.g_shift >= 0 ? (int)(i >> p.g_shift) : (int)(i / C);
+        const int c = (int)(i - (int64_t)k * C);
+        VEC v = VEC(0);
+        if (p.r_init) v = reinterpret_cast<const VEC *>(p.r_init)[c];
+        __builtin_nontemporal_store(v, reinterpret_cast<VEC *>(p.r_rows + rows_buf[k] * p.g_stride) + c);
+    }
+}
+
+__device__ __forceinline__ void reset_staged_rows(const Params &p, const int64_t *rows_buf, int count)
+{
+    if (!p.r_rows || count == 0) return;
+    if (p.g_wide) reset_rows_wave<u32x4>(p, rows_buf, count);
+    else reset_rows_wave<uint32_t>(p, rows_buf, count);
+}
+
+// Appends the staged evicted slots of one wavefront to table `table`'s list (and resets their rows).
+__device__ __forceinline__ void flush_evicted(const Params &p, const int64_t *buf, const int64_t *rows_buf, int &count,
+                                              int table)
 {
     if (count == 0) return;
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    reset_staged_rows(p, rows_buf, count);
     const int lane = lane_id();
     unsigned long long base = 0;
     if (lane == 0)
@@ -1421,8 +1451,8 @@ struct FinalizeState {
 
 // Called by all lanes of the wavefront.  `done` lanes finished a claimant of table f with
 // outcome 0 = insert, 1 = eviction of slot s, 2 = collision.
-__device__ __forceinline__ void finalize_account(const Params &p, FinalizeState &fs, int64_t *s_ev_w, bool done,
-                                                 int outcome, int64_t s, int f, bool want_stats)
+__device__ __forceinline__ void finalize_account(const Params &p, FinalizeState &fs, int64_t *s_ev_w, int64_t *s_row_w,
+                                                 bool done, int outcome, int64_t s, int f, bool want_stats)
 {
     const int lane = lane_id();
     if (want_stats) {
@@ -1457,9 +1487,14 @@ __device__ __forceinline__ void finalize_account(const Params &p, FinalizeState 
         const bool sel = done && outcome == 1 && f == tf;
         const uint64_t selm = __ballot(sel);
         const int add = __popcll(selm);
-        if ((fs.ev_cnt > 0 && tf != fs.ev_table) || fs.ev_cnt + add > kEvBuf) flush_evicted(p, s_ev_w, fs.ev_cnt, fs.ev_table);
+        if ((fs.ev_cnt > 0 && tf != fs.ev_table) || fs.ev_cnt + add > kEvBuf)
+            flush_evicted(p, s_ev_w, s_row_w, fs.ev_cnt, fs.ev_table);
         fs.ev_table = tf;
-        if (sel) s_ev_w[fs.ev_cnt + __popcll(selm & ((1ull << lane) - 1ull))] = s;
+        if (sel) {
+            const int at = fs.ev_cnt + __popcll(selm & ((1ull << lane) - 1ull));
+            s_ev_w[at] = s;
+            if (p.r_rows) s_row_w[at] = s >= p.g_num_rows ? s % p.g_num_rows : s;
+        }
         fs.ev_cnt += add;
         evm &= ~selm;
     }
@@ -1473,7 +1508,8 @@ __device__ __forceinline__ void finalize_account(const Params &p, FinalizeState 
 // before it reports in.  (A device-scope release fence here would also write back the die's whole L2,
 // once per workgroup.)
 __device__ __forceinline__ bool finalize_epilogue(const Params &p, FinalizeState &fs, int64_t (*s_ev)[kEvBuf],
-                                                  int *s_cnt, int *s_tab, unsigned long long *s_base, bool *s_last,
+                                                  int64_t (*s_row)[kEvBuf], int *s_cnt, int *s_tab,
+                                                  unsigned long long *s_base, bool *s_last,
                                                   unsigned long long (*s_red)[kStatCount], bool want_stats)
 {
     const int lane = lane_id(), w = threadIdx.x / kWave;
@@ -1496,7 +1532,7 @@ __device__ __forceinline__ bool finalize_epilogue(const Params &p, FinalizeState
         const unsigned long long vals[3] = {fs.st_ins, fs.st_evi, fs.st_col};
         block_stat_add(p, idx, vals, 3, fs.st_table, s_red, s_tab);
     }
-    if (multi && total > 0 && !same) flush_evicted(p, s_ev[w], fs.ev_cnt, fs.ev_table);
+    if (multi && total > 0 && !same) flush_evicted(p, s_ev[w], s_row[w], fs.ev_cnt, fs.ev_table);
     const bool reserve = total > 0 && (same || !multi);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __syncthreads();
@@ -1519,6 +1555,7 @@ __device__ __forceinline__ bool finalize_epilogue(const Params &p, FinalizeState
         const int64_t ev_cap = multi ? p.descs[tab].ev_cap : p.t0.ev_cap;
         for (int i = lane; i < fs.ev_cnt; i += kWave)
             if (base + i < ev_cap) p.out_evicted[ev_begin + base + i] = s_ev[w][i];
+        reset_staged_rows(p, s_row[w], fs.ev_cnt);
     }
     return *s_last;
 }
@@ -1533,6 +1570,7 @@ __device__ __forceinline__ bool finalize_epilogue(const Params &p, FinalizeState
 __device__ __forceinline__ void finalize_body(const Params &p)
 {
     __shared__ int64_t s_ev[kWavesPerBlock][kEvBuf];
+    __shared__ int64_t s_row[kWavesPerBlock][kEvBuf];              // fused row reset: the rows of the staged slots
     __shared__ unsigned long long s_red[kWavesPerBlock][kStatCount];
     __shared__ unsigned long long s_bins[kMaxTables][kStatCount];
     __shared__ int s_cnt[kWavesPerBlock];
@@ -1640,11 +1678,11 @@ __device__ __forceinline__ void finalize_body(const Params &p)
                 }
                 p.out_slots[pos] = s_final;
             }
-            finalize_account(p, fs, s_ev[w], agent, outcome, s_final, f, want_stats);
+            finalize_account(p, fs, s_ev[w], s_row[w], agent, outcome, s_final, f, want_stats);
         }
     }
     // the workgroup that finishes last publishes the call's counters
-    const bool last = finalize_epilogue(p, fs, s_ev, s_cnt, s_tab, &s_base, &s_last, s_red, want_stats);
+    const bool last = finalize_epilogue(p, fs, s_ev, s_row, s_cnt, s_tab, &s_base, &s_last, s_red, want_stats);
     if (last) publish_counters(p, s_bins);
 }
 

@@ -15,7 +15,8 @@ def say(*a):
 class Pair:
     """One table on both sides."""
 
-    def __init__(self, num_slots, max_probe, ttl, evict=True, hash_seed=0, emb=None, layout="separate"):
+    def __init__(self, num_slots, max_probe, ttl, evict=True, hash_seed=0, emb=None, layout="separate",
+                 fused_reset=False):
         # evict: True = TTL, False = off, "lru" = LRU, "expiry" = per-feature TTL (metadata = expiry step)
         kind_g = {"lru": mp.EVICT_LRU, "expiry": mp.EVICT_TTL_EXPIRY}.get(evict, mp.EVICT_TTL if evict else mp.EVICT_NONE)
         kind_o = {"lru": oracle.EVICT_LRU, "expiry": oracle.EVICT_TTL_EXPIRY}.get(
@@ -26,24 +27,30 @@ class Pair:
         self.o = oracle.Table(num_slots, max_probe, kind_o, ttl, hash_seed)
         self.emb_o = None
         self.emb_g = None
+        # fused_reset: rows are reset by mpzch_remap_reset instead of mpzch_remap + mpzch_reset_rows
+        self.fused_reset = fused_reset
         if emb is not None:                       # numpy 2-D pattern
             self.emb_o = emb.copy()
             self.emb_g = torch.from_numpy(emb).cuda()
 
     @classmethod
-    def from_spec(cls, spec: wl.TableSpec, with_emb=True, layout="separate"):
+    def from_spec(cls, spec: wl.TableSpec, with_emb=True, layout="separate", fused_reset=False):
         emb = None
         if with_emb and spec.emb_rows:
             emb = wl.embedding_pattern(spec.emb_rows, spec.emb_dim, np.float32)
-        return cls(spec.num_slots, spec.max_probe, spec.ttl, spec.evict, spec.hash_seed, emb, layout)
+        return cls(spec.num_slots, spec.max_probe, spec.ttl, spec.evict, spec.hash_seed, emb, layout, fused_reset)
 
     def step(self, ids_np, step, check_state=True, init_row=None, ttls=None):
         ids_np = np.ascontiguousarray(ids_np, dtype=np.int64)
         ids_g = torch.from_numpy(ids_np).cuda()
         ttls_g = None if ttls is None else torch.from_numpy(np.ascontiguousarray(ttls, dtype=np.int32)).cuda()
-        out_g = self.g.remap(ids_g, step, ttls=ttls_g)
-        if self.emb_g is not None and ids_np.size:
-            self.g.reset_rows(self.emb_g, None if init_row is None else torch.from_numpy(init_row).cuda())
+        init_g = None if init_row is None else torch.from_numpy(init_row).cuda()
+        if self.fused_reset and self.emb_g is not None and ttls is None:
+            out_g = self.g.remap_reset(ids_g, step, self.emb_g, init_g)
+        else:
+            out_g = self.g.remap(ids_g, step, ttls=ttls_g)
+            if self.emb_g is not None and ids_np.size:
+                self.g.reset_rows(self.emb_g, init_g)
         torch.cuda.synchronize()
         r = self.o.remap(ids_np, step, ttls)
         if self.emb_o is not None:

@@ -38,7 +38,7 @@ def _sampled_state_check(o, rng, ranges=4, width=1_000_000):
     assert bad == 0, first_bad
 
 
-def _stream_parity(spec, steps, emb_check_rows=0, lru=False, records=False):
+def _stream_parity(spec, steps, emb_check_rows=0, lru=False, records=False, fused_reset=False):
     t = spec.table
     kind_g, kind_o = (mp.EVICT_LRU, oracle.EVICT_LRU) if lru else (mp.EVICT_TTL, oracle.EVICT_TTL)
     g = mp.MpzchTable(t.num_slots, t.max_probe, kind_g, t.ttl, t.hash_seed, max_batch=1 << 24,
@@ -62,9 +62,12 @@ def _stream_parity(spec, steps, emb_check_rows=0, lru=False, records=False):
     for k in range(steps):
         step = spec.first_step + k
         ids = wl.stream_batch(spec, step)
-        out = g.remap(torch.from_numpy(ids).cuda(), step)
-        if emb is not None:
-            g.reset_rows(emb)
+        if emb is not None and fused_reset:
+            out = g.remap_reset(torch.from_numpy(ids).cuda(), step, emb)          # mpzch_remap_reset
+        else:
+            out = g.remap(torch.from_numpy(ids).cuda(), step)
+            if emb is not None:
+                g.reset_rows(emb)
         torch.cuda.synchronize()
         r = o.remap(ids, step)
         assert np.array_equal(out.cpu().numpy(), r.slots), f"out_slots differ at step {step}"
@@ -99,11 +102,12 @@ def test_headline_one_billion_slots_two_steps(layout):
     _stream_parity(wl.headline_spec(), steps=2, records=layout == "records")
 
 
-@pytest.mark.parametrize("layout", ["records", "separate"])
+@pytest.mark.parametrize("layout", ["records", "separate", "records-fused"])
 def test_config4_500m_slots_with_row_reset(layout):
     """500 M slots at load 0.9, 2 M ids per step, rows of a 100 M x 128 bf16 embedding
-    addressed as slot mod rows."""
-    _stream_parity(wl.c4_spec(), steps=3, emb_check_rows=1, records=layout == "records")
+    addressed as slot mod rows ("-fused": reset by mpzch_remap_reset, what bench.py times)."""
+    _stream_parity(wl.c4_spec(), steps=3, emb_check_rows=1, records=layout.startswith("records"),
+                   fused_reset=layout.endswith("fused"))
 
 
 def test_config4_500m_slots_lru():

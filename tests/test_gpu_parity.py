@@ -88,12 +88,12 @@ def test_empty_and_single_element_batches():
     p.close()
 
 
-@pytest.mark.parametrize("layout", LAYOUTS)
-def test_config2_one_million_slots(layout):
+@pytest.mark.parametrize("layout,fused", [("separate", False), ("records", False), ("records", True), ("separate", True)])
+def test_config2_one_million_slots(layout, fused):
     """1 M slots, P = 16, TTL 10, fp32 1Mx64 rows: prefill to load 0.3, then 50 batches of
-    65 536 Zipf(1.05) ids (+5 % never-seen ids) -- insert, evict and row reset."""
+    65 536 Zipf(1.05) ids (+5 % never-seen ids) -- insert, evict and row reset (fused: by mpzch_remap_reset)."""
     spec = wl.c2_spec()
-    p = Pair.from_spec(spec, layout=layout)
+    p = Pair.from_spec(spec, layout=layout, fused_reset=fused)
     step0, pre = wl.c2_prefill()
     p.step(pre, step0, check_state=False)
     tot_ev = 0
@@ -126,13 +126,14 @@ def test_config3_lookup_scaled():
     p.close()
 
 
-def test_config4_streaming_scaled():
+@pytest.mark.parametrize("fused", [False, True])
+def test_config4_streaming_scaled(fused):
     """Streaming freshness at 1/500 scale: 1 M slots prefilled to 0.9, TTL 20, 10 % brand-new
     ids per step, rows addressed as slot mod rows -> sustained eviction and reset."""
     spec = wl.c4_spec(1 / 500)
     t = spec.table
     emb = wl.embedding_pattern(t.emb_rows, 32, np.float32)
-    p = Pair(t.num_slots, t.max_probe, t.ttl, True, t.hash_seed, emb)
+    p = Pair(t.num_slots, t.max_probe, t.ttl, True, t.hash_seed, emb, fused_reset=fused)
     for lo in range(0, spec.prefill_ids, 200_000):
         p.step(wl.stream_prefill_ids(lo, min(lo + 200_000, spec.prefill_ids)), 0, check_state=False)
     p.check_state()
@@ -144,6 +145,51 @@ def test_config4_streaming_scaled():
     assert tot_ev > 30 * 0.05 * spec.batch
     p.check_state()
     p.close()
+
+
+@pytest.mark.parametrize("policy", ["ttl", "lru"])
+def test_remap_reset_equals_remap_then_reset_rows(policy):
+    """mpzch_remap_reset on small contended tables with half as many rows as slots: rows of 3 floats (4-byte
+    pieces) with an init row, rows of 8 floats (16-byte pieces) set to zero, rows of 40 floats with an init row;
+    and an evicted list too short for the evictions -- the fused call still resets every evicted slot's row."""
+    rng = np.random.Generator(np.random.Philox(key=4242))
+    evict = "lru" if policy == "lru" else True
+    geoms = [(97, 3, np.float32, True), (64, 8, np.float32, False), (300, 40, np.float32, True)]
+    for n_slots, dim, _, with_init in geoms:
+        emb = wl.embedding_pattern(max(n_slots // 2, 1), dim, np.float32)
+        p = Pair(n_slots, 8, 1, evict, 0xF00D + n_slots, emb, fused_reset=True)
+        init = (np.arange(dim, dtype=np.float32) + 0.25) if with_init else None
+        ev = 0
+        for step in range(8):
+            ids = wl.rank_to_id(rng.integers(0, 4 * n_slots, size=2 * n_slots))
+            say("remap_reset", n_slots, dim, "step", step)
+            ev += p.step(ids, 3 * step, init_row=init).stats["evictions"]
+        assert ev > 0
+        p.close()
+    # a list of 4 entries for many evictions: the count is the true one and every evicted row is reset
+    n_slots = 256
+    g = mp.MpzchTable(n_slots, 8, mp.EVICT_TTL, 0, 5)
+    o = oracle.Table(n_slots, 8, oracle.EVICT_TTL, 0, 5)
+    ids0 = np.arange(n_slots, dtype=np.int64)
+    g.remap(torch.from_numpy(ids0).cuda(), 0)
+    o.remap(ids0, 0)
+    rows = torch.ones((n_slots, 8), dtype=torch.bfloat16, device="cuda")
+    out = torch.empty(n_slots, dtype=torch.int64, device="cuda")
+    short = torch.full((4,), -7, dtype=torch.int64, device="cuda")
+    nev = torch.zeros(1, dtype=torch.int64, device="cuda")
+    ids1 = np.arange(1000, 1000 + n_slots, dtype=np.int64)
+    mp.mpzch_remap_reset(g.handle, g.identities, g.metadata, torch.from_numpy(ids1).cuda(), 5, out, short, nev, None, rows)
+    torch.cuda.synchronize()
+    r = o.remap(ids1, 5)
+    assert int(nev.item()) == len(r.evicted) > 4
+    assert np.array_equal(out.cpu().numpy(), r.slots)
+    want = np.ones((n_slots, 8), np.float32)
+    want[r.evicted] = 0
+    assert np.array_equal(rows.float().cpu().numpy(), want)
+    with pytest.raises(mp.MpzchError):                                   # rows of 6 bytes
+        mp.mpzch_remap_reset(g.handle, g.identities, g.metadata, torch.from_numpy(ids1).cuda(), 6, out, short, nev, None,
+                             torch.zeros(4, 3, dtype=torch.bfloat16, device="cuda"))
+    g.close()
 
 
 def test_reset_rows_init_row_and_strides():
