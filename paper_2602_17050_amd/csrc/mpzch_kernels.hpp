@@ -237,6 +237,30 @@ __device__ __forceinline__ Tab view(const TableDesc &d)
     return t;
 }
 
+// A value that is the same in every lane, read from lane 0 so that the compiler keeps it in scalar
+// registers (a descriptor loaded from memory arrives in vector registers: the kernels also store to
+// global memory, so the load cannot be a scalar one).
+__device__ __forceinline__ int32_t uniform32(int32_t v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ int64_t uniform64(int64_t v)
+{
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uint64_t)v);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uint64_t)v >> 32));
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+__device__ __forceinline__ Tab uniform(const Tab &d)
+{
+    Tab t;
+    t.I = (global_ptr<int64_t>)(uintptr_t)uniform64((int64_t)(uintptr_t)(int64_t *)d.I);
+    t.M = (global_ptr<int32_t>)(uintptr_t)uniform64((int64_t)(uintptr_t)(int32_t *)d.M);
+    t.N = uniform64(d.N);
+    t.seed = (uint64_t)uniform64((int64_t)d.seed);
+    t.P = uniform32(d.P);
+    t.ttl = uniform32(d.ttl);
+    t.evict = uniform32(d.evict);
+    t.sh = uniform32(d.sh);
+    return t;
+}
+
 // Metadata written for the id at batch position pos: the step (last seen), or with per-feature TTL
 // (Sec. 3.4) the step after which the id is expired: now + duration of its feature.
 __device__ __forceinline__ int32_t meta_value(const Params &p, const Tab &d, int64_t pos)
@@ -594,9 +618,9 @@ __device__ __forceinline__ void discover_body(const Params &p)
         if (hi <= upos) hi = upos + 1;
         if (lo > upos) lo = upos;
         if (lo < 0) lo = 0;
-        t_lo = lo;
-        t_hi = hi;
-        t_d = view(p.descs[t_f]);
+        t_lo = uniform64(lo);
+        t_hi = uniform64(hi);
+        t_d = uniform(view(p.descs[t_f]));
     };
 
     // counters are kept for one table at a time
@@ -651,7 +675,8 @@ __device__ __forceinline__ void discover_body(const Params &p)
             while (__any(todo)) {
                 const int f0 = cached ? t_f : __shfl(f, __ffsll((unsigned long long)__ballot(todo)) - 1);
                 const bool mine = todo && f == f0;
-                const Tab d = !multi ? view(p.t0) : cached ? t_d : view(p.descs[f0]);
+                Tab d = t_d;                                    // one table: t_d is the table
+                if (multi && !cached) d = uniform(view(p.descs[f0]));
                 stats_table(f0);
                 const int64_t home = mine ? home_slot(id, d.seed, d.N) : 0;
                 int dist = -1;
@@ -686,6 +711,10 @@ __device__ __forceinline__ void discover_body(const Params &p)
         }
         if (TRAIN) {
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            // (read through lane 0: as plain copies the compiler would fold them with the per-lane descriptor
+            // loads of the last branch below into loads through a selected pointer, which puts t_d in memory)
+            const uint64_t c_seed = (uint64_t)uniform64((int64_t)t_d.seed);
+            const int64_t c_n = uniform64(t_d.N);
             for (int j = lane; j < nmiss; j += kWave) {
                 const uint32_t pos = s_pos[w][j];
                 const int64_t id = p.ids[pos];
@@ -698,7 +727,7 @@ __device__ __forceinline__ void discover_body(const Params &p)
                 } else if (all_cached) {
                     sb = 2ull * (uint64_t)t_lo;
                     ss = 2ull * (uint64_t)(t_hi - t_lo);
-                    home = home_slot(id, t_d.seed, t_d.N);
+                    home = home_slot(id, c_seed, c_n);
                 } else {
                     set_region(p, (int64_t)pos, sb, ss);
                     const TableDesc &td = p.descs[find_table(p.offsets, p.num_tables, (int64_t)pos)];
@@ -826,7 +855,7 @@ __global__ __launch_bounds__(kBlock, 3) void k_lookup_counting(Params p)
     discover_body<false, false, false, true>(p);
 }
 
-__global__ __launch_bounds__(kBlock, 3) void k_discover_tables(Params p)
+__global__ __launch_bounds__(kBlock, 4) void k_discover_tables(Params p)
 {
     discover_body<true, true, false>(p);
 }
@@ -843,8 +872,8 @@ __global__ __launch_bounds__(kBlock, 4) void k_lookup_tables(Params p)
 __device__ __forceinline__ bool segment_table(const Params &p, int64_t seg_base, int64_t seg_len, int &f, Tab &d)
 {
     f = __builtin_amdgcn_readfirstlane(find_table(p.offsets, p.num_tables, seg_base));
-    d = view(p.descs[f]);
-    return f == p.num_tables - 1 || seg_base + seg_len <= p.offsets[f + 1];
+    d = uniform(view(p.descs[f]));
+    return f == p.num_tables - 1 || uniform64(seg_base) + seg_len <= uniform64(p.offsets[f + 1]);
 }
 
 // ------------------------------------------------------------------ allocation
@@ -1431,8 +1460,13 @@ __device__ __forceinline__ void flush_evicted(const Params &p, const int64_t *bu
         base = p.num_tables > 1 ? atomicAdd(&p.ctl->num_evicted[table], (unsigned long long)count)
                                 : atomicAdd(&p.ctl->done, (unsigned long long)count) & kEvictedMask;
     base = (unsigned long long)shfl64((int64_t)base, 0);
-    const int64_t ev_begin = p.num_tables > 1 ? p.descs[table].ev_begin : p.t0.ev_begin;
-    const int64_t ev_cap = p.num_tables > 1 ? p.descs[table].ev_cap : p.t0.ev_cap;
+    // (separate statements: a choice between the descriptor in the kernel arguments and one in global memory,
+    // written as one expression, is compiled into loads through a generic pointer)
+    int64_t ev_begin = p.t0.ev_begin, ev_cap = p.t0.ev_cap;
+    if (p.num_tables > 1) {
+        ev_begin = p.descs[table].ev_begin;
+        ev_cap = p.descs[table].ev_cap;
+    }
     for (int i = lane; i < count; i += kWave) {
         const int64_t at = (int64_t)base + i;
         if (at < ev_cap) p.out_evicted[ev_begin + at] = buf[i];
@@ -1551,8 +1585,11 @@ __device__ __forceinline__ bool finalize_epilogue(const Params &p, FinalizeState
     __syncthreads();
     if (reserve) {
         const int64_t base = (int64_t)*s_base + before;
-        const int64_t ev_begin = multi ? p.descs[tab].ev_begin : p.t0.ev_begin;
-        const int64_t ev_cap = multi ? p.descs[tab].ev_cap : p.t0.ev_cap;
+        int64_t ev_begin = p.t0.ev_begin, ev_cap = p.t0.ev_cap;
+        if (multi) {
+            ev_begin = p.descs[tab].ev_begin;
+            ev_cap = p.descs[tab].ev_cap;
+        }
         for (int i = lane; i < fs.ev_cnt; i += kWave)
             if (base + i < ev_cap) p.out_evicted[ev_begin + base + i] = s_ev[w][i];
         reset_staged_rows(p, s_row[w], fs.ev_cnt);
@@ -1640,7 +1677,8 @@ __device__ __forceinline__ void finalize_body(const Params &p)
                 const uint32_t cfirst = __shfl(first, src);
                 const int64_t cid = shfl64(id, src);
                 const int64_t chome = shfl64(home, src);
-                const Tab dw = view(multi ? p.descs[__shfl(f, src)] : p.t0);
+                Tab dw = view(p.t0);
+                if (multi) dw = uniform(view(p.descs[__shfl(f, src)]));
                 int found_round = -1;
                 uint32_t found_occ = 0;
                 for (int32_t c0 = 0; c0 < dw.P && found_round < 0; c0 += kWave) {
