@@ -61,6 +61,45 @@ def test_create_validates_arguments_without_a_gpu(binding):
     assert b.mpzch_status_string(1) == "invalid argument"
 
 
+def test_entry_points_reject_bad_arguments_before_touching_the_gpu(binding):
+    """Checks that run before the first HIP call: NULL handles and required pointers, sizes out of range, a slot
+    count beyond MPZCH_MAX_SLOTS, a table that would reach past the 48 bits the kernels keep of an address."""
+    b = binding
+    lib = b.load_library()
+    vp = ctypes.c_void_p
+    h = b.mpzch_create(1000, 8, (b.EVICT_TTL, 1), 0)
+    fake = vp(0x10000)                                        # never dereferenced: every call below fails first
+    INVALID = 1
+    assert lib.mpzch_remap(None, fake, fake, fake, 4, 1, fake, fake, 4, fake, None, None) == INVALID
+    assert lib.mpzch_remap(h, None, fake, fake, 4, 1, fake, fake, 4, fake, None, None) == INVALID
+    assert lib.mpzch_remap(h, fake, fake, fake, -1, 1, fake, fake, 4, fake, None, None) == INVALID
+    assert lib.mpzch_remap(h, fake, fake, fake, (1 << 30) + 1, 1, fake, fake, 4, fake, None, None) == INVALID
+    assert lib.mpzch_remap(h, fake, fake, fake, 4, -1, fake, fake, 4, fake, None, None) == INVALID      # step < 0
+    assert lib.mpzch_remap(h, fake, fake, fake, 4, 1, None, fake, 4, fake, None, None) == INVALID       # no out_slots
+    assert lib.mpzch_remap(h, fake, fake, fake, 4, 1, fake, None, 4, fake, None, None) == INVALID       # list of 4, no pointer
+    high = vp((1 << 48) - 4096)                                # identities would end beyond 2^48
+    assert lib.mpzch_remap(h, high, fake, fake, 4, 1, fake, fake, 4, fake, None, None) == INVALID
+    assert lib.mpzch_lookup(h, high, fake, 4, fake, None, None) == INVALID
+    assert lib.mpzch_remap_reset(h, fake, fake, fake, 4, 1, fake, fake, 4, fake, None, None, 10, 16, 16, None, None) == INVALID
+    assert lib.mpzch_remap_reset(h, fake, fake, fake, 4, 1, fake, fake, 4, fake, None, fake, 0, 16, 16, None, None) == INVALID
+    assert lib.mpzch_remap_reset(h, fake, fake, fake, 4, 1, fake, fake, 4, fake, None, fake, 10, 6, 8, None, None) == INVALID
+    assert lib.mpzch_remap_noalloc(h, fake, fake, fake, b.NOALLOC_MAX_BATCH + 1, 1, fake, fake, 4, fake, None, None) == 5
+    assert lib.mpzch_lookup(None, fake, fake, 4, fake, None, None) == INVALID
+    assert lib.mpzch_lookup_gather(h, fake, fake, 4, None, 10, 16, 16, fake, None, None, None) == INVALID  # no rows
+    assert lib.mpzch_reset_rows(fake, fake, 4, fake, 10, 6, 8, None, None) == INVALID                       # 6-byte rows
+    assert lib.mpzch_reserve(h, -1) == INVALID
+    b.mpzch_destroy(h)
+    with pytest.raises(b.MpzchError) as e:
+        b.mpzch_create((1 << 40) + 1, 8, (b.EVICT_TTL, 1), 0)
+    assert e.value.status == INVALID
+    hr = b.mpzch_create_with_layout(1000, 8, (b.EVICT_TTL, 1), 0, b.LAYOUT_RECORDS)
+    assert lib.mpzch_lookup(hr, vp(0x10008), fake, 4, fake, None, None) == INVALID      # records not 16-byte aligned
+    assert lib.mpzch_remap(hr, vp(0x10000), vp(0x10004), fake, 4, 1, fake, fake, 4, fake, None, None) == INVALID  # metadata elsewhere
+    b.mpzch_destroy(hr)
+    with pytest.raises(b.MpzchError):
+        b.mpzch_create_with_layout(1000, 8, (b.EVICT_TTL, 1), 0, 2)
+
+
 def test_group_create_validates_arguments(binding):
     b = binding
     hs = [b.mpzch_create(100 + i, 4, (b.EVICT_TTL, 1), i) for i in range(3)]
