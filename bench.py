@@ -134,7 +134,7 @@ def main():
                     help="bracket every kernel with events (a breakdown; costs a step some 30 us), not only Pass 1")
     ap.add_argument("--policy", default="ttl", choices=["ttl", "lru"], help="eviction policy (headline / c4 workloads)")
     ap.add_argument("--no-fused-reset", action="store_true",
-                    help="headline / c4: a step is mpzch_remap + mpzch_reset_rows (two calls, four launches) instead of "
+                    help="headline / c4 / c1 / c2: a step is mpzch_remap + mpzch_reset_rows (two calls, four launches) instead of "
                          "mpzch_remap_reset (the rows are reset by the finalize kernel)")
     ap.add_argument("--layout", default="records", choices=["separate", "records"],
                     help="headline / c4: identities and metadata as one tensor of 16-byte records {int64 id, int32 "
@@ -233,10 +233,11 @@ def main():
         host_M = np.ascontiguousarray(g.metadata.cpu().numpy())
         log(f"[bench] copied table state to host in {time.perf_counter() - t0:.2f}s")
 
-    # HIP events around the dominant kernel (Pass 1) of every timed step, recorded by the library on
-    # the stream it launches on; --all-kernel-timing brackets every kernel
+    # HIP events around the dominant kernel (Pass 1) of every fourth timed step (the 4th, 8th, ...),
+    # recorded by the library on the stream it launches on (a pair of events costs a step some 8 us);
+    # --all-kernel-timing brackets every kernel of every step
     if not args.no_kernel_timing:
-        mp.mpzch_set_kernel_timing(g.handle, 1 if args.all_kernel_timing else 2)
+        mp.mpzch_set_kernel_timing(g.handle, 1 if args.all_kernel_timing else 3)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(W, W + K):
@@ -338,7 +339,7 @@ def main():
             "collisions": round(collisions / K, 1), "mean_hit_probe_len": round(mean_probe, 3),
             "mean_miss_probe_len": round(mean_miss_len, 3),
         },
-        "kernel_ms_per_step": {k: round(v[0] / K, 4) for k, v in ktimes.items()},
+        "kernel_ms_per_step": kernel_ms_per_step(ktimes, K),
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
@@ -379,7 +380,7 @@ def bench_lookup(args, np, torch, mp, wl, dev):
     for i in range(W):
         one(i)
     torch.cuda.synchronize()
-    mp.mpzch_set_kernel_timing(g.handle, 1)
+    mp.mpzch_set_kernel_timing(g.handle, 1 if args.all_kernel_timing else 3)
     t0 = time.perf_counter()
     for i in range(W, W + K):
         one(i)
@@ -441,7 +442,7 @@ def bench_lookup(args, np, torch, mp, wl, dev):
                    "scale": args.scale},
         "per_step": {"distinct_resident_ids": round(u_hit / K, 1), "distinct_absent_ids": round(u_miss / K, 1),
                      "mean_hit_probe_len": round(mean_probe, 3), "mean_miss_probe_len": round(mean_miss_len, 3)},
-        "kernel_ms_per_step": {k: round(v[0] / K, 4) for k, v in ktimes.items()},
+        "kernel_ms_per_step": kernel_ms_per_step(ktimes, K),
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
@@ -463,13 +464,23 @@ def training_alg_bytes(np, positions, st_rows, distinct, names):
     return alg, lines, hit_pos
 
 
+def kernel_ms_per_step(ktimes, K):
+    """Milliseconds per step of every timed kernel; the steps that were timed are those whose Pass-1 kernel was
+    (all K of them, or a sample)."""
+    timed = K
+    for name in ("k_discover", "k_lookup"):
+        if name in ktimes:
+            timed = ktimes[name][1]
+    return {k: round(v[0] / max(timed, 1), 4) for k, v in ktimes.items()}
+
+
 def _emit(metric, value, K, W, elapsed, workload, ktimes, cpu, extra=None, roofline=None):
     dom = max(ktimes, key=lambda k: ktimes[k][0]) if ktimes else None
     result = {
         "metric": metric, "value": round(value, 1), "unit": "ids/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": round(elapsed / K * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int64", "data": "synthetic", "config": {"workload": workload},
-        "kernel_ms_per_step": {k: round(v[0] / K, 4) for k, v in ktimes.items()},
+        "kernel_ms_per_step": kernel_ms_per_step(ktimes, K),
         "roofline": roofline or {"bound": "hbm", "kernel": dom, "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                  "frac": None, "traffic": None,
                                  "avg_kernel_ms": round(ktimes[dom][0] / ktimes[dom][1], 4) if dom else None},
@@ -512,8 +523,11 @@ def bench_small_table(args, np, torch, mp, wl, dev):
 
     def one(i):
         s_, b_ = batches[i]
-        mp.mpzch_remap(g.handle, g.identities, g.metadata, b_, s_, outs[i], ev, nev, stats[i])
-        mp.mpzch_reset_rows(ev, nev, emb)
+        if args.no_fused_reset:
+            mp.mpzch_remap(g.handle, g.identities, g.metadata, b_, s_, outs[i], ev, nev, stats[i])
+            mp.mpzch_reset_rows(ev, nev, emb)
+        else:
+            mp.mpzch_remap_reset(g.handle, g.identities, g.metadata, b_, s_, outs[i], ev, nev, stats[i], emb)
 
     if args.graph:
         # the timed steps as one captured graph: the table state before the capture is restored before the
@@ -538,7 +552,7 @@ def bench_small_table(args, np, torch, mp, wl, dev):
     else:
         if not args.no_kernel_timing:
             # two event records per launch: every kernel costs these small steps some 30 us, Pass 1 alone a few
-            mp.mpzch_set_kernel_timing(g.handle, 1 if args.all_kernel_timing else 2)
+            mp.mpzch_set_kernel_timing(g.handle, 1 if args.all_kernel_timing else 3)
         t0 = time.perf_counter()
         for i in range(W, nb):
             one(i)

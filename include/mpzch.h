@@ -416,8 +416,9 @@ mpzch_status_t mpzch_lookup_jagged(mpzch_group_t *g, const int64_t *const *ident
 /*
  * Per-kernel timing for benchmarks.  enable = 1: every kernel launched through the handle is
  * bracketed by HIP events on the call's stream; enable = 2: only the Pass-1 kernel of each call
- * (k_discover / k_lookup), which costs the call a few microseconds instead of some thirty;
- * enable = 0: off.  mpzch_kernel_times
+ * (k_discover / k_lookup), which costs the call some eight microseconds instead of thirty;
+ * enable = 3: the Pass-1 kernel of every fourth call (the 4th, 8th, ... after this call: a
+ * sample, two microseconds per call on average); enable = 0: off.  mpzch_kernel_times
  * synchronises those events, adds up the durations per kernel and clears the record.
  * names [host] receives up to cap pointers to static strings, ms [host] the summed
  * milliseconds, launches [host] the number of launches; *count the number of kernels.

@@ -374,7 +374,7 @@ def _times(fn, handle):
 
 
 def mpzch_set_kernel_timing(handle, enable):
-    """enable: 0 / False = off, 1 / True = every kernel, 2 = the Pass-1 kernel only."""
+    """enable: 0 / False = off, 1 / True = every kernel, 2 = the Pass-1 kernel only, 3 = the Pass-1 kernel of every fourth call."""
     _check(load_library().mpzch_set_kernel_timing(handle, int(enable)), "mpzch_set_kernel_timing")
 
 

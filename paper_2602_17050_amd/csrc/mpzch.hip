@@ -30,7 +30,16 @@ const char *const kKernelNames[KernelCount] = {"k_discover", "k_allocate", "k_fi
 struct Timing {
     bool enabled = false;
     bool pass1_only = false;       // bracket k_discover / k_lookup only (two events per call instead of eight)
+    int every = 1;                 // ... and of those launches only every `every`-th
+    int64_t pass1_seen = 0;
     bool skipped = false;          // the launch between the last begin and end is not bracketed
+    void set_mode(int32_t enable)
+    {
+        enabled = enable != 0;
+        pass1_only = enable == 2 || enable == 3;
+        every = enable == 3 ? 4 : 1;
+        pass1_seen = 0;
+    }
     struct Rec { int kernel; hipEvent_t a, b; };
     std::vector<Rec> used;
     std::vector<std::pair<hipEvent_t, hipEvent_t>> pool;
@@ -38,6 +47,7 @@ struct Timing {
     bool begin(int kernel, hipStream_t s)
     {
         skipped = !enabled || (pass1_only && kernel != KDiscover && kernel != KLookup);
+        if (!skipped && pass1_only) skipped = (pass1_seen++ % every) != every - 1;
         if (skipped) return true;
         std::pair<hipEvent_t, hipEvent_t> ev;
         if (!pool.empty()) {
@@ -1136,8 +1146,7 @@ mpzch_status_t mpzch_reset_rows_jagged(mpzch_group_t *g, const int64_t *evicted_
 mpzch_status_t mpzch_set_kernel_timing(mpzch_table_t *t, int32_t enable)
 {
     if (!t) return MPZCH_ERR_INVALID_ARG;
-    t->tm.enabled = enable != 0;
-    t->tm.pass1_only = enable == 2;
+    t->tm.set_mode(enable);
     return MPZCH_OK;
 }
 
@@ -1151,8 +1160,7 @@ mpzch_status_t mpzch_kernel_times(mpzch_table_t *t, const char **names, double *
 mpzch_status_t mpzch_group_set_kernel_timing(mpzch_group_t *g, int32_t enable)
 {
     if (!g) return MPZCH_ERR_INVALID_ARG;
-    g->tm.enabled = enable != 0;
-    g->tm.pass1_only = enable == 2;
+    g->tm.set_mode(enable);
     return MPZCH_OK;
 }
 
