@@ -304,3 +304,33 @@ def test_a_record_table_is_rejected_unless_its_tensors_are_one_tensor_of_aligned
     mp.mpzch_lookup(h, good_i, ids, out)                               # and the well-formed call goes through
     torch.cuda.synchronize()
     mp.mpzch_destroy(h)
+
+
+def test_kernel_timing_modes_count_the_launches_they_bracket():
+    """mpzch_set_kernel_timing: 1 = every kernel of every call, 2 = the Pass-1 kernel of every call, 3 = the
+    Pass-1 kernel of every fourth call; mpzch_kernel_times returns what was bracketed and clears the record."""
+    g = mp.MpzchTable(5000, 8, mp.EVICT_TTL, 2, 11)
+    rng = np.random.Generator(np.random.Philox(key=99))
+    calls = 10
+
+    def run(mode):
+        mp.mpzch_set_kernel_timing(g.handle, mode)
+        for k in range(calls):
+            g.remap(torch.from_numpy(rng.integers(0, 20000, size=3000)).cuda(), k)
+        g.lookup(torch.from_numpy(rng.integers(0, 20000, size=3000)).cuda())
+        torch.cuda.synchronize()
+        t = mp.mpzch_kernel_times(g.handle)
+        mp.mpzch_set_kernel_timing(g.handle, 0)
+        return t
+
+    t = run(1)
+    assert {k: v[1] for k, v in t.items()} == {"k_discover": calls, "k_allocate": calls, "k_finalize": calls, "k_lookup": 1}
+    assert all(v[0] > 0 for v in t.values())
+    t = run(2)
+    assert {k: v[1] for k, v in t.items()} == {"k_discover": calls, "k_lookup": 1}
+    t = run(3)                                              # 11 Pass-1 launches: the 4th and the 8th are timed
+    assert sum(v[1] for v in t.values()) == 2 and t["k_discover"][1] == 2
+    assert mp.mpzch_kernel_times(g.handle) == {}             # the record was cleared
+    t = run(0)
+    assert t == {}
+    g.close()
