@@ -1,12 +1,13 @@
 // Device code of the MPZCH batched remap for gfx950 (wave64).
 //
 // Kernel sequence of one training remap (paper Sec. 3.2 / Algorithm 1, Sec. 3.4, Sec. 3.6):
-//   k_discover   Pass 1 for every position.  An 8-lane group reads the aligned 64 bytes that hold
-//                the id's home slot with one coalesced access and finds the id by ballot + ffs;
-//                the few ids whose window continues are parked in LDS and scanned 16 slots at
+//   k_discover   Pass 1 for every position.  An 8-lane group reads the aligned block of 8 slots
+//                that holds the id's home slot with one coalesced access; ids and results travel
+//                between the id's lane and the lanes that load for it through LDS (probe_pass);
+//                the few ids whose window continues are parked in LDS and scanned 8 slots at
 //                a time.  Hits store metadata = step and the output slot.  (k_lookup is the
 //                same body without writes, k_discover_tables / k_lookup_tables the bodies for
-//                several tables.)  Each
+//                several tables, k_discover_records the one for a table of 16-byte records.)  Each
 //                wavefront owns a contiguous range of positions (a segment) and appends the
 //                positions that missed to its segment's list; at the end it enters them into a
 //                scratch hash set that elects, per distinct missed id, the position of its first
@@ -43,7 +44,6 @@ constexpr int kBlock = 256;
 constexpr int kWavesPerBlock = kBlock / kWave;
 constexpr int kMaxTables = 64;
 constexpr int kStatCount = 9;
-constexpr int kLine = 16;              // identities per 128-byte line
 constexpr int kStage = 512;            // missed positions staged per wavefront before they are entered
 constexpr int kEvBuf = 256;            // evicted slots staged per wavefront before a flush
 
@@ -161,25 +161,6 @@ __device__ __forceinline__ int64_t shfl64(int64_t v, int src)
 }
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
-
-template <int G>
-__device__ __forceinline__ uint32_t group_bits(uint64_t ballot, int group)
-{
-    if constexpr (G == 64) return 0;  // a 64-lane group reads the whole ballot, see group_first
-    return (uint32_t)(ballot >> (group * G)) & (uint32_t)((1ull << G) - 1ull);
-}
-
-// first set bit (0-based) of this group's part of a ballot, or -1
-template <int G>
-__device__ __forceinline__ int group_first(uint64_t ballot, int group)
-{
-    if constexpr (G == 64) {
-        return ballot ? __ffsll((unsigned long long)ballot) - 1 : -1;
-    } else {
-        uint32_t b = group_bits<G>(ballot, group);
-        return b ? __ffs(b) - 1 : -1;
-    }
-}
 
 // table owning position pos (largest f with offsets[f] <= pos)
 __device__ __forceinline__ int find_table(const int64_t *offsets, int num_tables, int64_t pos)
