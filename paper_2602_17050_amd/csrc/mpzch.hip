@@ -262,12 +262,17 @@ TableDesc make_desc(const TableCfg &c, int64_t *I, int32_t *M, int64_t ev_begin,
         if (hipGetLastError() != hipSuccess) return MPZCH_ERR_HIP; \
     } while (0)
 
+// two-tensor tables from this size on (1 GiB of identities, four times the memory-side cache) are probed with
+// non-temporal loads in training
+constexpr int64_t kStreamingSlots = (int64_t)1 << 27;
+
 template <bool TRAIN>
 mpzch_status_t launch_discover(const Params &p, int grid, hipStream_t s)
 {
     if (TRAIN) {
         if (p.num_tables > 1) hipLaunchKernelGGL(k_discover_tables, dim3(grid), dim3(kBlock), 0, s, p);
         else if (p.t0.sh) hipLaunchKernelGGL(k_discover_records, dim3(grid), dim3(kBlock), 0, s, p);
+        else if (p.t0.N >= kStreamingSlots) hipLaunchKernelGGL(k_discover_streaming, dim3(grid), dim3(kBlock), 0, s, p);
         else hipLaunchKernelGGL(k_discover, dim3(grid), dim3(kBlock), 0, s, p);
     } else {
         if (p.num_tables > 1) hipLaunchKernelGGL(k_lookup_tables, dim3(grid), dim3(kBlock), 0, s, p);

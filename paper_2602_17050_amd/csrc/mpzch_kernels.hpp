@@ -446,7 +446,8 @@ constexpr int kWhereAddrBits = 48;
 // that exist below its own -- its own slot when its round exists, else the first slot (r < r_lo) or the one after
 // the last (r >= r_hi): valid addresses in or next to the line that is fetched anyway.  Slots past the end of the
 // table go on at slot 0.
-template <int G>
+// NT: the loads are marked non-temporal (see k_discover_streaming).
+template <int G, bool NT>
 __device__ __forceinline__ void probe_loads(const Tab &d, const ProbeReq *s_req, int64_t (&v)[G])
 {
     constexpr int IPI = kWave / G;
@@ -462,7 +463,8 @@ __device__ __forceinline__ void probe_loads(const Tab &d, const ProbeReq *s_req,
         const uint32_t k = (uint32_t)__popc((uint32_t)(where >> kWhereAddrBits) & below);
         uint64_t a = (where & ((1ull << kWhereAddrBits) - 1ull)) + (uint64_t)(k << sh3);
         if (a >= table_end) a -= table_bytes;
-        v[t] = *(global_ptr<int64_t>)(uintptr_t)a;
+        if constexpr (NT) v[t] = __builtin_nontemporal_load((global_ptr<int64_t>)(uintptr_t)a);
+        else v[t] = *(global_ptr<int64_t>)(uintptr_t)a;
     }
 }
 
@@ -471,7 +473,7 @@ __device__ __forceinline__ void probe_loads(const Tab &d, const ProbeReq *s_req,
 // slot, 0 = neither) goes back through LDS as one byte per slot, and the id's own lane reads its G
 // bytes at once and drops those of rounds that do not exist: no cross-lane operation depends on a
 // load, and nothing branches.
-template <int G>
+template <int G, bool NT = false>
 __device__ __forceinline__ int probe_pass(const Tab &d, int64_t id, int64_t home, int q, ProbeReq *s_req,
                                           uint8_t *s_code)
 {
@@ -490,7 +492,7 @@ __device__ __forceinline__ int probe_pass(const Tab &d, int64_t id, int64_t home
     s_req[lane] = ProbeReq{id, (uint64_t)(uintptr_t)(int64_t *)id_at(d, first_slot) | ((uint64_t)rounds << kWhereAddrBits)};
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     int64_t v[G];
-    probe_loads<G>(d, s_req, v);
+    probe_loads<G, NT>(d, s_req, v);
 #pragma unroll
     for (int t = 0; t < G; ++t) {
         const int64_t gid = s_req[t * IPI + g].id;
@@ -556,7 +558,7 @@ __device__ __forceinline__ void gather_wave(const Params &p, bool active, int64_
 // in LDS (position, next round) and resolved later, 64 at a time, so that the second
 // memory round trip is paid once per 64 parked ids instead of once per chunk.  What remains
 // unfound is the segment's miss list.
-template <bool TRAIN, bool MULTI, bool GATHER, bool COUNT = TRAIN>
+template <bool TRAIN, bool MULTI, bool GATHER, bool COUNT = TRAIN, bool NT = false>
 __device__ __forceinline__ void discover_body(const Params &p)
 {
     __shared__ uint32_t s_pos[kWavesPerBlock][kStage];
@@ -666,7 +668,7 @@ __device__ __forceinline__ void discover_body(const Params &p)
                 for (;;) {
                     const bool need = mine && dist < 0 && mlen == 0 && q < d.P;
                     if (!__any(need)) break;
-                    const int got = probe_pass<kNextG>(d, id, home, need ? q : d.P, s_req[w], s_code[w]);
+                    const int got = probe_pass<kNextG, NT>(d, id, home, need ? q : d.P, s_req[w], s_code[w]);
                     if (need) {
                         if (got >= 0) dist = got;
                         else if (got <= kProbeAbsent) mlen = absent_len(got);   // an empty slot ends the search
@@ -755,7 +757,7 @@ __device__ __forceinline__ void discover_body(const Params &p)
             const int64_t home = mine ? home_slot(id, d.seed, d.N) : 0;
             // first pass: the aligned 64 bytes that hold the home slot
             const int o = block_offset(d, home, kFirstG);
-            int res = probe_pass<kFirstG>(d, id, home, valid ? -o : d.P, s_req[w], s_code[w]);
+            int res = probe_pass<kFirstG, NT>(d, id, home, valid ? -o : d.P, s_req[w], s_code[w]);
             if (res == kProbeGoOn && kFirstG - o >= d.P) res = probe_absent(d.P - 1);    // the whole window was read
             const bool hit = valid && res >= 0;
             if (hit) finish_hit(d, pos, home, res, false);
@@ -813,6 +815,16 @@ __device__ __forceinline__ void discover_body(const Params &p)
 __global__ __launch_bounds__(kBlock, 4) void k_discover(Params p)
 {
     discover_body<true, false, false>(p);
+}
+
+// The same pass with the identities read by non-temporal loads, for a two-tensor table far larger than the
+// caches: a line of identities is not used again before it is evicted anyway, and not keeping it leaves the L2
+// to the lines of metadata that the hits write into (headline with two tensors: 0.295 -> 0.253 ms).  Not for
+// records -- there the refresh goes into the very line the probe has fetched (0.218 -> 0.277 ms with such
+// loads) -- and not for lookups, whose repeated ids do hit in the L2 (config 3: 0.029 -> 0.034 ms).
+__global__ __launch_bounds__(kBlock, 4) void k_discover_streaming(Params p)
+{
+    discover_body<true, false, false, true, true>(p);
 }
 
 // the same pass over a table kept as 16-byte records: the metadata store lands in the line just read
