@@ -114,7 +114,8 @@ __global__ void k_store4_bucketed(int *t, uint64_t n, uint64_t ops, uint64_t buc
 // The metadata refresh as part of the line that was fetched for the identities: 16 lanes read one random
 // aligned 128-byte line, then one of them stores 4 bytes -- into the SAME line (an interleaved
 // identities + metadata layout) or into a second array at the matching place (the two-tensor layout).
-template <bool SAME>
+// NT: the line is read with non-temporal loads.
+template <bool SAME, bool NT = false>
 __global__ void k_line_then_store4(long long *t, int *m, uint64_t n, uint64_t ops, long long *sink)
 {
     long long a = 0;
@@ -127,7 +128,7 @@ __global__ void k_line_then_store4(long long *t, int *m, uint64_t n, uint64_t op
             const uint64_t j = i + u * groups;
             if (j < ops) {
                 const uint64_t s = __umul64hi(mix64(j), n - 32) & ~15ull;
-                const long long v = t[s + r];
+                const long long v = NT ? __builtin_nontemporal_load(&t[s + r]) : t[s + r];
                 a += v;
                 if (r == 15) {
                     // the store depends on the value read, as a refresh depends on the match
@@ -260,6 +261,10 @@ int main(int argc, char **argv)
     report("random line read + 4-byte store into a second array", (double)ops, 132.0);
     TIME((k_line_then_store4<true><<<8192, 256>>>(t, m, n, ops, (long long *)c + 8)));
     report("random line read + 4-byte store into the same line", (double)ops, 132.0);
+    TIME((k_line_then_store4<false, true><<<8192, 256>>>(t, m, n, ops, (long long *)c + 8)));
+    report("non-temporal line read + 4-byte store into a second array", (double)ops, 132.0);
+    TIME((k_line_then_store4<true, true><<<8192, 256>>>(t, m, n, ops, (long long *)c + 8)));
+    report("non-temporal line read + 4-byte store into the same line", (double)ops, 132.0);
     TIME((k_store4<<<8192, 256>>>(m, n, ops)));
     report("random 4-byte stores (one per lane)", (double)ops, 4.0);
     for (uint64_t buckets : {2048ull, 65536ull, 2097152ull}) {
