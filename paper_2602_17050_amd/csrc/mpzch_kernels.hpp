@@ -772,7 +772,8 @@ __device__ __forceinline__ void discover_body(const Params &p)
             // pattern) and for a lookup miss, rewritten later otherwise.
             const int64_t slot = hit ? wrap(home + res, d.N) : home;
             if (mine) {
-                if (!GATHER || p.out_slots) p.out_slots[pos] = slot;
+                // (non-temporal: the outputs are not read by this call; nine in ten are final here)
+                if (!GATHER || p.out_slots) __builtin_nontemporal_store(slot, &p.out_slots[pos]);
                 if (!TRAIN && p.out_found) p.out_found[pos] = hit ? 1 : 0;
             }
             // not found so far: parked when its window goes on, or (training) to be listed as a miss
