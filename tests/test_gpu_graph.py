@@ -14,11 +14,14 @@ from gpu_common import say
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("policy", ["ttl", "lru"])
+@pytest.mark.parametrize("policy", ["ttl", "lru", "ttl-fused-records"])
 def test_captured_step_replays_match_the_oracle(policy):
+    """("-fused-records": the step is one mpzch_remap_reset call on a table of 16-byte records.)"""
     n_slots, max_probe, ttl, seed, n, step = 50_000, 16, 2, 77, 30_000, 5
     kind_g, kind_o = (mp.EVICT_LRU, oracle.EVICT_LRU) if policy == "lru" else (mp.EVICT_TTL, oracle.EVICT_TTL)
-    g = mp.MpzchTable(n_slots, max_probe, kind_g, ttl, seed, max_batch=n)
+    fused = policy.endswith("fused-records")
+    g = mp.MpzchTable(n_slots, max_probe, kind_g, ttl, seed, max_batch=n,
+                      layout=mp.LAYOUT_RECORDS if fused else mp.LAYOUT_SEPARATE)
     o = oracle.Table(n_slots, max_probe, kind_o, ttl, seed)
     emb_o = wl.embedding_pattern(n_slots, 8, np.float32)
     emb_g = torch.from_numpy(emb_o).cuda()
@@ -35,6 +38,9 @@ def test_captured_step_replays_match_the_oracle(policy):
     stats = torch.zeros(mp.STAT_COUNT, dtype=torch.int64, device="cuda")
 
     def one_step():
+        if fused:
+            mp.mpzch_remap_reset(g.handle, g.identities, g.metadata, ids_buf, step, out, evicted, nev, stats, emb_g)
+            return
         mp.mpzch_remap(g.handle, g.identities, g.metadata, ids_buf, step, out, evicted, nev, stats)
         mp.mpzch_reset_rows(evicted, nev, emb_g)
 
