@@ -97,6 +97,9 @@ enum {
 #define MPZCH_MAX_BATCH ((int64_t)1 << 30) /* positions per remap / lookup call          */
 #define MPZCH_MAX_PROBE (1 << 20)          /* upper bound accepted for max_probe          */
 #define MPZCH_MAX_SLOTS ((int64_t)1 << 40) /* upper bound accepted for num_slots (8 TB of identities) */
+/* The identities of a table must lie below address 2^48 (every device address of this GPU does): the
+   kernels keep the address of a slot in 48 bits.  Entry points that probe a table return INVALID_ARG
+   for one that does not. */
 #define MPZCH_MAX_GROUP_TABLES 64          /* tables per mpzch_group_t                    */
 #define MPZCH_MAX_PROBE_LRU 1024           /* largest max_probe with MPZCH_EVICT_LRU      */
 
